@@ -1,0 +1,160 @@
+/*
+ * heisd_verify.h - C ABI of the target-model verify step of HeiSD's hybrid
+ * speculative decoding, for one AMD MI355X (gfx950).
+ *
+ * What one call computes (paper Sec. 2.2, Eq. 2-2; Sec. 4.1; Sec. 4.2; App. A.1/A.2):
+ * given the cached keys/values of a vision+text prefix, a block of K drafted
+ * action tokens per episode (from the retrieval or the drafter branch), and the
+ * target model's weights, run ONE teacher-forced decoder forward over the K
+ * tokens, restrict the LM head to the 256 action bins, take the greedy bin per
+ * position, and apply the sequence-wise relaxed acceptance rule.  Episodes whose
+ * verify-skip flag is set bypass verification and keep their whole draft.
+ *
+ * Plain C99: no C++ types, no exceptions cross this boundary.  Every pointer is
+ * marked HOST or DEVICE.  The library never allocates device memory, never
+ * synchronises in heisd_verify_step, and keeps only what the opaque context holds.
+ */
+#ifndef HEISD_VERIFY_H
+#define HEISD_VERIFY_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* Return codes: 0 on success, negative on failure.  On failure nothing was enqueued. */
+#define HEISD_OK 0
+#define HEISD_EINVAL (-1)        /* NULL / out-of-range argument, inconsistent shapes        */
+#define HEISD_EUNSUPPORTED (-2)  /* shape the compiled kernels do not cover                   */
+#define HEISD_ENOMEM (-3)        /* workspace smaller than heisd_verify_workspace_bytes()     */
+#define HEISD_EHIP (-4)          /* the HIP runtime reported an error                          */
+
+#define HEISD_MAX_GROUPS 8
+
+typedef struct heisd_verify_ctx heisd_verify_ctx; /* opaque */
+
+/*
+ * The target model M_V: a Llama-2-style decoder (App. A.1) whose action head reads
+ * n_bins consecutive vocabulary ids (App. A.2: 256 bins per action dimension).
+ * All matrices are DEVICE pointers to bf16, row-major [out, in], caller-owned,
+ * read-only, and must outlive the context.  Gains are DEVICE fp32 vectors.
+ * The pointer tables themselves (wq[l] ...) are HOST arrays of n_layers device
+ * pointers; they are copied at init.
+ */
+typedef struct {
+  int32_t n_layers, d_model, n_heads, head_dim, d_ffn, vocab;
+  int32_t n_bins;         /* number of action bins (256)                                  */
+  int32_t bin_token_base; /* bin b <-> vocabulary id bin_token_base + b                   */
+  float rms_eps;          /* RMSNorm epsilon                                               */
+  float rope_base;        /* rotary base (rotate-half pairing, absolute positions)         */
+  int32_t max_batch;      /* largest `batch` a step may pass                               */
+  int32_t max_k;          /* largest `K` a step may pass                                   */
+  int32_t kv_capacity;    /* rows per (layer, episode, head) in the caller's KV cache      */
+  const void *tok_emb;    /* DEVICE bf16 [vocab, d_model]                                  */
+  const void *const *wq, *const *wk, *const *wv, *const *wo;    /* HOST tables of DEVICE bf16 [d_model, d_model] */
+  const void *const *w_gate, *const *w_up;                       /* ... DEVICE bf16 [d_ffn, d_model]              */
+  const void *const *w_down;                                     /* ... DEVICE bf16 [d_model, d_ffn]              */
+  const float *const *attn_norm, *const *ffn_norm;               /* HOST tables of DEVICE fp32 [d_model]          */
+  const float *final_norm;                                       /* DEVICE fp32 [d_model]                         */
+  const void *lm_head;    /* DEVICE bf16 [vocab, d_model]; only rows bin_token_base .. +n_bins-1 are read */
+  void *workspace;        /* DEVICE scratch, caller-allocated, 256-byte aligned, owned by the ctx until heisd_free */
+  size_t workspace_bytes; /* at least heisd_verify_workspace_bytes(desc)                   */
+} heisd_model_desc;
+
+/*
+ * The prefix (observations + prompt of Eq. 2-2) as cached keys and values.
+ * Layout: bf16 [n_layers][batch][n_heads][kv_capacity][head_dim], keys already
+ * rotated.  A step READS rows 0 .. prefix_len[b]-1 and WRITES rows prefix_len[b] ..
+ * prefix_len[b]+K-1 of every non-skipped episode b (the drafts' keys/values), so
+ * that the caller's next step can start at prefix_len[b] + accepted_len[b]; rows
+ * past that are garbage to be overwritten.  prefix_len[b] + K <= kv_capacity is the
+ * caller's duty (device data cannot be checked without a sync; the kernels clamp
+ * instead of faulting).
+ * first_pred[b] is the target's greedy bin after the last prefix position, i.e.
+ * a_hat_0 of Eq. 2-2, which depends on the prefix alone and is produced by whoever
+ * filled the cache.
+ */
+typedef struct {
+  void *k_cache;             /* DEVICE bf16, see layout above */
+  void *v_cache;             /* DEVICE bf16                   */
+  const int32_t *prefix_len; /* DEVICE i32 [batch]            */
+  const int32_t *first_pred; /* DEVICE i32 [batch], bin index in [0, n_bins) */
+} heisd_kv_desc;
+
+/*
+ * Sequence-wise relaxed acceptance (Sec. 4.2).  Draft positions are cut into
+ * consecutive groups following group_sizes, repeating every sum(group_sizes)
+ * positions (one action slice: (X,Y,Z), (rX,rY,rZ), (G)).  bias_j = |draft bin -
+ * target bin|.  A group is accepted iff every bias_j <= tok_threshold and the sum of
+ * its biases <= seq_budget; a group whose bit is set in exact_group_mask (the
+ * gripper) is accepted iff every bias is 0.  accepted_len is the total length of the
+ * leading run of accepted groups.  Strict verification (Eq. 2-2) is thresholds 0/0.
+ * The paper's values: tok_threshold 15, seq_budget 30, groups {3,3,1}, mask 1<<2.
+ * mode 0 is that rule.  mode 1 is a token-granular variant that is NOT in the paper:
+ * accept up to the first token whose bias exceeds tok_threshold, or whose running
+ * sum of biases over the block exceeds seq_budget, or exact-group token with bias != 0.
+ */
+typedef struct {
+  int32_t tok_threshold;
+  int32_t seq_budget;
+  int32_t n_groups;
+  int32_t group_sizes[HEISD_MAX_GROUPS];
+  uint32_t exact_group_mask;
+  int32_t mode;
+} heisd_accept_desc;
+
+/* Bytes of device workspace heisd_verify_init needs for this model description
+ * (depends only on the shape fields).  Returns 0 if the description is invalid. */
+size_t heisd_verify_workspace_bytes(const heisd_model_desc *desc);
+
+/*
+ * Validate the description, copy the pointer tables, lay out the workspace, build the
+ * rotary table.  May synchronise the device.  *out receives a context to be released
+ * with heisd_free.  Not thread-safe; one step in flight per context.
+ * Errors: EINVAL (NULL pointers, non-positive sizes, d_model != n_heads*head_dim,
+ * bins outside the vocabulary), EUNSUPPORTED (head_dim not 64 or 128, d_model or d_ffn
+ * not a multiple of 16, max_k > 64), ENOMEM (workspace too small), EHIP.
+ */
+int heisd_verify_init(const heisd_model_desc *desc, heisd_verify_ctx **out);
+
+/*
+ * Enqueue one verify step on `stream` (asynchronous; outputs are valid once the
+ * caller has synchronised the stream).  Idempotent for unchanged inputs.
+ *
+ *   draft_tokens  DEVICE i32 [batch][K]   vocabulary ids of the drafts (an id outside the
+ *                                         bin range is clamped for the embedding lookup and
+ *                                         makes its group fail)
+ *   skip_mask     DEVICE u8  [batch]      nonzero = bypass verification (Sec. 4.1, Sec. 6.2);
+ *                                         NULL = verify every episode
+ *   accepted_len  DEVICE i32 [batch] out  n in [0, K]; K for skipped episodes
+ *   next_token    DEVICE i32 [batch] out  vocabulary id of the target's own token at position
+ *                                         n (the correction after a rejection, or the bonus
+ *                                         token when n = K); -1 for skipped episodes
+ *   target_bins   DEVICE i32 [batch][K+1] out, optional (NULL ok): a_hat_0 .. a_hat_K as bins;
+ *                                         -1 for skipped episodes
+ *   bin_logits    DEVICE f32 [batch][K][n_bins] out, optional (NULL ok): logits of the action
+ *                                         bins at every draft position; NaN for skipped episodes
+ *   stream        hipStream_t passed as void*; NULL = the default stream
+ *
+ * Errors (nothing enqueued): EINVAL for NULL required pointers, K < 1, batch < 1,
+ * K > max_k, batch > max_batch, K > kv_capacity, n_groups outside [1, HEISD_MAX_GROUPS],
+ * a group size < 1, negative thresholds, mode not 0/1; EHIP if a launch fails.
+ */
+int heisd_verify_step(heisd_verify_ctx *ctx, const heisd_kv_desc *kv, const int32_t *draft_tokens,
+                      int32_t K, int32_t batch, const heisd_accept_desc *accept,
+                      const uint8_t *skip_mask, int32_t *accepted_len, int32_t *next_token,
+                      int32_t *target_bins, float *bin_logits, void *stream);
+
+/* Release the context (not the workspace, weights or caches: those are the caller's). NULL ok. */
+void heisd_free(heisd_verify_ctx *ctx);
+
+/* HOST string describing the last error of this context ("" if none); for ctx == NULL, the
+ * last error of a failed heisd_verify_init on this thread. */
+const char *heisd_last_error(const heisd_verify_ctx *ctx);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* HEISD_VERIFY_H */

@@ -1,0 +1,13 @@
+"""HeiSD target-model verify step for AMD MI355X: hand-written HIP kernels behind a C ABI.
+
+This package holds the kernels (csrc/), the build step and a ctypes binding with the same
+entry points as include/heisd_verify.h, plus a small torch-facing convenience class that
+only moves pointers around.
+"""
+from .binding import (heisd_model_desc, heisd_kv_desc, heisd_accept_desc, heisd_verify_workspace_bytes,
+                      heisd_verify_init, heisd_verify_step, heisd_free, heisd_last_error,
+                      make_accept_desc, make_model_desc, HEISD_OK, HEISD_EINVAL, HEISD_EUNSUPPORTED,
+                      HEISD_ENOMEM, HEISD_EHIP)
+from .runner import DeviceModel, Verifier
+
+__all__ = [n for n in dir() if not n.startswith("_")]

@@ -1,0 +1,128 @@
+"""ctypes binding of libheisd_verify.so: the same entry points as include/heisd_verify.h.
+
+Argument marshalling only.  Every step of the verify path runs in the library's HIP
+kernels; if the library is missing this module raises instead of computing anything
+itself.  PyTorch appears only as the owner of device memory and streams (callers pass
+tensor.data_ptr() and torch.cuda.current_stream().cuda_stream).
+"""
+import ctypes
+import os
+from ctypes import POINTER, Structure, c_char_p, c_float, c_int32, c_size_t, c_uint32, c_void_p
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "libheisd_verify.so")
+
+HEISD_OK, HEISD_EINVAL, HEISD_EUNSUPPORTED, HEISD_ENOMEM, HEISD_EHIP = 0, -1, -2, -3, -4
+HEISD_MAX_GROUPS = 8
+
+
+class heisd_model_desc(Structure):
+    _fields_ = [(n, c_int32) for n in ("n_layers", "d_model", "n_heads", "head_dim", "d_ffn", "vocab",
+                                      "n_bins", "bin_token_base")] + \
+               [("rms_eps", c_float), ("rope_base", c_float),
+                ("max_batch", c_int32), ("max_k", c_int32), ("kv_capacity", c_int32),
+                ("tok_emb", c_void_p)] + \
+               [(n, POINTER(c_void_p)) for n in ("wq", "wk", "wv", "wo", "w_gate", "w_up", "w_down",
+                                                 "attn_norm", "ffn_norm")] + \
+               [("final_norm", c_void_p), ("lm_head", c_void_p),
+                ("workspace", c_void_p), ("workspace_bytes", c_size_t)]
+
+
+class heisd_kv_desc(Structure):
+    _fields_ = [("k_cache", c_void_p), ("v_cache", c_void_p), ("prefix_len", c_void_p),
+                ("first_pred", c_void_p)]
+
+
+class heisd_accept_desc(Structure):
+    _fields_ = [("tok_threshold", c_int32), ("seq_budget", c_int32), ("n_groups", c_int32),
+                ("group_sizes", c_int32 * HEISD_MAX_GROUPS), ("exact_group_mask", c_uint32),
+                ("mode", c_int32)]
+
+
+_lib = None
+
+
+def load():
+    """Load the HIP library; raises if it has not been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError("libheisd_verify.so is not built; run paper_2603_17573_amd.build.build() "
+                               "(there is no CPU fallback)")
+        lib = ctypes.CDLL(LIB_PATH)
+        lib.heisd_verify_workspace_bytes.argtypes = [POINTER(heisd_model_desc)]
+        lib.heisd_verify_workspace_bytes.restype = c_size_t
+        lib.heisd_verify_init.argtypes = [POINTER(heisd_model_desc), POINTER(c_void_p)]
+        lib.heisd_verify_init.restype = ctypes.c_int
+        lib.heisd_verify_step.argtypes = [c_void_p, POINTER(heisd_kv_desc), c_void_p, c_int32, c_int32,
+                                          POINTER(heisd_accept_desc), c_void_p, c_void_p, c_void_p,
+                                          c_void_p, c_void_p, c_void_p]
+        lib.heisd_verify_step.restype = ctypes.c_int
+        lib.heisd_free.argtypes = [c_void_p]
+        lib.heisd_free.restype = None
+        lib.heisd_last_error.argtypes = [c_void_p]
+        lib.heisd_last_error.restype = c_char_p
+        _lib = lib
+    return _lib
+
+
+def heisd_verify_workspace_bytes(desc: heisd_model_desc) -> int:
+    return int(load().heisd_verify_workspace_bytes(ctypes.byref(desc)))
+
+
+def heisd_verify_init(desc: heisd_model_desc):
+    """Returns (rc, ctx handle or None)."""
+    ctx = c_void_p()
+    rc = load().heisd_verify_init(ctypes.byref(desc), ctypes.byref(ctx))
+    return rc, (ctx if rc == 0 else None)
+
+
+def heisd_verify_step(ctx, kv: heisd_kv_desc, draft_tokens, K, batch, accept: heisd_accept_desc,
+                      skip_mask, accepted_len, next_token, target_bins, bin_logits, stream) -> int:
+    """All array arguments are integer device addresses (0/None = NULL)."""
+    return load().heisd_verify_step(ctx, ctypes.byref(kv) if kv is not None else None, draft_tokens, K, batch,
+                                    ctypes.byref(accept) if accept is not None else None, skip_mask,
+                                    accepted_len, next_token, target_bins, bin_logits, stream)
+
+
+def heisd_free(ctx) -> None:
+    load().heisd_free(ctx)
+
+
+def heisd_last_error(ctx=None) -> str:
+    return load().heisd_last_error(ctx).decode()
+
+
+def make_accept_desc(tok_threshold=15, seq_budget=30, group_sizes=(3, 3, 1), exact_group_mask=0b100,
+                     mode=0) -> heisd_accept_desc:
+    a = heisd_accept_desc()
+    a.tok_threshold, a.seq_budget, a.n_groups = tok_threshold, seq_budget, len(group_sizes)
+    for i in range(HEISD_MAX_GROUPS):
+        a.group_sizes[i] = group_sizes[i] if i < len(group_sizes) else 0
+    a.exact_group_mask, a.mode = exact_group_mask, mode
+    return a
+
+
+def _ptr_table(ptrs):
+    arr = (c_void_p * len(ptrs))(*ptrs)
+    return arr
+
+
+def make_model_desc(shape: dict, ptrs: dict, max_batch, max_k, kv_capacity, workspace=0, workspace_bytes=0):
+    """shape: n_layers, d_model, n_heads, head_dim, d_ffn, vocab, n_bins, bin_token_base, rms_eps,
+    rope_base.  ptrs: device addresses: tok_emb, lm_head, final_norm (ints) and per-layer lists wq, wk, wv,
+    wo, w_gate, w_up, w_down, attn_norm, ffn_norm.  Returns (desc, keepalive) - keep `keepalive`
+    referenced while the descriptor is in use."""
+    d = heisd_model_desc()
+    for k in ("n_layers", "d_model", "n_heads", "head_dim", "d_ffn", "vocab", "n_bins", "bin_token_base",
+              "rms_eps", "rope_base"):
+        setattr(d, k, shape[k])
+    d.max_batch, d.max_k, d.kv_capacity = max_batch, max_k, kv_capacity
+    keep = []
+    for k in ("wq", "wk", "wv", "wo", "w_gate", "w_up", "w_down", "attn_norm", "ffn_norm"):
+        t = _ptr_table(ptrs[k])
+        keep.append(t)
+        setattr(d, k, ctypes.cast(t, POINTER(c_void_p)))
+    d.tok_emb, d.lm_head, d.final_norm = ptrs["tok_emb"], ptrs["lm_head"], ptrs["final_norm"]
+    d.workspace, d.workspace_bytes = workspace, workspace_bytes
+    return d, keep

@@ -1,0 +1,301 @@
+// C ABI of the verify step: context, argument checks, workspace layout and the launch
+// sequence of one step.  All arithmetic happens in the kernels included below.
+#include "../../include/heisd_verify.h"
+
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "heisd_attn.h"
+#include "heisd_gemm.h"
+#include "heisd_misc.h"
+
+using namespace heisd;
+
+struct heisd_verify_ctx {
+  heisd_model_desc d;
+  std::vector<const void *> wq, wk, wv, wo, w_gate, w_up, w_down;
+  std::vector<const float *> attn_norm, ffn_norm;
+  // workspace carve-up
+  float2 *rope;
+  float *x, *qkv, *attn_o, *act, *logits;
+  int32_t *tbins;
+  char err[256];
+};
+
+static thread_local char g_init_err[256] = "";
+
+static int fail(heisd_verify_ctx *ctx, int code, const char *fmt, ...) {
+  char *dst = ctx ? ctx->err : g_init_err;
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(dst, 256, fmt, ap);
+  va_end(ap);
+  return code;
+}
+
+static size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
+
+struct WsLayout {
+  size_t rope, x, qkv, attn_o, act, logits, tbins, total;
+};
+
+static bool shape_ok(const heisd_model_desc *d) {
+  return d && d->n_layers > 0 && d->d_model > 0 && d->n_heads > 0 && d->head_dim > 0 && d->d_ffn > 0 &&
+         d->vocab > 0 && d->n_bins > 0 && d->max_batch > 0 && d->max_k > 0 && d->kv_capacity > 0 &&
+         (int64_t)d->n_heads * d->head_dim == d->d_model && d->bin_token_base >= 0 &&
+         (int64_t)d->bin_token_base + d->n_bins <= d->vocab;
+}
+
+static WsLayout ws_layout(const heisd_model_desc *d) {
+  WsLayout w;
+  const size_t M = (size_t)d->max_batch * d->max_k;
+  size_t off = 0;
+  w.rope = off;   off += align256((size_t)d->kv_capacity * (d->head_dim / 2) * sizeof(float2));
+  w.x = off;      off += align256(M * d->d_model * sizeof(float));
+  w.qkv = off;    off += align256(M * 3 * d->d_model * sizeof(float));
+  w.attn_o = off; off += align256(M * d->d_model * sizeof(float));
+  w.act = off;    off += align256(M * d->d_ffn * sizeof(float));
+  w.logits = off; off += align256(M * d->n_bins * sizeof(float));
+  w.tbins = off;  off += align256((size_t)d->max_batch * (d->max_k + 1) * sizeof(int32_t));
+  w.total = off;
+  return w;
+}
+
+extern "C" size_t heisd_verify_workspace_bytes(const heisd_model_desc *desc) {
+  if (!shape_ok(desc)) return 0;
+  return ws_layout(desc).total;
+}
+
+// ---- GEMM dispatch -------------------------------------------------------------------
+
+template <int MC, int NT, int EPI>
+static hipError_t gemm_prepare() {
+  return hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_skinny<MC, NT, EPI>),
+                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)gemm_lds_bytes<MC>());
+}
+
+template <int MC>
+static hipError_t gemm_prepare_mc() {
+  hipError_t e;
+  if ((e = gemm_prepare<MC, 1, EPI_STORE>()) != hipSuccess) return e;
+  if ((e = gemm_prepare<MC, 2, EPI_SWIGLU>()) != hipSuccess) return e;
+  if (MC <= 4)
+    if ((e = gemm_prepare<(MC <= 4 ? MC : 1), 3, EPI_STORE>()) != hipSuccess) return e;
+  return hipSuccess;
+}
+
+template <int MC>
+static void gemm_launch_mc(const GemmArgs &a, int epi, hipStream_t st) {
+  const size_t lds = gemm_lds_bytes<MC>();
+  if (epi == EPI_SWIGLU) {
+    gemm_skinny<MC, 2, EPI_SWIGLU><<<dim3(a.n_units), dim3(kGemmThreads), lds, st>>>(a);
+  } else if (MC <= 4 && a.n_units >= 768 && a.n_units % 3 == 0) {
+    gemm_skinny<(MC <= 4 ? MC : 1), 3, EPI_STORE><<<dim3(a.n_units / 3), dim3(kGemmThreads), lds, st>>>(a);
+  } else {
+    gemm_skinny<MC, 1, EPI_STORE><<<dim3(a.n_units), dim3(kGemmThreads), lds, st>>>(a);
+  }
+}
+
+// y = act . W^T for all M rows, in row blocks of at most 64 rows (each block streams W once).
+static void gemm_launch(GemmArgs a, int M, int epi, hipStream_t st) {
+  const float *act = a.act;
+  float *out = a.out;
+  const float *resid = a.resid;
+  for (int m0 = 0; m0 < M; m0 += 64) {
+    const int mb = M - m0 < 64 ? M - m0 : 64;
+    a.act = act + (size_t)m0 * a.Kd;
+    a.out = out + (size_t)m0 * a.ldo;
+    a.resid = resid ? resid + (size_t)m0 * a.ldo : nullptr;
+    a.M = mb;
+    if (mb <= 8) gemm_launch_mc<1>(a, epi, st);
+    else if (mb <= 16) gemm_launch_mc<2>(a, epi, st);
+    else if (mb <= 32) gemm_launch_mc<4>(a, epi, st);
+    else gemm_launch_mc<8>(a, epi, st);
+  }
+}
+
+// ---- init / free ------------------------------------------------------------------------
+
+extern "C" int heisd_verify_init(const heisd_model_desc *desc, heisd_verify_ctx **out) {
+  if (!desc || !out) return fail(nullptr, HEISD_EINVAL, "init: NULL argument");
+  *out = nullptr;
+  if (!shape_ok(desc)) return fail(nullptr, HEISD_EINVAL, "init: inconsistent model shape");
+  if (!desc->tok_emb || !desc->wq || !desc->wk || !desc->wv || !desc->wo || !desc->w_gate || !desc->w_up ||
+      !desc->w_down || !desc->attn_norm || !desc->ffn_norm || !desc->final_norm || !desc->lm_head ||
+      !desc->workspace)
+    return fail(nullptr, HEISD_EINVAL, "init: NULL weight, table or workspace pointer");
+  for (int l = 0; l < desc->n_layers; ++l)
+    if (!desc->wq[l] || !desc->wk[l] || !desc->wv[l] || !desc->wo[l] || !desc->w_gate[l] || !desc->w_up[l] ||
+        !desc->w_down[l] || !desc->attn_norm[l] || !desc->ffn_norm[l])
+      return fail(nullptr, HEISD_EINVAL, "init: NULL weight pointer in layer %d", l);
+  if (desc->head_dim != 64 && desc->head_dim != 128)
+    return fail(nullptr, HEISD_EUNSUPPORTED, "init: head_dim %d (64 or 128 supported)", desc->head_dim);
+  if (desc->d_model % 16 || desc->d_ffn % 16 || desc->n_bins % 16)
+    return fail(nullptr, HEISD_EUNSUPPORTED, "init: d_model, d_ffn and n_bins must be multiples of 16");
+  if (desc->max_k > 256) return fail(nullptr, HEISD_EUNSUPPORTED, "init: max_k %d > 256", desc->max_k);
+  if (desc->kv_capacity > 4096)
+    return fail(nullptr, HEISD_EUNSUPPORTED, "init: kv_capacity %d > 4096", desc->kv_capacity);
+  if (((uintptr_t)desc->workspace & 255) != 0) return fail(nullptr, HEISD_EINVAL, "init: workspace not 256-byte aligned");
+  const WsLayout w = ws_layout(desc);
+  if (desc->workspace_bytes < w.total)
+    return fail(nullptr, HEISD_ENOMEM, "init: workspace %zu bytes < %zu needed", desc->workspace_bytes, w.total);
+
+  heisd_verify_ctx *c = new (std::nothrow) heisd_verify_ctx();
+  if (!c) return fail(nullptr, HEISD_EHIP, "init: host allocation failed");
+  c->d = *desc;
+  c->err[0] = 0;
+  const int L = desc->n_layers;
+  c->wq.assign(desc->wq, desc->wq + L);
+  c->wk.assign(desc->wk, desc->wk + L);
+  c->wv.assign(desc->wv, desc->wv + L);
+  c->wo.assign(desc->wo, desc->wo + L);
+  c->w_gate.assign(desc->w_gate, desc->w_gate + L);
+  c->w_up.assign(desc->w_up, desc->w_up + L);
+  c->w_down.assign(desc->w_down, desc->w_down + L);
+  c->attn_norm.assign(desc->attn_norm, desc->attn_norm + L);
+  c->ffn_norm.assign(desc->ffn_norm, desc->ffn_norm + L);
+  c->d.wq = c->d.wk = c->d.wv = c->d.wo = c->d.w_gate = c->d.w_up = c->d.w_down = nullptr;
+  c->d.attn_norm = c->d.ffn_norm = nullptr;
+  unsigned char *base = static_cast<unsigned char *>(desc->workspace);
+  c->rope = reinterpret_cast<float2 *>(base + w.rope);
+  c->x = reinterpret_cast<float *>(base + w.x);
+  c->qkv = reinterpret_cast<float *>(base + w.qkv);
+  c->attn_o = reinterpret_cast<float *>(base + w.attn_o);
+  c->act = reinterpret_cast<float *>(base + w.act);
+  c->logits = reinterpret_cast<float *>(base + w.logits);
+  c->tbins = reinterpret_cast<int32_t *>(base + w.tbins);
+
+  // rotary table: angle = position * rope_base^(-2i/head_dim), computed in double on the host
+  const int half = desc->head_dim / 2;
+  std::vector<float2> tab((size_t)desc->kv_capacity * half);
+  for (int p = 0; p < desc->kv_capacity; ++p)
+    for (int i = 0; i < half; ++i) {
+      const double ang = (double)p * std::pow((double)desc->rope_base, -2.0 * i / desc->head_dim);
+      tab[(size_t)p * half + i] = make_float2((float)std::cos(ang), (float)std::sin(ang));
+    }
+  hipError_t e = hipMemcpy(c->rope, tab.data(), tab.size() * sizeof(float2), hipMemcpyHostToDevice);
+  if (e == hipSuccess) e = gemm_prepare_mc<1>();
+  if (e == hipSuccess) e = gemm_prepare_mc<2>();
+  if (e == hipSuccess) e = gemm_prepare_mc<4>();
+  if (e == hipSuccess) e = gemm_prepare_mc<8>();
+  const int attn_lds = (int)attn_lds_bytes(desc->head_dim, desc->kv_capacity);
+  if (e == hipSuccess)
+    e = desc->head_dim == 128
+            ? hipFuncSetAttribute(reinterpret_cast<const void *>(&attn_verify<128>),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, attn_lds)
+            : hipFuncSetAttribute(reinterpret_cast<const void *>(&attn_verify<64>),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, attn_lds);
+  if (e != hipSuccess) {
+    const int rc = fail(nullptr, HEISD_EHIP, "init: %s", hipGetErrorString(e));
+    delete c;
+    return rc;
+  }
+  *out = c;
+  g_init_err[0] = 0;
+  return HEISD_OK;
+}
+
+extern "C" void heisd_free(heisd_verify_ctx *ctx) { delete ctx; }
+
+extern "C" const char *heisd_last_error(const heisd_verify_ctx *ctx) { return ctx ? ctx->err : g_init_err; }
+
+// ---- one verify step ----------------------------------------------------------------------
+
+extern "C" int heisd_verify_step(heisd_verify_ctx *ctx, const heisd_kv_desc *kv, const int32_t *draft_tokens,
+                                 int32_t K, int32_t batch, const heisd_accept_desc *accept,
+                                 const uint8_t *skip_mask, int32_t *accepted_len, int32_t *next_token,
+                                 int32_t *target_bins, float *bin_logits, void *stream) {
+  if (!ctx) return HEISD_EINVAL;
+  if (!kv || !kv->k_cache || !kv->v_cache || !kv->prefix_len || !kv->first_pred || !draft_tokens || !accept ||
+      !accepted_len || !next_token)
+    return fail(ctx, HEISD_EINVAL, "step: NULL required pointer");
+  const heisd_model_desc &d = ctx->d;
+  if (K < 1 || batch < 1 || K > d.max_k || batch > d.max_batch || K > d.kv_capacity)
+    return fail(ctx, HEISD_EINVAL, "step: K=%d batch=%d outside [1,%d] x [1,%d] (kv_capacity %d)", K, batch,
+                d.max_k, d.max_batch, d.kv_capacity);
+  if (accept->n_groups < 1 || accept->n_groups > HEISD_MAX_GROUPS)
+    return fail(ctx, HEISD_EINVAL, "step: n_groups=%d outside [1,%d]", accept->n_groups, HEISD_MAX_GROUPS);
+  for (int g = 0; g < accept->n_groups; ++g)
+    if (accept->group_sizes[g] < 1) return fail(ctx, HEISD_EINVAL, "step: group_sizes[%d] < 1", g);
+  if (accept->tok_threshold < 0 || accept->seq_budget < 0)
+    return fail(ctx, HEISD_EINVAL, "step: negative acceptance threshold");
+  if (accept->mode != 0 && accept->mode != 1) return fail(ctx, HEISD_EINVAL, "step: mode %d", accept->mode);
+
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  const int M = batch * K, dm = d.d_model, F = d.d_ffn, H = d.n_heads, HD = d.head_dim, cap = d.kv_capacity;
+  float *logits = bin_logits ? bin_logits : ctx->logits;
+  int32_t *tbins = target_bins ? target_bins : ctx->tbins;
+  (void)hipGetLastError();
+
+  embed_rows<<<dim3(M), dim3(256), 0, st>>>(draft_tokens, static_cast<const uint16_t *>(d.tok_emb), d.vocab, dm,
+                                            ctx->x);
+  const size_t layer_stride = (size_t)batch * H * cap * HD;
+  const size_t attn_lds = attn_lds_bytes(HD, cap);
+  for (int l = 0; l < d.n_layers; ++l) {
+    GemmArgs g{};
+    // q, k, v = RMSNorm(x) . {Wq, Wk, Wv}^T
+    g.act = ctx->x; g.gain = ctx->attn_norm[l];
+    g.w[0] = static_cast<const uint16_t *>(ctx->wq[l]);
+    g.w[1] = static_cast<const uint16_t *>(ctx->wk[l]);
+    g.w[2] = static_cast<const uint16_t *>(ctx->wv[l]);
+    g.seg_tiles = dm / 16; g.n_units = 3 * dm / 16; g.Kd = dm; g.eps = d.rms_eps;
+    g.out = ctx->qkv; g.ldo = 3 * dm; g.resid = nullptr;
+    gemm_launch(g, M, EPI_STORE, st);
+    // RoPE + KV-append + attention
+    AttnArgs a{};
+    a.qkv = ctx->qkv;
+    a.k_cache = static_cast<uint16_t *>(kv->k_cache) + (size_t)l * layer_stride;
+    a.v_cache = static_cast<uint16_t *>(kv->v_cache) + (size_t)l * layer_stride;
+    a.prefix_len = kv->prefix_len; a.skip = skip_mask; a.rope = ctx->rope; a.out = ctx->attn_o;
+    a.K = K; a.H = H; a.cap = cap; a.d = dm; a.scale = 1.0f / std::sqrt((float)HD);
+    if (HD == 128) attn_verify<128><<<dim3(H, batch), dim3(kAttnThreads), attn_lds, st>>>(a);
+    else attn_verify<64><<<dim3(H, batch), dim3(kAttnThreads), attn_lds, st>>>(a);
+    // x += o . Wo^T
+    g = GemmArgs{};
+    g.act = ctx->attn_o; g.gain = nullptr; g.w[0] = static_cast<const uint16_t *>(ctx->wo[l]);
+    g.seg_tiles = dm / 16; g.n_units = dm / 16; g.Kd = dm; g.eps = 0.f;
+    g.out = ctx->x; g.ldo = dm; g.resid = ctx->x;
+    gemm_launch(g, M, EPI_STORE, st);
+    // a = silu(RMSNorm(x) . Wg^T) * (RMSNorm(x) . Wu^T)
+    g = GemmArgs{};
+    g.act = ctx->x; g.gain = ctx->ffn_norm[l];
+    g.w[0] = static_cast<const uint16_t *>(ctx->w_gate[l]);
+    g.w[1] = static_cast<const uint16_t *>(ctx->w_up[l]);
+    g.seg_tiles = F / 16; g.n_units = F / 16; g.Kd = dm; g.eps = d.rms_eps;
+    g.out = ctx->act; g.ldo = F; g.resid = nullptr;
+    gemm_launch(g, M, EPI_SWIGLU, st);
+    // x += a . Wd^T
+    g = GemmArgs{};
+    g.act = ctx->act; g.gain = nullptr; g.w[0] = static_cast<const uint16_t *>(ctx->w_down[l]);
+    g.seg_tiles = dm / 16; g.n_units = dm / 16; g.Kd = F; g.eps = 0.f;
+    g.out = ctx->x; g.ldo = dm; g.resid = ctx->x;
+    gemm_launch(g, M, EPI_STORE, st);
+  }
+  // logits over the action bins = RMSNorm(x; final) . W_lm[bin rows]^T
+  {
+    GemmArgs g{};
+    g.act = ctx->x; g.gain = d.final_norm;
+    g.w[0] = static_cast<const uint16_t *>(d.lm_head) + (size_t)d.bin_token_base * dm;
+    g.seg_tiles = d.n_bins / 16; g.n_units = d.n_bins / 16; g.Kd = dm; g.eps = d.rms_eps;
+    g.out = logits; g.ldo = d.n_bins; g.resid = nullptr;
+    gemm_launch(g, M, EPI_STORE, st);
+  }
+  AcceptArgs aa{};
+  aa.logits = logits; aa.logits_rw = logits; aa.draft = draft_tokens; aa.first_pred = kv->first_pred;
+  aa.skip = skip_mask; aa.accepted_len = accepted_len; aa.next_token = next_token; aa.target_bins = tbins;
+  aa.K = K; aa.n_bins = d.n_bins; aa.bin_base = d.bin_token_base;
+  aa.tok_threshold = accept->tok_threshold; aa.seq_budget = accept->seq_budget;
+  aa.n_groups = accept->n_groups; aa.mode = accept->mode; aa.exact_mask = accept->exact_group_mask;
+  for (int i = 0; i < 8; ++i) aa.group_sizes[i] = i < accept->n_groups ? accept->group_sizes[i] : 1;
+  argmax_accept<<<dim3(batch), dim3(256), 0, st>>>(aa);
+  const hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return fail(ctx, HEISD_EHIP, "step: %s", hipGetErrorString(e));
+  ctx->err[0] = 0;
+  return HEISD_OK;
+}

@@ -1,0 +1,195 @@
+// Verify attention with fused RoPE and KV-append (paper Sec. 2.2: the target scores all K
+// drafts in one pass; App. A.2: causal attention over visual, text and earlier action
+// tokens).  One workgroup per (episode, head).
+//
+//   1. rotate this head's new keys (rotate-half, absolute position prefix_len + j), round
+//      keys and values to bf16 and append them to the episode's cache rows;
+//   2. per block of 8 queries: scores of every visible key into LDS (each key row is read
+//      once, 16 bytes per lane, and dotted with all 8 queries; partial dots are summed with
+//      wavefront shuffles), softmax per query with wavefront reductions, then one pass over
+//      the value rows accumulating all 8 outputs.
+// Skipped episodes (verify-skip, Sec. 4.1) touch neither the cache nor the scores.
+#pragma once
+#include "heisd_common.h"
+
+namespace heisd {
+
+constexpr int kAttnThreads = 256;
+constexpr int kAttnWaves = 4;
+constexpr int kAttnQB = 8;  // queries per block
+
+struct AttnArgs {
+  const float *qkv;          // [M][3*d] fp32: q | k | v of the new rows, not yet rotated
+  uint16_t *k_cache;         // this layer: bf16 [batch][H][cap][HD]
+  uint16_t *v_cache;
+  const int32_t *prefix_len; // [batch]
+  const uint8_t *skip;       // [batch] or nullptr
+  const float2 *rope;        // [cap][HD/2] (cos, sin) of position * theta_i
+  float *out;                // [M][d]
+  int K, H, cap, d;
+  float scale;               // 1/sqrt(HD)
+};
+
+inline size_t attn_lds_bytes(int hd, int cap) {
+  return sizeof(float) * ((size_t)kAttnQB * hd + (size_t)kAttnQB * cap + kAttnQB +
+                          (size_t)kAttnWaves * kAttnQB * hd);
+}
+
+template <int HD>
+__global__ __launch_bounds__(kAttnThreads) void attn_verify(AttnArgs a) {
+  constexpr int HALF = HD / 2;
+  constexpr int LPK = HD / 8;              // lanes that share one key row (16 bytes each)
+  constexpr int G = kAttnThreads / LPK;    // key rows in flight per pass
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  float *qs = reinterpret_cast<float *>(smem);        // [QB][HD]
+  float *sc = qs + kAttnQB * HD;                       // [QB][cap]
+  float *inv_l = sc + (size_t)kAttnQB * a.cap;         // [QB]
+  float *ored = inv_l + kAttnQB;                       // [waves][QB][HD]
+
+  const int h = blockIdx.x, b = blockIdx.y;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int K = a.K, d = a.d, cap = a.cap;
+  const int row0 = b * K;
+  if (a.skip && a.skip[b]) {
+    for (int idx = tid; idx < K * HD; idx += kAttnThreads)
+      a.out[(size_t)(row0 + idx / HD) * d + h * HD + (idx % HD)] = 0.f;
+    return;
+  }
+  int P = a.prefix_len[b];
+  P = max(0, min(P, cap - K));  // never index past the cache, whatever the caller passed
+  uint16_t *kc = a.k_cache + ((size_t)(b * a.H + h) * cap) * HD;
+  uint16_t *vc = a.v_cache + ((size_t)(b * a.H + h) * cap) * HD;
+
+  // ---- RoPE on the new keys, append keys and values (bf16) ----
+  for (int idx = tid; idx < K * HALF; idx += kAttnThreads) {
+    const int j = idx / HALF, i = idx - j * HALF;
+    const float *src = a.qkv + (size_t)(row0 + j) * 3 * d + h * HD;
+    const float2 cs = a.rope[(size_t)(P + j) * HALF + i];
+    const float k1 = src[d + i], k2 = src[d + i + HALF];
+    uint16_t *kr = kc + (size_t)(P + j) * HD;
+    kr[i] = (uint16_t)f32_to_bf16_bits(k1 * cs.x - k2 * cs.y);
+    kr[i + HALF] = (uint16_t)f32_to_bf16_bits(k2 * cs.x + k1 * cs.y);
+    uint16_t *vr = vc + (size_t)(P + j) * HD;
+    vr[i] = (uint16_t)f32_to_bf16_bits(src[2 * d + i]);
+    vr[i + HALF] = (uint16_t)f32_to_bf16_bits(src[2 * d + i + HALF]);
+  }
+  __syncthreads();  // the appended rows are read back below by other waves of this workgroup
+
+  const int li = tid % LPK;   // which 8 channels of a row this lane covers
+  const int g = tid / LPK;    // which key stream this lane belongs to
+  for (int j0 = 0; j0 < K; j0 += kAttnQB) {
+    const int nq = min(kAttnQB, K - j0);
+    const int nkeys = P + j0 + nq;  // keys visible to the last query of the block
+    for (int idx = tid; idx < kAttnQB * HALF; idx += kAttnThreads) {
+      const int j = idx / HALF, i = idx - j * HALF;
+      float r1 = 0.f, r2 = 0.f;
+      if (j < nq) {
+        const float *src = a.qkv + (size_t)(row0 + j0 + j) * 3 * d + h * HD;
+        const float2 cs = a.rope[(size_t)(P + j0 + j) * HALF + i];
+        const float q1 = src[i], q2 = src[i + HALF];
+        r1 = (q1 * cs.x - q2 * cs.y) * a.scale;
+        r2 = (q2 * cs.x + q1 * cs.y) * a.scale;
+      }
+      qs[j * HD + i] = r1;
+      qs[j * HD + i + HALF] = r2;
+    }
+    __syncthreads();
+    float qf[kAttnQB][8];
+#pragma unroll
+    for (int j = 0; j < kAttnQB; ++j)
+#pragma unroll
+      for (int i = 0; i < 8; ++i) qf[j][i] = qs[j * HD + li * 8 + i];
+
+    // ---- pass 1: scores ----
+    for (int r = g; r < nkeys; r += G) {
+      const uint4 kk = *reinterpret_cast<const uint4 *>(kc + (size_t)r * HD + li * 8);
+      const uint32_t kw[4] = {kk.x, kk.y, kk.z, kk.w};
+      float kf[8];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        kf[2 * i] = __uint_as_float(kw[i] << 16);
+        kf[2 * i + 1] = __uint_as_float(kw[i] & 0xFFFF0000u);
+      }
+      float s[kAttnQB];
+#pragma unroll
+      for (int j = 0; j < kAttnQB; ++j) {
+        float t = 0.f;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) t = fmaf(qf[j][i], kf[i], t);
+        s[j] = t;
+      }
+#pragma unroll
+      for (int off = LPK / 2; off > 0; off >>= 1)
+#pragma unroll
+        for (int j = 0; j < kAttnQB; ++j) s[j] += __shfl_xor(s[j], off, kWave);
+      float mine = s[0];
+#pragma unroll
+      for (int j = 1; j < kAttnQB; ++j) mine = (li == j) ? s[j] : mine;
+      if (li < kAttnQB) sc[(size_t)li * cap + r] = (r <= P + j0 + li) ? mine : -INFINITY;
+    }
+    __syncthreads();
+
+    // ---- softmax per query: one wave per row, lanes stride over the keys ----
+    for (int j = wave; j < nq; j += kAttnWaves) {
+      float *row = sc + (size_t)j * cap;
+      float mx = -INFINITY;
+      for (int r = lane; r < nkeys; r += kWave) mx = fmaxf(mx, row[r]);
+      mx = wave_max(mx);
+      float sum = 0.f;
+      for (int r = lane; r < nkeys; r += kWave) {
+        const float p = expf(row[r] - mx);
+        row[r] = p;
+        sum += p;
+      }
+      sum = wave_sum(sum);
+      if (lane == 0) inv_l[j] = 1.0f / sum;
+    }
+    __syncthreads();
+
+    // ---- pass 2: weighted sum of the value rows ----
+    float o[kAttnQB][8];
+#pragma unroll
+    for (int j = 0; j < kAttnQB; ++j)
+#pragma unroll
+      for (int i = 0; i < 8; ++i) o[j][i] = 0.f;
+    for (int r = g; r < nkeys; r += G) {
+      const uint4 vv = *reinterpret_cast<const uint4 *>(vc + (size_t)r * HD + li * 8);
+      const uint32_t vw[4] = {vv.x, vv.y, vv.z, vv.w};
+      float vf[8];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        vf[2 * i] = __uint_as_float(vw[i] << 16);
+        vf[2 * i + 1] = __uint_as_float(vw[i] & 0xFFFF0000u);
+      }
+#pragma unroll
+      for (int j = 0; j < kAttnQB; ++j) {
+        const float p = (j < nq) ? sc[(size_t)j * cap + r] : 0.f;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) o[j][i] = fmaf(p, vf[i], o[j][i]);
+      }
+    }
+#pragma unroll
+    for (int off = LPK; off < kWave; off <<= 1)
+#pragma unroll
+      for (int j = 0; j < kAttnQB; ++j)
+#pragma unroll
+        for (int i = 0; i < 8; ++i) o[j][i] += __shfl_xor(o[j][i], off, kWave);
+    if (lane < LPK) {
+#pragma unroll
+      for (int j = 0; j < kAttnQB; ++j)
+#pragma unroll
+        for (int i = 0; i < 8; ++i) ored[(size_t)(wave * kAttnQB + j) * HD + lane * 8 + i] = o[j][i];
+    }
+    __syncthreads();
+    for (int idx = tid; idx < nq * HD; idx += kAttnThreads) {
+      const int j = idx / HD, c = idx - j * HD;
+      float t = 0.f;
+#pragma unroll
+      for (int w = 0; w < kAttnWaves; ++w) t += ored[(size_t)(w * kAttnQB + j) * HD + c];
+      a.out[(size_t)(row0 + j0 + j) * d + h * HD + c] = t * inv_l[j];
+    }
+    __syncthreads();
+  }
+}
+
+}  // namespace heisd

@@ -1,0 +1,113 @@
+"""Runs the HIP path through the C ABI binding and compares it with oracle results.
+Shared by the GPU tests, smoke() and nothing else."""
+import numpy as np
+import torch
+
+import oracle
+import synth
+from paper_2603_17573_amd import DeviceModel, Verifier, make_accept_desc
+
+LOGIT_TOL = 3e-2      # max |delta logit| / (oracle row range), the bar the benchmark spec sets
+
+
+def accept_desc_of(rule: oracle.AcceptRule):
+    return make_accept_desc(rule.tok_threshold, rule.seq_budget, rule.group_sizes, rule.exact_group_mask,
+                            rule.mode)
+
+
+def _bits_to_dev(bits, device):
+    return torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)).to(device).view(torch.bfloat16)
+
+
+def _dev_to_bits(t):
+    return t.view(torch.int16).cpu().numpy().view(np.uint16)
+
+
+def run_gpu_step(shape, weights, kb, vb, plen, first, drafts, rule, skip, device="cuda:0",
+                 model=None, max_batch=None, max_k=None, repeat=1):
+    """One heisd_verify_step on the GPU.  kb/vb: bf16 bits [L][B][H][cap][hd].  Returns numpy outputs
+    plus the caches after the step."""
+    dm = model or DeviceModel(shape, weights, device)
+    B, K = drafts.shape
+    cap = kb.shape[3]
+    ver = Verifier(dm, max_batch or B, max_k or K, cap)
+    kc, vc = _bits_to_dev(kb, device), _bits_to_dev(vb, device)
+    t_plen = torch.from_numpy(np.asarray(plen, np.int32)).to(device)
+    t_first = torch.from_numpy(np.asarray(first, np.int32)).to(device)
+    t_drafts = torch.from_numpy(np.ascontiguousarray(drafts, dtype=np.int32)).to(device)
+    t_skip = None if skip is None else torch.from_numpy(np.asarray(skip, np.uint8)).to(device)
+    out = None
+    for _ in range(repeat):
+        out = ver.step(kc, vc, t_plen, t_first, t_drafts, accept_desc_of(rule), t_skip, out=out)
+    torch.cuda.synchronize()
+    res = {k: v.cpu().numpy() for k, v in out.items()}
+    res["k_cache"], res["v_cache"] = _dev_to_bits(kc), _dev_to_bits(vc)
+    ver.close()
+    return res
+
+
+def compare_with_oracle(got, ref, drafts, rule, shape, kb0=None, vb0=None, plen=None, skip=None,
+                        episodes=None):
+    """Element-by-element parity of one step.  `episodes` maps oracle rows to GPU rows when the
+    oracle only ran a sample of the batch.  Returns a dict of measured statistics."""
+    B, K = drafts.shape
+    eps = list(range(B)) if episodes is None else list(episodes)
+    skip = np.zeros(B, bool) if skip is None else np.asarray(skip).astype(bool)
+    worst, exempt, rows, mism_exempt = 0.0, 0, 0, 0
+    for i, b in enumerate(eps):
+        if skip[b]:
+            assert got["accepted_len"][b] == K and got["next_token"][b] == -1
+            assert np.all(got["target_bins"][b] == -1)
+            assert np.all(np.isnan(got["bin_logits"][b]))
+            assert ref["accepted_len"][i] == K and ref["next_token"][i] == -1
+            continue
+        lo = ref["bin_logits"][i]                       # [K, n_bins] fp64
+        lg = got["bin_logits"][b].astype(np.float64)
+        assert np.all(np.isfinite(lg))
+        rng_ = lo.max(axis=-1) - lo.min(axis=-1)
+        err = np.abs(lg - lo).max(axis=-1) / rng_
+        worst = max(worst, float(err.max()))
+        assert err.max() <= LOGIT_TOL, "logit error %.3g of the row range" % err.max()
+        srt = np.sort(lo, axis=-1)
+        margin = (srt[:, -1] - srt[:, -2]) / rng_
+        decided = margin > LOGIT_TOL                      # rows whose argmax the tolerance cannot flip
+        tb_ref, tb_got = ref["target_bins"][i], got["target_bins"][b]
+        assert tb_got[0] == tb_ref[0]
+        assert np.array_equal(tb_got[1:][decided], tb_ref[1:][decided]), "argmax differs on a decided row"
+        rows += K
+        exempt += int((~decided).sum())
+        mism_exempt += int((tb_got[1:] != tb_ref[1:]).sum())
+        if decided.all():
+            assert got["accepted_len"][b] == ref["accepted_len"][i]
+            assert got["next_token"][b] == ref["next_token"][i]
+        # the acceptance logic itself: bit-exact given the GPU's own argmax
+        n, nb = oracle.accept_block(np.asarray(drafts[b]) - shape.bin_base, tb_got, rule, shape.n_bins)
+        assert got["accepted_len"][b] == n and got["next_token"][b] == shape.bin_base + nb
+    stats = {"max_logit_err_over_range": worst, "rows": rows, "undecided_rows": exempt,
+             "argmax_mismatches": mism_exempt}
+    if kb0 is not None:
+        stats.update(compare_cache(got, ref, kb0, vb0, plen, skip, K, eps))
+    return stats
+
+
+def compare_cache(got, ref, kb0, vb0, plen, skip, K, eps):
+    """Appended rows equal the oracle's new keys/values up to one bf16 rounding (plus the fp32
+    arithmetic before it); every other row of the cache is untouched."""
+    worst = 0.0
+    for name, c0, new in (("k_cache", kb0, ref["k_new"]), ("v_cache", vb0, ref["v_new"])):
+        after = got[name]
+        keep = np.ones(after.shape, bool)
+        for i, b in enumerate(eps):
+            if skip[b]:
+                continue
+            p = int(plen[b])
+            keep[:, b, :, p:p + K, :] = False
+            a = synth.bf16_bits_to_f32(after[:, b, :, p:p + K, :]).astype(np.float64)
+            r = new[:, i]                                 # [L, H, K, hd]
+            scale = np.abs(r).max()
+            e = np.abs(a - r)
+            assert np.all(e <= np.abs(r) * 2.0 ** -8 + 2e-3 * scale), "appended %s rows off" % name
+            worst = max(worst, float((e / scale).max()))
+        if len(eps) == after.shape[1]:
+            assert np.array_equal(after[keep], c0[keep]), "%s modified outside the appended rows" % name
+    return {"max_kv_err_over_scale": worst}

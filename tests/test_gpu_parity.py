@@ -1,0 +1,132 @@
+"""Parity of the HIP path (through the C ABI) with the CPU oracle on the same seeded inputs:
+element by element at sizes the oracle finishes in seconds, spanning several tiles, ragged
+tails, every row-block width of the GEMM and both head sizes."""
+import numpy as np
+import pytest
+
+import oracle
+import synth
+from helpers import oracle_model, oracle_prefix_cache, teacher_forced_drafts
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+
+def _need_gpu():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+
+
+def run_case(wl, plen_override=None, skip=None, rule=None, drafts_mode="auto", check_cache=True):
+    from gpu_harness import run_gpu_step, compare_with_oracle
+    _need_gpu()
+    sh = wl.shape
+    weights = synth.make_weights(sh, wl.seed)
+    om = oracle_model(sh, weights)
+    cap = wl.prefix_len + wl.K + 3                        # capacity is not a multiple of anything
+    kb, vb, plen, first = oracle_prefix_cache(om, wl, cap)
+    if plen_override is not None:
+        plen = np.asarray(plen_override, np.int32)
+    rule = rule or oracle.AcceptRule(wl.tau_tok, wl.tau_seq)
+    if wl.draft[0] == "geometric":
+        off = synth.make_offsets_geometric(wl, wl.draft[1])
+        bins = teacher_forced_drafts(om, wl, kb, vb, plen, first, off)
+    else:
+        bins = synth.make_drafts_uniform(wl)
+    drafts = (sh.bin_base + bins).astype(np.int32)
+    ref = oracle.verify_step(om, kb, vb, plen, first, drafts, rule, skip)
+    got = run_gpu_step(sh, weights, kb, vb, plen, first, drafts, rule, skip)
+    stats = compare_with_oracle(got, ref, drafts, rule, sh, kb, vb, plen, skip)
+    print(wl.name, stats, "accepted", got["accepted_len"].tolist())
+    return got, ref, stats
+
+
+def test_c0_tiny_config():
+    got, ref, stats = run_case(synth.WORKLOADS["C0"])
+    assert stats["max_logit_err_over_range"] < 3e-2
+
+
+MID = synth.ModelShape(n_layers=3, d_model=512, n_heads=4, head_dim=128, d_ffn=1376, vocab=2048)
+SMALL64 = synth.ModelShape(n_layers=2, d_model=256, n_heads=4, head_dim=64, d_ffn=688, vocab=1024)
+
+
+def test_mid_hd128_ragged_prefixes_geometric_drafts():
+    wl = synth.Workload("mid_b3", MID, 50, 20, MID.bin_base, batch=3, K=7, draft=("geometric", 0.5), seed=11)
+    got, ref, stats = run_case(wl, plen_override=[70, 33, 64])
+    assert len(set(got["accepted_len"].tolist())) >= 1
+
+
+def test_hd64_two_row_blocks_with_skips_k14():
+    wl = synth.Workload("s64_b5k14", SMALL64, 0, 40, 1024, batch=5, K=14, skip_p=0.4,
+                        draft=("geometric", 0.6), seed=5)
+    skip = np.array([0, 1, 0, 0, 1], np.uint8)            # M = 70 rows: one 64-row block and a tail of 6
+    run_case(wl, skip=skip)
+
+
+@pytest.mark.parametrize("B,K", [(3, 4), (2, 10), (5, 7), (1, 1), (9, 7)])
+def test_row_block_widths(B, K):
+    """M = 12, 20, 35, 1, 63: the 16-, 32- and 64-row variants, a single row, and K not a multiple
+    of the 8-query attention block."""
+    wl = synth.Workload("w%dx%d" % (B, K), SMALL64, 8, 17, SMALL64.bin_base, batch=B, K=K, seed=B * 31 + K)
+    run_case(wl, rule=oracle.AcceptRule(15, 30))
+
+
+def test_strict_and_token_mode_rules_on_device():
+    wl = synth.Workload("rules", SMALL64, 0, 24, 1024, batch=6, K=7, draft=("geometric", 0.7), seed=3)
+    for rule in (oracle.AcceptRule(0, 0), oracle.AcceptRule(1, 2),
+                 oracle.AcceptRule(0, 0, group_sizes=(1,), exact_group_mask=0),
+                 oracle.AcceptRule(2, 3, mode=1)):
+        run_case(wl, rule=rule, check_cache=False)
+
+
+def test_idempotent_and_deterministic():
+    from gpu_harness import run_gpu_step
+    _need_gpu()
+    wl = synth.Workload("idem", SMALL64, 0, 30, 1024, batch=2, K=7, seed=9)
+    weights = synth.make_weights(wl.shape, wl.seed)
+    kb, vb, first = [], [], []
+    cap = 40
+    k0, v0, f0 = zip(*[synth.make_prefix_kv_direct(wl, e, cap) for e in range(2)])
+    kb = np.stack(k0, axis=1)
+    vb = np.stack(v0, axis=1)
+    drafts = (wl.shape.bin_base + synth.make_drafts_uniform(wl)).astype(np.int32)
+    rule = oracle.AcceptRule(2, 6)
+    a = run_gpu_step(wl.shape, weights, kb, vb, [30, 30], list(f0), drafts, rule, None, repeat=1)
+    b = run_gpu_step(wl.shape, weights, kb, vb, [30, 30], list(f0), drafts, rule, None, repeat=3)
+    for k in a:
+        assert np.array_equal(a[k], b[k], equal_nan=True), k
+
+
+def test_step_argument_errors_enqueue_nothing():
+    from paper_2603_17573_amd import DeviceModel, Verifier, make_accept_desc, binding as B
+    _need_gpu()
+    wl = synth.Workload("err", SMALL64, 0, 8, 1024, batch=2, K=7, seed=1)
+    dm = DeviceModel(wl.shape, synth.make_weights(wl.shape, 1))
+    ver = Verifier(dm, max_batch=2, max_k=7, kv_capacity=20)
+    kc, vc = ver.new_cache(2)
+    z = torch.zeros(2, dtype=torch.int32, device="cuda")
+    dr = torch.full((2, 7), wl.shape.bin_base, dtype=torch.int32, device="cuda")
+    acc = torch.full((2,), -7, dtype=torch.int32, device="cuda")
+    nxt = torch.full((2,), -7, dtype=torch.int32, device="cuda")
+    kv = B.heisd_kv_desc(kc.data_ptr(), vc.data_ptr(), z.data_ptr(), z.data_ptr())
+    ok = make_accept_desc(2, 6)
+
+    def call(K=7, batch=2, accept=ok, kvd=kv, drafts=dr.data_ptr(), out=acc.data_ptr()):
+        return B.heisd_verify_step(ver.ctx, kvd, drafts, K, batch, accept, None, out, nxt.data_ptr(), None, None, None)
+
+    assert call(K=8) == B.HEISD_EINVAL and "K=8" in B.heisd_last_error(ver.ctx)
+    assert call(batch=3) == B.HEISD_EINVAL
+    assert call(K=0) == B.HEISD_EINVAL
+    assert call(drafts=None) == B.HEISD_EINVAL
+    assert call(out=None) == B.HEISD_EINVAL
+    assert call(kvd=B.heisd_kv_desc(0, vc.data_ptr(), z.data_ptr(), z.data_ptr())) == B.HEISD_EINVAL
+    assert call(accept=make_accept_desc(2, 6, group_sizes=(3, 0, 1))) == B.HEISD_EINVAL
+    assert call(accept=make_accept_desc(-1, 6)) == B.HEISD_EINVAL
+    assert call(accept=make_accept_desc(2, 6, mode=2)) == B.HEISD_EINVAL
+    torch.cuda.synchronize()
+    assert acc.tolist() == [-7, -7] and nxt.tolist() == [-7, -7]      # nothing ran
+    assert call() == B.HEISD_OK and B.heisd_last_error(ver.ctx) == ""
+    torch.cuda.synchronize()
+    assert all(v in (0, 3, 6, 7) for v in acc.tolist())
+    ver.close()
