@@ -1,0 +1,194 @@
+#!/usr/bin/env python3
+"""Throughput of the verify step on one MI355X.
+
+A "step" is one pass of the whole hot path (embedding gather, 32 decoder layers, final norm,
+256-bin LM-head slice, argmax, relaxed acceptance) over one batch of seeded synthetic input,
+with every input already resident in HBM when the timed region starts.
+
+Prints ONE JSON line: verify steps/s at the headline workload (C1: 7B-shaped decoder, K=7,
+batch 1, 276-token prefix), plus a `roofline` object for the dominant kernel (event-timed on
+the launch stream inside the library) and a `cpu_baseline` object (the CPU oracle as it
+stands, timed on this machine's host cores).
+"""
+import argparse
+import json
+import os
+import re
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+sys.path.insert(0, os.path.join(ROOT, "tests"))
+
+HBM_PEAK = 8.0e12  # bytes/s, MI355X published
+
+
+def algorithmic_bytes(sh, batch, K, P, active=None):
+    """Bytes a step must move at least once: weights once, prefix K/V once per verified episode,
+    new K/V rows written.  Activations, partial sums and logits are implementation traffic."""
+    act = batch if active is None else active
+    d, f, L = sh.d_model, sh.d_ffn, sh.n_layers
+    per_class = {
+        "qkv": 3 * d * d * 2,
+        "oproj": d * d * 2,
+        "gateup": 2 * d * f * 2,
+        "down": d * f * 2,
+        "attn": act * (2 * P * d * 2 + 2 * K * d * 2),
+        "lmhead": sh.n_bins * d * 2,
+        "embed": act * K * d * 2,
+    }
+    total = L * (per_class["qkv"] + per_class["oproj"] + per_class["gateup"] + per_class["down"] +
+                 per_class["attn"]) + per_class["lmhead"] + per_class["embed"]
+    return total, per_class
+
+
+def read_traffic(kclass):
+    """HBM traffic per launch of a kernel class, if a counter summary under profiles/ states it."""
+    pdir = os.path.join(ROOT, "profiles")
+    if not os.path.isdir(pdir):
+        return None
+    for fn in sorted(os.listdir(pdir)):
+        if not fn.endswith((".md", ".txt")):
+            continue
+        m = re.search(r"^traffic_bytes_per_launch\[%s\]:\s*([0-9.eE+]+)" % kclass,
+                      open(os.path.join(pdir, fn)).read(), flags=re.M)
+        if m:
+            return float(m.group(1))
+    return None
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--workload", default="C1")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs the verify step on ONE GPU (episodes would shard by batch "
+              "with no exchange); --gpus %d is not supported" % args.gpus, file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    import synth
+    from paper_2603_17573_amd import (DeviceModel, Verifier, make_accept_desc, binding,
+                                      heisd_verify_profile_enable, heisd_verify_profile_read)
+    if not os.path.exists(binding.LIB_PATH):
+        from paper_2603_17573_amd import build
+        build.build(force=False)
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    dev = "cuda:0"
+    wl = synth.WORKLOADS[args.workload]
+    sh = wl.shape
+    B, K, P = wl.batch, wl.K, wl.prefix_len
+    cap = P + K
+    t0 = time.time()
+    weights = synth.make_weights(sh, wl.seed)
+    t_gen = time.time() - t0
+    dm = DeviceModel(sh, weights, dev)
+    ver = Verifier(dm, B, K, cap)
+    # prefix K/V drawn directly (the benchmark may not call the oracle's prefill); same shapes,
+    # same bytes, same launch configuration as a prefilled cache
+    kc, vc = ver.new_cache(B)
+    first = np.zeros(B, np.int32)
+    kb_host, vb_host = [], []
+    for e in range(B):
+        k, v, f = synth.make_prefix_kv_direct(wl, e, cap)
+        kc[:, e] = torch.from_numpy(k.view(np.int16)).to(dev).view(torch.bfloat16)
+        vc[:, e] = torch.from_numpy(v.view(np.int16)).to(dev).view(torch.bfloat16)
+        first[e] = f
+        if e == 0:
+            kb_host, vb_host = k, v
+    bins = synth.make_drafts_uniform(wl) if wl.draft[0] == "uniform" else \
+        np.clip(synth.make_drafts_uniform(wl) + synth.make_offsets_geometric(wl, wl.draft[1]), 0, sh.n_bins - 1)
+    drafts = (sh.bin_base + bins).astype(np.int32)
+    skip = synth.make_skip_mask(wl) if wl.skip_p > 0 else None
+    t_plen = torch.full((B,), P, dtype=torch.int32, device=dev)
+    t_first = torch.from_numpy(first).to(dev)
+    t_drafts = torch.from_numpy(drafts).to(dev)
+    t_skip = None if skip is None else torch.from_numpy(skip).to(dev)
+    acc = make_accept_desc(wl.tau_tok, wl.tau_seq)
+    stream = torch.cuda.current_stream(dev)
+
+    out = None
+    for _ in range(args.warmup):
+        out = ver.step(kc, vc, t_plen, t_first, t_drafts, acc, t_skip, want_aux=False, out=out, stream=stream)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        out = ver.step(kc, vc, t_plen, t_first, t_drafts, acc, t_skip, want_aux=False, out=out, stream=stream)
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / args.steps
+    accepted = out["accepted_len"].cpu().tolist()
+
+    # per-kernel durations: HIP events recorded by the library on the launch stream
+    n_prof = max(1, min(args.steps, 32))
+    heisd_verify_profile_enable(ver.ctx, True)
+    for _ in range(n_prof):
+        ver.step(kc, vc, t_plen, t_first, t_drafts, acc, t_skip, want_aux=False, out=out, stream=stream)
+    rc, prof = heisd_verify_profile_read(ver.ctx)
+    heisd_verify_profile_enable(ver.ctx, False)
+    assert rc == 0
+    active = B if skip is None else int(B - skip.sum())
+    total_bytes, per_class = algorithmic_bytes(sh, B, K, P, active)
+    kernels = {}
+    for kcls, (tot_ms, n) in prof.items():
+        if n:
+            avg = tot_ms / n
+            kernels[kcls] = {"avg_us": round(avg * 1e3, 3), "launches_per_step": n / n_prof,
+                             "share_of_step": round(tot_ms / n_prof / ms, 4)}
+            if kcls in per_class:
+                kernels[kcls]["GBps"] = round(per_class[kcls] / (avg * 1e-3) / 1e9, 1)
+    dom = max((k for k in kernels if k in per_class), key=lambda k: prof[k][0])
+    dom_avg_s = prof[dom][0] / prof[dom][1] * 1e-3
+    achieved = per_class[dom] / dom_avg_s
+    roofline = {"kernel": dom, "bound": "hbm", "achieved": round(achieved / 1e9, 1), "peak": HBM_PEAK / 1e9,
+                "unit": "GB/s", "frac": round(achieved / HBM_PEAK, 4),
+                "bytes_per_launch": per_class[dom], "avg_launch_us": round(dom_avg_s * 1e6, 3),
+                "traffic": read_traffic(dom)}
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        import oracle
+        from helpers import oracle_model
+        om = oracle_model(sh, weights)
+        n_ep = 1                                   # bounded sample: one episode of the workload
+        kb1 = kb_host[:, None]
+        vb1 = vb_host[:, None]
+        t0 = time.perf_counter()
+        ref = oracle.verify_step(om, kb1, vb1, [P], first[:1], drafts[:1],
+                                 oracle.AcceptRule(wl.tau_tok, wl.tau_seq))
+        dt = time.perf_counter() - t0
+        cores = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
+        cores = min(cores, os.cpu_count() or cores)
+        cpu = {"value": round(n_ep / B / dt, 5), "unit": "verify steps/s", "cores": cores, "kind": "oracle",
+               "sample": "1 oracle verify step over episode 0 of %s (K=%d rows through all %d layers), "
+                         "%.1f s wall" % (wl.name, K, sh.n_layers, dt),
+               "oracle_accepted_len": int(ref["accepted_len"][0])}
+
+    line = {
+        "metric": "verify steps/s (7B-shaped decoder, K=7, bs=1)" if wl.name == "C1" else
+                  "verify steps/s (%s)" % wl.name,
+        "value": round(1000.0 / ms, 2), "unit": "verify steps/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(ms, 4), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "%s: %d-layer d=%d decoder, prefix %d, batch %d, K=%d, thresholds %d/%d" %
+                               (wl.name, sh.n_layers, sh.d_model, P, B, K, wl.tau_tok, wl.tau_seq),
+                   "prefix_kv": "drawn directly (no prefill)", "global_batch": B, "K": K},
+        "hbm_frac_whole_step": round(total_bytes / (ms * 1e-3) / HBM_PEAK, 4),
+        "algorithmic_bytes_per_step": total_bytes,
+        "accepted_len": accepted[:8],
+        "weights_gen_s": round(t_gen, 1),
+        "kernels": kernels,
+        "roofline": roofline,
+        "cpu_baseline": cpu,
+    }
+    print(json.dumps(line))
+    ver.close()
+
+
+if __name__ == "__main__":
+    main()

@@ -115,7 +115,8 @@ size_t heisd_verify_workspace_bytes(const heisd_model_desc *desc);
  * with heisd_free.  Not thread-safe; one step in flight per context.
  * Errors: EINVAL (NULL pointers, non-positive sizes, d_model != n_heads*head_dim,
  * bins outside the vocabulary), EUNSUPPORTED (head_dim not 64 or 128, d_model or d_ffn
- * not a multiple of 16, max_k > 64), ENOMEM (workspace too small), EHIP.
+ * or n_bins not a multiple of 16, max_k > 256, kv_capacity > 4096), ENOMEM (workspace too
+ * small), EHIP.
  */
 int heisd_verify_init(const heisd_model_desc *desc, heisd_verify_ctx **out);
 
@@ -146,6 +147,28 @@ int heisd_verify_step(heisd_verify_ctx *ctx, const heisd_kv_desc *kv, const int3
                       int32_t K, int32_t batch, const heisd_accept_desc *accept,
                       const uint8_t *skip_mask, int32_t *accepted_len, int32_t *next_token,
                       int32_t *target_bins, float *bin_logits, void *stream);
+
+/*
+ * Per-kernel timing for measurement runs (not part of the method).  With profiling enabled,
+ * heisd_verify_step brackets every kernel launch with HIP events on the caller's stream;
+ * heisd_verify_profile_read waits for the recorded events, adds the elapsed milliseconds
+ * of each kernel class to ms[class] and the number of launches to launches[class] (HOST
+ * arrays of HEISD_N_KERNEL_CLASSES entries, overwritten), and clears the record.
+ * Enabling creates events (host objects); disabling destroys them.  At most
+ * HEISD_PROFILE_MAX_STEPS steps are kept between two reads; later steps are not recorded.
+ */
+#define HEISD_N_KERNEL_CLASSES 8
+#define HEISD_KC_EMBED 0
+#define HEISD_KC_QKV 1      /* RMSNorm + QKV projection                 */
+#define HEISD_KC_ATTN 2     /* RoPE + KV-append + verify attention      */
+#define HEISD_KC_OPROJ 3    /* output projection + residual             */
+#define HEISD_KC_GATEUP 4   /* RMSNorm + gate/up projection + SwiGLU    */
+#define HEISD_KC_DOWN 5     /* down projection + residual               */
+#define HEISD_KC_LMHEAD 6   /* final RMSNorm + 256-bin LM-head slice    */
+#define HEISD_KC_ACCEPT 7   /* argmax + relaxed acceptance scan         */
+#define HEISD_PROFILE_MAX_STEPS 64
+int heisd_verify_profile_enable(heisd_verify_ctx *ctx, int enable);
+int heisd_verify_profile_read(heisd_verify_ctx *ctx, double *ms, int64_t *launches);
 
 /* Release the context (not the workspace, weights or caches: those are the caller's). NULL ok. */
 void heisd_free(heisd_verify_ctx *ctx);

@@ -5,7 +5,7 @@ Python binding) may import, link or call this package; only tests/, the smoke
 check and the benchmark's cpu_baseline leg do.  It shares no code with the HIP
 path and imports neither it nor the input generators.
 """
-from .heisd_oracle import (OracleModel, widen_bf16, embed, rmsnorm, rope, silu, attention_block,
+from .heisd_oracle import (OracleModel, widen_bf16, linear_bf16w, embed, rmsnorm, rope, silu, attention_block,
                            forward_block, prefill, bin_logits, argmax_bins, accept_block,
                            AcceptRule, verify_step, build_native)
 

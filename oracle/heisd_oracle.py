@@ -47,25 +47,42 @@ def build_native(force: bool = False) -> str:
     src = os.path.join(_HERE, "widen.c")
     if force or not os.path.exists(_SO) or os.path.getmtime(_SO) < os.path.getmtime(src):
         tmp = _SO + ".tmp%d" % os.getpid()
-        subprocess.check_call(["gcc", "-O2", "-fPIC", "-shared", "-fopenmp", "-o", tmp, src])
+        subprocess.check_call(["gcc", "-O3", "-mavx2", "-mfma", "-fPIC", "-shared", "-fopenmp", "-o", tmp, src])
         os.replace(tmp, _SO)
     return _SO
 
 
-def widen_bf16(bits: np.ndarray) -> np.ndarray:
-    """bf16 bit patterns (uint16) -> the same values in fp64 (exact)."""
+def _native():
     global _lib
-    bits = np.ascontiguousarray(bits)
-    if bits.dtype != np.uint16:
-        return np.asarray(bits, dtype=np.float64)
     if _lib is None:
         build_native()
         _lib = ctypes.CDLL(_SO)
         _lib.oracle_widen_bf16_f64.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int64]
         _lib.oracle_widen_bf16_f64.restype = None
+        _lib.oracle_linear_bf16w.argtypes = [ctypes.c_void_p, ctypes.c_int64, ctypes.c_int64, ctypes.c_void_p,
+                                             ctypes.c_int64, ctypes.c_void_p]
+        _lib.oracle_linear_bf16w.restype = None
+    return _lib
+
+
+def widen_bf16(bits: np.ndarray) -> np.ndarray:
+    """bf16 bit patterns (uint16) -> the same values in fp64 (exact).  Floats pass through."""
+    bits = np.ascontiguousarray(bits)
+    if bits.dtype != np.uint16:
+        return np.asarray(bits, dtype=np.float64)
     out = np.empty(bits.shape, dtype=np.float64)
-    _lib.oracle_widen_bf16_f64(bits.ctypes.data, out.ctypes.data, bits.size)
+    _native().oracle_widen_bf16_f64(bits.ctypes.data, out.ctypes.data, bits.size)
     return out
+
+
+def linear_bf16w(x: np.ndarray, w_bits: np.ndarray) -> np.ndarray:
+    """y = x . W^T for W given as bf16 bit patterns [out, in]; products and sums in fp64."""
+    n_out, n_in = w_bits.shape
+    x2 = np.ascontiguousarray(x, dtype=np.float64).reshape(-1, n_in)
+    w_bits = np.ascontiguousarray(w_bits)
+    y = np.empty((x2.shape[0], n_out))
+    _native().oracle_linear_bf16w(x2.ctypes.data, x2.shape[0], n_in, w_bits.ctypes.data, n_out, y.ctypes.data)
+    return y.reshape(x.shape[:-1] + (n_out,))
 
 
 @dataclass
@@ -93,6 +110,14 @@ class OracleModel:
 
     def rows(self, name: str, idx) -> np.ndarray:
         return widen_bf16(np.asarray(self.weights[name])[idx])
+
+    def linear(self, x: np.ndarray, name: str, layer: Optional[int] = None) -> np.ndarray:
+        """y = x . W^T for W = weights[name][layer] ([out, in])."""
+        w = self.weights[name] if layer is None else self.weights[name][layer]
+        w = np.asarray(w)
+        if w.dtype == np.uint16:
+            return linear_bf16w(x, w)
+        return x @ np.asarray(w, dtype=np.float64).T
 
 
 # ----------------------------------------------------------------------------
@@ -162,9 +187,9 @@ def forward_block(model: OracleModel, x_in: np.ndarray, prefix_len: Sequence[int
     v_new = np.zeros((m.n_layers, B, H, T, hd))
     for l in range(m.n_layers):
         h = rmsnorm(x, m.weights["attn_norm"][l], m.rms_eps)
-        q = (h @ m.mat("wq", l).T).reshape(B, T, H, hd)
-        k = (h @ m.mat("wk", l).T).reshape(B, T, H, hd)
-        v = (h @ m.mat("wv", l).T).reshape(B, T, H, hd)
+        q = m.linear(h, "wq", l).reshape(B, T, H, hd)
+        k = m.linear(h, "wk", l).reshape(B, T, H, hd)
+        v = m.linear(h, "wv", l).reshape(B, T, H, hd)
         o = np.zeros((B, T, H, hd))
         for b in range(B):
             p0 = int(prefix_len[b])
@@ -182,10 +207,10 @@ def forward_block(model: OracleModel, x_in: np.ndarray, prefix_len: Sequence[int
             else:
                 k_all, v_all = kb_h, vb_h
             o[b] = attention_block(qb, k_all, v_all, p0)
-        x = x + o.reshape(B, T, d) @ m.mat("wo", l).T
+        x = x + m.linear(o.reshape(B, T, d), "wo", l)
         h = rmsnorm(x, m.weights["ffn_norm"][l], m.rms_eps)
-        a = silu(h @ m.mat("w_gate", l).T) * (h @ m.mat("w_up", l).T)
-        x = x + a @ m.mat("w_down", l).T
+        a = silu(m.linear(h, "w_gate", l)) * m.linear(h, "w_up", l)
+        x = x + m.linear(a, "w_down", l)
     feat = rmsnorm(x, m.weights["final_norm"], m.rms_eps)
     out = {"feat": feat, "k_new": k_new, "v_new": v_new}
     if want_logits:

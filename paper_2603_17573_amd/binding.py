@@ -60,6 +60,10 @@ def load():
         lib.heisd_verify_step.restype = ctypes.c_int
         lib.heisd_free.argtypes = [c_void_p]
         lib.heisd_free.restype = None
+        lib.heisd_verify_profile_enable.argtypes = [c_void_p, ctypes.c_int]
+        lib.heisd_verify_profile_enable.restype = ctypes.c_int
+        lib.heisd_verify_profile_read.argtypes = [c_void_p, POINTER(ctypes.c_double), POINTER(ctypes.c_int64)]
+        lib.heisd_verify_profile_read.restype = ctypes.c_int
         lib.heisd_last_error.argtypes = [c_void_p]
         lib.heisd_last_error.restype = c_char_p
         _lib = lib
@@ -91,6 +95,21 @@ def heisd_free(ctx) -> None:
 
 def heisd_last_error(ctx=None) -> str:
     return load().heisd_last_error(ctx).decode()
+
+
+KERNEL_CLASSES = ("embed", "qkv", "attn", "oproj", "gateup", "down", "lmhead", "accept")
+
+
+def heisd_verify_profile_enable(ctx, enable: bool) -> int:
+    return load().heisd_verify_profile_enable(ctx, 1 if enable else 0)
+
+
+def heisd_verify_profile_read(ctx):
+    """Returns (rc, {class: (total_ms, launches)})."""
+    ms = (ctypes.c_double * len(KERNEL_CLASSES))()
+    n = (ctypes.c_int64 * len(KERNEL_CLASSES))()
+    rc = load().heisd_verify_profile_read(ctx, ms, n)
+    return rc, {k: (ms[i], n[i]) for i, k in enumerate(KERNEL_CLASSES)}
 
 
 def make_accept_desc(tok_threshold=15, seq_budget=30, group_sizes=(3, 3, 1), exact_group_mask=0b100,

@@ -26,6 +26,31 @@ struct heisd_verify_ctx {
   float *x, *qkv, *attn_o, *act, *logits;
   int32_t *tbins;
   char err[256];
+  // optional per-launch event timing
+  bool prof_on = false;
+  std::vector<hipEvent_t> ev;      // pairs (start, stop)
+  std::vector<int> ev_class;       // kernel class of each recorded pair
+  size_t ev_used = 0;
+  int prof_steps = 0;
+};
+
+// Brackets the launches issued between its construction and destruction with two events.
+struct ProfScope {
+  heisd_verify_ctx *c;
+  hipStream_t st;
+  size_t slot;
+  bool on;
+  ProfScope(heisd_verify_ctx *ctx, int kclass, hipStream_t s, bool enabled) : c(ctx), st(s), slot(0), on(false) {
+    if (!enabled || c->ev_used + 2 > c->ev.size()) return;
+    on = true;
+    slot = c->ev_used;
+    c->ev_used += 2;
+    c->ev_class.push_back(kclass);
+    (void)hipEventRecord(c->ev[slot], st);
+  }
+  ~ProfScope() {
+    if (on) (void)hipEventRecord(c->ev[slot + 1], st);
+  }
 };
 
 static thread_local char g_init_err[256] = "";
@@ -201,7 +226,55 @@ extern "C" int heisd_verify_init(const heisd_model_desc *desc, heisd_verify_ctx 
   return HEISD_OK;
 }
 
-extern "C" void heisd_free(heisd_verify_ctx *ctx) { delete ctx; }
+extern "C" int heisd_verify_profile_enable(heisd_verify_ctx *ctx, int enable) {
+  if (!ctx) return HEISD_EINVAL;
+  for (hipEvent_t e : ctx->ev) (void)hipEventDestroy(e);
+  ctx->ev.clear();
+  ctx->ev_class.clear();
+  ctx->ev_used = 0;
+  ctx->prof_steps = 0;
+  ctx->prof_on = false;
+  if (enable) {
+    const size_t per_step = (size_t)ctx->d.n_layers * 5 * 8 + 16;   // launches of one step, row blocks included
+    ctx->ev.resize(per_step * 2 * HEISD_PROFILE_MAX_STEPS);
+    for (size_t i = 0; i < ctx->ev.size(); ++i)
+      if (hipEventCreate(&ctx->ev[i]) != hipSuccess) {
+        for (size_t j = 0; j < i; ++j) (void)hipEventDestroy(ctx->ev[j]);
+        ctx->ev.clear();
+        return fail(ctx, HEISD_EHIP, "profile: hipEventCreate failed");
+      }
+    ctx->ev_class.reserve(ctx->ev.size() / 2);
+    ctx->prof_on = true;
+  }
+  return HEISD_OK;
+}
+
+extern "C" int heisd_verify_profile_read(heisd_verify_ctx *ctx, double *ms, int64_t *launches) {
+  if (!ctx || !ms || !launches) return HEISD_EINVAL;
+  for (int i = 0; i < HEISD_N_KERNEL_CLASSES; ++i) { ms[i] = 0.0; launches[i] = 0; }
+  const size_t pairs = ctx->ev_used / 2;
+  if (pairs) {
+    if (hipEventSynchronize(ctx->ev[ctx->ev_used - 1]) != hipSuccess)
+      return fail(ctx, HEISD_EHIP, "profile: hipEventSynchronize failed");
+    for (size_t p = 0; p < pairs; ++p) {
+      float t = 0.f;
+      if (hipEventElapsedTime(&t, ctx->ev[2 * p], ctx->ev[2 * p + 1]) != hipSuccess)
+        return fail(ctx, HEISD_EHIP, "profile: hipEventElapsedTime failed");
+      ms[ctx->ev_class[p]] += t;
+      launches[ctx->ev_class[p]] += 1;
+    }
+  }
+  ctx->ev_used = 0;
+  ctx->ev_class.clear();
+  ctx->prof_steps = 0;
+  return HEISD_OK;
+}
+
+extern "C" void heisd_free(heisd_verify_ctx *ctx) {
+  if (!ctx) return;
+  for (hipEvent_t e : ctx->ev) (void)hipEventDestroy(e);
+  delete ctx;
+}
 
 extern "C" const char *heisd_last_error(const heisd_verify_ctx *ctx) { return ctx ? ctx->err : g_init_err; }
 
@@ -233,8 +306,13 @@ extern "C" int heisd_verify_step(heisd_verify_ctx *ctx, const heisd_kv_desc *kv,
   int32_t *tbins = target_bins ? target_bins : ctx->tbins;
   (void)hipGetLastError();
 
+  const bool prof = ctx->prof_on && ctx->prof_steps < HEISD_PROFILE_MAX_STEPS;
+  if (prof) ctx->prof_steps++;
+  {
+    ProfScope ps(ctx, HEISD_KC_EMBED, st, prof);
   embed_rows<<<dim3(M), dim3(256), 0, st>>>(draft_tokens, static_cast<const uint16_t *>(d.tok_emb), d.vocab, dm,
                                             ctx->x);
+  }
   const size_t layer_stride = (size_t)batch * H * cap * HD;
   const size_t attn_lds = attn_lds_bytes(HD, cap);
   for (int l = 0; l < d.n_layers; ++l) {
@@ -246,7 +324,7 @@ extern "C" int heisd_verify_step(heisd_verify_ctx *ctx, const heisd_kv_desc *kv,
     g.w[2] = static_cast<const uint16_t *>(ctx->wv[l]);
     g.seg_tiles = dm / 16; g.n_units = 3 * dm / 16; g.Kd = dm; g.eps = d.rms_eps;
     g.out = ctx->qkv; g.ldo = 3 * dm; g.resid = nullptr;
-    gemm_launch(g, M, EPI_STORE, st);
+    { ProfScope ps(ctx, HEISD_KC_QKV, st, prof); gemm_launch(g, M, EPI_STORE, st); }
     // RoPE + KV-append + attention
     AttnArgs a{};
     a.qkv = ctx->qkv;
@@ -254,14 +332,17 @@ extern "C" int heisd_verify_step(heisd_verify_ctx *ctx, const heisd_kv_desc *kv,
     a.v_cache = static_cast<uint16_t *>(kv->v_cache) + (size_t)l * layer_stride;
     a.prefix_len = kv->prefix_len; a.skip = skip_mask; a.rope = ctx->rope; a.out = ctx->attn_o;
     a.K = K; a.H = H; a.cap = cap; a.d = dm; a.scale = 1.0f / std::sqrt((float)HD);
-    if (HD == 128) attn_verify<128><<<dim3(H, batch), dim3(kAttnThreads), attn_lds, st>>>(a);
-    else attn_verify<64><<<dim3(H, batch), dim3(kAttnThreads), attn_lds, st>>>(a);
+    {
+      ProfScope ps(ctx, HEISD_KC_ATTN, st, prof);
+      if (HD == 128) attn_verify<128><<<dim3(H, batch), dim3(kAttnThreads), attn_lds, st>>>(a);
+      else attn_verify<64><<<dim3(H, batch), dim3(kAttnThreads), attn_lds, st>>>(a);
+    }
     // x += o . Wo^T
     g = GemmArgs{};
     g.act = ctx->attn_o; g.gain = nullptr; g.w[0] = static_cast<const uint16_t *>(ctx->wo[l]);
     g.seg_tiles = dm / 16; g.n_units = dm / 16; g.Kd = dm; g.eps = 0.f;
     g.out = ctx->x; g.ldo = dm; g.resid = ctx->x;
-    gemm_launch(g, M, EPI_STORE, st);
+    { ProfScope ps(ctx, HEISD_KC_OPROJ, st, prof); gemm_launch(g, M, EPI_STORE, st); }
     // a = silu(RMSNorm(x) . Wg^T) * (RMSNorm(x) . Wu^T)
     g = GemmArgs{};
     g.act = ctx->x; g.gain = ctx->ffn_norm[l];
@@ -269,13 +350,13 @@ extern "C" int heisd_verify_step(heisd_verify_ctx *ctx, const heisd_kv_desc *kv,
     g.w[1] = static_cast<const uint16_t *>(ctx->w_up[l]);
     g.seg_tiles = F / 16; g.n_units = F / 16; g.Kd = dm; g.eps = d.rms_eps;
     g.out = ctx->act; g.ldo = F; g.resid = nullptr;
-    gemm_launch(g, M, EPI_SWIGLU, st);
+    { ProfScope ps(ctx, HEISD_KC_GATEUP, st, prof); gemm_launch(g, M, EPI_SWIGLU, st); }
     // x += a . Wd^T
     g = GemmArgs{};
     g.act = ctx->act; g.gain = nullptr; g.w[0] = static_cast<const uint16_t *>(ctx->w_down[l]);
     g.seg_tiles = dm / 16; g.n_units = dm / 16; g.Kd = F; g.eps = 0.f;
     g.out = ctx->x; g.ldo = dm; g.resid = ctx->x;
-    gemm_launch(g, M, EPI_STORE, st);
+    { ProfScope ps(ctx, HEISD_KC_DOWN, st, prof); gemm_launch(g, M, EPI_STORE, st); }
   }
   // logits over the action bins = RMSNorm(x; final) . W_lm[bin rows]^T
   {
@@ -284,6 +365,7 @@ extern "C" int heisd_verify_step(heisd_verify_ctx *ctx, const heisd_kv_desc *kv,
     g.w[0] = static_cast<const uint16_t *>(d.lm_head) + (size_t)d.bin_token_base * dm;
     g.seg_tiles = d.n_bins / 16; g.n_units = d.n_bins / 16; g.Kd = dm; g.eps = d.rms_eps;
     g.out = logits; g.ldo = d.n_bins; g.resid = nullptr;
+    ProfScope ps(ctx, HEISD_KC_LMHEAD, st, prof);
     gemm_launch(g, M, EPI_STORE, st);
   }
   AcceptArgs aa{};
@@ -293,7 +375,10 @@ extern "C" int heisd_verify_step(heisd_verify_ctx *ctx, const heisd_kv_desc *kv,
   aa.tok_threshold = accept->tok_threshold; aa.seq_budget = accept->seq_budget;
   aa.n_groups = accept->n_groups; aa.mode = accept->mode; aa.exact_mask = accept->exact_group_mask;
   for (int i = 0; i < 8; ++i) aa.group_sizes[i] = i < accept->n_groups ? accept->group_sizes[i] : 1;
-  argmax_accept<<<dim3(batch), dim3(256), 0, st>>>(aa);
+  {
+    ProfScope ps(ctx, HEISD_KC_ACCEPT, st, prof);
+    argmax_accept<<<dim3(batch), dim3(256), 0, st>>>(aa);
+  }
   const hipError_t e = hipGetLastError();
   if (e != hipSuccess) return fail(ctx, HEISD_EHIP, "step: %s", hipGetErrorString(e));
   ctx->err[0] = 0;

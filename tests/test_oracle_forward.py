@@ -195,3 +195,21 @@ def test_bf16_prefix_cache_round_trip_on_c0_shape():
     assert out["target_bins"][0, 0] == first[0]
     assert out["accepted_len"][0] in (0, 3, 6, 7)
     assert out["next_token"][0] == wl.shape.bin_base + out["target_bins"][0, out["accepted_len"][0]]
+
+
+def test_c_linear_equals_library_matmul():
+    """The oracle's C routine for bf16-stored weights against numpy's matmul on the widened matrix,
+    including row counts that are not a multiple of its 4-row grouping."""
+    rng = np.random.default_rng(4)
+    for (T, Kd, N) in [(1, 8, 1), (7, 40, 6), (5, 33, 7), (3, 256, 17), (64, 100, 50)]:
+        w = synth.f32_to_bf16_bits(rng.normal(0, 0.3, (N, Kd)).astype(np.float32))
+        x = rng.normal(0, 1, (T, Kd))
+        ref = x @ oracle.widen_bf16(w).T
+        got = oracle.linear_bf16w(x, w)
+        assert got.shape == (T, N) and np.allclose(got, ref, rtol=1e-13, atol=1e-13)
+    # widening is exact: the fp64 value equals the fp32 reading of the same bits
+    bits = rng.integers(0, 0x7F80, 1000).astype(np.uint16)
+    assert np.array_equal(oracle.widen_bf16(bits), synth.bf16_bits_to_f32(bits).astype(np.float64))
+    x3 = rng.normal(0, 1, (2, 3, 40))
+    w = synth.f32_to_bf16_bits(rng.normal(0, 0.3, (6, 40)).astype(np.float32))
+    assert np.allclose(oracle.linear_bf16w(x3, w), x3 @ oracle.widen_bf16(w).T, atol=1e-13)
