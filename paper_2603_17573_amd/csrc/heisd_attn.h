@@ -3,7 +3,9 @@
 // tokens).  One workgroup per (episode, head).
 //
 //   1. rotate this head's new keys (rotate-half, absolute position prefix_len + j), round
-//      keys and values to bf16 and append them to the episode's cache rows;
+//      keys and values to bf16 and append them to the episode's cache rows; the rotated keys
+//      are also kept in fp32 (in place, in the projection scratch) so that the block attends
+//      to its own rows at full precision and only the prefix is read as bf16;
 //   2. per block of 8 queries: scores of every visible key into LDS (each key row is read
 //      once, 16 bytes per lane, and dotted with all 8 queries; partial dots are summed with
 //      wavefront shuffles), softmax per query with wavefront reductions, then one pass over
@@ -19,7 +21,7 @@ constexpr int kAttnWaves = 4;
 constexpr int kAttnQB = 8;  // queries per block
 
 struct AttnArgs {
-  const float *qkv;          // [M][3*d] fp32: q | k | v of the new rows, not yet rotated
+  float *qkv;                // [M][3*d] fp32: q | k | v of the new rows, not yet rotated; k is rotated in place
   uint16_t *k_cache;         // this layer: bf16 [batch][H][cap][HD]
   uint16_t *v_cache;
   const int32_t *prefix_len; // [batch]
@@ -63,17 +65,20 @@ __global__ __launch_bounds__(kAttnThreads) void attn_verify(AttnArgs a) {
   // ---- RoPE on the new keys, append keys and values (bf16) ----
   for (int idx = tid; idx < K * HALF; idx += kAttnThreads) {
     const int j = idx / HALF, i = idx - j * HALF;
-    const float *src = a.qkv + (size_t)(row0 + j) * 3 * d + h * HD;
+    float *src = a.qkv + (size_t)(row0 + j) * 3 * d + h * HD;
     const float2 cs = a.rope[(size_t)(P + j) * HALF + i];
     const float k1 = src[d + i], k2 = src[d + i + HALF];
+    const float kr1 = k1 * cs.x - k2 * cs.y, kr2 = k2 * cs.x + k1 * cs.y;
+    src[d + i] = kr1;
+    src[d + i + HALF] = kr2;
     uint16_t *kr = kc + (size_t)(P + j) * HD;
-    kr[i] = (uint16_t)f32_to_bf16_bits(k1 * cs.x - k2 * cs.y);
-    kr[i + HALF] = (uint16_t)f32_to_bf16_bits(k2 * cs.x + k1 * cs.y);
+    kr[i] = (uint16_t)f32_to_bf16_bits(kr1);
+    kr[i + HALF] = (uint16_t)f32_to_bf16_bits(kr2);
     uint16_t *vr = vc + (size_t)(P + j) * HD;
     vr[i] = (uint16_t)f32_to_bf16_bits(src[2 * d + i]);
     vr[i + HALF] = (uint16_t)f32_to_bf16_bits(src[2 * d + i + HALF]);
   }
-  __syncthreads();  // the appended rows are read back below by other waves of this workgroup
+  __syncthreads();  // the rotated fp32 keys are read back below by other waves of this workgroup
 
   const int li = tid % LPK;   // which 8 channels of a row this lane covers
   const int g = tid / LPK;    // which key stream this lane belongs to
@@ -102,13 +107,20 @@ __global__ __launch_bounds__(kAttnThreads) void attn_verify(AttnArgs a) {
 
     // ---- pass 1: scores ----
     for (int r = g; r < nkeys; r += G) {
-      const uint4 kk = *reinterpret_cast<const uint4 *>(kc + (size_t)r * HD + li * 8);
-      const uint32_t kw[4] = {kk.x, kk.y, kk.z, kk.w};
       float kf[8];
+      if (r < P) {
+        const uint4 kk = *reinterpret_cast<const uint4 *>(kc + (size_t)r * HD + li * 8);
+        const uint32_t kw[4] = {kk.x, kk.y, kk.z, kk.w};
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        kf[2 * i] = __uint_as_float(kw[i] << 16);
-        kf[2 * i + 1] = __uint_as_float(kw[i] & 0xFFFF0000u);
+        for (int i = 0; i < 4; ++i) {
+          kf[2 * i] = __uint_as_float(kw[i] << 16);
+          kf[2 * i + 1] = __uint_as_float(kw[i] & 0xFFFF0000u);
+        }
+      } else {
+        const float *kp = a.qkv + (size_t)(row0 + r - P) * 3 * d + d + h * HD + li * 8;
+        const float4 k0 = *reinterpret_cast<const float4 *>(kp), k1 = *reinterpret_cast<const float4 *>(kp + 4);
+        kf[0] = k0.x; kf[1] = k0.y; kf[2] = k0.z; kf[3] = k0.w;
+        kf[4] = k1.x; kf[5] = k1.y; kf[6] = k1.z; kf[7] = k1.w;
       }
       float s[kAttnQB];
 #pragma unroll
@@ -153,13 +165,20 @@ __global__ __launch_bounds__(kAttnThreads) void attn_verify(AttnArgs a) {
 #pragma unroll
       for (int i = 0; i < 8; ++i) o[j][i] = 0.f;
     for (int r = g; r < nkeys; r += G) {
-      const uint4 vv = *reinterpret_cast<const uint4 *>(vc + (size_t)r * HD + li * 8);
-      const uint32_t vw[4] = {vv.x, vv.y, vv.z, vv.w};
       float vf[8];
+      if (r < P) {
+        const uint4 vv = *reinterpret_cast<const uint4 *>(vc + (size_t)r * HD + li * 8);
+        const uint32_t vw[4] = {vv.x, vv.y, vv.z, vv.w};
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        vf[2 * i] = __uint_as_float(vw[i] << 16);
-        vf[2 * i + 1] = __uint_as_float(vw[i] & 0xFFFF0000u);
+        for (int i = 0; i < 4; ++i) {
+          vf[2 * i] = __uint_as_float(vw[i] << 16);
+          vf[2 * i + 1] = __uint_as_float(vw[i] & 0xFFFF0000u);
+        }
+      } else {
+        const float *vp = a.qkv + (size_t)(row0 + r - P) * 3 * d + 2 * d + h * HD + li * 8;
+        const float4 v0 = *reinterpret_cast<const float4 *>(vp), v1 = *reinterpret_cast<const float4 *>(vp + 4);
+        vf[0] = v0.x; vf[1] = v0.y; vf[2] = v0.z; vf[3] = v0.w;
+        vf[4] = v1.x; vf[5] = v1.y; vf[6] = v1.z; vf[7] = v1.w;
       }
 #pragma unroll
       for (int j = 0; j < kAttnQB; ++j) {

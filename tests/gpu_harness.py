@@ -91,12 +91,19 @@ def compare_with_oracle(got, ref, drafts, rule, shape, kb0=None, vb0=None, plen=
 
 
 def compare_cache(got, ref, kb0, vb0, plen, skip, K, eps):
-    """Appended rows equal the oracle's new keys/values up to one bf16 rounding (plus the fp32
-    arithmetic before it); every other row of the cache is untouched."""
+    """Appended rows equal the oracle's new keys/values up to one bf16 rounding plus the arithmetic
+    error of the layers below them; every other row of the cache is untouched.
+
+    Tolerance per element of layer l: |r| * 2^-8 (half a bf16 ulp, with slack for a value that
+    rounds across a binade) + (5e-5 + 2e-5 * l) * max|r|: fp32 accumulation and 16-bit split
+    activations, compounding with depth."""
     worst = 0.0
+    per_layer = []
     for name, c0, new in (("k_cache", kb0, ref["k_new"]), ("v_cache", vb0, ref["v_new"])):
         after = got[name]
+        L = after.shape[0]
         keep = np.ones(after.shape, bool)
+        lay_err = np.zeros(L)
         for i, b in enumerate(eps):
             if skip[b]:
                 continue
@@ -104,10 +111,16 @@ def compare_cache(got, ref, kb0, vb0, plen, skip, K, eps):
             keep[:, b, :, p:p + K, :] = False
             a = synth.bf16_bits_to_f32(after[:, b, :, p:p + K, :]).astype(np.float64)
             r = new[:, i]                                 # [L, H, K, hd]
-            scale = np.abs(r).max()
-            e = np.abs(a - r)
-            assert np.all(e <= np.abs(r) * 2.0 ** -8 + 2e-3 * scale), "appended %s rows off" % name
-            worst = max(worst, float((e / scale).max()))
+            scale = np.abs(r).reshape(L, -1).max(axis=1)
+            e = np.abs(a - r) - np.abs(r) * 2.0 ** -8
+            rel = e.reshape(L, -1).max(axis=1) / scale
+            lay_err = np.maximum(lay_err, rel)
+        per_layer.append(lay_err)
+        tol = 5e-5 + 2e-5 * np.arange(L)
+        assert np.all(lay_err <= tol), "appended %s rows off; excess error per layer / scale: %s" % (
+            name, np.array2string(lay_err, precision=5))
+        worst = max(worst, float(lay_err.max()))
         if len(eps) == after.shape[1]:
             assert np.array_equal(after[keep], c0[keep]), "%s modified outside the appended rows" % name
-    return {"max_kv_err_over_scale": worst}
+    return {"max_kv_excess_err_over_scale": worst,
+            "kv_err_first_last_layer": [float(per_layer[0][0]), float(per_layer[0][-1])]}
