@@ -170,6 +170,17 @@ int heisd_verify_step(heisd_verify_ctx *ctx, const heisd_kv_desc *kv, const int3
 int heisd_verify_profile_enable(heisd_verify_ctx *ctx, int enable);
 int heisd_verify_profile_read(heisd_verify_ctx *ctx, double *ms, int64_t *launches);
 
+/*
+ * Kernel-path selection, for tests and measurement.  AUTO (default) picks the fastest path
+ * that covers the call; GENERIC forces the any-M path (LDS-staged activations, one launch
+ * per phase); FAST forces the batch*K <= 8 path and makes a larger step fail with
+ * EUNSUPPORTED.  Results of the paths agree to fp32 rounding.
+ */
+#define HEISD_PATH_AUTO 0
+#define HEISD_PATH_GENERIC 1
+#define HEISD_PATH_FAST 2
+int heisd_verify_set_path(heisd_verify_ctx *ctx, int path);
+
 /* Release the context (not the workspace, weights or caches: those are the caller's). NULL ok. */
 void heisd_free(heisd_verify_ctx *ctx);
 

@@ -64,6 +64,8 @@ def load():
         lib.heisd_verify_profile_enable.restype = ctypes.c_int
         lib.heisd_verify_profile_read.argtypes = [c_void_p, POINTER(ctypes.c_double), POINTER(ctypes.c_int64)]
         lib.heisd_verify_profile_read.restype = ctypes.c_int
+        lib.heisd_verify_set_path.argtypes = [c_void_p, ctypes.c_int]
+        lib.heisd_verify_set_path.restype = ctypes.c_int
         lib.heisd_last_error.argtypes = [c_void_p]
         lib.heisd_last_error.restype = c_char_p
         _lib = lib
@@ -95,6 +97,13 @@ def heisd_free(ctx) -> None:
 
 def heisd_last_error(ctx=None) -> str:
     return load().heisd_last_error(ctx).decode()
+
+
+HEISD_PATH_AUTO, HEISD_PATH_GENERIC, HEISD_PATH_FAST = 0, 1, 2
+
+
+def heisd_verify_set_path(ctx, path: int) -> int:
+    return load().heisd_verify_set_path(ctx, path)
 
 
 KERNEL_CLASSES = ("embed", "qkv", "attn", "oproj", "gateup", "down", "lmhead", "accept")

@@ -12,6 +12,7 @@
 #include <vector>
 
 #include "heisd_attn.h"
+#include "heisd_fast.h"
 #include "heisd_gemm.h"
 #include "heisd_misc.h"
 
@@ -25,6 +26,11 @@ struct heisd_verify_ctx {
   float2 *rope;
   float *x, *qkv, *attn_o, *act, *logits;
   int32_t *tbins;
+  uint16_t *pl_x, *pl_attn, *pl_act;   // fast path: activation planes [16][d], [16][d], [16][d_ffn]
+  float *ssq;                          // fast path: [8][d/16] partial sums of squares
+  int n_cu = 256;
+  int path = 0;                        // HEISD_PATH_*
+  bool fast_ok = false;                // the shape fits the fast kernels
   char err[256];
   // optional per-launch event timing
   bool prof_on = false;
@@ -67,7 +73,7 @@ static int fail(heisd_verify_ctx *ctx, int code, const char *fmt, ...) {
 static size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
 
 struct WsLayout {
-  size_t rope, x, qkv, attn_o, act, logits, tbins, total;
+  size_t rope, x, qkv, attn_o, act, logits, tbins, pl_x, pl_attn, pl_act, ssq, total;
 };
 
 static bool shape_ok(const heisd_model_desc *d) {
@@ -88,6 +94,10 @@ static WsLayout ws_layout(const heisd_model_desc *d) {
   w.act = off;    off += align256(M * d->d_ffn * sizeof(float));
   w.logits = off; off += align256(M * d->n_bins * sizeof(float));
   w.tbins = off;  off += align256((size_t)d->max_batch * (d->max_k + 1) * sizeof(int32_t));
+  w.pl_x = off;   off += align256((size_t)16 * d->d_model * sizeof(uint16_t));
+  w.pl_attn = off; off += align256((size_t)16 * d->d_model * sizeof(uint16_t));
+  w.pl_act = off; off += align256((size_t)16 * d->d_ffn * sizeof(uint16_t));
+  w.ssq = off;    off += align256((size_t)8 * (d->d_model / 16 + 1) * sizeof(float));
   w.total = off;
   return w;
 }
@@ -145,6 +155,102 @@ static void gemm_launch(GemmArgs a, int M, int epi, hipStream_t st) {
   }
 }
 
+// ---- fast path (M <= 8 rows) ------------------------------------------------------------
+
+static hipError_t fast_prepare(int hd, int cap) {
+  hipError_t e;
+  const int lds = (int)kFastLds;
+  if ((e = hipFuncSetAttribute(reinterpret_cast<const void *>(&fast_gemm_kernel<FEPI_STORE, 1>),
+                               hipFuncAttributeMaxDynamicSharedMemorySize, lds)) != hipSuccess) return e;
+  if ((e = hipFuncSetAttribute(reinterpret_cast<const void *>(&fast_gemm_kernel<FEPI_RESID_NORM, 1>),
+                               hipFuncAttributeMaxDynamicSharedMemorySize, lds)) != hipSuccess) return e;
+  if ((e = hipFuncSetAttribute(reinterpret_cast<const void *>(&fast_gemm_kernel<FEPI_RESID_NORM, 3>),
+                               hipFuncAttributeMaxDynamicSharedMemorySize, lds)) != hipSuccess) return e;
+  if ((e = hipFuncSetAttribute(reinterpret_cast<const void *>(&fast_gemm_kernel<FEPI_SWIGLU, 1>),
+                               hipFuncAttributeMaxDynamicSharedMemorySize, lds)) != hipSuccess) return e;
+  const int alds = (int)fast_attn_lds(hd, cap);
+  if (hd == 128)
+    e = hipFuncSetAttribute(reinterpret_cast<const void *>(&fast_attn_kernel<128>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, alds);
+  else
+    e = hipFuncSetAttribute(reinterpret_cast<const void *>(&fast_attn_kernel<64>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, alds);
+  return e;
+}
+
+// The decoder forward for M <= 8 rows, one launch per phase; leaves the bin logits in `logits`.
+static void fast_forward(heisd_verify_ctx *ctx, const heisd_kv_desc *kv, const int32_t *draft_tokens, int K,
+                         int batch, const uint8_t *skip_mask, float *logits, hipStream_t st, bool prof) {
+  const heisd_model_desc &d = ctx->d;
+  const int M = batch * K, dm = d.d_model, F = d.d_ffn, H = d.n_heads, HD = d.head_dim, cap = d.kv_capacity;
+  const int ncu = ctx->n_cu;
+  auto grid_for = [&](int units) { return dim3(units < ncu ? units : ncu); };
+  {
+    ProfScope ps(ctx, HEISD_KC_EMBED, st, prof);
+    fast_embed<<<dim3(dm / 16), dim3(128), 0, st>>>(draft_tokens, static_cast<const uint16_t *>(d.tok_emb), d.vocab,
+                                                    dm, M, ctx->attn_norm[0], ctx->x, ctx->pl_x, ctx->ssq);
+  }
+  const size_t layer_stride = (size_t)batch * H * cap * HD;
+  const size_t alds = fast_attn_lds(HD, cap);
+  for (int l = 0; l < d.n_layers; ++l) {
+    FastGemm g{};
+    g.w[0] = static_cast<const uint16_t *>(ctx->wq[l]);
+    g.w[1] = static_cast<const uint16_t *>(ctx->wk[l]);
+    g.w[2] = static_cast<const uint16_t *>(ctx->wv[l]);
+    g.seg_tiles = dm / 16; g.n_units = 3 * dm / 16; g.Kd = dm; g.b = ctx->pl_x; g.ssq = ctx->ssq;
+    g.n_ssq = dm / 16; g.eps = d.rms_eps; g.M = M; g.out = ctx->qkv; g.ldo = 3 * dm;
+    {
+      ProfScope ps(ctx, HEISD_KC_QKV, st, prof);
+      fast_gemm_kernel<FEPI_STORE, 1><<<grid_for(g.n_units), dim3(kFastThreads), kFastLds, st>>>(g);
+    }
+    FastAttn a{};
+    a.qkv = ctx->qkv;
+    a.k_cache = static_cast<uint16_t *>(kv->k_cache) + (size_t)l * layer_stride;
+    a.v_cache = static_cast<uint16_t *>(kv->v_cache) + (size_t)l * layer_stride;
+    a.prefix_len = kv->prefix_len; a.skip = skip_mask; a.rope = ctx->rope; a.o_planes = ctx->pl_attn;
+    a.K = K; a.H = H; a.cap = cap; a.d = dm; a.batch = batch; a.scale = 1.0f / std::sqrt((float)HD);
+    {
+      ProfScope ps(ctx, HEISD_KC_ATTN, st, prof);
+      if (HD == 128) fast_attn_kernel<128><<<dim3(H, batch), dim3(kFastThreads), alds, st>>>(a);
+      else fast_attn_kernel<64><<<dim3(H, batch), dim3(kFastThreads), alds, st>>>(a);
+    }
+    g = FastGemm{};
+    g.w[0] = static_cast<const uint16_t *>(ctx->wo[l]);
+    g.seg_tiles = dm / 16; g.n_units = dm / 16; g.Kd = dm; g.b = ctx->pl_attn; g.ssq = nullptr; g.M = M;
+    g.out = ctx->x; g.ldo = dm; g.next_gain = ctx->ffn_norm[l]; g.o_planes = ctx->pl_x; g.ssq_out = ctx->ssq;
+    {
+      ProfScope ps(ctx, HEISD_KC_OPROJ, st, prof);
+      fast_gemm_kernel<FEPI_RESID_NORM, 1><<<grid_for(g.n_units), dim3(kFastThreads), kFastLds, st>>>(g);
+    }
+    g = FastGemm{};
+    g.w[0] = static_cast<const uint16_t *>(ctx->w_gate[l]);
+    g.w[1] = static_cast<const uint16_t *>(ctx->w_up[l]);
+    g.seg_tiles = F / 16; g.n_units = F / 16; g.Kd = dm; g.b = ctx->pl_x; g.ssq = ctx->ssq; g.n_ssq = dm / 16;
+    g.eps = d.rms_eps; g.M = M; g.o_planes = ctx->pl_act; g.ldo = F;
+    {
+      ProfScope ps(ctx, HEISD_KC_GATEUP, st, prof);
+      fast_gemm_kernel<FEPI_SWIGLU, 1><<<grid_for(g.n_units), dim3(kFastThreads), kFastLds, st>>>(g);
+    }
+    g = FastGemm{};
+    g.w[0] = static_cast<const uint16_t *>(ctx->w_down[l]);
+    g.seg_tiles = dm / 16; g.n_units = dm / 16; g.Kd = F; g.b = ctx->pl_act; g.ssq = nullptr; g.M = M;
+    g.out = ctx->x; g.ldo = dm; g.next_gain = (l + 1 < d.n_layers) ? ctx->attn_norm[l + 1] : d.final_norm;
+    g.o_planes = ctx->pl_x; g.ssq_out = ctx->ssq;
+    {
+      ProfScope ps(ctx, HEISD_KC_DOWN, st, prof);
+      fast_gemm_kernel<FEPI_RESID_NORM, 3><<<grid_for(g.n_units), dim3(kFastThreads), kFastLds, st>>>(g);
+    }
+  }
+  FastGemm g{};
+  g.w[0] = static_cast<const uint16_t *>(d.lm_head) + (size_t)d.bin_token_base * dm;
+  g.seg_tiles = d.n_bins / 16; g.n_units = d.n_bins / 16; g.Kd = dm; g.b = ctx->pl_x; g.ssq = ctx->ssq;
+  g.n_ssq = dm / 16; g.eps = d.rms_eps; g.M = M; g.out = logits; g.ldo = d.n_bins;
+  {
+    ProfScope ps(ctx, HEISD_KC_LMHEAD, st, prof);
+    fast_gemm_kernel<FEPI_STORE, 1><<<grid_for(g.n_units), dim3(kFastThreads), kFastLds, st>>>(g);
+  }
+}
+
 // ---- init / free ------------------------------------------------------------------------
 
 extern "C" int heisd_verify_init(const heisd_model_desc *desc, heisd_verify_ctx **out) {
@@ -195,6 +301,12 @@ extern "C" int heisd_verify_init(const heisd_model_desc *desc, heisd_verify_ctx 
   c->act = reinterpret_cast<float *>(base + w.act);
   c->logits = reinterpret_cast<float *>(base + w.logits);
   c->tbins = reinterpret_cast<int32_t *>(base + w.tbins);
+  c->pl_x = reinterpret_cast<uint16_t *>(base + w.pl_x);
+  c->pl_attn = reinterpret_cast<uint16_t *>(base + w.pl_attn);
+  c->pl_act = reinterpret_cast<uint16_t *>(base + w.pl_act);
+  c->ssq = reinterpret_cast<float *>(base + w.ssq);
+  c->fast_ok = desc->d_model <= kChunkK && desc->d_ffn <= 3 * kChunkK;
+  c->path = HEISD_PATH_AUTO;
 
   // rotary table: angle = position * rope_base^(-2i/head_dim), computed in double on the host
   const int half = desc->head_dim / 2;
@@ -205,6 +317,15 @@ extern "C" int heisd_verify_init(const heisd_model_desc *desc, heisd_verify_ctx 
       tab[(size_t)p * half + i] = make_float2((float)std::cos(ang), (float)std::sin(ang));
     }
   hipError_t e = hipMemcpy(c->rope, tab.data(), tab.size() * sizeof(float2), hipMemcpyHostToDevice);
+  if (e == hipSuccess) e = hipMemset(base + w.pl_x, 0, w.total - w.pl_x);   // planes start as zeros
+  if (e == hipSuccess) {
+    int dev = 0;
+    hipDeviceProp_t prop;
+    e = hipGetDevice(&dev);
+    if (e == hipSuccess) e = hipGetDeviceProperties(&prop, dev);
+    if (e == hipSuccess) c->n_cu = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
+  }
+  if (e == hipSuccess) e = fast_prepare(desc->head_dim, desc->kv_capacity);
   if (e == hipSuccess) e = gemm_prepare_mc<1>();
   if (e == hipSuccess) e = gemm_prepare_mc<2>();
   if (e == hipSuccess) e = gemm_prepare_mc<4>();
@@ -223,6 +344,16 @@ extern "C" int heisd_verify_init(const heisd_model_desc *desc, heisd_verify_ctx 
   }
   *out = c;
   g_init_err[0] = 0;
+  return HEISD_OK;
+}
+
+extern "C" int heisd_verify_set_path(heisd_verify_ctx *ctx, int path) {
+  if (!ctx) return HEISD_EINVAL;
+  if (path != HEISD_PATH_AUTO && path != HEISD_PATH_GENERIC && path != HEISD_PATH_FAST)
+    return fail(ctx, HEISD_EINVAL, "set_path: unknown path %d", path);
+  if (path == HEISD_PATH_FAST && !ctx->fast_ok)
+    return fail(ctx, HEISD_EUNSUPPORTED, "set_path: model shape outside the fast kernels");
+  ctx->path = path;
   return HEISD_OK;
 }
 
@@ -278,36 +409,11 @@ extern "C" void heisd_free(heisd_verify_ctx *ctx) {
 
 extern "C" const char *heisd_last_error(const heisd_verify_ctx *ctx) { return ctx ? ctx->err : g_init_err; }
 
-// ---- one verify step ----------------------------------------------------------------------
-
-extern "C" int heisd_verify_step(heisd_verify_ctx *ctx, const heisd_kv_desc *kv, const int32_t *draft_tokens,
-                                 int32_t K, int32_t batch, const heisd_accept_desc *accept,
-                                 const uint8_t *skip_mask, int32_t *accepted_len, int32_t *next_token,
-                                 int32_t *target_bins, float *bin_logits, void *stream) {
-  if (!ctx) return HEISD_EINVAL;
-  if (!kv || !kv->k_cache || !kv->v_cache || !kv->prefix_len || !kv->first_pred || !draft_tokens || !accept ||
-      !accepted_len || !next_token)
-    return fail(ctx, HEISD_EINVAL, "step: NULL required pointer");
+// The decoder forward for any M, one launch per phase (LDS-staged activations, 64-row blocks).
+static void generic_forward(heisd_verify_ctx *ctx, const heisd_kv_desc *kv, const int32_t *draft_tokens, int K,
+                            int batch, const uint8_t *skip_mask, float *logits, hipStream_t st, bool prof) {
   const heisd_model_desc &d = ctx->d;
-  if (K < 1 || batch < 1 || K > d.max_k || batch > d.max_batch || K > d.kv_capacity)
-    return fail(ctx, HEISD_EINVAL, "step: K=%d batch=%d outside [1,%d] x [1,%d] (kv_capacity %d)", K, batch,
-                d.max_k, d.max_batch, d.kv_capacity);
-  if (accept->n_groups < 1 || accept->n_groups > HEISD_MAX_GROUPS)
-    return fail(ctx, HEISD_EINVAL, "step: n_groups=%d outside [1,%d]", accept->n_groups, HEISD_MAX_GROUPS);
-  for (int g = 0; g < accept->n_groups; ++g)
-    if (accept->group_sizes[g] < 1) return fail(ctx, HEISD_EINVAL, "step: group_sizes[%d] < 1", g);
-  if (accept->tok_threshold < 0 || accept->seq_budget < 0)
-    return fail(ctx, HEISD_EINVAL, "step: negative acceptance threshold");
-  if (accept->mode != 0 && accept->mode != 1) return fail(ctx, HEISD_EINVAL, "step: mode %d", accept->mode);
-
-  hipStream_t st = static_cast<hipStream_t>(stream);
   const int M = batch * K, dm = d.d_model, F = d.d_ffn, H = d.n_heads, HD = d.head_dim, cap = d.kv_capacity;
-  float *logits = bin_logits ? bin_logits : ctx->logits;
-  int32_t *tbins = target_bins ? target_bins : ctx->tbins;
-  (void)hipGetLastError();
-
-  const bool prof = ctx->prof_on && ctx->prof_steps < HEISD_PROFILE_MAX_STEPS;
-  if (prof) ctx->prof_steps++;
   {
     ProfScope ps(ctx, HEISD_KC_EMBED, st, prof);
   embed_rows<<<dim3(M), dim3(256), 0, st>>>(draft_tokens, static_cast<const uint16_t *>(d.tok_emb), d.vocab, dm,
@@ -367,6 +473,46 @@ extern "C" int heisd_verify_step(heisd_verify_ctx *ctx, const heisd_kv_desc *kv,
     g.out = logits; g.ldo = d.n_bins; g.resid = nullptr;
     ProfScope ps(ctx, HEISD_KC_LMHEAD, st, prof);
     gemm_launch(g, M, EPI_STORE, st);
+  }
+}
+
+// ---- one verify step ----------------------------------------------------------------------
+
+extern "C" int heisd_verify_step(heisd_verify_ctx *ctx, const heisd_kv_desc *kv, const int32_t *draft_tokens,
+                                 int32_t K, int32_t batch, const heisd_accept_desc *accept,
+                                 const uint8_t *skip_mask, int32_t *accepted_len, int32_t *next_token,
+                                 int32_t *target_bins, float *bin_logits, void *stream) {
+  if (!ctx) return HEISD_EINVAL;
+  if (!kv || !kv->k_cache || !kv->v_cache || !kv->prefix_len || !kv->first_pred || !draft_tokens || !accept ||
+      !accepted_len || !next_token)
+    return fail(ctx, HEISD_EINVAL, "step: NULL required pointer");
+  const heisd_model_desc &d = ctx->d;
+  if (K < 1 || batch < 1 || K > d.max_k || batch > d.max_batch || K > d.kv_capacity)
+    return fail(ctx, HEISD_EINVAL, "step: K=%d batch=%d outside [1,%d] x [1,%d] (kv_capacity %d)", K, batch,
+                d.max_k, d.max_batch, d.kv_capacity);
+  if (accept->n_groups < 1 || accept->n_groups > HEISD_MAX_GROUPS)
+    return fail(ctx, HEISD_EINVAL, "step: n_groups=%d outside [1,%d]", accept->n_groups, HEISD_MAX_GROUPS);
+  for (int g = 0; g < accept->n_groups; ++g)
+    if (accept->group_sizes[g] < 1) return fail(ctx, HEISD_EINVAL, "step: group_sizes[%d] < 1", g);
+  if (accept->tok_threshold < 0 || accept->seq_budget < 0)
+    return fail(ctx, HEISD_EINVAL, "step: negative acceptance threshold");
+  if (accept->mode != 0 && accept->mode != 1) return fail(ctx, HEISD_EINVAL, "step: mode %d", accept->mode);
+
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  const int M = batch * K, dm = d.d_model, F = d.d_ffn, H = d.n_heads, HD = d.head_dim, cap = d.kv_capacity;
+  float *logits = bin_logits ? bin_logits : ctx->logits;
+  int32_t *tbins = target_bins ? target_bins : ctx->tbins;
+  (void)hipGetLastError();
+
+  const bool prof = ctx->prof_on && ctx->prof_steps < HEISD_PROFILE_MAX_STEPS;
+  if (prof) ctx->prof_steps++;
+  const bool use_fast = ctx->fast_ok && M <= 8 && ctx->path != HEISD_PATH_GENERIC;
+  if (ctx->path == HEISD_PATH_FAST && !use_fast)
+    return fail(ctx, HEISD_EUNSUPPORTED, "step: the fast path needs batch*K <= 8 (got %d)", M);
+  if (use_fast) {
+    fast_forward(ctx, kv, draft_tokens, K, batch, skip_mask, logits, st, prof);
+  } else {
+    generic_forward(ctx, kv, draft_tokens, K, batch, skip_mask, logits, st, prof);
   }
   AcceptArgs aa{};
   aa.logits = logits; aa.logits_rw = logits; aa.draft = draft_tokens; aa.first_pred = kv->first_pred;

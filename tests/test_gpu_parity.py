@@ -13,12 +13,16 @@ pytestmark = pytest.mark.gpu
 torch = pytest.importorskip("torch")
 
 
+MID = synth.ModelShape(n_layers=3, d_model=512, n_heads=4, head_dim=128, d_ffn=1376, vocab=2048)
+SMALL64 = synth.ModelShape(n_layers=2, d_model=256, n_heads=4, head_dim=64, d_ffn=688, vocab=1024)
+
+
 def _need_gpu():
     if not torch.cuda.is_available():
         pytest.skip("no GPU")
 
 
-def run_case(wl, plen_override=None, skip=None, rule=None, drafts_mode="auto", check_cache=True):
+def run_case(wl, plen_override=None, skip=None, rule=None, drafts_mode="auto", check_cache=True, path=0):
     from gpu_harness import run_gpu_step, compare_with_oracle
     _need_gpu()
     sh = wl.shape
@@ -36,19 +40,29 @@ def run_case(wl, plen_override=None, skip=None, rule=None, drafts_mode="auto", c
         bins = synth.make_drafts_uniform(wl)
     drafts = (sh.bin_base + bins).astype(np.int32)
     ref = oracle.verify_step(om, kb, vb, plen, first, drafts, rule, skip)
-    got = run_gpu_step(sh, weights, kb, vb, plen, first, drafts, rule, skip)
+    got = run_gpu_step(sh, weights, kb, vb, plen, first, drafts, rule, skip, path=path)
     stats = compare_with_oracle(got, ref, drafts, rule, sh, kb, vb, plen, skip)
-    print(wl.name, stats, "accepted", got["accepted_len"].tolist())
+    print(wl.name, "path", path, stats, "accepted", got["accepted_len"].tolist())
     return got, ref, stats
 
 
-def test_c0_tiny_config():
-    got, ref, stats = run_case(synth.WORKLOADS["C0"])
+@pytest.mark.parametrize("path", [0, 1, 2])
+def test_c0_tiny_config(path):
+    """C0 through the automatic choice, the any-M path and the <=8-row path."""
+    got, ref, stats = run_case(synth.WORKLOADS["C0"], path=path)
     assert stats["max_logit_err_over_range"] < 3e-2
 
 
-MID = synth.ModelShape(n_layers=3, d_model=512, n_heads=4, head_dim=128, d_ffn=1376, vocab=2048)
-SMALL64 = synth.ModelShape(n_layers=2, d_model=256, n_heads=4, head_dim=64, d_ffn=688, vocab=1024)
+@pytest.mark.parametrize("path", [1, 2])
+@pytest.mark.parametrize("shape_name,B,K,skip", [("mid", 1, 7, None), ("mid", 2, 4, [0, 1]), ("mid", 1, 8, None),
+                                                 ("s64", 2, 3, None), ("s64", 1, 5, None)])
+def test_small_row_counts_on_both_paths(path, shape_name, B, K, skip):
+    """M <= 8 rows (one or two episodes) on a multi-tile shape, forced through each kernel path."""
+    shape = MID if shape_name == "mid" else SMALL64
+    wl = synth.Workload("%s_%dx%d" % (shape_name, B, K), shape, 30, 11, shape.bin_base, batch=B, K=K,
+                        draft=("geometric", 0.5), seed=B * 7 + K)
+    run_case(wl, skip=None if skip is None else np.array(skip, np.uint8), path=path,
+             plen_override=[41, 17][:B] if B > 1 else None)
 
 
 def test_mid_hd128_ragged_prefixes_geometric_drafts():
