@@ -26,8 +26,7 @@ struct heisd_verify_ctx {
   float2 *rope;
   float *x, *qkv, *attn_o, *act, *logits;
   int32_t *tbins;
-  uint16_t *pl_x, *pl_attn, *pl_act;   // fast path: activation planes [16][d], [16][d], [16][d_ffn]
-  float *ssq;                          // fast path: [8][d/16] partial sums of squares
+  unsigned char *fscr;                 // fast path: per-layer exchange records (see FastScratch)
   int n_cu = 256;
   int path = 0;                        // HEISD_PATH_*
   bool fast_ok = false;                // the shape fits the fast kernels
@@ -73,7 +72,25 @@ static int fail(heisd_verify_ctx *ctx, int code, const char *fmt, ...) {
 static size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
 
 struct WsLayout {
-  size_t rope, x, qkv, attn_o, act, logits, tbins, pl_x, pl_attn, pl_act, ssq, total;
+  size_t rope, x, qkv, attn_o, act, logits, tbins, fscr, fscr_bytes, total;
+};
+
+// Per-layer exchange buffers of the fast path.  Every buffer is written once per step, so an
+// address is never re-read with stale contents inside one launch.
+struct FastScratch {
+  size_t rec_x_a, ssq_a, qkv, rec_attn, rec_x_b, ssq_b, rec_act, stride;
+  explicit FastScratch(const heisd_model_desc *d) {
+    const size_t nt = d->d_model / 16, nf = d->d_ffn / 16;
+    size_t off = 0;
+    rec_x_a = off;  off += nt * 512;
+    ssq_a = off;    off += nt * kSsqStride * sizeof(float);
+    qkv = off;      off += 3 * nt * 512;
+    rec_attn = off; off += nt * 512;
+    rec_x_b = off;  off += nt * 512;
+    ssq_b = off;    off += nt * kSsqStride * sizeof(float);
+    rec_act = off;  off += nf * 512;
+    stride = align256(off);
+  }
 };
 
 static bool shape_ok(const heisd_model_desc *d) {
@@ -94,10 +111,9 @@ static WsLayout ws_layout(const heisd_model_desc *d) {
   w.act = off;    off += align256(M * d->d_ffn * sizeof(float));
   w.logits = off; off += align256(M * d->n_bins * sizeof(float));
   w.tbins = off;  off += align256((size_t)d->max_batch * (d->max_k + 1) * sizeof(int32_t));
-  w.pl_x = off;   off += align256((size_t)16 * d->d_model * sizeof(uint16_t));
-  w.pl_attn = off; off += align256((size_t)16 * d->d_model * sizeof(uint16_t));
-  w.pl_act = off; off += align256((size_t)16 * d->d_ffn * sizeof(uint16_t));
-  w.ssq = off;    off += align256((size_t)8 * (d->d_model / 16 + 1) * sizeof(float));
+  w.fscr = off;
+  w.fscr_bytes = FastScratch(d).stride * (size_t)(d->n_layers + 1);
+  off += w.fscr_bytes;
   w.total = off;
   return w;
 }
@@ -160,14 +176,13 @@ static void gemm_launch(GemmArgs a, int M, int epi, hipStream_t st) {
 static hipError_t fast_prepare(int hd, int cap) {
   hipError_t e;
   const int lds = (int)kFastLds;
-  if ((e = hipFuncSetAttribute(reinterpret_cast<const void *>(&fast_gemm_kernel<FEPI_STORE, 1>),
-                               hipFuncAttributeMaxDynamicSharedMemorySize, lds)) != hipSuccess) return e;
-  if ((e = hipFuncSetAttribute(reinterpret_cast<const void *>(&fast_gemm_kernel<FEPI_RESID_NORM, 1>),
-                               hipFuncAttributeMaxDynamicSharedMemorySize, lds)) != hipSuccess) return e;
-  if ((e = hipFuncSetAttribute(reinterpret_cast<const void *>(&fast_gemm_kernel<FEPI_RESID_NORM, 3>),
-                               hipFuncAttributeMaxDynamicSharedMemorySize, lds)) != hipSuccess) return e;
-  if ((e = hipFuncSetAttribute(reinterpret_cast<const void *>(&fast_gemm_kernel<FEPI_SWIGLU, 1>),
-                               hipFuncAttributeMaxDynamicSharedMemorySize, lds)) != hipSuccess) return e;
+  const void *fns[] = {reinterpret_cast<const void *>(&fast_gemm_kernel<FEPI_STORE_REC>),
+                       reinterpret_cast<const void *>(&fast_gemm_kernel<FEPI_STORE_ROWS>),
+                       reinterpret_cast<const void *>(&fast_gemm_kernel<FEPI_RESID_NORM>),
+                       reinterpret_cast<const void *>(&fast_gemm_kernel<FEPI_SWIGLU>),
+                       reinterpret_cast<const void *>(&fast_gemm_stream_kernel<FEPI_RESID_NORM>)};
+  for (const void *f : fns)
+    if ((e = hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, lds)) != hipSuccess) return e;
   const int alds = (int)fast_attn_lds(hd, cap);
   if (hd == 128)
     e = hipFuncSetAttribute(reinterpret_cast<const void *>(&fast_attn_kernel<128>),
@@ -178,76 +193,123 @@ static hipError_t fast_prepare(int hd, int cap) {
   return e;
 }
 
+// GEMM descriptors of layer l (and of the LM head for l == n_layers), shared by both fast drivers.
+struct FastLayerDescs {
+  FastGemm qkv, oproj, gateup, down;
+  FastAttn attn;
+};
+
+static FastGemm fast_lm_desc(const heisd_verify_ctx *ctx, int M, float *logits) {
+  const heisd_model_desc &d = ctx->d;
+  const FastScratch fs(&d);
+  unsigned char *base = ctx->fscr + fs.stride * (size_t)d.n_layers;
+  FastGemm g{};
+  g.w[0] = static_cast<const uint16_t *>(d.lm_head) + (size_t)d.bin_token_base * d.d_model;
+  g.seg_tiles = d.n_bins / 16; g.n_units = d.n_bins / 16; g.Kd = d.d_model;
+  g.b = reinterpret_cast<const uint16_t *>(base + fs.rec_x_a);
+  g.ssq = reinterpret_cast<const float *>(base + fs.ssq_a);
+  g.n_ssq = d.d_model / 16; g.eps = d.rms_eps; g.M = M; g.out = logits; g.ldo = d.n_bins;
+  return g;
+}
+
+static FastLayerDescs fast_layer_descs(const heisd_verify_ctx *ctx, const heisd_kv_desc *kv, int l, int K, int batch,
+                                       const uint8_t *skip_mask) {
+  const heisd_model_desc &d = ctx->d;
+  const int M = batch * K, dm = d.d_model, F = d.d_ffn, H = d.n_heads, HD = d.head_dim, cap = d.kv_capacity;
+  const FastScratch fs(&d);
+  unsigned char *base = ctx->fscr + fs.stride * (size_t)l;
+  unsigned char *nbase = ctx->fscr + fs.stride * (size_t)(l + 1);
+  FastLayerDescs L{};
+  FastGemm &q = L.qkv;
+  q.w[0] = static_cast<const uint16_t *>(ctx->wq[l]);
+  q.w[1] = static_cast<const uint16_t *>(ctx->wk[l]);
+  q.w[2] = static_cast<const uint16_t *>(ctx->wv[l]);
+  q.seg_tiles = dm / 16; q.n_units = 3 * dm / 16; q.Kd = dm;
+  q.b = reinterpret_cast<const uint16_t *>(base + fs.rec_x_a);
+  q.ssq = reinterpret_cast<const float *>(base + fs.ssq_a);
+  q.n_ssq = dm / 16; q.eps = d.rms_eps; q.M = M;
+  q.out = reinterpret_cast<float *>(base + fs.qkv);
+  FastAttn &a = L.attn;
+  const size_t layer_stride = (size_t)batch * H * cap * HD;
+  a.qkv = reinterpret_cast<const float *>(base + fs.qkv);
+  a.k_cache = static_cast<uint16_t *>(kv->k_cache) + (size_t)l * layer_stride;
+  a.v_cache = static_cast<uint16_t *>(kv->v_cache) + (size_t)l * layer_stride;
+  a.prefix_len = kv->prefix_len; a.skip = skip_mask; a.rope = ctx->rope;
+  a.o_planes = reinterpret_cast<uint16_t *>(base + fs.rec_attn);
+  a.K = K; a.H = H; a.cap = cap; a.d = dm; a.batch = batch; a.scale = 1.0f / std::sqrt((float)HD);
+  FastGemm &o = L.oproj;
+  o.w[0] = static_cast<const uint16_t *>(ctx->wo[l]);
+  o.seg_tiles = dm / 16; o.n_units = dm / 16; o.Kd = dm;
+  o.b = reinterpret_cast<const uint16_t *>(base + fs.rec_attn);
+  o.ssq = nullptr; o.M = M; o.out = ctx->x; o.ldo = dm; o.next_gain = ctx->ffn_norm[l];
+  o.o_planes = reinterpret_cast<uint16_t *>(base + fs.rec_x_b);
+  o.ssq_out = reinterpret_cast<float *>(base + fs.ssq_b);
+  FastGemm &g = L.gateup;
+  g.w[0] = static_cast<const uint16_t *>(ctx->w_gate[l]);
+  g.w[1] = static_cast<const uint16_t *>(ctx->w_up[l]);
+  g.seg_tiles = F / 16; g.n_units = F / 16; g.Kd = dm;
+  g.b = reinterpret_cast<const uint16_t *>(base + fs.rec_x_b);
+  g.ssq = reinterpret_cast<const float *>(base + fs.ssq_b);
+  g.n_ssq = dm / 16; g.eps = d.rms_eps; g.M = M;
+  g.o_planes = reinterpret_cast<uint16_t *>(base + fs.rec_act);
+  FastGemm &w = L.down;
+  w.w[0] = static_cast<const uint16_t *>(ctx->w_down[l]);
+  w.seg_tiles = dm / 16; w.n_units = dm / 16; w.Kd = F;
+  w.b = reinterpret_cast<const uint16_t *>(base + fs.rec_act);
+  w.ssq = nullptr; w.M = M; w.out = ctx->x; w.ldo = dm;
+  w.next_gain = (l + 1 < d.n_layers) ? ctx->attn_norm[l + 1] : d.final_norm;
+  w.o_planes = reinterpret_cast<uint16_t *>(nbase + fs.rec_x_a);
+  w.ssq_out = reinterpret_cast<float *>(nbase + fs.ssq_a);
+  return L;
+}
+
 // The decoder forward for M <= 8 rows, one launch per phase; leaves the bin logits in `logits`.
 static void fast_forward(heisd_verify_ctx *ctx, const heisd_kv_desc *kv, const int32_t *draft_tokens, int K,
                          int batch, const uint8_t *skip_mask, float *logits, hipStream_t st, bool prof) {
   const heisd_model_desc &d = ctx->d;
-  const int M = batch * K, dm = d.d_model, F = d.d_ffn, H = d.n_heads, HD = d.head_dim, cap = d.kv_capacity;
+  const int M = batch * K, dm = d.d_model, H = d.n_heads, HD = d.head_dim, cap = d.kv_capacity;
   const int ncu = ctx->n_cu;
+  const FastScratch fs(&d);
   auto grid_for = [&](int units) { return dim3(units < ncu ? units : ncu); };
   {
     ProfScope ps(ctx, HEISD_KC_EMBED, st, prof);
-    fast_embed<<<dim3(dm / 16), dim3(128), 0, st>>>(draft_tokens, static_cast<const uint16_t *>(d.tok_emb), d.vocab,
-                                                    dm, M, ctx->attn_norm[0], ctx->x, ctx->pl_x, ctx->ssq);
+    fast_embed_kernel<<<dim3(dm / 16), dim3(64), 0, st>>>(
+        draft_tokens, static_cast<const uint16_t *>(d.tok_emb), d.vocab, dm, M, ctx->attn_norm[0], ctx->x,
+        reinterpret_cast<uint16_t *>(ctx->fscr + fs.rec_x_a), reinterpret_cast<float *>(ctx->fscr + fs.ssq_a));
   }
-  const size_t layer_stride = (size_t)batch * H * cap * HD;
   const size_t alds = fast_attn_lds(HD, cap);
+  const bool stream_down = d.d_ffn > kFastWaves * kKS * 32;
   for (int l = 0; l < d.n_layers; ++l) {
-    FastGemm g{};
-    g.w[0] = static_cast<const uint16_t *>(ctx->wq[l]);
-    g.w[1] = static_cast<const uint16_t *>(ctx->wk[l]);
-    g.w[2] = static_cast<const uint16_t *>(ctx->wv[l]);
-    g.seg_tiles = dm / 16; g.n_units = 3 * dm / 16; g.Kd = dm; g.b = ctx->pl_x; g.ssq = ctx->ssq;
-    g.n_ssq = dm / 16; g.eps = d.rms_eps; g.M = M; g.out = ctx->qkv; g.ldo = 3 * dm;
+    const FastLayerDescs L = fast_layer_descs(ctx, kv, l, K, batch, skip_mask);
     {
       ProfScope ps(ctx, HEISD_KC_QKV, st, prof);
-      fast_gemm_kernel<FEPI_STORE, 1><<<grid_for(g.n_units), dim3(kFastThreads), kFastLds, st>>>(g);
+      fast_gemm_kernel<FEPI_STORE_REC><<<grid_for(L.qkv.n_units), dim3(kFastThreads), kFastLds, st>>>(L.qkv);
     }
-    FastAttn a{};
-    a.qkv = ctx->qkv;
-    a.k_cache = static_cast<uint16_t *>(kv->k_cache) + (size_t)l * layer_stride;
-    a.v_cache = static_cast<uint16_t *>(kv->v_cache) + (size_t)l * layer_stride;
-    a.prefix_len = kv->prefix_len; a.skip = skip_mask; a.rope = ctx->rope; a.o_planes = ctx->pl_attn;
-    a.K = K; a.H = H; a.cap = cap; a.d = dm; a.batch = batch; a.scale = 1.0f / std::sqrt((float)HD);
     {
       ProfScope ps(ctx, HEISD_KC_ATTN, st, prof);
-      if (HD == 128) fast_attn_kernel<128><<<dim3(H, batch), dim3(kFastThreads), alds, st>>>(a);
-      else fast_attn_kernel<64><<<dim3(H, batch), dim3(kFastThreads), alds, st>>>(a);
+      if (HD == 128) fast_attn_kernel<128><<<dim3(H, batch), dim3(kFastThreads), alds, st>>>(L.attn);
+      else fast_attn_kernel<64><<<dim3(H, batch), dim3(kFastThreads), alds, st>>>(L.attn);
     }
-    g = FastGemm{};
-    g.w[0] = static_cast<const uint16_t *>(ctx->wo[l]);
-    g.seg_tiles = dm / 16; g.n_units = dm / 16; g.Kd = dm; g.b = ctx->pl_attn; g.ssq = nullptr; g.M = M;
-    g.out = ctx->x; g.ldo = dm; g.next_gain = ctx->ffn_norm[l]; g.o_planes = ctx->pl_x; g.ssq_out = ctx->ssq;
     {
       ProfScope ps(ctx, HEISD_KC_OPROJ, st, prof);
-      fast_gemm_kernel<FEPI_RESID_NORM, 1><<<grid_for(g.n_units), dim3(kFastThreads), kFastLds, st>>>(g);
+      fast_gemm_kernel<FEPI_RESID_NORM><<<grid_for(L.oproj.n_units), dim3(kFastThreads), kFastLds, st>>>(L.oproj);
     }
-    g = FastGemm{};
-    g.w[0] = static_cast<const uint16_t *>(ctx->w_gate[l]);
-    g.w[1] = static_cast<const uint16_t *>(ctx->w_up[l]);
-    g.seg_tiles = F / 16; g.n_units = F / 16; g.Kd = dm; g.b = ctx->pl_x; g.ssq = ctx->ssq; g.n_ssq = dm / 16;
-    g.eps = d.rms_eps; g.M = M; g.o_planes = ctx->pl_act; g.ldo = F;
     {
       ProfScope ps(ctx, HEISD_KC_GATEUP, st, prof);
-      fast_gemm_kernel<FEPI_SWIGLU, 1><<<grid_for(g.n_units), dim3(kFastThreads), kFastLds, st>>>(g);
+      fast_gemm_kernel<FEPI_SWIGLU><<<grid_for(L.gateup.n_units), dim3(kFastThreads), kFastLds, st>>>(L.gateup);
     }
-    g = FastGemm{};
-    g.w[0] = static_cast<const uint16_t *>(ctx->w_down[l]);
-    g.seg_tiles = dm / 16; g.n_units = dm / 16; g.Kd = F; g.b = ctx->pl_act; g.ssq = nullptr; g.M = M;
-    g.out = ctx->x; g.ldo = dm; g.next_gain = (l + 1 < d.n_layers) ? ctx->attn_norm[l + 1] : d.final_norm;
-    g.o_planes = ctx->pl_x; g.ssq_out = ctx->ssq;
     {
       ProfScope ps(ctx, HEISD_KC_DOWN, st, prof);
-      fast_gemm_kernel<FEPI_RESID_NORM, 3><<<grid_for(g.n_units), dim3(kFastThreads), kFastLds, st>>>(g);
+      if (stream_down)
+        fast_gemm_stream_kernel<FEPI_RESID_NORM><<<grid_for(L.down.n_units), dim3(kFastThreads), kFastLds, st>>>(L.down);
+      else
+        fast_gemm_kernel<FEPI_RESID_NORM><<<grid_for(L.down.n_units), dim3(kFastThreads), kFastLds, st>>>(L.down);
     }
   }
-  FastGemm g{};
-  g.w[0] = static_cast<const uint16_t *>(d.lm_head) + (size_t)d.bin_token_base * dm;
-  g.seg_tiles = d.n_bins / 16; g.n_units = d.n_bins / 16; g.Kd = dm; g.b = ctx->pl_x; g.ssq = ctx->ssq;
-  g.n_ssq = dm / 16; g.eps = d.rms_eps; g.M = M; g.out = logits; g.ldo = d.n_bins;
+  const FastGemm g = fast_lm_desc(ctx, M, logits);
   {
     ProfScope ps(ctx, HEISD_KC_LMHEAD, st, prof);
-    fast_gemm_kernel<FEPI_STORE, 1><<<grid_for(g.n_units), dim3(kFastThreads), kFastLds, st>>>(g);
+    fast_gemm_kernel<FEPI_STORE_ROWS><<<grid_for(g.n_units), dim3(kFastThreads), kFastLds, st>>>(g);
   }
 }
 
@@ -301,11 +363,8 @@ extern "C" int heisd_verify_init(const heisd_model_desc *desc, heisd_verify_ctx 
   c->act = reinterpret_cast<float *>(base + w.act);
   c->logits = reinterpret_cast<float *>(base + w.logits);
   c->tbins = reinterpret_cast<int32_t *>(base + w.tbins);
-  c->pl_x = reinterpret_cast<uint16_t *>(base + w.pl_x);
-  c->pl_attn = reinterpret_cast<uint16_t *>(base + w.pl_attn);
-  c->pl_act = reinterpret_cast<uint16_t *>(base + w.pl_act);
-  c->ssq = reinterpret_cast<float *>(base + w.ssq);
-  c->fast_ok = desc->d_model <= kChunkK && desc->d_ffn <= 3 * kChunkK;
+  c->fscr = base + w.fscr;
+  c->fast_ok = desc->d_model <= kFastWaves * kKS * 32;
   c->path = HEISD_PATH_AUTO;
 
   // rotary table: angle = position * rope_base^(-2i/head_dim), computed in double on the host
@@ -317,7 +376,7 @@ extern "C" int heisd_verify_init(const heisd_model_desc *desc, heisd_verify_ctx 
       tab[(size_t)p * half + i] = make_float2((float)std::cos(ang), (float)std::sin(ang));
     }
   hipError_t e = hipMemcpy(c->rope, tab.data(), tab.size() * sizeof(float2), hipMemcpyHostToDevice);
-  if (e == hipSuccess) e = hipMemset(base + w.pl_x, 0, w.total - w.pl_x);   // planes start as zeros
+  if (e == hipSuccess) e = hipMemset(base + w.fscr, 0, w.fscr_bytes);   // records start as zeros
   if (e == hipSuccess) {
     int dev = 0;
     hipDeviceProp_t prop;
