@@ -40,6 +40,7 @@ def algorithmic_bytes(sh, batch, K, P, active=None):
     }
     total = L * (per_class["qkv"] + per_class["oproj"] + per_class["gateup"] + per_class["down"] +
                  per_class["attn"]) + per_class["lmhead"] + per_class["embed"]
+    per_class["persist"] = total          # the persistent kernel is the whole decoder forward
     return total, per_class
 
 

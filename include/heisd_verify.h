@@ -157,7 +157,7 @@ int heisd_verify_step(heisd_verify_ctx *ctx, const heisd_kv_desc *kv, const int3
  * Enabling creates events (host objects); disabling destroys them.  At most
  * HEISD_PROFILE_MAX_STEPS steps are kept between two reads; later steps are not recorded.
  */
-#define HEISD_N_KERNEL_CLASSES 8
+#define HEISD_N_KERNEL_CLASSES 9
 #define HEISD_KC_EMBED 0
 #define HEISD_KC_QKV 1      /* RMSNorm + QKV projection                 */
 #define HEISD_KC_ATTN 2     /* RoPE + KV-append + verify attention      */
@@ -166,6 +166,7 @@ int heisd_verify_step(heisd_verify_ctx *ctx, const heisd_kv_desc *kv, const int3
 #define HEISD_KC_DOWN 5     /* down projection + residual               */
 #define HEISD_KC_LMHEAD 6   /* final RMSNorm + 256-bin LM-head slice    */
 #define HEISD_KC_ACCEPT 7   /* argmax + relaxed acceptance scan         */
+#define HEISD_KC_PERSIST 8  /* whole decoder forward in one persistent kernel (embedding .. LM-head slice) */
 #define HEISD_PROFILE_MAX_STEPS 64
 int heisd_verify_profile_enable(heisd_verify_ctx *ctx, int enable);
 int heisd_verify_profile_read(heisd_verify_ctx *ctx, double *ms, int64_t *launches);
@@ -173,12 +174,21 @@ int heisd_verify_profile_read(heisd_verify_ctx *ctx, double *ms, int64_t *launch
 /*
  * Kernel-path selection, for tests and measurement.  AUTO (default) picks the fastest path
  * that covers the call; GENERIC forces the any-M path (LDS-staged activations, one launch
- * per phase); FAST forces the batch*K <= 8 path and makes a larger step fail with
+ * per phase); FAST forces the batch*K <= 8 kernels with one launch per phase; PERSIST forces
+ * the batch*K <= 8 persistent kernel (the whole decoder forward in one launch, one workgroup
+ * per compute unit, grid barriers inside).  FAST and PERSIST make a larger step fail with
  * EUNSUPPORTED.  Results of the paths agree to fp32 rounding.
+ *
+ * The persistent kernel spins at its grid barriers with a bound; if the bound expires (the
+ * GPU was shared with work that kept some of its workgroups from running) it raises a device
+ * error word and ends.  heisd_verify_check synchronises the device and returns EHIP if that
+ * word is set (and clears it), else OK.
  */
 #define HEISD_PATH_AUTO 0
 #define HEISD_PATH_GENERIC 1
 #define HEISD_PATH_FAST 2
+#define HEISD_PATH_PERSIST 3
+int heisd_verify_check(heisd_verify_ctx *ctx);
 int heisd_verify_set_path(heisd_verify_ctx *ctx, int path);
 
 /* Release the context (not the workspace, weights or caches: those are the caller's). NULL ok. */

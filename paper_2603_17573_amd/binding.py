@@ -66,6 +66,8 @@ def load():
         lib.heisd_verify_profile_read.restype = ctypes.c_int
         lib.heisd_verify_set_path.argtypes = [c_void_p, ctypes.c_int]
         lib.heisd_verify_set_path.restype = ctypes.c_int
+        lib.heisd_verify_check.argtypes = [c_void_p]
+        lib.heisd_verify_check.restype = ctypes.c_int
         lib.heisd_last_error.argtypes = [c_void_p]
         lib.heisd_last_error.restype = c_char_p
         _lib = lib
@@ -99,14 +101,18 @@ def heisd_last_error(ctx=None) -> str:
     return load().heisd_last_error(ctx).decode()
 
 
-HEISD_PATH_AUTO, HEISD_PATH_GENERIC, HEISD_PATH_FAST = 0, 1, 2
+HEISD_PATH_AUTO, HEISD_PATH_GENERIC, HEISD_PATH_FAST, HEISD_PATH_PERSIST = 0, 1, 2, 3
+
+
+def heisd_verify_check(ctx) -> int:
+    return load().heisd_verify_check(ctx)
 
 
 def heisd_verify_set_path(ctx, path: int) -> int:
     return load().heisd_verify_set_path(ctx, path)
 
 
-KERNEL_CLASSES = ("embed", "qkv", "attn", "oproj", "gateup", "down", "lmhead", "accept")
+KERNEL_CLASSES = ("embed", "qkv", "attn", "oproj", "gateup", "down", "lmhead", "accept", "persist")
 
 
 def heisd_verify_profile_enable(ctx, enable: bool) -> int:

@@ -13,6 +13,7 @@
 
 #include "heisd_attn.h"
 #include "heisd_fast.h"
+#include "heisd_persist.h"
 #include "heisd_gemm.h"
 #include "heisd_misc.h"
 
@@ -27,6 +28,11 @@ struct heisd_verify_ctx {
   float *x, *qkv, *attn_o, *act, *logits;
   int32_t *tbins;
   unsigned char *fscr;                 // fast path: per-layer exchange records (see FastScratch)
+  Phase *prog;                         // persistent kernel: the phase program in device memory
+  int n_phases = 0;
+  unsigned *flags, *dev_err;           // persistent kernel: barrier flags [n_cu][16], error word
+  unsigned epoch = 0;                  // last barrier epoch handed out
+  bool persist_ok = false;
   int n_cu = 256;
   int path = 0;                        // HEISD_PATH_*
   bool fast_ok = false;                // the shape fits the fast kernels
@@ -72,7 +78,7 @@ static int fail(heisd_verify_ctx *ctx, int code, const char *fmt, ...) {
 static size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
 
 struct WsLayout {
-  size_t rope, x, qkv, attn_o, act, logits, tbins, fscr, fscr_bytes, total;
+  size_t rope, x, qkv, attn_o, act, logits, tbins, fscr, fscr_bytes, players, flags, total;
 };
 
 // Per-layer exchange buffers of the fast path.  Every buffer is written once per step, so an
@@ -80,15 +86,17 @@ struct WsLayout {
 struct FastScratch {
   size_t rec_x_a, ssq_a, qkv, rec_attn, rec_x_b, ssq_b, rec_act, stride;
   explicit FastScratch(const heisd_model_desc *d) {
-    const size_t nt = d->d_model / 16, nf = d->d_ffn / 16;
+    const size_t nt = d->d_model / 16;
+    // plane buffers end with all-zero records that out-of-range k-steps are pointed at
+    const size_t pd = (size_t)fast_plane_records(d->d_model), pf = (size_t)fast_plane_records(d->d_ffn);
     size_t off = 0;
-    rec_x_a = off;  off += nt * 512;
+    rec_x_a = off;  off += pd * 512;
     ssq_a = off;    off += nt * kSsqStride * sizeof(float);
     qkv = off;      off += 3 * nt * 512;
-    rec_attn = off; off += nt * 512;
-    rec_x_b = off;  off += nt * 512;
+    rec_attn = off; off += pd * 512;
+    rec_x_b = off;  off += pd * 512;
     ssq_b = off;    off += nt * kSsqStride * sizeof(float);
-    rec_act = off;  off += nf * 512;
+    rec_act = off;  off += pf * 512;
     stride = align256(off);
   }
 };
@@ -114,6 +122,8 @@ static WsLayout ws_layout(const heisd_model_desc *d) {
   w.fscr = off;
   w.fscr_bytes = FastScratch(d).stride * (size_t)(d->n_layers + 1);
   off += w.fscr_bytes;
+  w.players = off; off += align256((size_t)(5 * d->n_layers + 2) * sizeof(Phase));
+  w.flags = off;   off += align256((size_t)(1024 + 1) * kFlagStride * sizeof(unsigned));
   w.total = off;
   return w;
 }
@@ -176,11 +186,8 @@ static void gemm_launch(GemmArgs a, int M, int epi, hipStream_t st) {
 static hipError_t fast_prepare(int hd, int cap) {
   hipError_t e;
   const int lds = (int)kFastLds;
-  const void *fns[] = {reinterpret_cast<const void *>(&fast_gemm_kernel<FEPI_STORE_REC>),
-                       reinterpret_cast<const void *>(&fast_gemm_kernel<FEPI_STORE_ROWS>),
-                       reinterpret_cast<const void *>(&fast_gemm_kernel<FEPI_RESID_NORM>),
-                       reinterpret_cast<const void *>(&fast_gemm_kernel<FEPI_SWIGLU>),
-                       reinterpret_cast<const void *>(&fast_gemm_stream_kernel<FEPI_RESID_NORM>)};
+  const void *fns[] = {reinterpret_cast<const void *>(&fast_gemm_kernel),
+                       reinterpret_cast<const void *>(&fast_gemm_stream_kernel)};
   for (const void *f : fns)
     if ((e = hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, lds)) != hipSuccess) return e;
   const int alds = (int)fast_attn_lds(hd, cap);
@@ -204,6 +211,7 @@ static FastGemm fast_lm_desc(const heisd_verify_ctx *ctx, int M, float *logits) 
   const FastScratch fs(&d);
   unsigned char *base = ctx->fscr + fs.stride * (size_t)d.n_layers;
   FastGemm g{};
+  g.epi = FEPI_STORE_ROWS;
   g.w[0] = static_cast<const uint16_t *>(d.lm_head) + (size_t)d.bin_token_base * d.d_model;
   g.seg_tiles = d.n_bins / 16; g.n_units = d.n_bins / 16; g.Kd = d.d_model;
   g.b = reinterpret_cast<const uint16_t *>(base + fs.rec_x_a);
@@ -221,6 +229,7 @@ static FastLayerDescs fast_layer_descs(const heisd_verify_ctx *ctx, const heisd_
   unsigned char *nbase = ctx->fscr + fs.stride * (size_t)(l + 1);
   FastLayerDescs L{};
   FastGemm &q = L.qkv;
+  q.epi = FEPI_STORE_REC;
   q.w[0] = static_cast<const uint16_t *>(ctx->wq[l]);
   q.w[1] = static_cast<const uint16_t *>(ctx->wk[l]);
   q.w[2] = static_cast<const uint16_t *>(ctx->wv[l]);
@@ -238,6 +247,7 @@ static FastLayerDescs fast_layer_descs(const heisd_verify_ctx *ctx, const heisd_
   a.o_planes = reinterpret_cast<uint16_t *>(base + fs.rec_attn);
   a.K = K; a.H = H; a.cap = cap; a.d = dm; a.batch = batch; a.scale = 1.0f / std::sqrt((float)HD);
   FastGemm &o = L.oproj;
+  o.epi = FEPI_RESID_NORM;
   o.w[0] = static_cast<const uint16_t *>(ctx->wo[l]);
   o.seg_tiles = dm / 16; o.n_units = dm / 16; o.Kd = dm;
   o.b = reinterpret_cast<const uint16_t *>(base + fs.rec_attn);
@@ -245,6 +255,7 @@ static FastLayerDescs fast_layer_descs(const heisd_verify_ctx *ctx, const heisd_
   o.o_planes = reinterpret_cast<uint16_t *>(base + fs.rec_x_b);
   o.ssq_out = reinterpret_cast<float *>(base + fs.ssq_b);
   FastGemm &g = L.gateup;
+  g.epi = FEPI_SWIGLU;
   g.w[0] = static_cast<const uint16_t *>(ctx->w_gate[l]);
   g.w[1] = static_cast<const uint16_t *>(ctx->w_up[l]);
   g.seg_tiles = F / 16; g.n_units = F / 16; g.Kd = dm;
@@ -253,6 +264,7 @@ static FastLayerDescs fast_layer_descs(const heisd_verify_ctx *ctx, const heisd_
   g.n_ssq = dm / 16; g.eps = d.rms_eps; g.M = M;
   g.o_planes = reinterpret_cast<uint16_t *>(base + fs.rec_act);
   FastGemm &w = L.down;
+  w.epi = FEPI_RESID_NORM;
   w.w[0] = static_cast<const uint16_t *>(ctx->w_down[l]);
   w.seg_tiles = dm / 16; w.n_units = dm / 16; w.Kd = F;
   w.b = reinterpret_cast<const uint16_t *>(base + fs.rec_act);
@@ -283,34 +295,111 @@ static void fast_forward(heisd_verify_ctx *ctx, const heisd_kv_desc *kv, const i
     const FastLayerDescs L = fast_layer_descs(ctx, kv, l, K, batch, skip_mask);
     {
       ProfScope ps(ctx, HEISD_KC_QKV, st, prof);
-      fast_gemm_kernel<FEPI_STORE_REC><<<grid_for(L.qkv.n_units), dim3(kFastThreads), kFastLds, st>>>(L.qkv);
+      fast_gemm_kernel<<<grid_for(L.qkv.n_units), dim3(kFastThreads), kFastLds, st>>>(L.qkv);
     }
     {
       ProfScope ps(ctx, HEISD_KC_ATTN, st, prof);
-      if (HD == 128) fast_attn_kernel<128><<<dim3(H, batch), dim3(kFastThreads), alds, st>>>(L.attn);
-      else fast_attn_kernel<64><<<dim3(H, batch), dim3(kFastThreads), alds, st>>>(L.attn);
+      if (HD == 128) fast_attn_kernel<128><<<dim3(H, batch * K), dim3(kFastThreads), alds, st>>>(L.attn);
+      else fast_attn_kernel<64><<<dim3(H, batch * K), dim3(kFastThreads), alds, st>>>(L.attn);
     }
     {
       ProfScope ps(ctx, HEISD_KC_OPROJ, st, prof);
-      fast_gemm_kernel<FEPI_RESID_NORM><<<grid_for(L.oproj.n_units), dim3(kFastThreads), kFastLds, st>>>(L.oproj);
+      fast_gemm_kernel<<<grid_for(L.oproj.n_units), dim3(kFastThreads), kFastLds, st>>>(L.oproj);
     }
     {
       ProfScope ps(ctx, HEISD_KC_GATEUP, st, prof);
-      fast_gemm_kernel<FEPI_SWIGLU><<<grid_for(L.gateup.n_units), dim3(kFastThreads), kFastLds, st>>>(L.gateup);
+      fast_gemm_kernel<<<grid_for(L.gateup.n_units), dim3(kFastThreads), kFastLds, st>>>(L.gateup);
     }
     {
       ProfScope ps(ctx, HEISD_KC_DOWN, st, prof);
       if (stream_down)
-        fast_gemm_stream_kernel<FEPI_RESID_NORM><<<grid_for(L.down.n_units), dim3(kFastThreads), kFastLds, st>>>(L.down);
+        fast_gemm_stream_kernel<<<grid_for(L.down.n_units), dim3(kFastThreads), kFastLds, st>>>(L.down);
       else
-        fast_gemm_kernel<FEPI_RESID_NORM><<<grid_for(L.down.n_units), dim3(kFastThreads), kFastLds, st>>>(L.down);
+        fast_gemm_kernel<<<grid_for(L.down.n_units), dim3(kFastThreads), kFastLds, st>>>(L.down);
     }
   }
   const FastGemm g = fast_lm_desc(ctx, M, logits);
   {
     ProfScope ps(ctx, HEISD_KC_LMHEAD, st, prof);
-    fast_gemm_kernel<FEPI_STORE_ROWS><<<grid_for(g.n_units), dim3(kFastThreads), kFastLds, st>>>(g);
+    fast_gemm_kernel<<<grid_for(g.n_units), dim3(kFastThreads), kFastLds, st>>>(g);
   }
+}
+
+// ---- persistent whole-step kernel ----------------------------------------------------------
+
+static const void *persist_pick(const heisd_verify_ctx *c) {
+  return c->d.head_dim == 128 ? reinterpret_cast<const void *>(&persist_forward<128>)
+                              : reinterpret_cast<const void *>(&persist_forward<64>);
+}
+
+static size_t persist_lds(const heisd_verify_ctx *c) {
+  const size_t a = fast_attn_lds(c->d.head_dim, c->d.kv_capacity);
+  return a > kFastLds ? a : kFastLds;
+}
+
+// The persistent kernel needs every workgroup resident at once: one per compute unit.
+static hipError_t persist_prepare(heisd_verify_ctx *c) {
+  c->persist_ok = false;
+  if (!c->fast_ok || c->n_cu > 1024) return hipSuccess;
+  const void *fn = persist_pick(c);
+  hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)persist_lds(c));
+  if (e != hipSuccess) return e;
+  int per_cu = 0;
+  e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, fn, kFastThreads, persist_lds(c));
+  if (e != hipSuccess) return e;
+  c->persist_ok = per_cu >= 1;
+  return hipSuccess;
+}
+
+// The phase program of one step (everything that does not change from step to step).
+static hipError_t persist_build_program(heisd_verify_ctx *ctx) {
+  const heisd_model_desc &d = ctx->d;
+  const int L = d.n_layers;
+  const FastScratch fs(&d);
+  const bool stream_down = d.d_ffn > kFastWaves * kKS * 32;
+  std::vector<Phase> prog;
+  heisd_kv_desc no_kv{};
+  Phase e{};
+  e.kind = PH_EMBED; e.next_gemm = 1;
+  e.g.next_gain = ctx->attn_norm[0]; e.g.out = ctx->x;
+  e.g.o_planes = reinterpret_cast<uint16_t *>(ctx->fscr + fs.rec_x_a);
+  e.g.ssq_out = reinterpret_cast<float *>(ctx->fscr + fs.ssq_a);
+  prog.push_back(e);
+  for (int l = 0; l < L; ++l) {
+    const FastLayerDescs D = fast_layer_descs(ctx, &no_kv, l, 1, 1, nullptr);
+    const int base = 1 + 5 * l;
+    Phase q{}; q.kind = PH_GEMM; q.g = D.qkv; q.next_gemm = base + 2; prog.push_back(q);
+    Phase a{}; a.kind = PH_ATTN; a.layer = l; a.next_gemm = -1;
+    a.g.b = reinterpret_cast<const uint16_t *>(D.attn.qkv); a.g.o_planes = D.attn.o_planes; prog.push_back(a);
+    Phase o{}; o.kind = PH_GEMM; o.g = D.oproj; o.next_gemm = base + 3; prog.push_back(o);
+    Phase g{}; g.kind = PH_GEMM; g.g = D.gateup; g.next_gemm = base + 4; prog.push_back(g);
+    Phase w{}; w.kind = stream_down ? PH_GEMM_STREAM : PH_GEMM; w.g = D.down; w.next_gemm = base + 5; prog.push_back(w);
+  }
+  Phase lm{}; lm.kind = PH_GEMM; lm.g = fast_lm_desc(ctx, 1, nullptr); lm.next_gemm = -1; prog.push_back(lm);
+  ctx->n_phases = (int)prog.size();
+  return hipMemcpy(ctx->prog, prog.data(), prog.size() * sizeof(Phase), hipMemcpyHostToDevice);
+}
+
+static void persist_launch(heisd_verify_ctx *ctx, const heisd_kv_desc *kv, const int32_t *draft_tokens, int K,
+                           int batch, const uint8_t *skip_mask, float *logits, hipStream_t st) {
+  const heisd_model_desc &d = ctx->d;
+  PersistArgs p{};
+  p.prog = ctx->prog; p.n_phases = ctx->n_phases;
+  p.d = d.d_model; p.H = d.n_heads; p.vocab = d.vocab; p.cap = d.kv_capacity;
+  p.tok_emb = static_cast<const uint16_t *>(d.tok_emb);
+  p.scale = 1.0f / std::sqrt((float)d.head_dim);
+  p.rope = ctx->rope;
+  p.ids = draft_tokens;
+  p.k_cache = static_cast<uint16_t *>(kv->k_cache); p.v_cache = static_cast<uint16_t *>(kv->v_cache);
+  p.kv_layer_stride = (size_t)batch * d.n_heads * d.kv_capacity * d.head_dim;
+  p.prefix_len = kv->prefix_len; p.skip = skip_mask; p.K = K; p.batch = batch; p.logits = logits;
+  p.flags = ctx->flags; p.err = ctx->dev_err;
+  p.epoch0 = ctx->epoch;
+  ctx->epoch += persist_epochs(ctx->n_phases);
+  const dim3 grid(ctx->n_cu), block(kFastThreads);
+  const size_t lds = persist_lds(ctx);
+  if (d.head_dim == 128) persist_forward<128><<<grid, block, lds, st>>>(p);
+  else persist_forward<64><<<grid, block, lds, st>>>(p);
 }
 
 // ---- init / free ------------------------------------------------------------------------
@@ -364,6 +453,9 @@ extern "C" int heisd_verify_init(const heisd_model_desc *desc, heisd_verify_ctx 
   c->logits = reinterpret_cast<float *>(base + w.logits);
   c->tbins = reinterpret_cast<int32_t *>(base + w.tbins);
   c->fscr = base + w.fscr;
+  c->prog = reinterpret_cast<Phase *>(base + w.players);
+  c->flags = reinterpret_cast<unsigned *>(base + w.flags);
+  c->dev_err = c->flags + 1024 * kFlagStride;
   c->fast_ok = desc->d_model <= kFastWaves * kKS * 32;
   c->path = HEISD_PATH_AUTO;
 
@@ -384,7 +476,10 @@ extern "C" int heisd_verify_init(const heisd_model_desc *desc, heisd_verify_ctx 
     if (e == hipSuccess) e = hipGetDeviceProperties(&prop, dev);
     if (e == hipSuccess) c->n_cu = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
   }
+  if (e == hipSuccess) e = hipMemset(base + w.flags, 0, (size_t)(1024 + 1) * kFlagStride * sizeof(unsigned));
   if (e == hipSuccess) e = fast_prepare(desc->head_dim, desc->kv_capacity);
+  if (e == hipSuccess) e = persist_prepare(c);
+  if (e == hipSuccess && c->persist_ok) e = persist_build_program(c);
   if (e == hipSuccess) e = gemm_prepare_mc<1>();
   if (e == hipSuccess) e = gemm_prepare_mc<2>();
   if (e == hipSuccess) e = gemm_prepare_mc<4>();
@@ -408,11 +503,26 @@ extern "C" int heisd_verify_init(const heisd_model_desc *desc, heisd_verify_ctx 
 
 extern "C" int heisd_verify_set_path(heisd_verify_ctx *ctx, int path) {
   if (!ctx) return HEISD_EINVAL;
-  if (path != HEISD_PATH_AUTO && path != HEISD_PATH_GENERIC && path != HEISD_PATH_FAST)
+  if (path != HEISD_PATH_AUTO && path != HEISD_PATH_GENERIC && path != HEISD_PATH_FAST && path != HEISD_PATH_PERSIST)
     return fail(ctx, HEISD_EINVAL, "set_path: unknown path %d", path);
   if (path == HEISD_PATH_FAST && !ctx->fast_ok)
     return fail(ctx, HEISD_EUNSUPPORTED, "set_path: model shape outside the fast kernels");
+  if (path == HEISD_PATH_PERSIST && !ctx->persist_ok)
+    return fail(ctx, HEISD_EUNSUPPORTED, "set_path: the persistent kernel does not fit this device or shape");
   ctx->path = path;
+  return HEISD_OK;
+}
+
+extern "C" int heisd_verify_check(heisd_verify_ctx *ctx) {
+  if (!ctx) return HEISD_EINVAL;
+  unsigned w = 0;
+  if (hipDeviceSynchronize() != hipSuccess ||
+      hipMemcpy(&w, ctx->dev_err, sizeof(w), hipMemcpyDeviceToHost) != hipSuccess)
+    return fail(ctx, HEISD_EHIP, "check: device error");
+  if (w != 0) {
+    (void)hipMemset(ctx->dev_err, 0, sizeof(w));
+    return fail(ctx, HEISD_EHIP, "check: a grid barrier of the persistent kernel timed out");
+  }
   return HEISD_OK;
 }
 
@@ -425,7 +535,7 @@ extern "C" int heisd_verify_profile_enable(heisd_verify_ctx *ctx, int enable) {
   ctx->prof_steps = 0;
   ctx->prof_on = false;
   if (enable) {
-    const size_t per_step = (size_t)ctx->d.n_layers * 5 * 8 + 16;   // launches of one step, row blocks included
+    const size_t per_step = (size_t)ctx->d.n_layers * 5 * 8 + 17;   // launches of one step, row blocks included
     ctx->ev.resize(per_step * 2 * HEISD_PROFILE_MAX_STEPS);
     for (size_t i = 0; i < ctx->ev.size(); ++i)
       if (hipEventCreate(&ctx->ev[i]) != hipSuccess) {
@@ -566,9 +676,13 @@ extern "C" int heisd_verify_step(heisd_verify_ctx *ctx, const heisd_kv_desc *kv,
   const bool prof = ctx->prof_on && ctx->prof_steps < HEISD_PROFILE_MAX_STEPS;
   if (prof) ctx->prof_steps++;
   const bool use_fast = ctx->fast_ok && M <= 8 && ctx->path != HEISD_PATH_GENERIC;
-  if (ctx->path == HEISD_PATH_FAST && !use_fast)
-    return fail(ctx, HEISD_EUNSUPPORTED, "step: the fast path needs batch*K <= 8 (got %d)", M);
-  if (use_fast) {
+  if ((ctx->path == HEISD_PATH_FAST || ctx->path == HEISD_PATH_PERSIST) && !use_fast)
+    return fail(ctx, HEISD_EUNSUPPORTED, "step: this path needs batch*K <= 8 (got %d)", M);
+  const bool use_persist = use_fast && ctx->persist_ok && ctx->path != HEISD_PATH_FAST;
+  if (use_persist) {
+    ProfScope ps(ctx, HEISD_KC_PERSIST, st, prof);
+    persist_launch(ctx, kv, draft_tokens, K, batch, skip_mask, logits, st);
+  } else if (use_fast) {
     fast_forward(ctx, kv, draft_tokens, K, batch, skip_mask, logits, st, prof);
   } else {
     generic_forward(ctx, kv, draft_tokens, K, batch, skip_mask, logits, st, prof);

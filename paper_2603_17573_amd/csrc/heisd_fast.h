@@ -23,11 +23,13 @@
 // A workgroup (8 waves) owns a list of 16-row weight tiles over the whole reduction; wave w owns
 // a contiguous share of the k-steps.  Weight tiles go straight from HBM into the MFMA A-operand
 // register layout (lane l: 16 bytes at W[n0 + l%16][k + 8*(l/16)]); the waves are reduced through
-// LDS in a fixed order.  For Kd <= 4096 a wave keeps its 16 B fragments in registers and streams
-// tiles through two 16-fragment buffers; for longer reductions (the down projection) A and B
-// fragments stream together through a ring of three 8-step buffers.  Each phase can be told that
-// its first buffers were requested earlier and is handed a callback that requests the next
-// phase's first tiles before it starts its own epilogue, so HBM stays busy across grid barriers.
+// LDS in a fixed order.  A wave keeps one ring of 16 weight fragments: a fragment's registers are
+// refilled with the same k-step of the next tile right after the MFMA that consumed it, so 16
+// loads (16 KB) per wave are always in flight.  For Kd <= 4096 the wave's 16 B fragments stay in
+// registers; for longer reductions (the down projection) B fragments stream through a second
+// ring.  A phase can be told that the ring already holds its first tile, and is handed a callback
+// that requests the next phase's first tile before it starts its own epilogue, so HBM stays busy
+// across grid barriers.
 #pragma once
 #include "heisd_common.h"
 
@@ -36,7 +38,6 @@ namespace heisd {
 constexpr int kFastThreads = 512;
 constexpr int kFastWaves = 8;
 constexpr int kKS = 16;      // k-steps (of 32) per register buffer, resident-B phases
-constexpr int kKS2 = 8;      // k-steps per ring slot, streaming phases
 constexpr int kMaxT = 6;     // weight tiles a workgroup accumulates at once (resident-B phases)
 constexpr int kSsqStride = 32;  // floats per partial-sum record (8 used): one 128-byte line
 
@@ -55,6 +56,7 @@ __device__ __forceinline__ void st_dev2(float *p, float a, float b) {
 }
 
 struct FastGemm {
+  int epi;                // FEPI_*: how tiles map to units and what the epilogue does
   const uint16_t *w[3];   // weight segments, bf16 row-major [rows][Kd]
   int seg_tiles;          // n-tiles per segment
   int n_units;            // n-tiles, or (gate, up) pairs for FEPI_SWIGLU
@@ -73,13 +75,15 @@ struct FastGemm {
   float *ssq_out;         // RESID_NORM: [n_units][kSsqStride]
 };
 
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 struct Frag16 {
-  uint4 v[kKS];
+  u32x4 v[kKS];
 };
-struct Frag8 {
-  uint4 a[kKS2];
-  uint4 b[kKS2];
-};
+
+typedef const u32x4 __attribute__((address_space(1))) *gptr_u4;   // global address space: no flat loads
+__device__ __forceinline__ u32x4 ld_g(const void *p) {
+  return *reinterpret_cast<gptr_u4>(reinterpret_cast<uintptr_t>(p));
+}
 
 // k-steps per wave (wave w owns steps [w*ksw, w*ksw + fast_steps(w)))
 __device__ __forceinline__ int fast_ksw(int Kd) { return ((Kd + 31) / 32 + kFastWaves - 1) / kFastWaves; }
@@ -90,10 +94,9 @@ __device__ __forceinline__ int fast_steps(int Kd, int wave) {
 
 // Which weight tile is list entry `e` of workgroup `wg` (of `nwg`)?  Units are dealt round-robin,
 // so unit u always belongs to workgroup u % nwg.
-template <int EPI>
 __device__ __forceinline__ bool fast_tile(const FastGemm &g, int wg, int nwg, int e, const uint16_t *&wbase,
                                           int &wrow0, int &unit) {
-  if (EPI == FEPI_SWIGLU) {
+  if (g.epi == FEPI_SWIGLU) {
     unit = wg + (e >> 1) * nwg;
     wbase = (e & 1) ? g.w[1] : g.w[0];
     wrow0 = unit * 16;
@@ -107,45 +110,45 @@ __device__ __forceinline__ bool fast_tile(const FastGemm &g, int wg, int nwg, in
   return unit < g.n_units;
 }
 
-template <int EPI>
 __device__ __forceinline__ int fast_my_entries(const FastGemm &g, int wg, int nwg) {
   const int my_units = g.n_units > wg ? (g.n_units - wg + nwg - 1) / nwg : 0;
-  return my_units * (EPI == FEPI_SWIGLU ? 2 : 1);
+  return my_units * (g.epi == FEPI_SWIGLU ? 2 : 1);
 }
 
-// Address of the B fragment of k-step `ks` for lane (lr, lg): record ks*2 + lg/2, row lr, half lg&1.
-__device__ __forceinline__ const uint4 *fast_b_ptr(const uint16_t *planes, int ks, int lr, int lg) {
-  return reinterpret_cast<const uint4 *>(planes + ((size_t)(ks * 2 + (lg >> 1)) * 256 + lr * 16 + (lg & 1) * 8));
+// All fragment loads are unconditional: instead of predicating lanes, an out-of-range k-step reads
+// a clamped (valid) weight address and is paired with an all-zero B record.  The plane buffers end
+// with zero records for that purpose.
+__host__ __device__ __forceinline__ int fast_plane_records(int Kd) { return 2 * ((Kd + 31) / 32) + 2; }
+
+// Weight fragment of k-step `ks` (clamped into the matrix) for lane group lg; wrow = this lane's row.
+__device__ __forceinline__ u32x4 fast_ld_a(const uint16_t *wrow, int Kd, int ks, int lg) {
+  const int total = (Kd + 31) / 32;
+  const int kse = min(ks, total - 1);
+  const int k = min(kse * 32 + lg * 8, Kd - 8);
+  return ld_g(wrow + k);
+}
+// B fragment of step `s` of a wave that owns `ns` steps from ks0 (the zero records if s >= ns):
+// record ks*2 + lg/2, row lr, half lg&1.
+__device__ __forceinline__ u32x4 fast_ld_b(const uint16_t *planes, int Kd, int ks0, int s, int ns, int lr, int lg) {
+  const int total = (Kd + 31) / 32;
+  const int ks = (s < ns) ? ks0 + s : total;
+  return ld_g(planes + ((size_t)(ks * 2 + (lg >> 1)) * 256 + lr * 16 + (lg & 1) * 8));
 }
 
-// ---- resident-B phases (Kd <= 4096: at most kKS steps per wave) --------------------------------
+__device__ __forceinline__ f32x4 fast_mfma(const u32x4 a, const u32x4 b, const f32x4 acc) {
+  return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), acc, 0, 0, 0);
+}
 
-template <int EPI>
+// Fill the ring with the first kKS weight fragments of tile entry e (this wave's k-steps 0..15).
 __device__ __forceinline__ void fast_issue16(Frag16 &A, const FastGemm &g, int wg, int nwg, int e, int wave, int lr,
                                              int lg) {
   const uint16_t *wbase;
   int wrow0, unit;
-  const bool ok = fast_tile<EPI>(g, wg, nwg, e, wbase, wrow0, unit);
-  const int ks0 = wave * fast_ksw(g.Kd), ns = ok ? fast_steps(g.Kd, wave) : 0;
-  const uint16_t *p = wbase + (size_t)(wrow0 + lr) * g.Kd + ks0 * 32 + lg * 8;
+  if (!fast_tile(g, wg, nwg, e, wbase, wrow0, unit)) return;   // uniform: the ring stays unused
+  const int ks0 = wave * fast_ksw(g.Kd);
+  const uint16_t *wrow = wbase + (size_t)(wrow0 + lr) * g.Kd;
 #pragma unroll
-  for (int s = 0; s < kKS; ++s)
-    A.v[s] = (s < ns && (ks0 + s) * 32 + lg * 8 + 8 <= g.Kd) ? *reinterpret_cast<const uint4 *>(p + s * 32)
-                                                              : make_uint4(0, 0, 0, 0);
-}
-
-__device__ __forceinline__ void fast_load_b16(Frag16 &Bf, const FastGemm &g, int wave, int lr, int lg) {
-  const int ks0 = wave * fast_ksw(g.Kd), ns = fast_steps(g.Kd, wave);
-#pragma unroll
-  for (int s = 0; s < kKS; ++s)
-    Bf.v[s] = (s < ns && (ks0 + s) * 32 + lg * 8 + 8 <= g.Kd) ? *fast_b_ptr(g.b, ks0 + s, lr, lg) : make_uint4(0, 0, 0, 0);
-}
-
-__device__ __forceinline__ void fast_mma16(f32x4 &acc, const Frag16 &A, const Frag16 &Bf) {
-#pragma unroll
-  for (int s = 0; s < kKS; ++s)
-    acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, A.v[s]), __builtin_bit_cast(bf16x8, Bf.v[s]),
-                                                  acc, 0, 0, 0);
+  for (int s = 0; s < kKS; ++s) A.v[s] = fast_ld_a(wrow, g.Kd, ks0 + s, lg);
 }
 
 // LDS of a GEMM phase: reduction buffer [waves][kMaxT][64 lanes][4] + 8 scales.
@@ -167,10 +170,10 @@ __device__ __forceinline__ void fast_row_scales(const FastGemm &g, float *scale_
 
 // Reduction over the waves (fixed order) and epilogue of `n_tiles` accumulated tile entries
 // starting at list entry e0.  acc tiles were stored to `red` by the caller.
-template <int EPI>
 __device__ __forceinline__ void fast_epilogue(const FastGemm &g, int wg, int nwg, int e0, int n_tiles, const float *red,
                                               const float *scale_s) {
-  constexpr int UT = (EPI == FEPI_SWIGLU) ? 2 : 1;
+  const int EPI = g.epi;
+  const int UT = (EPI == FEPI_SWIGLU) ? 2 : 1;
   const int tid = threadIdx.x;
   const int n_units_out = (n_tiles + UT - 1) / UT;
   for (int o = tid; o < n_units_out * 64; o += kFastThreads) {
@@ -195,7 +198,7 @@ __device__ __forceinline__ void fast_epilogue(const FastGemm &g, int wg, int nwg
     }
     const uint16_t *wbase;
     int wrow0, unit;
-    fast_tile<EPI>(g, wg, nwg, e0 + t, wbase, wrow0, unit);
+    fast_tile(g, wg, nwg, e0 + t, wbase, wrow0, unit);
     const float sc = scale_s[jm];
     const bool live = jm < g.M;
     if (EPI == FEPI_STORE_REC) {
@@ -237,37 +240,54 @@ __device__ __forceinline__ void fast_epilogue(const FastGemm &g, int wg, int nwg
   }
 }
 
-// One resident-B GEMM phase for workgroup `wg` of `nwg`.  NPRE leading tile entries (0, 1 or 2)
-// were already requested by the caller into buf0 / buf1.  `next()` is called once after the last
-// weight tile has been consumed (buffers free), before the reduction and the epilogue.
-template <int EPI, int NPRE, typename Next>
-__device__ __forceinline__ void fast_gemm_phase(const FastGemm &g, int wg, int nwg, unsigned char *smem, Frag16 &buf0,
-                                                Frag16 &buf1, Next next) {
+// One resident-B GEMM phase (Kd <= 4096: at most kKS steps per wave) for workgroup `wg` of `nwg`.
+// The ring A holds the weight fragments of the tile being multiplied; as soon as a fragment has
+// been consumed its registers are refilled with the same step of the next tile, so kKS loads per
+// wave are always in flight.  `pre`: the ring already holds tile entry 0 (requested by the caller
+// before it waited for this phase's inputs).  `next()` runs once after the last tile has been
+// consumed - the ring is free - and before the reduction and the epilogue; the persistent kernel
+// uses it to request the next phase's first tile.
+template <typename Next>
+__device__ __forceinline__ void fast_gemm_phase(const FastGemm &g, int wg, int nwg, unsigned char *smem, Frag16 &A,
+                                                bool pre, Next next) {
   float *red = reinterpret_cast<float *>(smem);
   float *scale_s = reinterpret_cast<float *>(smem + kFastRedBytes);
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int lr = lane & 15, lg = lane >> 4;
-  const int my_entries = fast_my_entries<EPI>(g, wg, nwg);
+  const int my_entries = fast_my_entries(g, wg, nwg);
   fast_row_scales(g, scale_s, wave, lane);
   if (my_entries == 0) {
     next();
     __syncthreads();
     return;
   }
+  const int ks0 = wave * fast_ksw(g.Kd), ns = fast_steps(g.Kd, wave);
   Frag16 Bf;
-  fast_load_b16(Bf, g, wave, lr, lg);
+#pragma unroll
+  for (int s = 0; s < kKS; ++s) Bf.v[s] = fast_ld_b(g.b, g.Kd, ks0, s, ns, lr, lg);
   for (int e0 = 0; e0 < my_entries; e0 += kMaxT) {
     f32x4 acc[kMaxT];
 #pragma unroll
     for (int t = 0; t < kMaxT; ++t) acc[t] = f32x4{0.f, 0.f, 0.f, 0.f};
-    const bool first = (e0 == 0);
-    if (!(first && NPRE >= 1)) fast_issue16<EPI>(buf0, g, wg, nwg, e0, wave, lr, lg);
-    if (!(first && NPRE >= 2) && e0 + 1 < my_entries) fast_issue16<EPI>(buf1, g, wg, nwg, e0 + 1, wave, lr, lg);
+    if (!(pre && e0 == 0)) fast_issue16(A, g, wg, nwg, e0, wave, lr, lg);
 #pragma unroll
     for (int t = 0; t < kMaxT; ++t) {
-      Frag16 &cur = (t & 1) ? buf1 : buf0;
-      if (e0 + t < my_entries) fast_mma16(acc[t], cur, Bf);
-      if (t + 2 < kMaxT && e0 + t + 2 < my_entries) fast_issue16<EPI>(cur, g, wg, nwg, e0 + t + 2, wave, lr, lg);
+      if (e0 + t < my_entries) {
+        if (t + 1 < kMaxT && e0 + t + 1 < my_entries) {
+          const uint16_t *wbase;
+          int wrow0, unit;
+          fast_tile(g, wg, nwg, e0 + t + 1, wbase, wrow0, unit);
+          const uint16_t *wrow = wbase + (size_t)(wrow0 + lr) * g.Kd;
+#pragma unroll
+          for (int s = 0; s < kKS; ++s) {
+            acc[t] = fast_mfma(A.v[s], Bf.v[s], acc[t]);
+            A.v[s] = fast_ld_a(wrow, g.Kd, ks0 + s, lg);
+          }
+        } else {
+#pragma unroll
+          for (int s = 0; s < kKS; ++s) acc[t] = fast_mfma(A.v[s], Bf.v[s], acc[t]);
+        }
+      }
     }
     if (e0 + kMaxT >= my_entries) next();
     __syncthreads();
@@ -275,99 +295,60 @@ __device__ __forceinline__ void fast_gemm_phase(const FastGemm &g, int wg, int n
     for (int t = 0; t < kMaxT; ++t)
       *reinterpret_cast<f32x4 *>(red + ((size_t)(wave * kMaxT + t) * 64 + lane) * 4) = acc[t];
     __syncthreads();
-    fast_epilogue<EPI>(g, wg, nwg, e0, min(kMaxT, my_entries - e0), red, scale_s);
+    fast_epilogue(g, wg, nwg, e0, min(kMaxT, my_entries - e0), red, scale_s);
     __syncthreads();
   }
 }
 
-// ---- streaming phases (long reductions: A and B fragments stream together) -------------------------
-
-template <int EPI>
-__device__ __forceinline__ void fast_issue8(Frag8 &F, const FastGemm &g, const uint16_t *wrow, bool ok, int ks0, int ns,
-                                            int grp, int lr, int lg) {
-  // group `grp` of this wave: steps ks0 + grp*8 .. +7, limited to ns steps in total
-#pragma unroll
-  for (int s = 0; s < kKS2; ++s) {
-    const int sl = grp * kKS2 + s;
-    const bool v = ok && sl < ns && (ks0 + sl) * 32 + lg * 8 + 8 <= g.Kd;
-    F.a[s] = v ? *reinterpret_cast<const uint4 *>(wrow + (size_t)(ks0 + sl) * 32) : make_uint4(0, 0, 0, 0);
-  }
-}
-__device__ __forceinline__ void fast_issue8_b(Frag8 &F, const FastGemm &g, int ks0, int ns, int grp, int lr, int lg) {
-#pragma unroll
-  for (int s = 0; s < kKS2; ++s) {
-    const int sl = grp * kKS2 + s;
-    const bool v = sl < ns && (ks0 + sl) * 32 + lg * 8 + 8 <= g.Kd;
-    F.b[s] = v ? *fast_b_ptr(g.b, ks0 + sl, lr, lg) : make_uint4(0, 0, 0, 0);
-  }
-}
-__device__ __forceinline__ void fast_mma8(f32x4 &acc, const Frag8 &F) {
-#pragma unroll
-  for (int s = 0; s < kKS2; ++s)
-    acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, F.a[s]), __builtin_bit_cast(bf16x8, F.b[s]),
-                                                  acc, 0, 0, 0);
-}
-
-// Request the weight halves of the first two ring slots of a streaming phase (entry 0); used by a
-// preceding phase before the grid barrier.  The B halves are loaded by the phase itself.
-template <int EPI>
-__device__ __forceinline__ void fast_stream_prefetch(const FastGemm &g, int wg, int nwg, Frag8 &r0, Frag8 &r1) {
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, lr = lane & 15, lg = lane >> 4;
-  const uint16_t *wbase;
-  int wrow0, unit;
-  const bool ok = fast_tile<EPI>(g, wg, nwg, 0, wbase, wrow0, unit);
-  const int ks0 = wave * fast_ksw(g.Kd), ns = fast_steps(g.Kd, wave);
-  const uint16_t *wrow = wbase + (size_t)(wrow0 + lr) * g.Kd + lg * 8;
-  fast_issue8<EPI>(r0, g, wrow, ok, ks0, ns, 0, lr, lg);
-  fast_issue8<EPI>(r1, g, wrow, ok, ks0, ns, 1, lr, lg);
-}
-
-// One streaming GEMM phase: one tile entry per pass, ring of three (A, B) slots of 8 k-steps.
-// PRE: the weight halves of slots r0, r1 for (entry 0, groups 0 and 1) were requested by the caller.
-template <int EPI, bool PRE, typename Next>
-__device__ __forceinline__ void fast_gemm_stream_phase(const FastGemm &g, int wg, int nwg, unsigned char *smem, Frag8 &r0,
-                                                       Frag8 &r1, Frag8 &r2, Next next) {
+// One streaming GEMM phase (long reductions, e.g. the down projection): one tile entry per pass;
+// weight and activation fragments stream together through two rings of kKS steps.  `pre`: ring A
+// already holds steps 0..kKS-1 of tile entry 0.
+template <typename Next>
+__device__ __forceinline__ void fast_gemm_stream_phase(const FastGemm &g, int wg, int nwg, unsigned char *smem, Frag16 &A,
+                                                       bool pre, Next next) {
   float *red = reinterpret_cast<float *>(smem);
   float *scale_s = reinterpret_cast<float *>(smem + kFastRedBytes);
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int lr = lane & 15, lg = lane >> 4;
-  const int my_entries = fast_my_entries<EPI>(g, wg, nwg);
+  const int my_entries = fast_my_entries(g, wg, nwg);
   fast_row_scales(g, scale_s, wave, lane);
   if (my_entries == 0) {
     next();
     __syncthreads();
     return;
   }
-  const int ks0 = wave * fast_ksw(g.Kd), ns = fast_steps(g.Kd, wave);
-  const int ngrp = (fast_ksw(g.Kd) + kKS2 - 1) / kKS2;     // same for every wave (tail groups are empty)
+  const int ksw = fast_ksw(g.Kd), ks0 = wave * ksw, ns = fast_steps(g.Kd, wave);
   for (int e = 0; e < my_entries; ++e) {
     const uint16_t *wbase;
     int wrow0, unit;
-    const bool ok = fast_tile<EPI>(g, wg, nwg, e, wbase, wrow0, unit);
-    const uint16_t *wrow = wbase + (size_t)(wrow0 + lr) * g.Kd + lg * 8;
+    fast_tile(g, wg, nwg, e, wbase, wrow0, unit);     // e < my_entries: always a valid tile
+    const uint16_t *wrow = wbase + (size_t)(wrow0 + lr) * g.Kd;
     f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
-    if (!(PRE && e == 0)) {
-      fast_issue8<EPI>(r0, g, wrow, ok, ks0, ns, 0, lr, lg);
-      fast_issue8<EPI>(r1, g, wrow, ok, ks0, ns, 1, lr, lg);
+    Frag16 Bs;
+    if (!(pre && e == 0)) {
+#pragma unroll
+      for (int s = 0; s < kKS; ++s) A.v[s] = fast_ld_a(wrow, g.Kd, ks0 + s, lg);
     }
-    fast_issue8_b(r0, g, ks0, ns, 0, lr, lg);
-    fast_issue8_b(r1, g, ks0, ns, 1, lr, lg);
-    for (int gi = 0; gi < ngrp; gi += 3) {
-      fast_issue8<EPI>(r2, g, wrow, ok, ks0, ns, gi + 2, lr, lg);
-      fast_issue8_b(r2, g, ks0, ns, gi + 2, lr, lg);
-      fast_mma8(acc, r0);
-      fast_issue8<EPI>(r0, g, wrow, ok, ks0, ns, gi + 3, lr, lg);
-      fast_issue8_b(r0, g, ks0, ns, gi + 3, lr, lg);
-      fast_mma8(acc, r1);
-      fast_issue8<EPI>(r1, g, wrow, ok, ks0, ns, gi + 4, lr, lg);
-      fast_issue8_b(r1, g, ks0, ns, gi + 4, lr, lg);
-      fast_mma8(acc, r2);
+#pragma unroll
+    for (int s = 0; s < kKS; ++s) Bs.v[s] = fast_ld_b(g.b, g.Kd, ks0, s, ns, lr, lg);
+    for (int base = 0; base < ksw; base += kKS) {
+      if (base + kKS < ksw) {        // uniform: more steps follow, refill while multiplying
+#pragma unroll
+        for (int s = 0; s < kKS; ++s) {
+          acc = fast_mfma(A.v[s], Bs.v[s], acc);
+          A.v[s] = fast_ld_a(wrow, g.Kd, ks0 + base + kKS + s, lg);
+          Bs.v[s] = fast_ld_b(g.b, g.Kd, ks0, base + kKS + s, ns, lr, lg);
+        }
+      } else {
+#pragma unroll
+        for (int s = 0; s < kKS; ++s) acc = fast_mfma(A.v[s], Bs.v[s], acc);
+      }
     }
     if (e + 1 == my_entries) next();
     __syncthreads();
     *reinterpret_cast<f32x4 *>(red + ((size_t)(wave * kMaxT) * 64 + lane) * 4) = acc;
     __syncthreads();
-    fast_epilogue<EPI>(g, wg, nwg, e, 1, red, scale_s);
+    fast_epilogue(g, wg, nwg, e, 1, red, scale_s);
     __syncthreads();
   }
 }
@@ -417,10 +398,10 @@ struct FastAttn {
   float scale;
 };
 
-constexpr int kAttnR = 12;   // prefix rows a key stream requests at once
+constexpr int kAttnR = 10;   // prefix rows a key stream requests at once
 
 inline size_t fast_attn_lds(int hd, int cap) {
-  return sizeof(float) * ((size_t)8 * hd * 3 + (size_t)8 * cap + 8 + (size_t)kFastWaves * 8 * hd);
+  return sizeof(float) * ((size_t)hd * (1 + 8 + 8) + (size_t)cap + 32 + (size_t)kFastWaves * hd);
 }
 
 __device__ __forceinline__ void unpack8(const uint4 v, float (&f)[8]) {
@@ -457,31 +438,33 @@ __device__ __forceinline__ void fast_attn_prefetch(const FastAttn &a, int b, int
   }
 }
 
-// K <= 8 queries of episode b, head h.  512 threads = 512/(HD/8) key streams; `pre` holds the
-// first kAttnR rows of each stream.  Scores in LDS; softmax one wave per query; the block's own
-// keys and values stay in fp32 (LDS), only the stored cache rows are rounded to bf16.
+// Query jq (< K <= 8) of episode b, head h: one workgroup.  512 threads = 512/(HD/8) key streams;
+// `pre` holds the first kAttnR prefix rows of each stream.  The unit rotates the block's keys
+// 0..jq itself (fp32, LDS) and appends row jq to the cache; scores live in LDS; the softmax is a
+// workgroup reduction; only the stored cache rows are rounded to bf16.
 template <int HD>
-__device__ __forceinline__ void fast_attn_unit(const FastAttn &a, int b, int h, unsigned char *smem, const AttnPre &pre) {
+__device__ __forceinline__ void fast_attn_unit(const FastAttn &a, int b, int h, int jq, unsigned char *smem,
+                                               const AttnPre &pre) {
   constexpr int HALF = HD / 2;
   constexpr int LPK = HD / 8;
   constexpr int G = kFastThreads / LPK;
   constexpr int TPH = HD / 16;                      // 16-column tiles per head
-  float *qs = reinterpret_cast<float *>(smem);     // [8][HD] rotated, scaled queries
-  float *kb = qs + 8 * HD;                          // [8][HD] rotated keys of the block
+  float *qs = reinterpret_cast<float *>(smem);     // [HD] rotated, scaled query
+  float *kb = qs + HD;                              // [8][HD] rotated keys of the block
   float *vb = kb + 8 * HD;                          // [8][HD] values of the block
-  float *sc = vb + 8 * HD;                          // [8][cap]
-  float *inv_l = sc + (size_t)8 * a.cap;            // [8]
-  float *ored = inv_l + 8;                          // [waves][8][HD]
+  float *sc = vb + 8 * HD;                          // [cap]
+  float *wred = sc + a.cap;                         // [32] per-wave partials
+  float *ored = wred + 32;                          // [waves][HD]
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int K = a.K, d = a.d, cap = a.cap;
-  const int row0 = b * K;
+  const int m = b * K + jq;                         // activation row of this query
   const int li = tid % LPK, g = tid / LPK;
   if (a.skip && a.skip[b]) {
-    for (int idx = tid; idx < K * HALF; idx += kFastThreads) {       // zero this head's slice of the records
-      const int j = idx / HALF, c = (idx - j * HALF) * 2;
+    for (int c2 = tid; c2 < HALF; c2 += kFastThreads) {     // zero this row's slice of the records
+      const int c = c2 * 2;
       uint32_t *rec = reinterpret_cast<uint32_t *>(a.o_planes + (size_t)(h * TPH + c / 16) * 256);
-      st_dev(rec + ((row0 + j) * 16 + (c & 15)) / 2, 0u);
-      st_dev(rec + ((row0 + j + 8) * 16 + (c & 15)) / 2, 0u);
+      st_dev(rec + (m * 16 + (c & 15)) / 2, 0u);
+      st_dev(rec + ((m + 8) * 16 + (c & 15)) / 2, 0u);
     }
     return;
   }
@@ -491,23 +474,24 @@ __device__ __forceinline__ void fast_attn_unit(const FastAttn &a, int b, int h, 
   uint16_t *vc = a.v_cache + ((size_t)(b * a.H + h) * cap) * HD;
   const int n_t = d / 16;
 
-  // rotate q (scaled) and k into LDS, copy v; append k and v (bf16) to the cache
-  for (int idx = tid; idx < 8 * HALF; idx += kFastThreads) {
+  // rotate keys 0..jq into LDS, copy values, rotate + scale the query; append row jq (bf16)
+  for (int idx = tid; idx < (jq + 1) * HALF; idx += kFastThreads) {
     const int j = idx / HALF, i = idx - j * HALF;
-    float r1 = 0.f, r2 = 0.f, kr1 = 0.f, kr2 = 0.f, v1 = 0.f, v2 = 0.f;
-    if (j < K) {
-      const int m = row0 + j;
-      const float *qa = a.qkv + (size_t)(h * TPH + i / 16) * 128 + m * 16 + (i & 15);
-      const float *qb = a.qkv + (size_t)(h * TPH + (i + HALF) / 16) * 128 + m * 16 + ((i + HALF) & 15);
-      const size_t ko = (size_t)n_t * 128, vo = (size_t)2 * n_t * 128;
-      const float2 cs = a.rope[(size_t)(P + j) * HALF + i];
-      const float q1 = qa[0], q2 = qb[0], k1 = qa[ko], k2 = qb[ko];
-      v1 = qa[vo];
-      v2 = qb[vo];
-      r1 = (q1 * cs.x - q2 * cs.y) * a.scale;
-      r2 = (q2 * cs.x + q1 * cs.y) * a.scale;
-      kr1 = k1 * cs.x - k2 * cs.y;
-      kr2 = k2 * cs.x + k1 * cs.y;
+    const int mj = b * K + j;
+    const float *qa = a.qkv + (size_t)(h * TPH + i / 16) * 128 + mj * 16 + (i & 15);
+    const float *qb = a.qkv + (size_t)(h * TPH + (i + HALF) / 16) * 128 + mj * 16 + ((i + HALF) & 15);
+    const size_t ko = (size_t)n_t * 128, vo = (size_t)2 * n_t * 128;
+    const float2 cs = a.rope[(size_t)(P + j) * HALF + i];
+    const float k1 = qa[ko], k2 = qb[ko], v1 = qa[vo], v2 = qb[vo];
+    const float kr1 = k1 * cs.x - k2 * cs.y, kr2 = k2 * cs.x + k1 * cs.y;
+    kb[j * HD + i] = kr1;
+    kb[j * HD + i + HALF] = kr2;
+    vb[j * HD + i] = v1;
+    vb[j * HD + i + HALF] = v2;
+    if (j == jq) {
+      const float q1 = qa[0], q2 = qb[0];
+      qs[i] = (q1 * cs.x - q2 * cs.y) * a.scale;
+      qs[i + HALF] = (q2 * cs.x + q1 * cs.y) * a.scale;
       uint16_t *kr = kc + (size_t)(P + j) * HD;
       kr[i] = (uint16_t)f32_to_bf16_bits(kr1);
       kr[i + HALF] = (uint16_t)f32_to_bf16_bits(kr2);
@@ -515,40 +499,21 @@ __device__ __forceinline__ void fast_attn_unit(const FastAttn &a, int b, int h, 
       vr[i] = (uint16_t)f32_to_bf16_bits(v1);
       vr[i + HALF] = (uint16_t)f32_to_bf16_bits(v2);
     }
-    qs[j * HD + i] = r1;
-    qs[j * HD + i + HALF] = r2;
-    kb[j * HD + i] = kr1;
-    kb[j * HD + i + HALF] = kr2;
-    vb[j * HD + i] = v1;
-    vb[j * HD + i + HALF] = v2;
   }
   __syncthreads();
-  float qf[8][8];
+  float qf[8];
 #pragma unroll
-  for (int j = 0; j < 8; ++j)
-#pragma unroll
-    for (int i = 0; i < 8; ++i) qf[j][i] = qs[j * HD + li * 8 + i];
+  for (int i = 0; i < 8; ++i) qf[i] = qs[li * 8 + i];
 
   auto score_row = [&](const float (&kf)[8], int r) {
-    float s[8];
+    float t = 0.f;
 #pragma unroll
-    for (int j = 0; j < 8; ++j) {
-      float t = 0.f;
+    for (int i = 0; i < 8; ++i) t = fmaf(qf[i], kf[i], t);
 #pragma unroll
-      for (int i = 0; i < 8; ++i) t = fmaf(qf[j][i], kf[i], t);
-      s[j] = t;
-    }
-#pragma unroll
-    for (int off = LPK / 2; off > 0; off >>= 1)
-#pragma unroll
-      for (int j = 0; j < 8; ++j) s[j] += __shfl_xor(s[j], off, kWave);
-    float mine = s[0];
-#pragma unroll
-    for (int j = 1; j < 8; ++j) mine = (li == j) ? s[j] : mine;
-    if (li < 8) sc[(size_t)li * cap + r] = (r <= P + li) ? mine : -INFINITY;
+    for (int off = LPK / 2; off > 0; off >>= 1) t += __shfl_xor(t, off, kWave);
+    if (li == 0) sc[r] = t;
   };
-
-  // ---- pass 1: prefix keys ----
+  // ---- pass 1: scores of the prefix keys, then of the block's keys 0..jq ----
 #pragma unroll
   for (int u = 0; u < kAttnR; ++u) {
     const int r = u * G + g;
@@ -575,51 +540,49 @@ __device__ __forceinline__ void fast_attn_unit(const FastAttn &a, int b, int h, 
       }
     }
   }
-  if (g < K) {   // the block's own keys at fp32
+  if (g <= jq) {
     float kf[8];
 #pragma unroll
     for (int i = 0; i < 8; ++i) kf[i] = kb[g * HD + li * 8 + i];
     score_row(kf, P + g);
   }
   __syncthreads();
-  const int nkeys = P + K;
-  // ---- softmax: wave j owns query j ----
-  if (wave < K) {
-    float *row = sc + (size_t)wave * cap;
-    float mx = -INFINITY;
-    for (int r = lane; r < nkeys; r += kWave) mx = fmaxf(mx, row[r]);
-    mx = wave_max(mx);
-    float sum = 0.f;
-    for (int r = lane; r < nkeys; r += kWave) {
-      const float p = expf(row[r] - mx);
-      row[r] = p;
-      sum += p;
-    }
-    sum = wave_sum(sum);
-    if (lane == 0) inv_l[wave] = 1.0f / sum;
-  }
+  const int nkeys = P + jq + 1;
+  // ---- softmax over the visible keys (workgroup reduction) ----
+  float mx = -INFINITY;
+  for (int r = tid; r < nkeys; r += kFastThreads) mx = fmaxf(mx, sc[r]);
+  mx = wave_max(mx);
+  if (lane == 0) wred[wave] = mx;
   __syncthreads();
-  // ---- pass 2: values ----
-  float o[8][8];
+  mx = wred[0];
 #pragma unroll
-  for (int j = 0; j < 8; ++j)
+  for (int w = 1; w < kFastWaves; ++w) mx = fmaxf(mx, wred[w]);
+  float sum = 0.f;
+  for (int r = tid; r < nkeys; r += kFastThreads) {
+    const float pr = expf(sc[r] - mx);
+    sc[r] = pr;
+    sum += pr;
+  }
+  sum = wave_sum(sum);
+  if (lane == 0) wred[8 + wave] = sum;
+  __syncthreads();
+  float tot = 0.f;
 #pragma unroll
-    for (int i = 0; i < 8; ++i) o[j][i] = 0.f;
-  auto add_row = [&](const float (&vf)[8], int r) {
+  for (int w = 0; w < kFastWaves; ++w) tot += wred[8 + w];
+  const float inv_l = 1.0f / tot;
+  // ---- pass 2: weighted sum of the value rows ----
+  float o[8];
 #pragma unroll
-    for (int j = 0; j < 8; ++j) {
-      const float p = (j < K) ? sc[(size_t)j * cap + r] : 0.f;
-#pragma unroll
-      for (int i = 0; i < 8; ++i) o[j][i] = fmaf(p, vf[i], o[j][i]);
-    }
-  };
+  for (int i = 0; i < 8; ++i) o[i] = 0.f;
 #pragma unroll
   for (int u = 0; u < kAttnR; ++u) {
     const int r = u * G + g;
     if (r < P) {
       float vf[8];
       unpack8(pre.v[u], vf);
-      add_row(vf, r);
+      const float pr = sc[r];
+#pragma unroll
+      for (int i = 0; i < 8; ++i) o[i] = fmaf(pr, vf[i], o[i]);
     }
   }
   for (int r0 = G * kAttnR; r0 < P; r0 += G * kAttnR) {
@@ -635,43 +598,40 @@ __device__ __forceinline__ void fast_attn_unit(const FastAttn &a, int b, int h, 
       if (r < P) {
         float vf[8];
         unpack8(vv[u], vf);
-        add_row(vf, r);
+        const float pr = sc[r];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) o[i] = fmaf(pr, vf[i], o[i]);
       }
     }
   }
-  if (g < K) {
-    float vf[8];
+  if (g <= jq) {
+    const float pr = sc[P + g];
 #pragma unroll
-    for (int i = 0; i < 8; ++i) vf[i] = vb[g * HD + li * 8 + i];
-    add_row(vf, P + g);
+    for (int i = 0; i < 8; ++i) o[i] = fmaf(pr, vb[g * HD + li * 8 + i], o[i]);
   }
 #pragma unroll
   for (int off = LPK; off < kWave; off <<= 1)
 #pragma unroll
-    for (int j = 0; j < 8; ++j)
-#pragma unroll
-      for (int i = 0; i < 8; ++i) o[j][i] += __shfl_xor(o[j][i], off, kWave);
+    for (int i = 0; i < 8; ++i) o[i] += __shfl_xor(o[i], off, kWave);
   if (lane < LPK) {
 #pragma unroll
-    for (int j = 0; j < 8; ++j)
-#pragma unroll
-      for (int i = 0; i < 8; ++i) ored[(size_t)(wave * 8 + j) * HD + lane * 8 + i] = o[j][i];
+    for (int i = 0; i < 8; ++i) ored[wave * HD + lane * 8 + i] = o[i];
   }
   __syncthreads();
-  for (int idx = tid; idx < K * HALF; idx += kFastThreads) {      // two adjacent channels per thread
-    const int j = idx / HALF, c = (idx - j * HALF) * 2;
+  for (int c2 = tid; c2 < HALF; c2 += kFastThreads) {      // two adjacent channels per thread
+    const int c = c2 * 2;
     float t0 = 0.f, t1 = 0.f;
 #pragma unroll
     for (int w = 0; w < kFastWaves; ++w) {
-      t0 += ored[(size_t)(w * 8 + j) * HD + c];
-      t1 += ored[(size_t)(w * 8 + j) * HD + c + 1];
+      t0 += ored[w * HD + c];
+      t1 += ored[w * HD + c + 1];
     }
     uint32_t h0, l0, h1, l1;
-    split_bf16(t0 * inv_l[j], h0, l0);
-    split_bf16(t1 * inv_l[j], h1, l1);
+    split_bf16(t0 * inv_l, h0, l0);
+    split_bf16(t1 * inv_l, h1, l1);
     uint32_t *rec = reinterpret_cast<uint32_t *>(a.o_planes + (size_t)(h * TPH + c / 16) * 256);
-    st_dev(rec + ((row0 + j) * 16 + (c & 15)) / 2, h0 | (h1 << 16));
-    st_dev(rec + ((row0 + j + 8) * 16 + (c & 15)) / 2, l0 | (l1 << 16));
+    st_dev(rec + (m * 16 + (c & 15)) / 2, h0 | (h1 << 16));
+    st_dev(rec + ((m + 8) * 16 + (c & 15)) / 2, l0 | (l1 << 16));
   }
   __syncthreads();
 }
@@ -682,26 +642,25 @@ struct NoNext {
   __device__ __forceinline__ void operator()() const {}
 };
 
-template <int EPI>
 __global__ __launch_bounds__(kFastThreads) void fast_gemm_kernel(FastGemm g) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-  Frag16 b0, b1;
-  fast_gemm_phase<EPI, 0>(g, blockIdx.x, gridDim.x, smem, b0, b1, NoNext());
+  Frag16 A;
+  fast_gemm_phase(g, blockIdx.x, gridDim.x, smem, A, false, NoNext());
 }
 
-template <int EPI>
 __global__ __launch_bounds__(kFastThreads) void fast_gemm_stream_kernel(FastGemm g) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-  Frag8 r0, r1, r2;
-  fast_gemm_stream_phase<EPI, false>(g, blockIdx.x, gridDim.x, smem, r0, r1, r2, NoNext());
+  Frag16 A;
+  fast_gemm_stream_phase(g, blockIdx.x, gridDim.x, smem, A, false, NoNext());
 }
 
 template <int HD>
 __global__ __launch_bounds__(kFastThreads) void fast_attn_kernel(FastAttn a) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   AttnPre pre;
-  fast_attn_prefetch<HD>(a, blockIdx.y, blockIdx.x, pre);
-  fast_attn_unit<HD>(a, blockIdx.y, blockIdx.x, smem, pre);
+  const int b = blockIdx.y / a.K, jq = blockIdx.y - b * a.K;     // grid (H, batch*K)
+  fast_attn_prefetch<HD>(a, b, blockIdx.x, pre);
+  fast_attn_unit<HD>(a, b, blockIdx.x, jq, smem, pre);
 }
 
 __global__ __launch_bounds__(64) void fast_embed_kernel(const int32_t *ids, const uint16_t *emb, int vocab, int d, int M,

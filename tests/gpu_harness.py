@@ -42,6 +42,8 @@ def run_gpu_step(shape, weights, kb, vb, plen, first, drafts, rule, skip, device
     for _ in range(repeat):
         out = ver.step(kc, vc, t_plen, t_first, t_drafts, accept_desc_of(rule), t_skip, out=out)
     torch.cuda.synchronize()
+    from paper_2603_17573_amd import heisd_verify_check
+    assert heisd_verify_check(ver.ctx) == 0, "device error word set"
     res = {k: v.cpu().numpy() for k, v in out.items()}
     res["k_cache"], res["v_cache"] = _dev_to_bits(kc), _dev_to_bits(vc)
     ver.close()

@@ -46,14 +46,14 @@ def run_case(wl, plen_override=None, skip=None, rule=None, drafts_mode="auto", c
     return got, ref, stats
 
 
-@pytest.mark.parametrize("path", [0, 1, 2])
+@pytest.mark.parametrize("path", [0, 1, 2, 3])
 def test_c0_tiny_config(path):
-    """C0 through the automatic choice, the any-M path and the <=8-row path."""
+    """C0 through the automatic choice, the any-M path, the <=8-row kernels and the persistent kernel."""
     got, ref, stats = run_case(synth.WORKLOADS["C0"], path=path)
     assert stats["max_logit_err_over_range"] < 3e-2
 
 
-@pytest.mark.parametrize("path", [1, 2])
+@pytest.mark.parametrize("path", [1, 2, 3])
 @pytest.mark.parametrize("shape_name,B,K,skip", [("mid", 1, 7, None), ("mid", 2, 4, [0, 1]), ("mid", 1, 8, None),
                                                  ("s64", 2, 3, None), ("s64", 1, 5, None)])
 def test_small_row_counts_on_both_paths(path, shape_name, B, K, skip):
