@@ -66,6 +66,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="C1")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--path", type=int, default=0, help="0 auto, 1 generic, 2 fast (launch per phase), 3 persistent")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs the verify step on ONE GPU (episodes would shard by batch "
@@ -91,6 +92,8 @@ def main():
     t_gen = time.time() - t0
     dm = DeviceModel(sh, weights, dev)
     ver = Verifier(dm, B, K, cap)
+    from paper_2603_17573_amd import heisd_verify_set_path
+    assert heisd_verify_set_path(ver.ctx, args.path) == 0
     # prefix K/V drawn directly (the benchmark may not call the oracle's prefill); same shapes,
     # same bytes, same launch configuration as a prefilled cache
     kc, vc = ver.new_cache(B)
@@ -179,6 +182,7 @@ def main():
         "config": {"workload": "%s: %d-layer d=%d decoder, prefix %d, batch %d, K=%d, thresholds %d/%d" %
                                (wl.name, sh.n_layers, sh.d_model, P, B, K, wl.tau_tok, wl.tau_seq),
                    "prefix_kv": "drawn directly (no prefill)", "global_batch": B, "K": K},
+        "kernel_path": args.path,
         "hbm_frac_whole_step": round(total_bytes / (ms * 1e-3) / HBM_PEAK, 4),
         "algorithmic_bytes_per_step": total_bytes,
         "accepted_len": accepted[:8],

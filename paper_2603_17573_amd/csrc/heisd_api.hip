@@ -33,6 +33,8 @@ struct heisd_verify_ctx {
   unsigned *flags, *dev_err;           // persistent kernel: barrier flags [n_cu][16], error word
   unsigned epoch = 0;                  // last barrier epoch handed out
   bool persist_ok = false;
+  unsigned long long *trace = nullptr; // device buffer [n_phases][8] when tracing is on
+  bool trace_on = false;
   int n_cu = 256;
   int path = 0;                        // HEISD_PATH_*
   bool fast_ok = false;                // the shape fits the fast kernels
@@ -78,7 +80,7 @@ static int fail(heisd_verify_ctx *ctx, int code, const char *fmt, ...) {
 static size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
 
 struct WsLayout {
-  size_t rope, x, qkv, attn_o, act, logits, tbins, fscr, fscr_bytes, players, flags, total;
+  size_t rope, x, qkv, attn_o, act, logits, tbins, fscr, fscr_bytes, players, flags, trace, total;
 };
 
 // Per-layer exchange buffers of the fast path.  Every buffer is written once per step, so an
@@ -124,6 +126,7 @@ static WsLayout ws_layout(const heisd_model_desc *d) {
   off += w.fscr_bytes;
   w.players = off; off += align256((size_t)(5 * d->n_layers + 2) * sizeof(Phase));
   w.flags = off;   off += align256((size_t)(1024 + 1) * kFlagStride * sizeof(unsigned));
+  w.trace = off;   off += align256((size_t)(5 * d->n_layers + 2) * 8 * sizeof(unsigned long long));
   w.total = off;
   return w;
 }
@@ -368,8 +371,8 @@ static hipError_t persist_build_program(heisd_verify_ctx *ctx) {
   for (int l = 0; l < L; ++l) {
     const FastLayerDescs D = fast_layer_descs(ctx, &no_kv, l, 1, 1, nullptr);
     const int base = 1 + 5 * l;
-    Phase q{}; q.kind = PH_GEMM; q.g = D.qkv; q.next_gemm = base + 2; prog.push_back(q);
-    Phase a{}; a.kind = PH_ATTN; a.layer = l; a.next_gemm = -1;
+    Phase q{}; q.kind = PH_GEMM; q.g = D.qkv; q.next_gemm = -1; prog.push_back(q);
+    Phase a{}; a.kind = PH_ATTN; a.layer = l; a.next_gemm = base + 2;
     a.g.b = reinterpret_cast<const uint16_t *>(D.attn.qkv); a.g.o_planes = D.attn.o_planes; prog.push_back(a);
     Phase o{}; o.kind = PH_GEMM; o.g = D.oproj; o.next_gemm = base + 3; prog.push_back(o);
     Phase g{}; g.kind = PH_GEMM; g.g = D.gateup; g.next_gemm = base + 4; prog.push_back(g);
@@ -394,6 +397,7 @@ static void persist_launch(heisd_verify_ctx *ctx, const heisd_kv_desc *kv, const
   p.kv_layer_stride = (size_t)batch * d.n_heads * d.kv_capacity * d.head_dim;
   p.prefix_len = kv->prefix_len; p.skip = skip_mask; p.K = K; p.batch = batch; p.logits = logits;
   p.flags = ctx->flags; p.err = ctx->dev_err;
+  p.trace = ctx->trace_on ? ctx->trace : nullptr;
   p.epoch0 = ctx->epoch;
   ctx->epoch += persist_epochs(ctx->n_phases);
   const dim3 grid(ctx->n_cu), block(kFastThreads);
@@ -456,6 +460,7 @@ extern "C" int heisd_verify_init(const heisd_model_desc *desc, heisd_verify_ctx 
   c->prog = reinterpret_cast<Phase *>(base + w.players);
   c->flags = reinterpret_cast<unsigned *>(base + w.flags);
   c->dev_err = c->flags + 1024 * kFlagStride;
+  c->trace = reinterpret_cast<unsigned long long *>(base + w.trace);
   c->fast_ok = desc->d_model <= kFastWaves * kKS * 32;
   c->path = HEISD_PATH_AUTO;
 
@@ -510,6 +515,22 @@ extern "C" int heisd_verify_set_path(heisd_verify_ctx *ctx, int path) {
   if (path == HEISD_PATH_PERSIST && !ctx->persist_ok)
     return fail(ctx, HEISD_EUNSUPPORTED, "set_path: the persistent kernel does not fit this device or shape");
   ctx->path = path;
+  return HEISD_OK;
+}
+
+// Measurement aid, not part of the public header: timestamps (100 MHz counter) of workgroup 0 at
+// phase start / weights consumed / epilogue done / barrier passed, for every phase of the last
+// persistent step.  enable != 0 switches recording on; out (HOST, n_phases*8 entries) may be NULL.
+extern "C" int heisd_debug_trace(heisd_verify_ctx *ctx, int enable, unsigned long long *out, int max_entries) {
+  if (!ctx) return HEISD_EINVAL;
+  ctx->trace_on = enable != 0;
+  if (out) {
+    const int n = ctx->n_phases * 8 < max_entries ? ctx->n_phases * 8 : max_entries;
+    if (hipDeviceSynchronize() != hipSuccess ||
+        hipMemcpy(out, ctx->trace, (size_t)n * sizeof(unsigned long long), hipMemcpyDeviceToHost) != hipSuccess)
+      return HEISD_EHIP;
+    return n;
+  }
   return HEISD_OK;
 }
 

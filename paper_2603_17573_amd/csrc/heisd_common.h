@@ -26,6 +26,14 @@ __device__ __forceinline__ void split_bf16(float x, uint32_t &hi, uint32_t &lo) 
   lo = f32_to_bf16_bits(x - bf16_bits_to_f32(hi));
 }
 
+// Workgroup barrier that orders LDS traffic only: outstanding global loads (prefetched weight
+// tiles) keep flying across it, which __syncthreads() would wait for.
+__device__ __forceinline__ void lds_barrier() {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+  __builtin_amdgcn_s_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+}
+
 __device__ __forceinline__ float wave_sum(float v) {
 #pragma unroll
   for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, kWave);

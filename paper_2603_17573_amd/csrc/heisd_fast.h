@@ -27,9 +27,8 @@
 // refilled with the same k-step of the next tile right after the MFMA that consumed it, so 16
 // loads (16 KB) per wave are always in flight.  For Kd <= 4096 the wave's 16 B fragments stay in
 // registers; for longer reductions (the down projection) B fragments stream through a second
-// ring.  A phase can be told that the ring already holds its first tile, and is handed a callback
-// that requests the next phase's first tile before it starts its own epilogue, so HBM stays busy
-// across grid barriers.
+// ring.  A phase can be told that the ring already holds its first tile (the persistent kernel
+// requests it while it waits at the grid barrier), so HBM stays busy across barriers.
 #pragma once
 #include "heisd_common.h"
 
@@ -244,12 +243,9 @@ __device__ __forceinline__ void fast_epilogue(const FastGemm &g, int wg, int nwg
 // The ring A holds the weight fragments of the tile being multiplied; as soon as a fragment has
 // been consumed its registers are refilled with the same step of the next tile, so kKS loads per
 // wave are always in flight.  `pre`: the ring already holds tile entry 0 (requested by the caller
-// before it waited for this phase's inputs).  `next()` runs once after the last tile has been
-// consumed - the ring is free - and before the reduction and the epilogue; the persistent kernel
-// uses it to request the next phase's first tile.
-template <typename Next>
+// before it waited for this phase's inputs).  On return the ring is free.
 __device__ __forceinline__ void fast_gemm_phase(const FastGemm &g, int wg, int nwg, unsigned char *smem, Frag16 &A,
-                                                bool pre, Next next) {
+                                                bool pre) {
   float *red = reinterpret_cast<float *>(smem);
   float *scale_s = reinterpret_cast<float *>(smem + kFastRedBytes);
   const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -257,8 +253,7 @@ __device__ __forceinline__ void fast_gemm_phase(const FastGemm &g, int wg, int n
   const int my_entries = fast_my_entries(g, wg, nwg);
   fast_row_scales(g, scale_s, wave, lane);
   if (my_entries == 0) {
-    next();
-    __syncthreads();
+    lds_barrier();
     return;
   }
   const int ks0 = wave * fast_ksw(g.Kd), ns = fast_steps(g.Kd, wave);
@@ -289,23 +284,21 @@ __device__ __forceinline__ void fast_gemm_phase(const FastGemm &g, int wg, int n
         }
       }
     }
-    if (e0 + kMaxT >= my_entries) next();
-    __syncthreads();
+    lds_barrier();
 #pragma unroll
     for (int t = 0; t < kMaxT; ++t)
       *reinterpret_cast<f32x4 *>(red + ((size_t)(wave * kMaxT + t) * 64 + lane) * 4) = acc[t];
-    __syncthreads();
+    lds_barrier();
     fast_epilogue(g, wg, nwg, e0, min(kMaxT, my_entries - e0), red, scale_s);
-    __syncthreads();
+    lds_barrier();
   }
 }
 
 // One streaming GEMM phase (long reductions, e.g. the down projection): one tile entry per pass;
 // weight and activation fragments stream together through two rings of kKS steps.  `pre`: ring A
 // already holds steps 0..kKS-1 of tile entry 0.
-template <typename Next>
 __device__ __forceinline__ void fast_gemm_stream_phase(const FastGemm &g, int wg, int nwg, unsigned char *smem, Frag16 &A,
-                                                       bool pre, Next next) {
+                                                       bool pre) {
   float *red = reinterpret_cast<float *>(smem);
   float *scale_s = reinterpret_cast<float *>(smem + kFastRedBytes);
   const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -313,8 +306,7 @@ __device__ __forceinline__ void fast_gemm_stream_phase(const FastGemm &g, int wg
   const int my_entries = fast_my_entries(g, wg, nwg);
   fast_row_scales(g, scale_s, wave, lane);
   if (my_entries == 0) {
-    next();
-    __syncthreads();
+    lds_barrier();
     return;
   }
   const int ksw = fast_ksw(g.Kd), ks0 = wave * ksw, ns = fast_steps(g.Kd, wave);
@@ -344,12 +336,11 @@ __device__ __forceinline__ void fast_gemm_stream_phase(const FastGemm &g, int wg
         for (int s = 0; s < kKS; ++s) acc = fast_mfma(A.v[s], Bs.v[s], acc);
       }
     }
-    if (e + 1 == my_entries) next();
-    __syncthreads();
+    lds_barrier();
     *reinterpret_cast<f32x4 *>(red + ((size_t)(wave * kMaxT) * 64 + lane) * 4) = acc;
-    __syncthreads();
+    lds_barrier();
     fast_epilogue(g, wg, nwg, e, 1, red, scale_s);
-    __syncthreads();
+    lds_barrier();
   }
 }
 
@@ -638,20 +629,16 @@ __device__ __forceinline__ void fast_attn_unit(const FastAttn &a, int b, int h, 
 
 // ---- one launch per phase ---------------------------------------------------------------------
 
-struct NoNext {
-  __device__ __forceinline__ void operator()() const {}
-};
-
 __global__ __launch_bounds__(kFastThreads) void fast_gemm_kernel(FastGemm g) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   Frag16 A;
-  fast_gemm_phase(g, blockIdx.x, gridDim.x, smem, A, false, NoNext());
+  fast_gemm_phase(g, blockIdx.x, gridDim.x, smem, A, false);
 }
 
 __global__ __launch_bounds__(kFastThreads) void fast_gemm_stream_kernel(FastGemm g) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   Frag16 A;
-  fast_gemm_stream_phase(g, blockIdx.x, gridDim.x, smem, A, false, NoNext());
+  fast_gemm_stream_phase(g, blockIdx.x, gridDim.x, smem, A, false);
 }
 
 template <int HD>

@@ -5,8 +5,8 @@
 //
 // Why: at 7B shape one layer is five dependent phases of 4-23 microseconds of HBM time each.
 // Launching them one by one costs a ramp-up and a drain per phase; here every workgroup requests
-// the first weight tile of the NEXT GEMM phase as soon as its own weights are consumed, before
-// its epilogue and the barrier, so HBM keeps streaming while the activations are exchanged.
+// the first weight tile of the NEXT GEMM phase right after it has published its outputs, so HBM
+// keeps streaming while the workgroups wait for each other and fetch their activations.
 //
 // Grid barrier: one 64-byte-padded flag per workgroup holding the last epoch it reached; wave 0 of
 // every workgroup publishes its flag and polls all flags with device-scope loads.  No L2
@@ -52,16 +52,27 @@ struct PersistArgs {
   unsigned *flags;                       // [nwg][kFlagStride]
   unsigned epoch0;                       // flags hold values <= epoch0 when the kernel starts
   unsigned *err;
+  unsigned long long *trace;             // optional [n_phases][8] timestamps of workgroup 0 (measurement aid)
 };
 
-// Arrive and wait.  Returns false if the wait gave up (error word raised) or an error was seen.
-__device__ __forceinline__ bool grid_sync(const PersistArgs &p, int wg, int nwg, unsigned epoch) {
-  __builtin_amdgcn_s_waitcnt(0);         // this wave's device-scope stores have been acknowledged
-  __syncthreads();
+// Grid barrier, split in two so that weight prefetches can be slotted in between.
+// Arrive: every wave waits for its own device-scope stores (nothing else is outstanding at that
+// point), then the workgroup publishes the epoch.
+__device__ __forceinline__ void grid_arrive(const PersistArgs &p, int wg, unsigned epoch) {
+  __builtin_amdgcn_s_waitcnt(0);
+  lds_barrier();
+  if (threadIdx.x == 0)
+    __hip_atomic_store(&p.flags[wg * kFlagStride], epoch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// Wait: wave 0 polls every workgroup's flag (it must not have loads of its own in flight, its polls
+// would queue behind them); the other waves just meet it at the workgroup barrier, their
+// prefetched loads still flying.  Returns false if the wait gave up (error word raised) or an
+// error was seen.
+__device__ __forceinline__ bool grid_wait(const PersistArgs &p, int nwg, unsigned epoch) {
   __shared__ int s_ok;
   if (threadIdx.x < kWave) {
     const int lane = threadIdx.x;
-    if (lane == 0) __hip_atomic_store(&p.flags[wg * kFlagStride], epoch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     int spins = 0;
     bool good = true;
     while (true) {
@@ -80,8 +91,10 @@ __device__ __forceinline__ bool grid_sync(const PersistArgs &p, int wg, int nwg,
     if (!good && lane == 0) __hip_atomic_store(p.err, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     if (lane == 0) s_ok = good ? 1 : 0;
   }
-  __syncthreads();
-  return s_ok != 0;
+  lds_barrier();
+  const bool r = s_ok != 0;
+  lds_barrier();          // s_ok may be rewritten only after everybody has read it
+  return r;
 }
 
 // Attention unit t (t = 0, 1, ...) of workgroup wg: queries of one head stay on one XCD (workgroup
@@ -123,22 +136,18 @@ __global__ __launch_bounds__(kFastThreads) void persist_forward(PersistArgs p) {
   Frag16 A;                                // the weight ring, carried across phases and barriers
   unsigned epoch = p.epoch0;
 
+  auto stamp = [&](int ph, int slot) __attribute__((always_inline)) {
+    if (p.trace && wg == 0 && threadIdx.x == 0) p.trace[ph * 8 + slot] = wall_clock64();
+  };
   for (int ph = 0; ph < p.n_phases; ++ph) {
     const int kind = p.prog[ph].kind;
-    // request the first weight tile of the next GEMM phase (the ring is free at that point)
-    auto prefetch = [&]() __attribute__((always_inline)) {
-      const int ng = p.prog[ph].next_gemm;
-      if (ng >= 0) {
-        const FastGemm gn = phase_gemm(p, ng);
-        fast_issue16(A, gn, wg, nwg, 0, wave, lr, lg);
-      }
-    };
+    stamp(ph, 0);
     if (kind == PH_GEMM) {
       const FastGemm g = phase_gemm(p, ph);
-      fast_gemm_phase(g, wg, nwg, smem, A, true, prefetch);
+      fast_gemm_phase(g, wg, nwg, smem, A, true);
     } else if (kind == PH_GEMM_STREAM) {
       const FastGemm g = phase_gemm(p, ph);
-      fast_gemm_stream_phase(g, wg, nwg, smem, A, true, prefetch);
+      fast_gemm_stream_phase(g, wg, nwg, smem, A, true);
     } else if (kind == PH_ATTN) {
       const Phase &P = p.prog[ph];
       FastAttn at{};
@@ -160,9 +169,24 @@ __global__ __launch_bounds__(kFastThreads) void persist_forward(PersistArgs p) {
       for (int tile = wg; tile < p.d / 16; tile += nwg)
         fast_embed_tile(p.ids, p.tok_emb, p.vocab, p.d, p.batch * p.K, tile, P.g.next_gain, P.g.out, P.g.o_planes,
                         P.g.ssq_out);
-      prefetch();
     }
-    if (ph + 1 < p.n_phases && !grid_sync(p, wg, nwg, ++epoch)) return;
+    stamp(ph, 1);
+    if (ph + 1 == p.n_phases) break;
+    // barrier; the first weight tile of the next GEMM phase is requested while waiting
+    ++epoch;
+    grid_arrive(p, wg, epoch);
+    const int ng = p.prog[ph].next_gemm;
+    if (ng >= 0 && wave != 0) {
+      const FastGemm gn = phase_gemm(p, ng);
+      fast_issue16(A, gn, wg, nwg, 0, wave, lr, lg);
+    }
+    stamp(ph, 2);
+    if (!grid_wait(p, nwg, epoch)) return;
+    if (ng >= 0 && wave == 0) {
+      const FastGemm gn = phase_gemm(p, ng);
+      fast_issue16(A, gn, wg, nwg, 0, wave, lr, lg);
+    }
+    stamp(ph, 3);
   }
 }
 
