@@ -66,6 +66,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="C1")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run three plain 1 GiB device copies (reference kernel for HBM traffic counters)")
     ap.add_argument("--path", type=int, default=0, help="0 auto, 1 generic, 2 fast (launch per phase), 3 persistent")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -117,6 +119,13 @@ def main():
     acc = make_accept_desc(wl.tau_tok, wl.tau_seq)
     stream = torch.cuda.current_stream(dev)
 
+    if args.calibrate_copy:
+        src = torch.empty(1 << 28, dtype=torch.float32, device=dev).normal_()
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     out = None
     for _ in range(args.warmup):
         out = ver.step(kc, vc, t_plen, t_first, t_drafts, acc, t_skip, want_aux=False, out=out, stream=stream)

@@ -699,7 +699,7 @@ extern "C" int heisd_verify_step(heisd_verify_ctx *ctx, const heisd_kv_desc *kv,
   const bool use_fast = ctx->fast_ok && M <= 8 && ctx->path != HEISD_PATH_GENERIC;
   if ((ctx->path == HEISD_PATH_FAST || ctx->path == HEISD_PATH_PERSIST) && !use_fast)
     return fail(ctx, HEISD_EUNSUPPORTED, "step: this path needs batch*K <= 8 (got %d)", M);
-  const bool use_persist = use_fast && ctx->persist_ok && ctx->path != HEISD_PATH_FAST;
+  const bool use_persist = use_fast && ctx->persist_ok && ctx->path == HEISD_PATH_PERSIST;   // AUTO: launch per phase
   if (use_persist) {
     ProfScope ps(ctx, HEISD_KC_PERSIST, st, prof);
     persist_launch(ctx, kv, draft_tokens, K, batch, skip_mask, logits, st);

@@ -175,17 +175,15 @@ __global__ __launch_bounds__(kFastThreads) void persist_forward(PersistArgs p) {
     // barrier; the first weight tile of the next GEMM phase is requested while waiting
     ++epoch;
     grid_arrive(p, wg, epoch);
+    // (the polls of wave 0 queue behind these loads in the compute unit's memory pipeline: the
+    // barrier is seen once they have drained, and HBM stays busy meanwhile)
     const int ng = p.prog[ph].next_gemm;
-    if (ng >= 0 && wave != 0) {
+    if (ng >= 0) {
       const FastGemm gn = phase_gemm(p, ng);
       fast_issue16(A, gn, wg, nwg, 0, wave, lr, lg);
     }
     stamp(ph, 2);
     if (!grid_wait(p, nwg, epoch)) return;
-    if (ng >= 0 && wave == 0) {
-      const FastGemm gn = phase_gemm(p, ng);
-      fast_issue16(A, gn, wg, nwg, 0, wave, lr, lg);
-    }
     stamp(ph, 3);
   }
 }
