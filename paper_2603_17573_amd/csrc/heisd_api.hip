@@ -189,8 +189,12 @@ static void gemm_launch(GemmArgs a, int M, int epi, hipStream_t st) {
 static hipError_t fast_prepare(int hd, int cap) {
   hipError_t e;
   const int lds = (int)kFastLds;
-  const void *fns[] = {reinterpret_cast<const void *>(&fast_gemm_kernel),
-                       reinterpret_cast<const void *>(&fast_gemm_stream_kernel)};
+  const void *fns[] = {reinterpret_cast<const void *>(&fast_gemm_kernel<HEISD_KC_QKV>),
+                       reinterpret_cast<const void *>(&fast_gemm_kernel<HEISD_KC_OPROJ>),
+                       reinterpret_cast<const void *>(&fast_gemm_kernel<HEISD_KC_GATEUP>),
+                       reinterpret_cast<const void *>(&fast_gemm_kernel<HEISD_KC_DOWN>),
+                       reinterpret_cast<const void *>(&fast_gemm_kernel<HEISD_KC_LMHEAD>),
+                       reinterpret_cast<const void *>(&fast_gemm_stream_kernel<HEISD_KC_DOWN>)};
   for (const void *f : fns)
     if ((e = hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, lds)) != hipSuccess) return e;
   const int alds = (int)fast_attn_lds(hd, cap);
@@ -294,11 +298,12 @@ static void fast_forward(heisd_verify_ctx *ctx, const heisd_kv_desc *kv, const i
   }
   const size_t alds = fast_attn_lds(HD, cap);
   const bool stream_down = d.d_ffn > kFastWaves * kKS * 32;
+  const FastGemm lm = fast_lm_desc(ctx, M, logits);
   for (int l = 0; l < d.n_layers; ++l) {
     const FastLayerDescs L = fast_layer_descs(ctx, kv, l, K, batch, skip_mask);
     {
       ProfScope ps(ctx, HEISD_KC_QKV, st, prof);
-      fast_gemm_kernel<<<grid_for(L.qkv.n_units), dim3(kFastThreads), kFastLds, st>>>(L.qkv);
+      fast_gemm_kernel<HEISD_KC_QKV><<<grid_for(L.qkv.n_units), dim3(kFastThreads), kFastLds, st>>>(L.qkv);
     }
     {
       ProfScope ps(ctx, HEISD_KC_ATTN, st, prof);
@@ -307,24 +312,23 @@ static void fast_forward(heisd_verify_ctx *ctx, const heisd_kv_desc *kv, const i
     }
     {
       ProfScope ps(ctx, HEISD_KC_OPROJ, st, prof);
-      fast_gemm_kernel<<<grid_for(L.oproj.n_units), dim3(kFastThreads), kFastLds, st>>>(L.oproj);
+      fast_gemm_kernel<HEISD_KC_OPROJ><<<grid_for(L.oproj.n_units), dim3(kFastThreads), kFastLds, st>>>(L.oproj);
     }
     {
       ProfScope ps(ctx, HEISD_KC_GATEUP, st, prof);
-      fast_gemm_kernel<<<grid_for(L.gateup.n_units), dim3(kFastThreads), kFastLds, st>>>(L.gateup);
+      fast_gemm_kernel<HEISD_KC_GATEUP><<<grid_for(L.gateup.n_units), dim3(kFastThreads), kFastLds, st>>>(L.gateup);
     }
     {
       ProfScope ps(ctx, HEISD_KC_DOWN, st, prof);
       if (stream_down)
-        fast_gemm_stream_kernel<<<grid_for(L.down.n_units), dim3(kFastThreads), kFastLds, st>>>(L.down);
+        fast_gemm_stream_kernel<HEISD_KC_DOWN><<<grid_for(L.down.n_units), dim3(kFastThreads), kFastLds, st>>>(L.down);
       else
-        fast_gemm_kernel<<<grid_for(L.down.n_units), dim3(kFastThreads), kFastLds, st>>>(L.down);
+        fast_gemm_kernel<HEISD_KC_DOWN><<<grid_for(L.down.n_units), dim3(kFastThreads), kFastLds, st>>>(L.down);
     }
   }
-  const FastGemm g = fast_lm_desc(ctx, M, logits);
   {
     ProfScope ps(ctx, HEISD_KC_LMHEAD, st, prof);
-    fast_gemm_kernel<<<grid_for(g.n_units), dim3(kFastThreads), kFastLds, st>>>(g);
+    fast_gemm_kernel<HEISD_KC_LMHEAD><<<grid_for(lm.n_units), dim3(kFastThreads), kFastLds, st>>>(lm);
   }
 }
 
