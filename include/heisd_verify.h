@@ -173,11 +173,13 @@ int heisd_verify_profile_read(heisd_verify_ctx *ctx, double *ms, int64_t *launch
 
 /*
  * Kernel-path selection, for tests and measurement.  AUTO (default) picks the fastest path
- * that covers the call; GENERIC forces the any-M path (LDS-staged activations, one launch
- * per phase); FAST forces the batch*K <= 8 kernels with one launch per phase; PERSIST forces
- * the batch*K <= 8 persistent kernel (the whole decoder forward in one launch, one workgroup
- * per compute unit, grid barriers inside).  FAST and PERSIST make a larger step fail with
- * EUNSUPPORTED.  Results of the paths agree to fp32 rounding.
+ * that covers the call: FAST for batch*K <= 8, BATCH above.  GENERIC forces the first any-M path
+ * (activations converted and staged through LDS by every workgroup, one launch per phase);
+ * BATCH forces the any-M path that exchanges pre-split bf16 activation records (waves arranged
+ * over rows and over the reduction according to batch*K); FAST forces the batch*K <= 8 kernels
+ * with one launch per phase; PERSIST forces the batch*K <= 8 persistent kernel (the whole decoder
+ * forward in one launch, one workgroup per compute unit, grid barriers inside).  FAST and PERSIST
+ * make a larger step fail with EUNSUPPORTED.  Results of the paths agree to fp32 rounding.
  *
  * The persistent kernel spins at its grid barriers with a bound; if the bound expires (the
  * GPU was shared with work that kept some of its workgroups from running) it raises a device
@@ -188,6 +190,7 @@ int heisd_verify_profile_read(heisd_verify_ctx *ctx, double *ms, int64_t *launch
 #define HEISD_PATH_GENERIC 1
 #define HEISD_PATH_FAST 2
 #define HEISD_PATH_PERSIST 3
+#define HEISD_PATH_BATCH 4
 int heisd_verify_check(heisd_verify_ctx *ctx);
 int heisd_verify_set_path(heisd_verify_ctx *ctx, int path);
 

@@ -8,7 +8,7 @@ from .binding import (heisd_model_desc, heisd_kv_desc, heisd_accept_desc, heisd_
                       heisd_verify_init, heisd_verify_step, heisd_free, heisd_last_error,
                       heisd_verify_profile_enable, heisd_verify_profile_read, KERNEL_CLASSES,
                       heisd_verify_set_path, heisd_verify_check, HEISD_PATH_AUTO, HEISD_PATH_GENERIC, HEISD_PATH_FAST,
-                      HEISD_PATH_PERSIST,
+                      HEISD_PATH_PERSIST, HEISD_PATH_BATCH,
                       make_accept_desc, make_model_desc, HEISD_OK, HEISD_EINVAL, HEISD_EUNSUPPORTED,
                       HEISD_ENOMEM, HEISD_EHIP)
 from .runner import DeviceModel, Verifier

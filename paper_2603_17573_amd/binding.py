@@ -101,7 +101,7 @@ def heisd_last_error(ctx=None) -> str:
     return load().heisd_last_error(ctx).decode()
 
 
-HEISD_PATH_AUTO, HEISD_PATH_GENERIC, HEISD_PATH_FAST, HEISD_PATH_PERSIST = 0, 1, 2, 3
+HEISD_PATH_AUTO, HEISD_PATH_GENERIC, HEISD_PATH_FAST, HEISD_PATH_PERSIST, HEISD_PATH_BATCH = 0, 1, 2, 3, 4
 
 
 def heisd_verify_check(ctx) -> int:

@@ -14,6 +14,7 @@
 #include "heisd_attn.h"
 #include "heisd_fast.h"
 #include "heisd_persist.h"
+#include "heisd_batch.h"
 #include "heisd_gemm.h"
 #include "heisd_misc.h"
 
@@ -28,6 +29,7 @@ struct heisd_verify_ctx {
   float *x, *qkv, *attn_o, *act, *logits;
   int32_t *tbins;
   unsigned char *fscr;                 // fast path: per-layer exchange records (see FastScratch)
+  unsigned char *bscr;                 // batched path (M > 8): records and row statistics (see BatScratch)
   Phase *prog;                         // persistent kernel: the phase program in device memory
   int n_phases = 0;
   unsigned *flags, *dev_err;           // persistent kernel: barrier flags [n_cu][16], error word
@@ -80,7 +82,26 @@ static int fail(heisd_verify_ctx *ctx, int code, const char *fmt, ...) {
 static size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
 
 struct WsLayout {
-  size_t rope, x, qkv, attn_o, act, logits, tbins, fscr, fscr_bytes, players, flags, trace, total;
+  size_t rope, x, qkv, attn_o, act, logits, tbins, fscr, fscr_bytes, bscr, bscr_bytes, players, flags, trace, total;
+};
+
+// Buffers of the batched path (M > 8 rows).  One launch per phase, so one set serves every layer.
+struct BatScratch {
+  int CTS;                         // column tiles allocated: those of max_batch*max_k rows, at least 8
+  size_t rec_x, rec_o, rec_act, ssq, inv_rms, total;
+  explicit BatScratch(const heisd_model_desc *d) {
+    const size_t M = (size_t)d->max_batch * d->max_k;
+    CTS = (int)((M + 7) / 8);
+    if (CTS < 8) CTS = 8;
+    const size_t kd = 2 * (((size_t)d->d_model + 31) / 32), kf = 2 * (((size_t)d->d_ffn + 31) / 32);
+    size_t off = 0;
+    rec_x = off;   off += kd * CTS * 512;
+    rec_o = off;   off += kd * CTS * 512;
+    rec_act = off; off += kf * CTS * 512;
+    ssq = off;     off += align256((size_t)(d->d_model / 16) * CTS * 8 * sizeof(float));
+    inv_rms = off; off += align256((size_t)CTS * 8 * sizeof(float));
+    total = align256(off);
+  }
 };
 
 // Per-layer exchange buffers of the fast path.  Every buffer is written once per step, so an
@@ -103,6 +124,8 @@ struct FastScratch {
   }
 };
 
+static hipError_t bat_prepare();
+
 static bool shape_ok(const heisd_model_desc *d) {
   return d && d->n_layers > 0 && d->d_model > 0 && d->n_heads > 0 && d->head_dim > 0 && d->d_ffn > 0 &&
          d->vocab > 0 && d->n_bins > 0 && d->max_batch > 0 && d->max_k > 0 && d->kv_capacity > 0 &&
@@ -124,6 +147,9 @@ static WsLayout ws_layout(const heisd_model_desc *d) {
   w.fscr = off;
   w.fscr_bytes = FastScratch(d).stride * (size_t)(d->n_layers + 1);
   off += w.fscr_bytes;
+  w.bscr = off;
+  w.bscr_bytes = BatScratch(d).total;
+  off += w.bscr_bytes;
   w.players = off; off += align256((size_t)(5 * d->n_layers + 2) * sizeof(Phase));
   w.flags = off;   off += align256((size_t)(1024 + 1) * kFlagStride * sizeof(unsigned));
   w.trace = off;   off += align256((size_t)(5 * d->n_layers + 2) * 8 * sizeof(unsigned long long));
@@ -461,6 +487,7 @@ extern "C" int heisd_verify_init(const heisd_model_desc *desc, heisd_verify_ctx 
   c->logits = reinterpret_cast<float *>(base + w.logits);
   c->tbins = reinterpret_cast<int32_t *>(base + w.tbins);
   c->fscr = base + w.fscr;
+  c->bscr = base + w.bscr;
   c->prog = reinterpret_cast<Phase *>(base + w.players);
   c->flags = reinterpret_cast<unsigned *>(base + w.flags);
   c->dev_err = c->flags + 1024 * kFlagStride;
@@ -478,6 +505,7 @@ extern "C" int heisd_verify_init(const heisd_model_desc *desc, heisd_verify_ctx 
     }
   hipError_t e = hipMemcpy(c->rope, tab.data(), tab.size() * sizeof(float2), hipMemcpyHostToDevice);
   if (e == hipSuccess) e = hipMemset(base + w.fscr, 0, w.fscr_bytes);   // records start as zeros
+  if (e == hipSuccess) e = hipMemset(base + w.bscr, 0, w.bscr_bytes);   // (the zero k-tiles stay zero)
   if (e == hipSuccess) {
     int dev = 0;
     hipDeviceProp_t prop;
@@ -489,6 +517,7 @@ extern "C" int heisd_verify_init(const heisd_model_desc *desc, heisd_verify_ctx 
   if (e == hipSuccess) e = fast_prepare(desc->head_dim, desc->kv_capacity);
   if (e == hipSuccess) e = persist_prepare(c);
   if (e == hipSuccess && c->persist_ok) e = persist_build_program(c);
+  if (e == hipSuccess) e = bat_prepare();
   if (e == hipSuccess) e = gemm_prepare_mc<1>();
   if (e == hipSuccess) e = gemm_prepare_mc<2>();
   if (e == hipSuccess) e = gemm_prepare_mc<4>();
@@ -512,7 +541,8 @@ extern "C" int heisd_verify_init(const heisd_model_desc *desc, heisd_verify_ctx 
 
 extern "C" int heisd_verify_set_path(heisd_verify_ctx *ctx, int path) {
   if (!ctx) return HEISD_EINVAL;
-  if (path != HEISD_PATH_AUTO && path != HEISD_PATH_GENERIC && path != HEISD_PATH_FAST && path != HEISD_PATH_PERSIST)
+  if (path != HEISD_PATH_AUTO && path != HEISD_PATH_GENERIC && path != HEISD_PATH_FAST && path != HEISD_PATH_PERSIST &&
+      path != HEISD_PATH_BATCH)
     return fail(ctx, HEISD_EINVAL, "set_path: unknown path %d", path);
   if (path == HEISD_PATH_FAST && !ctx->fast_ok)
     return fail(ctx, HEISD_EUNSUPPORTED, "set_path: model shape outside the fast kernels");
@@ -604,6 +634,138 @@ extern "C" void heisd_free(heisd_verify_ctx *ctx) {
 extern "C" const char *heisd_last_error(const heisd_verify_ctx *ctx) { return ctx ? ctx->err : g_init_err; }
 
 // The decoder forward for any M, one launch per phase (LDS-staged activations, 64-row blocks).
+// ---- batched path (any M; the automatic choice for M > 8 rows) -------------------------------
+
+template <int MC>
+static hipError_t bat_prepare_mc() {
+  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&bat_gemm<MC, 3>),
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)bat_lds_bytes<MC>());
+  if (e != hipSuccess) return e;
+  return hipFuncSetAttribute(reinterpret_cast<const void *>(&bat_gemm<MC, 2>),
+                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)bat_lds_bytes<MC>());
+}
+
+static hipError_t bat_prepare() {
+  hipError_t e;
+  if ((e = bat_prepare_mc<2>()) != hipSuccess) return e;
+  if ((e = bat_prepare_mc<4>()) != hipSuccess) return e;
+  if ((e = bat_prepare_mc<7>()) != hipSuccess) return e;
+  return bat_prepare_mc<8>();
+}
+
+template <int MC>
+static void bat_launch_mc(const BatGemm &g, int grid, hipStream_t st) {
+  if (g.epi == FEPI_SWIGLU)
+    bat_gemm<MC, 2><<<dim3(grid), dim3(kBatThreads), bat_lds_bytes<MC>(), st>>>(g);
+  else
+    bat_gemm<MC, 3><<<dim3(grid), dim3(kBatThreads), bat_lds_bytes<MC>(), st>>>(g);
+}
+
+// Wave arrangement for CT column tiles: MW groups of MC tiles (MC from the compiled set).
+static void bat_launch(BatGemm g, int n_cu, hipStream_t st) {
+  const int CT = g.CT;
+  const int MW = CT <= 8 ? 1 : (CT <= 16 ? 2 : (CT <= 32 ? 4 : 8));
+  const int need = (CT + MW - 1) / MW < 8 ? (CT + MW - 1) / MW : 8;
+  g.MW = MW;
+  const int grid = g.n_units < n_cu ? g.n_units : n_cu;
+  if (need <= 2) bat_launch_mc<2>(g, grid, st);
+  else if (need <= 4) bat_launch_mc<4>(g, grid, st);
+  else if (need <= 7) bat_launch_mc<7>(g, grid, st);
+  else bat_launch_mc<8>(g, grid, st);
+}
+
+static void batch_forward(heisd_verify_ctx *ctx, const heisd_kv_desc *kv, const int32_t *draft_tokens, int K,
+                          int batch, const uint8_t *skip_mask, float *logits, hipStream_t st, bool prof) {
+  const heisd_model_desc &d = ctx->d;
+  const int M = batch * K, dm = d.d_model, F = d.d_ffn, H = d.n_heads, HD = d.head_dim, cap = d.kv_capacity;
+  const BatScratch bs(&d);
+  const int CT = (M + 7) / 8, CTS = bs.CTS;
+  uint16_t *rec_x = reinterpret_cast<uint16_t *>(ctx->bscr + bs.rec_x);
+  uint16_t *rec_o = reinterpret_cast<uint16_t *>(ctx->bscr + bs.rec_o);
+  uint16_t *rec_act = reinterpret_cast<uint16_t *>(ctx->bscr + bs.rec_act);
+  float *ssq = reinterpret_cast<float *>(ctx->bscr + bs.ssq);
+  float *inv_rms = reinterpret_cast<float *>(ctx->bscr + bs.inv_rms);
+  auto row_scales = [&]() {
+    bat_row_scales<<<dim3((CT * 8 + kBatWaves - 1) / kBatWaves), dim3(kBatThreads), 0, st>>>(ssq, dm / 16, CT * 8,
+                                                                                            CTS * 8, dm, d.rms_eps, inv_rms);
+  };
+  {
+    ProfScope ps(ctx, HEISD_KC_EMBED, st, prof);
+    bat_embed<<<dim3(dm / 16), dim3(64), 0, st>>>(draft_tokens, static_cast<const uint16_t *>(d.tok_emb), d.vocab, dm, M,
+                                                  CT, CTS, ctx->attn_norm[0], ctx->x, rec_x, ssq);
+    row_scales();
+  }
+  const size_t layer_stride = (size_t)batch * H * cap * HD;
+  const size_t attn_lds = attn_lds_bytes(HD, cap);
+  BatGemm base{};
+  base.CT = CT; base.CTS = CTS; base.M = M;
+  for (int l = 0; l < d.n_layers; ++l) {
+    // q, k, v = RMSNorm(x) . {Wq, Wk, Wv}^T  (fp32 rows for the attention kernel)
+    BatGemm g = base;
+    g.epi = FEPI_STORE_ROWS;
+    g.w[0] = static_cast<const uint16_t *>(ctx->wq[l]);
+    g.w[1] = static_cast<const uint16_t *>(ctx->wk[l]);
+    g.w[2] = static_cast<const uint16_t *>(ctx->wv[l]);
+    g.seg_tiles = dm / 16; g.n_units = 3 * dm / 16; g.Kd = dm;
+    g.b = rec_x; g.inv_rms = inv_rms; g.out = ctx->qkv; g.ldo = 3 * dm;
+    { ProfScope ps(ctx, HEISD_KC_QKV, st, prof); bat_launch(g, ctx->n_cu, st); }
+    // RoPE + KV-append + attention; the output goes straight into records
+    AttnArgs a{};
+    a.qkv = ctx->qkv;
+    a.k_cache = static_cast<uint16_t *>(kv->k_cache) + (size_t)l * layer_stride;
+    a.v_cache = static_cast<uint16_t *>(kv->v_cache) + (size_t)l * layer_stride;
+    a.prefix_len = kv->prefix_len; a.skip = skip_mask; a.rope = ctx->rope; a.out = nullptr;
+    a.o_planes = rec_o; a.CTS = CTS;
+    a.K = K; a.H = H; a.cap = cap; a.d = dm; a.scale = 1.0f / std::sqrt((float)HD);
+    {
+      ProfScope ps(ctx, HEISD_KC_ATTN, st, prof);
+      if (HD == 128) attn_verify<128><<<dim3(H, batch), dim3(kAttnThreads), attn_lds, st>>>(a);
+      else attn_verify<64><<<dim3(H, batch), dim3(kAttnThreads), attn_lds, st>>>(a);
+    }
+    // x += o . Wo^T; records of x * ffn gain, partial sums of squares
+    g = base;
+    g.epi = FEPI_RESID_NORM;
+    g.w[0] = static_cast<const uint16_t *>(ctx->wo[l]);
+    g.seg_tiles = dm / 16; g.n_units = dm / 16; g.Kd = dm;
+    g.b = rec_o; g.inv_rms = nullptr; g.out = ctx->x; g.ldo = dm;
+    g.next_gain = ctx->ffn_norm[l]; g.o_planes = rec_x; g.ssq_out = ssq;
+    {
+      ProfScope ps(ctx, HEISD_KC_OPROJ, st, prof);
+      bat_launch(g, ctx->n_cu, st);
+      row_scales();
+    }
+    // a = silu(RMSNorm(x) . Wg^T) * (RMSNorm(x) . Wu^T), as records
+    g = base;
+    g.epi = FEPI_SWIGLU;
+    g.w[0] = static_cast<const uint16_t *>(ctx->w_gate[l]);
+    g.w[1] = static_cast<const uint16_t *>(ctx->w_up[l]);
+    g.seg_tiles = F / 16; g.n_units = F / 16; g.Kd = dm;
+    g.b = rec_x; g.inv_rms = inv_rms; g.o_planes = rec_act;
+    { ProfScope ps(ctx, HEISD_KC_GATEUP, st, prof); bat_launch(g, ctx->n_cu, st); }
+    // x += a . Wd^T; records of x * (next norm's gain), partial sums of squares
+    g = base;
+    g.epi = FEPI_RESID_NORM;
+    g.w[0] = static_cast<const uint16_t *>(ctx->w_down[l]);
+    g.seg_tiles = dm / 16; g.n_units = dm / 16; g.Kd = F;
+    g.b = rec_act; g.inv_rms = nullptr; g.out = ctx->x; g.ldo = dm;
+    g.next_gain = (l + 1 < d.n_layers) ? ctx->attn_norm[l + 1] : d.final_norm;
+    g.o_planes = rec_x; g.ssq_out = ssq;
+    {
+      ProfScope ps(ctx, HEISD_KC_DOWN, st, prof);
+      bat_launch(g, ctx->n_cu, st);
+      row_scales();
+    }
+  }
+  // logits over the action bins = RMSNorm(x; final) . W_lm[bin rows]^T
+  BatGemm g = base;
+  g.epi = FEPI_STORE_ROWS;
+  g.w[0] = static_cast<const uint16_t *>(d.lm_head) + (size_t)d.bin_token_base * dm;
+  g.seg_tiles = d.n_bins / 16; g.n_units = d.n_bins / 16; g.Kd = dm;
+  g.b = rec_x; g.inv_rms = inv_rms; g.out = logits; g.ldo = d.n_bins;
+  ProfScope ps(ctx, HEISD_KC_LMHEAD, st, prof);
+  bat_launch(g, ctx->n_cu, st);
+}
+
 static void generic_forward(heisd_verify_ctx *ctx, const heisd_kv_desc *kv, const int32_t *draft_tokens, int K,
                             int batch, const uint8_t *skip_mask, float *logits, hipStream_t st, bool prof) {
   const heisd_model_desc &d = ctx->d;
@@ -709,6 +871,8 @@ extern "C" int heisd_verify_step(heisd_verify_ctx *ctx, const heisd_kv_desc *kv,
     persist_launch(ctx, kv, draft_tokens, K, batch, skip_mask, logits, st);
   } else if (use_fast) {
     fast_forward(ctx, kv, draft_tokens, K, batch, skip_mask, logits, st, prof);
+  } else if (ctx->path == HEISD_PATH_BATCH || (ctx->path == HEISD_PATH_AUTO && M > 8)) {
+    batch_forward(ctx, kv, draft_tokens, K, batch, skip_mask, logits, st, prof);
   } else {
     generic_forward(ctx, kv, draft_tokens, K, batch, skip_mask, logits, st, prof);
   }

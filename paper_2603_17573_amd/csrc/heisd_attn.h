@@ -27,7 +27,9 @@ struct AttnArgs {
   const int32_t *prefix_len; // [batch]
   const uint8_t *skip;       // [batch] or nullptr
   const float2 *rope;        // [cap][HD/2] (cos, sin) of position * theta_i
-  float *out;                // [M][d]
+  float *out;                // [M][d] fp32 rows, or nullptr
+  uint16_t *o_planes;        // or: records [d/16][CTS][16][16] bf16 (head rows 0-7, tail rows 8-15 of each
+  int CTS;                   //     column tile of 8 activation rows), the B-operand format of the GEMMs
   int K, H, cap, d;
   float scale;               // 1/sqrt(HD)
 };
@@ -35,6 +37,18 @@ struct AttnArgs {
 inline size_t attn_lds_bytes(int hd, int cap) {
   return sizeof(float) * ((size_t)kAttnQB * hd + (size_t)kAttnQB * cap + kAttnQB +
                           (size_t)kAttnWaves * kAttnQB * hd);
+}
+
+// Attention output element (row m, column col).
+__device__ __forceinline__ void attn_store(const AttnArgs &a, int m, int col, float v) {
+  if (a.out) a.out[(size_t)m * a.d + col] = v;
+  if (a.o_planes) {
+    uint32_t hi, lo;
+    split_bf16(v, hi, lo);
+    uint16_t *rec = a.o_planes + ((size_t)(col >> 4) * a.CTS + (m >> 3)) * 256 + (m & 7) * 16 + (col & 15);
+    rec[0] = (uint16_t)hi;
+    rec[128] = (uint16_t)lo;
+  }
 }
 
 template <int HD>
@@ -53,8 +67,7 @@ __global__ __launch_bounds__(kAttnThreads) void attn_verify(AttnArgs a) {
   const int K = a.K, d = a.d, cap = a.cap;
   const int row0 = b * K;
   if (a.skip && a.skip[b]) {
-    for (int idx = tid; idx < K * HD; idx += kAttnThreads)
-      a.out[(size_t)(row0 + idx / HD) * d + h * HD + (idx % HD)] = 0.f;
+    for (int idx = tid; idx < K * HD; idx += kAttnThreads) attn_store(a, row0 + idx / HD, h * HD + (idx % HD), 0.f);
     return;
   }
   int P = a.prefix_len[b];
@@ -205,7 +218,7 @@ __global__ __launch_bounds__(kAttnThreads) void attn_verify(AttnArgs a) {
       float t = 0.f;
 #pragma unroll
       for (int w = 0; w < kAttnWaves; ++w) t += ored[(size_t)(w * kAttnQB + j) * HD + c];
-      a.out[(size_t)(row0 + j0 + j) * d + h * HD + c] = t * inv_l[j];
+      attn_store(a, row0 + j0 + j, h * HD + c, t * inv_l[j]);
     }
     __syncthreads();
   }

@@ -1,0 +1,283 @@
+// Verify forward for M = batch*K > 8 rows (several episodes verified in one pass: paper Sec. 2.2
+// "parallel verification", batched over episodes).
+//
+// Same exchange format as the M <= 8 kernels, widened by a column-tile index: the activation rows
+// are cut into column tiles of 8 rows, and for every 16-wide k-tile and every column tile there is
+// one 512-byte record [16][16] of bf16 (rows 0-7 = bf16 heads of the 8 activation rows, rows
+// 8-15 = tails, columns = 16 consecutive k), laid out [k-tile][column tile][16][16].  A record row
+// is a piece of one column of the MFMA B operand, so a lane loads its B fragment with one 16-byte
+// read.  Producers split every element once; no consumer converts anything.
+//
+// GEMM: a workgroup owns a list of 16-row weight tiles and multiplies up to NT of them per pass.
+// Its 8 waves are arranged MW x KW: MW groups of MC column tiles each, KW shares of the k-steps, so
+// few rows mean a deep k split (every wave streams different weight bytes) and many rows mean all
+// waves multiply the same weight fragments with different rows.  Weight fragments go from global
+// memory straight into the MFMA A layout through a ring kBatRing k-steps deep; B fragments are
+// double buffered.  The KW partial sums meet in LDS in a fixed order.  RMSNorm is folded in as in
+// the M <= 8 kernels: records hold x*gain, a small kernel turns per-tile partial sums of squares
+// into 1/rms per row, and the consuming GEMM scales its output rows.
+#pragma once
+#include "heisd_fast.h"
+
+namespace heisd {
+
+constexpr int kBatThreads = 512;
+constexpr int kBatWaves = 8;
+constexpr int kBatRing = 4;       // k-steps of weight fragments requested ahead, per tile
+
+struct BatGemm {
+  int epi;                // FEPI_STORE_ROWS, FEPI_RESID_NORM or FEPI_SWIGLU
+  const uint16_t *w[3];   // weight segments, bf16 row-major [rows][Kd]
+  int seg_tiles;          // n-tiles per segment
+  int n_units;            // n-tiles, or (gate, up) pairs for FEPI_SWIGLU
+  int Kd;
+  const uint16_t *b;      // records [2*ceil(Kd/32)][CTS][16][16]; a k-tile past Kd/16 is all zero
+  int CT;                 // column tiles in use = ceil(M/8)
+  int CTS;                // column tiles allocated per k-tile (the stride; fixed at init, so that the
+                          // zero k-tile stays where it is when M changes between calls)
+  int M;
+  const float *inv_rms;   // [CT*8] scale of each output row, or nullptr
+  float *out;             // STORE_ROWS: [M][ldo]; RESID_NORM: residual stream x [M][ldo], updated in place
+  int ldo;
+  const float *next_gain; // RESID_NORM: gain of the norm that consumes x next
+  uint16_t *o_planes;     // RESID_NORM / SWIGLU: records [unit][CTS][16][16]
+  float *ssq_out;         // RESID_NORM: [n_units][CTS*8] partial sums of squares of the new x
+  int MW;                 // waves across column tiles (1, 2, 4 or 8); the other 8/MW split k
+};
+
+template <int MC>
+constexpr size_t bat_lds_bytes() {
+  return (size_t)2 * kBatWaves * MC * 64 * 16;     // two tiles (gate and up) of per-wave accumulators
+}
+
+// Tile entry e of workgroup wg: weight rows and output unit.
+__device__ __forceinline__ void bat_tile(const BatGemm &g, int wg, int nwg, int e, const uint16_t *&wbase, int &wrow0,
+                                         int &unit) {
+  if (g.epi == FEPI_SWIGLU) {
+    unit = wg + (e >> 1) * nwg;
+    wbase = (e & 1) ? g.w[1] : g.w[0];
+    wrow0 = unit * 16;
+    return;
+  }
+  unit = wg + e * nwg;
+  const int seg = unit / g.seg_tiles;
+  wbase = seg == 0 ? g.w[0] : (seg == 1 ? g.w[1] : g.w[2]);
+  wrow0 = (unit - seg * g.seg_tiles) * 16;
+}
+
+// One output pair (row rr of this workgroup's row block, columns 2*c2, 2*c2+1) of tile entry e:
+// sum of the k shares and of head and tail columns, then the projection's epilogue.
+template <int MC>
+__device__ __forceinline__ void bat_epilogue(const BatGemm &g, int wg, int nwg, int e, int cb, const float *red) {
+  const int MW = g.MW, KW = kBatWaves / MW;
+  const int pairs = MW * MC * 64;                        // 8 rows x 8 pairs per column tile
+  const uint16_t *wbase;
+  int wrow0, unit;
+  bat_tile(g, wg, nwg, e, wbase, wrow0, unit);
+  for (int o = threadIdx.x; o < pairs; o += kBatThreads) {
+    const int c2 = o & 7, jm = (o >> 3) & 7, cc = o >> 6;            // cc = mw*MC + c
+    const int mw = cc / MC, c = cc - mw * MC;
+    const int ct = cb + cc;
+    if (ct >= g.CT) continue;                                          // uniform over the 8 lanes of a row
+    const int i = 2 * c2;
+    const int l_hi = (i >> 2) * 16 + jm, r = i & 3;
+    float s0 = 0.f, s1 = 0.f, u0 = 0.f, u1 = 0.f;
+    for (int kw = 0; kw < KW; ++kw) {
+      const float *p = red + ((size_t)((kw * MW + mw) * MC + c) * 64) * 4;
+      const float2 a = *reinterpret_cast<const float2 *>(p + l_hi * 4 + r);
+      const float2 b = *reinterpret_cast<const float2 *>(p + (l_hi + 8) * 4 + r);
+      s0 += a.x + b.x;
+      s1 += a.y + b.y;
+      if (g.epi == FEPI_SWIGLU) {
+        const float *q = p + (size_t)kBatWaves * MC * 256;
+        const float2 cg = *reinterpret_cast<const float2 *>(q + l_hi * 4 + r);
+        const float2 dg = *reinterpret_cast<const float2 *>(q + (l_hi + 8) * 4 + r);
+        u0 += cg.x + dg.x;
+        u1 += cg.y + dg.y;
+      }
+    }
+    const int m = ct * 8 + jm;
+    const bool live = m < g.M;
+    const float sc = g.inv_rms ? g.inv_rms[m] : 1.0f;
+    if (g.epi == FEPI_STORE_ROWS) {
+      if (live) *reinterpret_cast<float2 *>(g.out + (size_t)m * g.ldo + unit * 16 + i) = make_float2(s0 * sc, s1 * sc);
+      continue;
+    }
+    float a0 = 0.f, a1 = 0.f;
+    if (g.epi == FEPI_SWIGLU) {
+      const float g0 = s0 * sc, g1 = s1 * sc;
+      if (live) {
+        a0 = g0 / (1.0f + expf(-g0)) * (u0 * sc);
+        a1 = g1 / (1.0f + expf(-g1)) * (u1 * sc);
+      }
+    } else {
+      if (live) {
+        float *xp = g.out + (size_t)m * g.ldo + unit * 16 + i;
+        const float2 xo = *reinterpret_cast<const float2 *>(xp);
+        a0 = xo.x + s0 * sc;
+        a1 = xo.y + s1 * sc;
+        *reinterpret_cast<float2 *>(xp) = make_float2(a0, a1);
+      }
+      float q = a0 * a0 + a1 * a1;          // over the tile's 16 columns: 8 adjacent lanes
+      q += __shfl_xor(q, 4, kWave);
+      q += __shfl_xor(q, 2, kWave);
+      q += __shfl_xor(q, 1, kWave);
+      if (c2 == 0) g.ssq_out[(size_t)unit * (g.CTS * 8) + m] = q;
+      const float2 gn = *reinterpret_cast<const float2 *>(g.next_gain + unit * 16 + i);
+      a0 *= gn.x;
+      a1 *= gn.y;
+    }
+    uint32_t h0, l0, h1, l1;
+    split_bf16(a0, h0, l0);
+    split_bf16(a1, h1, l1);
+    uint32_t *rec = reinterpret_cast<uint32_t *>(g.o_planes + ((size_t)unit * g.CTS + ct) * 256);
+    rec[(jm * 16 + i) / 2] = h0 | (h1 << 16);
+    rec[((jm + 8) * 16 + i) / 2] = l0 | (l1 << 16);
+  }
+}
+
+template <int MC, int NT>
+__global__ __launch_bounds__(kBatThreads) void bat_gemm(BatGemm g) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  float *red = reinterpret_cast<float *>(smem);
+  const int wg = blockIdx.x, nwg = gridDim.x;
+  const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int lr = lane & 15, lg = lane >> 4;
+  const int MW = g.MW, KW = kBatWaves / MW;
+  const int mw = wave % MW, kw = wave / MW;
+  const int total = (g.Kd + 31) / 32;
+  const int ksw = (total + KW - 1) / KW;
+  const int ks0 = kw * ksw;
+  const int ns = max(0, min(ksw, total - ks0));
+  const bool swiglu = g.epi == FEPI_SWIGLU;
+  const int UT = swiglu ? 2 : 1;
+  const int my_units = g.n_units > wg ? (g.n_units - wg + nwg - 1) / nwg : 0;
+  const int my_entries = my_units * UT;
+  if (my_entries == 0) return;
+
+  for (int cb = 0; cb < g.CT; cb += MW * MC) {          // more than 64*MW... rows: weights are streamed again
+    // this wave's B fragments: column tiles cb + mw*MC + c (clamped; surplus results are dropped)
+    const uint16_t *bcol[MC];
+#pragma unroll
+    for (int c = 0; c < MC; ++c) {
+      const int ct = min(cb + mw * MC + c, g.CT - 1);
+      bcol[c] = g.b + ((size_t)(lg >> 1) * g.CTS + ct) * 256 + lr * 16 + (lg & 1) * 8;
+    }
+    const size_t bstep = (size_t)2 * g.CTS * 256;        // elements per k-step (two k-tiles)
+    for (int e0 = 0; e0 < my_entries; e0 += NT) {
+      const uint16_t *wrow[NT];
+#pragma unroll
+      for (int t = 0; t < NT; ++t) {
+        const uint16_t *wbase;
+        int wrow0, unit;
+        bat_tile(g, wg, nwg, min(e0 + t, my_entries - 1), wbase, wrow0, unit);
+        wrow[t] = wbase + (size_t)(wrow0 + lr) * g.Kd;
+      }
+      f32x4 acc[NT][MC];
+#pragma unroll
+      for (int t = 0; t < NT; ++t)
+#pragma unroll
+        for (int c = 0; c < MC; ++c) acc[t][c] = f32x4{0.f, 0.f, 0.f, 0.f};
+      u32x4 A[kBatRing][NT], Bc[MC];
+      if (ns > 0) {
+#pragma unroll
+        for (int c = 0; c < MC; ++c) Bc[c] = ld_g(bcol[c] + (size_t)ks0 * bstep);
+#pragma unroll
+        for (int u = 0; u < kBatRing; ++u)
+#pragma unroll
+          for (int t = 0; t < NT; ++t) A[u][t] = fast_ld_a(wrow[t], g.Kd, ks0 + u, lg);
+        for (int s0 = 0; s0 < ns; s0 += kBatRing) {
+#pragma unroll
+          for (int u = 0; u < kBatRing; ++u) {
+            const int s = s0 + u;
+            if (s < ns) {
+              u32x4 Bn[MC];
+              const int ksn = min(ks0 + s + 1, total - 1);
+#pragma unroll
+              for (int c = 0; c < MC; ++c) Bn[c] = ld_g(bcol[c] + (size_t)ksn * bstep);
+#pragma unroll
+              for (int t = 0; t < NT; ++t) {
+#pragma unroll
+                for (int c = 0; c < MC; ++c) acc[t][c] = fast_mfma(A[u][t], Bc[c], acc[t][c]);
+                A[u][t] = fast_ld_a(wrow[t], g.Kd, ks0 + s + kBatRing, lg);
+              }
+#pragma unroll
+              for (int c = 0; c < MC; ++c) Bc[c] = Bn[c];
+            }
+          }
+        }
+      }
+      // the KW partial sums meet in LDS; SwiGLU needs gate and up together, the others go tile by tile
+      if (swiglu) {
+        __syncthreads();
+#pragma unroll
+        for (int t = 0; t < 2 && t < NT; ++t)
+#pragma unroll
+          for (int c = 0; c < MC; ++c)
+            *reinterpret_cast<f32x4 *>(red + ((size_t)((t * kBatWaves + wave) * MC + c) * 64 + lane) * 4) = acc[t][c];
+        __syncthreads();
+        bat_epilogue<MC>(g, wg, nwg, e0, cb, red);
+      } else {
+#pragma unroll
+        for (int t = 0; t < NT; ++t) {
+          if (e0 + t < my_entries) {
+            __syncthreads();
+#pragma unroll
+            for (int c = 0; c < MC; ++c)
+              *reinterpret_cast<f32x4 *>(red + ((size_t)(wave * MC + c) * 64 + lane) * 4) = acc[t][c];
+            __syncthreads();
+            bat_epilogue<MC>(g, wg, nwg, e0 + t, cb, red);
+          }
+        }
+      }
+    }
+  }
+}
+
+// ---- embedding: x rows (fp32), records of x*gain, partial sums of squares --------------------------
+// One 16-column tile per workgroup (64 threads); thread (c2, jm) walks the column tiles.
+__global__ __launch_bounds__(64) void bat_embed(const int32_t *ids, const uint16_t *emb, int vocab, int d, int M, int CT, int CTS,
+                                                const float *gain, float *x, uint16_t *planes, float *ssq_out) {
+  const int tile = blockIdx.x, tid = threadIdx.x;
+  const int c2 = tid & 7, jm = tid >> 3;
+  const int col = tile * 16 + 2 * c2;
+  const float2 gn = *reinterpret_cast<const float2 *>(gain + col);
+  for (int ct = 0; ct < CT; ++ct) {
+    const int m = ct * 8 + jm;
+    float v0 = 0.f, v1 = 0.f;
+    if (m < M) {
+      int id = ids[m];
+      id = max(0, min(id, vocab - 1));
+      const uint32_t pr = *reinterpret_cast<const uint32_t *>(emb + (size_t)id * d + col);
+      v0 = __uint_as_float(pr << 16);
+      v1 = __uint_as_float(pr & 0xFFFF0000u);
+      *reinterpret_cast<float2 *>(x + (size_t)m * d + col) = make_float2(v0, v1);
+    }
+    float q = v0 * v0 + v1 * v1;
+    q += __shfl_xor(q, 4, kWave);
+    q += __shfl_xor(q, 2, kWave);
+    q += __shfl_xor(q, 1, kWave);
+    if (c2 == 0) ssq_out[(size_t)tile * (CTS * 8) + m] = q;
+    uint32_t h0, l0, h1, l1;
+    split_bf16(v0 * gn.x, h0, l0);
+    split_bf16(v1 * gn.y, h1, l1);
+    uint32_t *rec = reinterpret_cast<uint32_t *>(planes + ((size_t)tile * CTS + ct) * 256);
+    rec[(jm * 16 + 2 * c2) / 2] = h0 | (h1 << 16);
+    rec[((jm + 8) * 16 + 2 * c2) / 2] = l0 | (l1 << 16);
+  }
+}
+
+// inv_rms[m] = 1/sqrt(mean(x[m]^2) + eps) from the per-tile partial sums [n_tiles][stride] (fixed
+// order: lanes stride over the tiles, butterfly sum).  One wave per row.
+__global__ __launch_bounds__(kBatThreads) void bat_row_scales(const float *ssq, int n_tiles, int rows, int stride, int d,
+                                                             float eps, float *inv_rms) {
+  const int lane = threadIdx.x & 63;
+  const int m = blockIdx.x * kBatWaves + (threadIdx.x >> 6);
+  if (m >= rows) return;
+  float t = 0.f;
+  for (int p = lane; p < n_tiles; p += kWave) t += ssq[(size_t)p * stride + m];
+  t = wave_sum(t);
+  if (lane == 0) inv_rms[m] = rsqrtf(t / (float)d + eps);
+}
+
+}  // namespace heisd

@@ -22,7 +22,8 @@ def _need_gpu():
         pytest.skip("no GPU")
 
 
-def run_case(wl, plen_override=None, skip=None, rule=None, drafts_mode="auto", check_cache=True, path=0):
+def run_case(wl, plen_override=None, skip=None, rule=None, drafts_mode="auto", check_cache=True, path=0,
+             max_batch=None):
     from gpu_harness import run_gpu_step, compare_with_oracle
     _need_gpu()
     sh = wl.shape
@@ -40,21 +41,21 @@ def run_case(wl, plen_override=None, skip=None, rule=None, drafts_mode="auto", c
         bins = synth.make_drafts_uniform(wl)
     drafts = (sh.bin_base + bins).astype(np.int32)
     ref = oracle.verify_step(om, kb, vb, plen, first, drafts, rule, skip)
-    got = run_gpu_step(sh, weights, kb, vb, plen, first, drafts, rule, skip, path=path)
+    got = run_gpu_step(sh, weights, kb, vb, plen, first, drafts, rule, skip, path=path, max_batch=max_batch)
     stats = compare_with_oracle(got, ref, drafts, rule, sh, kb, vb, plen, skip)
     print(wl.name, "path", path, stats, "accepted", got["accepted_len"].tolist())
     return got, ref, stats
 
 
-@pytest.mark.parametrize("path", [0, 1, 2, 3])
+@pytest.mark.parametrize("path", [0, 1, 2, 3, 4])
 def test_c0_tiny_config(path):
-    """C0 through the automatic choice, the any-M path, the <=8-row kernels and the persistent kernel
+    """C0 through the automatic choice, both any-M paths, the <=8-row kernels and the persistent kernel
     (FFN width 688 = 21.5 k-steps: exercises the clamped tail of the reduction)."""
     got, ref, stats = run_case(synth.WORKLOADS["C0"], path=path)
     assert stats["max_logit_err_over_range"] < 3e-2
 
 
-@pytest.mark.parametrize("path", [1, 2, 3])
+@pytest.mark.parametrize("path", [1, 2, 3, 4])
 @pytest.mark.parametrize("shape_name,B,K,skip", [("mid", 1, 7, None), ("mid", 2, 4, [0, 1]), ("mid", 1, 8, None),
                                                  ("s64", 2, 3, None), ("s64", 1, 5, None)])
 def test_small_row_counts_on_both_paths(path, shape_name, B, K, skip):
@@ -79,12 +80,34 @@ def test_hd64_two_row_blocks_with_skips_k14():
     run_case(wl, skip=skip)
 
 
+@pytest.mark.parametrize("path", [1, 4])
 @pytest.mark.parametrize("B,K", [(3, 4), (2, 10), (5, 7), (1, 1), (9, 7)])
-def test_row_block_widths(B, K):
-    """M = 12, 20, 35, 1, 63: the 16-, 32- and 64-row variants, a single row, and K not a multiple
-    of the 8-query attention block."""
+def test_row_block_widths(B, K, path):
+    """M = 12, 20, 35, 1, 63: the 16-, 32- and 64-row variants of the first any-M path and the 2-, 4-, 7-
+    and 8-column-tile variants of the record path, a single row, and K not a multiple of the
+    8-query attention block."""
     wl = synth.Workload("w%dx%d" % (B, K), SMALL64, 8, 17, SMALL64.bin_base, batch=B, K=K, seed=B * 31 + K)
-    run_case(wl, rule=oracle.AcceptRule(15, 30))
+    run_case(wl, rule=oracle.AcceptRule(15, 30), path=path)
+
+
+@pytest.mark.parametrize("shape_name,B,K", [("s64", 10, 7), ("mid", 19, 7), ("s64", 24, 11), ("s64", 40, 13)])
+def test_wave_arrangements_of_the_record_path(shape_name, B, K):
+    """M = 70, 133, 264, 520 rows: 2, 4 and 8 wave groups across the rows (reduction split 4, 2, 1
+    ways), and more than 64 column tiles, where the weights are streamed twice."""
+    shape = MID if shape_name == "mid" else SMALL64
+    wl = synth.Workload("%s_%dx%d" % (shape_name, B, K), shape, 4, 9, shape.bin_base, batch=B, K=K,
+                        draft=("geometric", 0.5), seed=B + K)
+    run_case(wl, path=4)
+
+
+def test_context_sized_for_more_rows_than_the_call_uses():
+    """A context initialised for 12 episodes verifies 3 (the record stride is that of the context,
+    the column-tile count that of the call), on the automatic path and on the <=8-row path."""
+    wl = synth.Workload("wide_ctx", SMALL64, 6, 13, SMALL64.bin_base, batch=3, K=7, draft=("geometric", 0.5), seed=77)
+    run_case(wl, max_batch=12)
+    wl1 = synth.Workload("wide_ctx1", SMALL64, 6, 13, SMALL64.bin_base, batch=1, K=7, draft=("geometric", 0.5), seed=78)
+    run_case(wl1, max_batch=12)
+    run_case(wl1, max_batch=12, path=4)
 
 
 def test_strict_and_token_mode_rules_on_device():
