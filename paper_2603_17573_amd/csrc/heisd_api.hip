@@ -93,7 +93,7 @@ struct BatScratch {
     const size_t M = (size_t)d->max_batch * d->max_k;
     CTS = (int)((M + 7) / 8);
     if (CTS < 8) CTS = 8;
-    const size_t kd = 2 * (((size_t)d->d_model + 31) / 32), kf = 2 * (((size_t)d->d_ffn + 31) / 32);
+    const size_t kd = 2 * (((size_t)d->d_model + 31) / 32) + 2, kf = 2 * (((size_t)d->d_ffn + 31) / 32) + 2;   // + a zero k-step
     size_t off = 0;
     rec_x = off;   off += kd * CTS * 512;
     rec_o = off;   off += kd * CTS * 512;

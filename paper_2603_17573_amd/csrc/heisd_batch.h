@@ -12,9 +12,9 @@
 // Its 8 waves are arranged MW x KW: MW groups of MC column tiles each, KW shares of the k-steps, so
 // few rows mean a deep k split (every wave streams different weight bytes) and many rows mean all
 // waves multiply the same weight fragments with different rows.  Weight fragments go from global
-// memory straight into the MFMA A layout through a ring kBatRing k-steps deep; B fragments are
-// double buffered.  The KW partial sums meet in LDS in a fixed order.  RMSNorm is folded in as in
-// the M <= 8 kernels: records hold x*gain, a small kernel turns per-tile partial sums of squares
+// memory straight into the MFMA A layout through a ring kBatRing k-steps deep, and the B fragments
+// travel through the same ring.  The KW partial sums meet in LDS in a fixed order.  RMSNorm is
+// folded in as in the M <= 8 kernels: records hold x*gain, a small kernel turns per-tile partial sums of squares
 // into 1/rms per row, and the consuming GEMM scales its output rows.
 #pragma once
 #include "heisd_fast.h"
@@ -23,7 +23,7 @@ namespace heisd {
 
 constexpr int kBatThreads = 512;
 constexpr int kBatWaves = 8;
-constexpr int kBatRing = 4;       // k-steps of weight fragments requested ahead, per tile
+constexpr int kBatRing = 3;       // k-steps of fragments (weights and activations) requested ahead
 
 struct BatGemm {
   int epi;                // FEPI_STORE_ROWS, FEPI_RESID_NORM or FEPI_SWIGLU
@@ -31,7 +31,7 @@ struct BatGemm {
   int seg_tiles;          // n-tiles per segment
   int n_units;            // n-tiles, or (gate, up) pairs for FEPI_SWIGLU
   int Kd;
-  const uint16_t *b;      // records [2*ceil(Kd/32)][CTS][16][16]; a k-tile past Kd/16 is all zero
+  const uint16_t *b;      // records [2*ceil(Kd/32) + 2][CTS][16][16]; the k-tiles past Kd/16 are all zero
   int CT;                 // column tiles in use = ceil(M/8)
   int CTS;                // column tiles allocated per k-tile (the stride; fixed at init, so that the
                           // zero k-tile stays where it is when M changes between calls)
@@ -65,6 +65,14 @@ __device__ __forceinline__ void bat_tile(const BatGemm &g, int wg, int nwg, int 
   wrow0 = (unit - seg * g.seg_tiles) * 16;
 }
 
+// First column tile of wave group mw in the block that starts at cb: groups that would run past
+// the last tile are moved back so that every tile they read exists (tiles are then computed twice;
+// the epilogue takes each from the group bat_group_of names).  Needs CTS >= MC.
+template <int MC>
+__device__ __forceinline__ int bat_c0(int cb, int mw, int CT) {
+  return max(0, min(cb + mw * MC, CT - MC));
+}
+
 // One output pair (row rr of this workgroup's row block, columns 2*c2, 2*c2+1) of tile entry e:
 // sum of the k shares and of head and tail columns, then the projection's epilogue.
 template <int MC>
@@ -75,10 +83,10 @@ __device__ __forceinline__ void bat_epilogue(const BatGemm &g, int wg, int nwg, 
   int wrow0, unit;
   bat_tile(g, wg, nwg, e, wbase, wrow0, unit);
   for (int o = threadIdx.x; o < pairs; o += kBatThreads) {
-    const int c2 = o & 7, jm = (o >> 3) & 7, cc = o >> 6;            // cc = mw*MC + c
-    const int mw = cc / MC, c = cc - mw * MC;
+    const int c2 = o & 7, jm = (o >> 3) & 7, cc = o >> 6;
     const int ct = cb + cc;
     if (ct >= g.CT) continue;                                          // uniform over the 8 lanes of a row
+    const int mw = cc / MC, c = ct - bat_c0<MC>(cb, mw, g.CT);         // the wave group that holds tile ct, and where
     const int i = 2 * c2;
     const int l_hi = (i >> 2) * 16 + jm, r = i & 3;
     float s0 = 0.f, s1 = 0.f, u0 = 0.f, u1 = 0.f;
@@ -137,7 +145,7 @@ __device__ __forceinline__ void bat_epilogue(const BatGemm &g, int wg, int nwg, 
 }
 
 template <int MC, int NT>
-__global__ __launch_bounds__(kBatThreads) void bat_gemm(BatGemm g) {
+__global__ __launch_bounds__(kBatThreads) __attribute__((amdgpu_waves_per_eu(2, 2))) void bat_gemm(BatGemm g) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   float *red = reinterpret_cast<float *>(smem);
   const int wg = blockIdx.x, nwg = gridDim.x;
@@ -154,16 +162,11 @@ __global__ __launch_bounds__(kBatThreads) void bat_gemm(BatGemm g) {
   const int my_units = g.n_units > wg ? (g.n_units - wg + nwg - 1) / nwg : 0;
   const int my_entries = my_units * UT;
   if (my_entries == 0) return;
+  const size_t bstep = (size_t)2 * g.CTS * 256;          // elements per k-step (two k-tiles)
 
-  for (int cb = 0; cb < g.CT; cb += MW * MC) {          // more than 64*MW... rows: weights are streamed again
-    // this wave's B fragments: column tiles cb + mw*MC + c (clamped; surplus results are dropped)
-    const uint16_t *bcol[MC];
-#pragma unroll
-    for (int c = 0; c < MC; ++c) {
-      const int ct = min(cb + mw * MC + c, g.CT - 1);
-      bcol[c] = g.b + ((size_t)(lg >> 1) * g.CTS + ct) * 256 + lr * 16 + (lg & 1) * 8;
-    }
-    const size_t bstep = (size_t)2 * g.CTS * 256;        // elements per k-step (two k-tiles)
+  for (int cb = 0; cb < g.CT; cb += MW * MC) {            // more than MW*MC column tiles: weights are streamed again
+    // this lane's piece of the B fragment of column tile c0 + c at k-step ks: bfrag + ks*bstep + c*256
+    const uint16_t *bfrag = g.b + ((size_t)(lg >> 1) * g.CTS + bat_c0<MC>(cb, mw, g.CT)) * 256 + lr * 16 + (lg & 1) * 8;
     for (int e0 = 0; e0 < my_entries; e0 += NT) {
       const uint16_t *wrow[NT];
 #pragma unroll
@@ -178,33 +181,39 @@ __global__ __launch_bounds__(kBatThreads) void bat_gemm(BatGemm g) {
       for (int t = 0; t < NT; ++t)
 #pragma unroll
         for (int c = 0; c < MC; ++c) acc[t][c] = f32x4{0.f, 0.f, 0.f, 0.f};
-      u32x4 A[kBatRing][NT], Bc[MC];
+      // One ring for both operands, kBatRing k-steps deep: the fragments of step s + kBatRing are
+      // requested into the registers step s has just released.  (Loads return in order, so the two
+      // operands must be requested equally far ahead: a B fragment requested late would make the
+      // wait for it cover every weight fragment requested before it.)
+      // The loop body has no branch: steps past this wave's share read the all-zero k-step of the
+      // record buffer (and a clamped, valid weight address), so the trip count can be rounded up
+      // and the compiler's count of outstanding loads stays exact across the back edge.
+      u32x4 A[kBatRing][NT], B[kBatRing][MC];
       if (ns > 0) {
 #pragma unroll
-        for (int c = 0; c < MC; ++c) Bc[c] = ld_g(bcol[c] + (size_t)ks0 * bstep);
-#pragma unroll
-        for (int u = 0; u < kBatRing; ++u)
+        for (int u = 0; u < kBatRing; ++u) {
+          const int ksb = u < ns ? ks0 + u : total;
 #pragma unroll
           for (int t = 0; t < NT; ++t) A[u][t] = fast_ld_a(wrow[t], g.Kd, ks0 + u, lg);
+#pragma unroll
+          for (int c = 0; c < MC; ++c) B[u][c] = ld_g(bfrag + (size_t)ksb * bstep + c * 256);
+          __builtin_amdgcn_sched_barrier(0);        // same request order as in the loop body
+        }
         for (int s0 = 0; s0 < ns; s0 += kBatRing) {
 #pragma unroll
           for (int u = 0; u < kBatRing; ++u) {
-            const int s = s0 + u;
-            if (s < ns) {
-              u32x4 Bn[MC];
-              const int ksn = min(ks0 + s + 1, total - 1);
+            const int sn = s0 + u + kBatRing;
+            const int ksn = sn < ns ? ks0 + sn : total;
 #pragma unroll
-              for (int c = 0; c < MC; ++c) Bn[c] = ld_g(bcol[c] + (size_t)ksn * bstep);
+            for (int t = 0; t < NT; ++t) {
 #pragma unroll
-              for (int t = 0; t < NT; ++t) {
-#pragma unroll
-                for (int c = 0; c < MC; ++c) acc[t][c] = fast_mfma(A[u][t], Bc[c], acc[t][c]);
-                A[u][t] = fast_ld_a(wrow[t], g.Kd, ks0 + s + kBatRing, lg);
-              }
-#pragma unroll
-              for (int c = 0; c < MC; ++c) Bc[c] = Bn[c];
+              for (int c = 0; c < MC; ++c) acc[t][c] = fast_mfma(A[u][t], B[u][c], acc[t][c]);
+              A[u][t] = fast_ld_a(wrow[t], g.Kd, ks0 + sn, lg);
             }
-          }
+#pragma unroll
+            for (int c = 0; c < MC; ++c) B[u][c] = ld_g(bfrag + (size_t)ksn * bstep + c * 256);
+            __builtin_amdgcn_sched_barrier(0);      // the requests stay in this step: the scheduler may not
+          }                                         // sink them towards their use to save registers
         }
       }
       // the KW partial sums meet in LDS; SwiGLU needs gate and up together, the others go tile by tile

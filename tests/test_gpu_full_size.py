@@ -60,3 +60,57 @@ def test_c2_full_size_batch8_teacher_forced_drafts(big):
     stats = compare_with_oracle(got, ref, drafts, rule, sh, kb, vb, plen, None)
     print("C2", stats, got["accepted_len"].tolist(), ref["accepted_len"].tolist(), flush=True)
     assert len(set(ref["accepted_len"].tolist())) > 1          # acceptance lengths vary over the batch
+
+
+def _sampled_case(big, name, n_sample=3):
+    """Full batch on the GPU, the oracle on a sample of episodes (episodes do not interact: each
+    attends to its own cache rows only).  Sampled episodes get teacher-forced drafts with the
+    workload's geometric offsets, the others uniform drafts."""
+    from gpu_harness import run_gpu_step, compare_with_oracle
+    sh, weights, om, dm = big
+    wl = synth.WORKLOADS[name]
+    B, K = wl.batch, wl.K
+    cap = wl.prefix_len + K
+    skip = synth.make_skip_mask(wl) if wl.skip_p > 0 else None
+    eps = sorted({0, B // 2, B - 1})
+    if skip is not None:
+        live = [e for e in eps if not skip[e]]
+        if len(live) == len(eps):                       # the sample must hold a skipped episode
+            eps[-1] = int(np.flatnonzero(skip)[0])
+        if len(live) == 0:                              # ... and one that is verified
+            eps[0] = int(np.flatnonzero(skip == 0)[0])
+        eps = sorted(set(eps))
+    t0 = time.time()
+    kb, vb, plen, first = direct_prefix_cache(wl, cap)
+    print("%s: drew %d prefix caches in %.1f s" % (name, B, time.time() - t0), flush=True)
+    bins = synth.make_drafts_uniform(wl)
+    off = synth.make_offsets_geometric(wl, wl.draft[1])
+    t0 = time.time()
+    kbs, vbs = np.ascontiguousarray(kb[:, eps]), np.ascontiguousarray(vb[:, eps])
+    bins[eps] = teacher_forced_drafts(om, wl, kbs, vbs, plen[eps], first[eps], off[eps])
+    drafts = (sh.bin_base + bins).astype(np.int32)
+    rule = oracle.AcceptRule(wl.tau_tok, wl.tau_seq)
+    ref = oracle.verify_step(om, kbs, vbs, plen[eps], first[eps], drafts[eps], rule,
+                             None if skip is None else skip[eps])
+    print("%s: oracle on episodes %s in %.1f s" % (name, eps, time.time() - t0), flush=True)
+    got = run_gpu_step(sh, weights, kb, vb, plen, first, drafts, rule, skip, model=dm)
+    stats = compare_with_oracle(got, ref, drafts, rule, sh, kb, vb, plen, skip, episodes=eps)
+    print(name, stats, got["accepted_len"].tolist(), flush=True)
+    # properties that hold for every episode, sampled or not
+    acc = got["accepted_len"]
+    assert np.all((acc >= 0) & (acc <= K))
+    if skip is not None:
+        assert np.all(acc[skip.astype(bool)] == K) and np.all(got["next_token"][skip.astype(bool)] == -1)
+    livem = np.ones(B, bool) if skip is None else ~skip.astype(bool)
+    nt = got["next_token"][livem]
+    assert np.all((nt >= sh.bin_base) & (nt < sh.bin_base + sh.n_bins))
+    assert np.all(np.isfinite(got["bin_logits"][livem]))
+    return got, ref
+
+
+def test_c3_full_size_batch16_k14_with_skips_sampled(big):
+    _sampled_case(big, "C3")
+
+
+def test_c4_full_size_batch64_sampled(big):
+    _sampled_case(big, "C4")
