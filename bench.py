@@ -168,19 +168,29 @@ def main():
         import oracle
         from helpers import oracle_model
         om = oracle_model(sh, weights)
-        n_ep = 1                                   # bounded sample: one episode of the workload
-        kb1 = kb_host[:, None]
-        vb1 = vb_host[:, None]
-        t0 = time.perf_counter()
-        ref = oracle.verify_step(om, kb1, vb1, [P], first[:1], drafts[:1],
-                                 oracle.AcceptRule(wl.tau_tok, wl.tau_seq))
-        dt = time.perf_counter() - t0
+        # bounded sample: oracle verify steps over successive episodes of the workload's recipe, until
+        # about 12 s of oracle time have been spent (drawing an episode's prefix K/V is not timed)
+        rule = oracle.AcceptRule(wl.tau_tok, wl.tau_seq)
+        spent, n_done, ref_acc = 0.0, 0, []
+        while spent < 12.0 and n_done < 64:
+            e = n_done
+            if e == 0:
+                k1, v1, f1 = kb_host, vb_host, first[0]
+            else:
+                k1, v1, f1 = synth.make_prefix_kv_direct(wl, e % max(B, 1) if B > 1 else e, cap)
+            d1 = drafts[e % B][None, :]
+            t0 = time.perf_counter()
+            ref = oracle.verify_step(om, k1[:, None], v1[:, None], [P], np.array([f1], np.int32), d1, rule)
+            spent += time.perf_counter() - t0
+            n_done += 1
+            ref_acc.append(int(ref["accepted_len"][0]))
         cores = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
         cores = min(cores, os.cpu_count() or cores)
-        cpu = {"value": round(n_ep / B / dt, 5), "unit": "verify steps/s", "cores": cores, "kind": "oracle",
-               "sample": "1 oracle verify step over episode 0 of %s (K=%d rows through all %d layers), "
-                         "%.1f s wall" % (wl.name, K, sh.n_layers, dt),
-               "oracle_accepted_len": int(ref["accepted_len"][0])}
+        # one verify step of the workload covers B episodes
+        cpu = {"value": round(n_done / B / spent, 5), "unit": "verify steps/s", "cores": cores, "kind": "oracle",
+               "sample": "%d oracle verify steps over single episodes of %s (K=%d rows through all %d layers each), "
+                         "%.1f s of oracle time" % (n_done, wl.name, K, sh.n_layers, spent),
+               "oracle_accepted_len": ref_acc[:8]}
 
     line = {
         "metric": "verify steps/s (7B-shaped decoder, K=7, bs=1)" if wl.name == "C1" else

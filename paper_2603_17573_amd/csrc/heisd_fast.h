@@ -330,6 +330,9 @@ __device__ __forceinline__ void fast_gemm_stream_phase(const FastGemm &g, int wg
     return;
   }
   const int ksw = fast_ksw(g.Kd), ks0 = wave * ksw, ns = fast_steps(g.Kd, wave);
+  // Steps past this wave's share are multiplied with zero records; their weight fragment is read
+  // from the wave's own last step (a line it has just fetched), not from the next wave's share.
+  const int ks_last = ks0 + max(ns, 1) - 1;
   for (int e = 0; e < my_entries; ++e) {
     const uint16_t *wbase;
     int wrow0, unit;
@@ -340,7 +343,7 @@ __device__ __forceinline__ void fast_gemm_stream_phase(const FastGemm &g, int wg
     const EpiPre ep = fast_epilogue_preload(g, wg, nwg, e, 1);
     if (!(pre && e == 0)) {
 #pragma unroll
-      for (int s = 0; s < kKS; ++s) A.v[s] = fast_ld_a(wrow, g.Kd, ks0 + s, lg);
+      for (int s = 0; s < kKS; ++s) A.v[s] = fast_ld_a(wrow, g.Kd, min(ks0 + s, ks_last), lg);
     }
 #pragma unroll
     for (int s = 0; s < kKS; ++s) Bs.v[s] = fast_ld_b(g.b, g.Kd, ks0, s, ns, lr, lg);
@@ -349,7 +352,7 @@ __device__ __forceinline__ void fast_gemm_stream_phase(const FastGemm &g, int wg
 #pragma unroll
         for (int s = 0; s < kKS; ++s) {
           acc = fast_mfma(A.v[s], Bs.v[s], acc);
-          A.v[s] = fast_ld_a(wrow, g.Kd, ks0 + base + kKS + s, lg);
+          A.v[s] = fast_ld_a(wrow, g.Kd, min(ks0 + base + kKS + s, ks_last), lg);
           Bs.v[s] = fast_ld_b(g.b, g.Kd, ks0, base + kKS + s, ns, lr, lg);
         }
       } else {
