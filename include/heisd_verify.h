@@ -106,12 +106,17 @@ typedef struct {
 } heisd_accept_desc;
 
 /* Bytes of device workspace heisd_verify_init needs for this model description
- * (depends only on the shape fields).  Returns 0 if the description is invalid. */
+ * (depends only on the shape fields).  Returns 0 if the description is invalid.
+ * The workspace holds, besides activations and exchange buffers, one copy of every projection
+ * matrix (and of the n_bins LM-head rows) in the order the matrix cores consume them, so it is
+ * a little larger than the decoder's weights (13.1 GB at the 7B shape). */
 size_t heisd_verify_workspace_bytes(const heisd_model_desc *desc);
 
 /*
  * Validate the description, copy the pointer tables, lay out the workspace, build the
- * rotary table.  May synchronise the device.  *out receives a context to be released
+ * rotary table, copy the projection matrices into the workspace in fragment order (the weights
+ * must hold their final values when init is called; later changes to them are not seen by the
+ * record kernels).  Synchronises the device.  *out receives a context to be released
  * with heisd_free.  Not thread-safe; one step in flight per context.
  * Errors: EINVAL (NULL pointers, non-positive sizes, d_model != n_heads*head_dim,
  * bins outside the vocabulary), EUNSUPPORTED (head_dim not 64 or 128, d_model or d_ffn

@@ -24,6 +24,9 @@ struct heisd_verify_ctx {
   heisd_model_desc d;
   std::vector<const void *> wq, wk, wv, wo, w_gate, w_up, w_down;
   std::vector<const float *> attn_norm, ffn_norm;
+  // copies of the matrices in MFMA fragment order (see fast_pack_weights), in the workspace
+  std::vector<const uint16_t *> pq, pk, pv, po, pg, pu, pd;
+  const uint16_t *plm = nullptr;       // the n_bins LM-head rows
   // workspace carve-up
   float2 *rope;
   float *x, *qkv, *attn_o, *act, *logits;
@@ -82,7 +85,7 @@ static int fail(heisd_verify_ctx *ctx, int code, const char *fmt, ...) {
 static size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
 
 struct WsLayout {
-  size_t rope, x, qkv, attn_o, act, logits, tbins, fscr, fscr_bytes, bscr, bscr_bytes, players, flags, trace, total;
+  size_t rope, x, qkv, attn_o, act, logits, tbins, fscr, fscr_bytes, bscr, bscr_bytes, players, flags, trace, packed, packed_bytes, total;
 };
 
 // Buffers of the batched path (M > 8 rows).  One launch per phase, so one set serves every layer.
@@ -153,6 +156,12 @@ static WsLayout ws_layout(const heisd_model_desc *d) {
   w.players = off; off += align256((size_t)(5 * d->n_layers + 2) * sizeof(Phase));
   w.flags = off;   off += align256((size_t)(1024 + 1) * kFlagStride * sizeof(unsigned));
   w.trace = off;   off += align256((size_t)(5 * d->n_layers + 2) * 8 * sizeof(unsigned long long));
+  w.packed = off;
+  const size_t per_layer = 4 * align256(fast_packed_elems(d->d_model, d->d_model) * 2) +
+                           2 * align256(fast_packed_elems(d->d_ffn, d->d_model) * 2) +
+                           align256(fast_packed_elems(d->d_model, d->d_ffn) * 2);
+  w.packed_bytes = per_layer * (size_t)d->n_layers + align256(fast_packed_elems(d->n_bins, d->d_model) * 2);
+  off += w.packed_bytes;
   w.total = off;
   return w;
 }
@@ -210,6 +219,39 @@ static void gemm_launch(GemmArgs a, int M, int epi, hipStream_t st) {
   }
 }
 
+// ---- weights in fragment order ------------------------------------------------------------
+
+static hipError_t pack_one(const void *src, int rows, int Kd, unsigned char *&cursor, const uint16_t *&out) {
+  uint16_t *dst = reinterpret_cast<uint16_t *>(cursor);
+  const size_t pieces = fast_packed_elems(rows, Kd) / 8;
+  const unsigned grid = (unsigned)((pieces + 255) / 256 < 65535 * 16 ? (pieces + 255) / 256 : 65535 * 16);
+  fast_pack_weights<<<dim3(grid), dim3(256)>>>(static_cast<const uint16_t *>(src), rows, Kd, dst);
+  out = dst;
+  cursor += align256(fast_packed_elems(rows, Kd) * 2);
+  return hipGetLastError();
+}
+
+// Copies every matrix the record kernels multiply into the workspace, in fragment order (init only).
+static hipError_t pack_all(heisd_verify_ctx *c, unsigned char *cursor) {
+  const heisd_model_desc &d = c->d;
+  const int L = d.n_layers, dm = d.d_model, F = d.d_ffn;
+  c->pq.resize(L); c->pk.resize(L); c->pv.resize(L); c->po.resize(L); c->pg.resize(L); c->pu.resize(L); c->pd.resize(L);
+  hipError_t e = hipSuccess;
+  for (int l = 0; l < L && e == hipSuccess; ++l) {
+    e = pack_one(c->wq[l], dm, dm, cursor, c->pq[l]);
+    if (e == hipSuccess) e = pack_one(c->wk[l], dm, dm, cursor, c->pk[l]);
+    if (e == hipSuccess) e = pack_one(c->wv[l], dm, dm, cursor, c->pv[l]);
+    if (e == hipSuccess) e = pack_one(c->wo[l], dm, dm, cursor, c->po[l]);
+    if (e == hipSuccess) e = pack_one(c->w_gate[l], F, dm, cursor, c->pg[l]);
+    if (e == hipSuccess) e = pack_one(c->w_up[l], F, dm, cursor, c->pu[l]);
+    if (e == hipSuccess) e = pack_one(c->w_down[l], dm, F, cursor, c->pd[l]);
+  }
+  if (e == hipSuccess)
+    e = pack_one(static_cast<const uint16_t *>(d.lm_head) + (size_t)d.bin_token_base * dm, d.n_bins, dm, cursor, c->plm);
+  if (e == hipSuccess) e = hipDeviceSynchronize();
+  return e;
+}
+
 // ---- fast path (M <= 8 rows) ------------------------------------------------------------
 
 static hipError_t fast_prepare(int hd, int cap) {
@@ -245,7 +287,7 @@ static FastGemm fast_lm_desc(const heisd_verify_ctx *ctx, int M, float *logits) 
   unsigned char *base = ctx->fscr + fs.stride * (size_t)d.n_layers;
   FastGemm g{};
   g.epi = FEPI_STORE_ROWS;
-  g.w[0] = static_cast<const uint16_t *>(d.lm_head) + (size_t)d.bin_token_base * d.d_model;
+  g.w[0] = ctx->plm;
   g.seg_tiles = d.n_bins / 16; g.n_units = d.n_bins / 16; g.Kd = d.d_model;
   g.b = reinterpret_cast<const uint16_t *>(base + fs.rec_x_a);
   g.ssq = reinterpret_cast<const float *>(base + fs.ssq_a);
@@ -263,9 +305,9 @@ static FastLayerDescs fast_layer_descs(const heisd_verify_ctx *ctx, const heisd_
   FastLayerDescs L{};
   FastGemm &q = L.qkv;
   q.epi = FEPI_STORE_REC;
-  q.w[0] = static_cast<const uint16_t *>(ctx->wq[l]);
-  q.w[1] = static_cast<const uint16_t *>(ctx->wk[l]);
-  q.w[2] = static_cast<const uint16_t *>(ctx->wv[l]);
+  q.w[0] = ctx->pq[l];
+  q.w[1] = ctx->pk[l];
+  q.w[2] = ctx->pv[l];
   q.seg_tiles = dm / 16; q.n_units = 3 * dm / 16; q.Kd = dm;
   q.b = reinterpret_cast<const uint16_t *>(base + fs.rec_x_a);
   q.ssq = reinterpret_cast<const float *>(base + fs.ssq_a);
@@ -281,7 +323,7 @@ static FastLayerDescs fast_layer_descs(const heisd_verify_ctx *ctx, const heisd_
   a.K = K; a.H = H; a.cap = cap; a.d = dm; a.batch = batch; a.scale = 1.0f / std::sqrt((float)HD);
   FastGemm &o = L.oproj;
   o.epi = FEPI_RESID_NORM;
-  o.w[0] = static_cast<const uint16_t *>(ctx->wo[l]);
+  o.w[0] = ctx->po[l];
   o.seg_tiles = dm / 16; o.n_units = dm / 16; o.Kd = dm;
   o.b = reinterpret_cast<const uint16_t *>(base + fs.rec_attn);
   o.ssq = nullptr; o.M = M; o.out = ctx->x; o.ldo = dm; o.next_gain = ctx->ffn_norm[l];
@@ -289,8 +331,8 @@ static FastLayerDescs fast_layer_descs(const heisd_verify_ctx *ctx, const heisd_
   o.ssq_out = reinterpret_cast<float *>(base + fs.ssq_b);
   FastGemm &g = L.gateup;
   g.epi = FEPI_SWIGLU;
-  g.w[0] = static_cast<const uint16_t *>(ctx->w_gate[l]);
-  g.w[1] = static_cast<const uint16_t *>(ctx->w_up[l]);
+  g.w[0] = ctx->pg[l];
+  g.w[1] = ctx->pu[l];
   g.seg_tiles = F / 16; g.n_units = F / 16; g.Kd = dm;
   g.b = reinterpret_cast<const uint16_t *>(base + fs.rec_x_b);
   g.ssq = reinterpret_cast<const float *>(base + fs.ssq_b);
@@ -298,7 +340,7 @@ static FastLayerDescs fast_layer_descs(const heisd_verify_ctx *ctx, const heisd_
   g.o_planes = reinterpret_cast<uint16_t *>(base + fs.rec_act);
   FastGemm &w = L.down;
   w.epi = FEPI_RESID_NORM;
-  w.w[0] = static_cast<const uint16_t *>(ctx->w_down[l]);
+  w.w[0] = ctx->pd[l];
   w.seg_tiles = dm / 16; w.n_units = dm / 16; w.Kd = F;
   w.b = reinterpret_cast<const uint16_t *>(base + fs.rec_act);
   w.ssq = nullptr; w.M = M; w.out = ctx->x; w.ldo = dm;
@@ -514,6 +556,7 @@ extern "C" int heisd_verify_init(const heisd_model_desc *desc, heisd_verify_ctx 
     if (e == hipSuccess) c->n_cu = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
   }
   if (e == hipSuccess) e = hipMemset(base + w.flags, 0, (size_t)(1024 + 1) * kFlagStride * sizeof(unsigned));
+  if (e == hipSuccess) e = pack_all(c, base + w.packed);
   if (e == hipSuccess) e = fast_prepare(desc->head_dim, desc->kv_capacity);
   if (e == hipSuccess) e = persist_prepare(c);
   if (e == hipSuccess && c->persist_ok) e = persist_build_program(c);
@@ -703,9 +746,9 @@ static void batch_forward(heisd_verify_ctx *ctx, const heisd_kv_desc *kv, const 
     // q, k, v = RMSNorm(x) . {Wq, Wk, Wv}^T  (fp32 rows for the attention kernel)
     BatGemm g = base;
     g.epi = FEPI_STORE_ROWS;
-    g.w[0] = static_cast<const uint16_t *>(ctx->wq[l]);
-    g.w[1] = static_cast<const uint16_t *>(ctx->wk[l]);
-    g.w[2] = static_cast<const uint16_t *>(ctx->wv[l]);
+    g.w[0] = ctx->pq[l];
+    g.w[1] = ctx->pk[l];
+    g.w[2] = ctx->pv[l];
     g.seg_tiles = dm / 16; g.n_units = 3 * dm / 16; g.Kd = dm;
     g.b = rec_x; g.inv_rms = inv_rms; g.out = ctx->qkv; g.ldo = 3 * dm;
     { ProfScope ps(ctx, HEISD_KC_QKV, st, prof); bat_launch(g, ctx->n_cu, st); }
@@ -725,7 +768,7 @@ static void batch_forward(heisd_verify_ctx *ctx, const heisd_kv_desc *kv, const 
     // x += o . Wo^T; records of x * ffn gain, partial sums of squares
     g = base;
     g.epi = FEPI_RESID_NORM;
-    g.w[0] = static_cast<const uint16_t *>(ctx->wo[l]);
+    g.w[0] = ctx->po[l];
     g.seg_tiles = dm / 16; g.n_units = dm / 16; g.Kd = dm;
     g.b = rec_o; g.inv_rms = nullptr; g.out = ctx->x; g.ldo = dm;
     g.next_gain = ctx->ffn_norm[l]; g.o_planes = rec_x; g.ssq_out = ssq;
@@ -737,15 +780,15 @@ static void batch_forward(heisd_verify_ctx *ctx, const heisd_kv_desc *kv, const 
     // a = silu(RMSNorm(x) . Wg^T) * (RMSNorm(x) . Wu^T), as records
     g = base;
     g.epi = FEPI_SWIGLU;
-    g.w[0] = static_cast<const uint16_t *>(ctx->w_gate[l]);
-    g.w[1] = static_cast<const uint16_t *>(ctx->w_up[l]);
+    g.w[0] = ctx->pg[l];
+    g.w[1] = ctx->pu[l];
     g.seg_tiles = F / 16; g.n_units = F / 16; g.Kd = dm;
     g.b = rec_x; g.inv_rms = inv_rms; g.o_planes = rec_act;
     { ProfScope ps(ctx, HEISD_KC_GATEUP, st, prof); bat_launch(g, ctx->n_cu, st); }
     // x += a . Wd^T; records of x * (next norm's gain), partial sums of squares
     g = base;
     g.epi = FEPI_RESID_NORM;
-    g.w[0] = static_cast<const uint16_t *>(ctx->w_down[l]);
+    g.w[0] = ctx->pd[l];
     g.seg_tiles = dm / 16; g.n_units = dm / 16; g.Kd = F;
     g.b = rec_act; g.inv_rms = nullptr; g.out = ctx->x; g.ldo = dm;
     g.next_gain = (l + 1 < d.n_layers) ? ctx->attn_norm[l + 1] : d.final_norm;
@@ -759,7 +802,7 @@ static void batch_forward(heisd_verify_ctx *ctx, const heisd_kv_desc *kv, const 
   // logits over the action bins = RMSNorm(x; final) . W_lm[bin rows]^T
   BatGemm g = base;
   g.epi = FEPI_STORE_ROWS;
-  g.w[0] = static_cast<const uint16_t *>(d.lm_head) + (size_t)d.bin_token_base * dm;
+  g.w[0] = ctx->plm;
   g.seg_tiles = d.n_bins / 16; g.n_units = d.n_bins / 16; g.Kd = dm;
   g.b = rec_x; g.inv_rms = inv_rms; g.out = logits; g.ldo = d.n_bins;
   ProfScope ps(ctx, HEISD_KC_LMHEAD, st, prof);

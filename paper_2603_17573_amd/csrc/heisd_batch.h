@@ -27,7 +27,7 @@ constexpr int kBatRing = 3;       // k-steps of fragments (weights and activatio
 
 struct BatGemm {
   int epi;                // FEPI_STORE_ROWS, FEPI_RESID_NORM or FEPI_SWIGLU
-  const uint16_t *w[3];   // weight segments, bf16 row-major [rows][Kd]
+  const uint16_t *w[3];   // weight segments, bf16, in the packed fragment order of fast_pack_weights
   int seg_tiles;          // n-tiles per segment
   int n_units;            // n-tiles, or (gate, up) pairs for FEPI_SWIGLU
   int Kd;
@@ -168,13 +168,13 @@ __global__ __launch_bounds__(kBatThreads) __attribute__((amdgpu_waves_per_eu(2, 
     // this lane's piece of the B fragment of column tile c0 + c at k-step ks: bfrag + ks*bstep + c*256
     const uint16_t *bfrag = g.b + ((size_t)(lg >> 1) * g.CTS + bat_c0<MC>(cb, mw, g.CT)) * 256 + lr * 16 + (lg & 1) * 8;
     for (int e0 = 0; e0 < my_entries; e0 += NT) {
-      const uint16_t *wrow[NT];
+      const uint16_t *wf[NT];
 #pragma unroll
       for (int t = 0; t < NT; ++t) {
         const uint16_t *wbase;
         int wrow0, unit;
         bat_tile(g, wg, nwg, min(e0 + t, my_entries - 1), wbase, wrow0, unit);
-        wrow[t] = wbase + (size_t)(wrow0 + lr) * g.Kd;
+        wf[t] = fast_wfrag(wbase, wrow0, g.Kd, lane);
       }
       f32x4 acc[NT][MC];
 #pragma unroll
@@ -194,7 +194,7 @@ __global__ __launch_bounds__(kBatThreads) __attribute__((amdgpu_waves_per_eu(2, 
         for (int u = 0; u < kBatRing; ++u) {
           const int ksb = u < ns ? ks0 + u : total;
 #pragma unroll
-          for (int t = 0; t < NT; ++t) A[u][t] = fast_ld_a(wrow[t], g.Kd, ks0 + u, lg);
+          for (int t = 0; t < NT; ++t) A[u][t] = fast_ld_a(wf[t], g.Kd, ks0 + u);
 #pragma unroll
           for (int c = 0; c < MC; ++c) B[u][c] = ld_g(bfrag + (size_t)ksb * bstep + c * 256);
           __builtin_amdgcn_sched_barrier(0);        // same request order as in the loop body
@@ -208,7 +208,7 @@ __global__ __launch_bounds__(kBatThreads) __attribute__((amdgpu_waves_per_eu(2, 
             for (int t = 0; t < NT; ++t) {
 #pragma unroll
               for (int c = 0; c < MC; ++c) acc[t][c] = fast_mfma(A[u][t], B[u][c], acc[t][c]);
-              A[u][t] = fast_ld_a(wrow[t], g.Kd, ks0 + sn, lg);
+              A[u][t] = fast_ld_a(wf[t], g.Kd, ks0 + sn);
             }
 #pragma unroll
             for (int c = 0; c < MC; ++c) B[u][c] = ld_g(bfrag + (size_t)ksn * bstep + c * 256);

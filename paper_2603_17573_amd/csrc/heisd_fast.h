@@ -22,7 +22,8 @@
 // -----------
 // A workgroup (8 waves) owns a list of 16-row weight tiles over the whole reduction; wave w owns
 // a contiguous share of the k-steps.  Weight tiles go straight from HBM into the MFMA A-operand
-// register layout (lane l: 16 bytes at W[n0 + l%16][k + 8*(l/16)]); the waves are reduced through
+// register layout (lane l: 16 bytes = W[n0 + l%16][k + 8*(l/16) .. +8), read from a copy of the
+// weights stored in exactly that order); the waves are reduced through
 // LDS in a fixed order.  A wave keeps one ring of 16 weight fragments: a fragment's registers are
 // refilled with the same k-step of the next tile right after the MFMA that consumed it, so 16
 // loads (16 KB) per wave are always in flight.  For Kd <= 4096 the wave's 16 B fragments stay in
@@ -56,7 +57,7 @@ __device__ __forceinline__ void st_dev2(float *p, float a, float b) {
 
 struct FastGemm {
   int epi;                // FEPI_*: how tiles map to units and what the epilogue does
-  const uint16_t *w[3];   // weight segments, bf16 row-major [rows][Kd]
+  const uint16_t *w[3];   // weight segments, bf16, in the packed fragment order of fast_pack_weights
   int seg_tiles;          // n-tiles per segment
   int n_units;            // n-tiles, or (gate, up) pairs for FEPI_SWIGLU
   int Kd;
@@ -119,12 +120,38 @@ __device__ __forceinline__ int fast_my_entries(const FastGemm &g, int wg, int nw
 // with zero records for that purpose.
 __host__ __device__ __forceinline__ int fast_plane_records(int Kd) { return 2 * ((Kd + 31) / 32) + 2; }
 
-// Weight fragment of k-step `ks` (clamped into the matrix) for lane group lg; wrow = this lane's row.
-__device__ __forceinline__ u32x4 fast_ld_a(const uint16_t *wrow, int Kd, int ks, int lg) {
+// Weights are read from a copy made once at init, laid out the way the MFMA consumes them:
+// [16-row tile][k-step of 32][lane][8 bf16], lane l holding W[16*tile + l%16][32*ks + 8*(l/16) .. +8)
+// (k past Kd is stored as zero).  A fragment load is then 1 KB of consecutive bytes and a wave's
+// walk along k is one sequential stream, instead of 64-byte pieces of 16 rows that lie a whole
+// matrix row apart: measured 4 % of the step at M = 7 (mostly the down projection, whose rows are
+// 22 KB long) and 18 % at M = 56.
+__host__ __device__ __forceinline__ size_t fast_packed_elems(int rows, int Kd) {
+  return (size_t)(rows / 16) * (size_t)((Kd + 31) / 32) * 512;
+}
+// This lane's piece of k-step 0 of the tile that starts at row wrow0 (a multiple of 16).
+__device__ __forceinline__ const uint16_t *fast_wfrag(const uint16_t *wbase, int wrow0, int Kd, int lane) {
+  return wbase + ((size_t)(wrow0 >> 4) * (size_t)((Kd + 31) / 32) * 64 + lane) * 8;
+}
+// Weight fragment of k-step `ks` (clamped into the matrix).
+__device__ __forceinline__ u32x4 fast_ld_a(const uint16_t *wfrag, int Kd, int ks) {
   const int total = (Kd + 31) / 32;
-  const int kse = min(ks, total - 1);
-  const int k = min(kse * 32 + lg * 8, Kd - 8);
-  return ld_g(wrow + k);
+  return ld_g(wfrag + (size_t)min(ks, total - 1) * 512);
+}
+// The copy: one thread per 16-byte piece of dst.
+__global__ __launch_bounds__(256) void fast_pack_weights(const uint16_t *src, int rows, int Kd, uint16_t *dst) {
+  const int KS = (Kd + 31) / 32;
+  const size_t n = (size_t)(rows / 16) * KS * 64;
+  for (size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x; idx < n; idx += (size_t)gridDim.x * 256) {
+    const int lane = (int)(idx & 63);
+    const size_t q = idx >> 6;
+    const int ks = (int)(q % KS);
+    const size_t tile = q / KS;
+    const int k = ks * 32 + (lane >> 4) * 8;
+    uint4 v = make_uint4(0, 0, 0, 0);
+    if (k + 8 <= Kd) v = *reinterpret_cast<const uint4 *>(src + (tile * 16 + (lane & 15)) * (size_t)Kd + k);
+    *reinterpret_cast<uint4 *>(dst + idx * 8) = v;
+  }
 }
 // B fragment of step `s` of a wave that owns `ns` steps from ks0 (the zero records if s >= ns):
 // record ks*2 + lg/2, row lr, half lg&1.
@@ -145,9 +172,9 @@ __device__ __forceinline__ void fast_issue16(Frag16 &A, const FastGemm &g, int w
   int wrow0, unit;
   if (!fast_tile(g, wg, nwg, e, wbase, wrow0, unit)) return;   // uniform: the ring stays unused
   const int ks0 = wave * fast_ksw(g.Kd);
-  const uint16_t *wrow = wbase + (size_t)(wrow0 + lr) * g.Kd;
+  const uint16_t *wf = fast_wfrag(wbase, wrow0, g.Kd, lg * 16 + lr);
 #pragma unroll
-  for (int s = 0; s < kKS; ++s) A.v[s] = fast_ld_a(wrow, g.Kd, ks0 + s, lg);
+  for (int s = 0; s < kKS; ++s) A.v[s] = fast_ld_a(wf, g.Kd, ks0 + s);
 }
 
 // LDS of a GEMM phase: reduction buffer [waves][kMaxT][64 lanes][4] + 8 scales.
@@ -292,11 +319,11 @@ __device__ __forceinline__ void fast_gemm_phase(const FastGemm &g, int wg, int n
           const uint16_t *wbase;
           int wrow0, unit;
           fast_tile(g, wg, nwg, e0 + t + 1, wbase, wrow0, unit);
-          const uint16_t *wrow = wbase + (size_t)(wrow0 + lr) * g.Kd;
+          const uint16_t *wf = fast_wfrag(wbase, wrow0, g.Kd, lane);
 #pragma unroll
           for (int s = 0; s < kKS; ++s) {
             acc[t] = fast_mfma(A.v[s], Bf.v[s], acc[t]);
-            A.v[s] = fast_ld_a(wrow, g.Kd, ks0 + s, lg);
+            A.v[s] = fast_ld_a(wf, g.Kd, ks0 + s);
           }
         } else {
 #pragma unroll
@@ -337,13 +364,13 @@ __device__ __forceinline__ void fast_gemm_stream_phase(const FastGemm &g, int wg
     const uint16_t *wbase;
     int wrow0, unit;
     fast_tile(g, wg, nwg, e, wbase, wrow0, unit);     // e < my_entries: always a valid tile
-    const uint16_t *wrow = wbase + (size_t)(wrow0 + lr) * g.Kd;
+    const uint16_t *wf = fast_wfrag(wbase, wrow0, g.Kd, lane);
     f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
     Frag16 Bs;
     const EpiPre ep = fast_epilogue_preload(g, wg, nwg, e, 1);
     if (!(pre && e == 0)) {
 #pragma unroll
-      for (int s = 0; s < kKS; ++s) A.v[s] = fast_ld_a(wrow, g.Kd, min(ks0 + s, ks_last), lg);
+      for (int s = 0; s < kKS; ++s) A.v[s] = fast_ld_a(wf, g.Kd, min(ks0 + s, ks_last));
     }
 #pragma unroll
     for (int s = 0; s < kKS; ++s) Bs.v[s] = fast_ld_b(g.b, g.Kd, ks0, s, ns, lr, lg);
@@ -352,7 +379,7 @@ __device__ __forceinline__ void fast_gemm_stream_phase(const FastGemm &g, int wg
 #pragma unroll
         for (int s = 0; s < kKS; ++s) {
           acc = fast_mfma(A.v[s], Bs.v[s], acc);
-          A.v[s] = fast_ld_a(wrow, g.Kd, min(ks0 + base + kKS + s, ks_last), lg);
+          A.v[s] = fast_ld_a(wf, g.Kd, min(ks0 + base + kKS + s, ks_last));
           Bs.v[s] = fast_ld_b(g.b, g.Kd, ks0, base + kKS + s, ns, lr, lg);
         }
       } else {
