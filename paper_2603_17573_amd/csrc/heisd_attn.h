@@ -19,6 +19,16 @@ namespace heisd {
 constexpr int kAttnThreads = 256;
 constexpr int kAttnWaves = 4;
 constexpr int kAttnQB = 8;  // queries per block
+constexpr int kAttnU = 6;   // cache rows a key stream requests at once
+
+__device__ __forceinline__ void attn_unpack8(const uint4 v, float (&f)[8]) {
+  const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    f[2 * i] = __uint_as_float(w[i] << 16);
+    f[2 * i + 1] = __uint_as_float(w[i] & 0xFFFF0000u);
+  }
+}
 
 struct AttnArgs {
   float *qkv;                // [M][3*d] fp32: q | k | v of the new rows, not yet rotated; k is rotated in place
@@ -119,22 +129,7 @@ __global__ __launch_bounds__(kAttnThreads) void attn_verify(AttnArgs a) {
       for (int i = 0; i < 8; ++i) qf[j][i] = qs[j * HD + li * 8 + i];
 
     // ---- pass 1: scores ----
-    for (int r = g; r < nkeys; r += G) {
-      float kf[8];
-      if (r < P) {
-        const uint4 kk = *reinterpret_cast<const uint4 *>(kc + (size_t)r * HD + li * 8);
-        const uint32_t kw[4] = {kk.x, kk.y, kk.z, kk.w};
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          kf[2 * i] = __uint_as_float(kw[i] << 16);
-          kf[2 * i + 1] = __uint_as_float(kw[i] & 0xFFFF0000u);
-        }
-      } else {
-        const float *kp = a.qkv + (size_t)(row0 + r - P) * 3 * d + d + h * HD + li * 8;
-        const float4 k0 = *reinterpret_cast<const float4 *>(kp), k1 = *reinterpret_cast<const float4 *>(kp + 4);
-        kf[0] = k0.x; kf[1] = k0.y; kf[2] = k0.z; kf[3] = k0.w;
-        kf[4] = k1.x; kf[5] = k1.y; kf[6] = k1.z; kf[7] = k1.w;
-      }
+    auto score_key = [&](const float (&kf)[8], int r) __attribute__((always_inline)) {
       float s[kAttnQB];
 #pragma unroll
       for (int j = 0; j < kAttnQB; ++j) {
@@ -151,6 +146,32 @@ __global__ __launch_bounds__(kAttnThreads) void attn_verify(AttnArgs a) {
 #pragma unroll
       for (int j = 1; j < kAttnQB; ++j) mine = (li == j) ? s[j] : mine;
       if (li < kAttnQB) sc[(size_t)li * cap + r] = (r <= P + j0 + li) ? mine : -INFINITY;
+    };
+    // prefix rows (bf16, from the cache): kAttnU rows of this lane's stream are requested before
+    // the first is used, so a stream is a few round trips to memory instead of one per row
+    for (int r0 = g; r0 < P; r0 += G * kAttnU) {
+      uint4 kk[kAttnU];
+#pragma unroll
+      for (int u = 0; u < kAttnU; ++u) {
+        const int r = r0 + u * G;
+        kk[u] = r < P ? *reinterpret_cast<const uint4 *>(kc + (size_t)r * HD + li * 8) : make_uint4(0, 0, 0, 0);
+      }
+#pragma unroll
+      for (int u = 0; u < kAttnU; ++u) {
+        const int r = r0 + u * G;
+        if (r < P) {
+          float kf[8];
+          attn_unpack8(kk[u], kf);
+          score_key(kf, r);
+        }
+      }
+    }
+    // the block's own rows (fp32, rotated in place above)
+    for (int r = P + g; r < nkeys; r += G) {
+      const float *kp = a.qkv + (size_t)(row0 + r - P) * 3 * d + d + h * HD + li * 8;
+      const float4 k0 = *reinterpret_cast<const float4 *>(kp), k1 = *reinterpret_cast<const float4 *>(kp + 4);
+      const float kf[8] = {k0.x, k0.y, k0.z, k0.w, k1.x, k1.y, k1.z, k1.w};
+      score_key(kf, r);
     }
     __syncthreads();
 
@@ -177,28 +198,36 @@ __global__ __launch_bounds__(kAttnThreads) void attn_verify(AttnArgs a) {
     for (int j = 0; j < kAttnQB; ++j)
 #pragma unroll
       for (int i = 0; i < 8; ++i) o[j][i] = 0.f;
-    for (int r = g; r < nkeys; r += G) {
-      float vf[8];
-      if (r < P) {
-        const uint4 vv = *reinterpret_cast<const uint4 *>(vc + (size_t)r * HD + li * 8);
-        const uint32_t vw[4] = {vv.x, vv.y, vv.z, vv.w};
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          vf[2 * i] = __uint_as_float(vw[i] << 16);
-          vf[2 * i + 1] = __uint_as_float(vw[i] & 0xFFFF0000u);
-        }
-      } else {
-        const float *vp = a.qkv + (size_t)(row0 + r - P) * 3 * d + 2 * d + h * HD + li * 8;
-        const float4 v0 = *reinterpret_cast<const float4 *>(vp), v1 = *reinterpret_cast<const float4 *>(vp + 4);
-        vf[0] = v0.x; vf[1] = v0.y; vf[2] = v0.z; vf[3] = v0.w;
-        vf[4] = v1.x; vf[5] = v1.y; vf[6] = v1.z; vf[7] = v1.w;
-      }
+    auto add_value = [&](const float (&vf)[8], int r) __attribute__((always_inline)) {
 #pragma unroll
       for (int j = 0; j < kAttnQB; ++j) {
         const float p = (j < nq) ? sc[(size_t)j * cap + r] : 0.f;
 #pragma unroll
         for (int i = 0; i < 8; ++i) o[j][i] = fmaf(p, vf[i], o[j][i]);
       }
+    };
+    for (int r0 = g; r0 < P; r0 += G * kAttnU) {
+      uint4 vv[kAttnU];
+#pragma unroll
+      for (int u = 0; u < kAttnU; ++u) {
+        const int r = r0 + u * G;
+        vv[u] = r < P ? *reinterpret_cast<const uint4 *>(vc + (size_t)r * HD + li * 8) : make_uint4(0, 0, 0, 0);
+      }
+#pragma unroll
+      for (int u = 0; u < kAttnU; ++u) {
+        const int r = r0 + u * G;
+        if (r < P) {
+          float vf[8];
+          attn_unpack8(vv[u], vf);
+          add_value(vf, r);
+        }
+      }
+    }
+    for (int r = P + g; r < nkeys; r += G) {
+      const float *vp = a.qkv + (size_t)(row0 + r - P) * 3 * d + 2 * d + h * HD + li * 8;
+      const float4 v0 = *reinterpret_cast<const float4 *>(vp), v1 = *reinterpret_cast<const float4 *>(vp + 4);
+      const float vf[8] = {v0.x, v0.y, v0.z, v0.w, v1.x, v1.y, v1.z, v1.w};
+      add_value(vf, r);
     }
 #pragma unroll
     for (int off = LPK; off < kWave; off <<= 1)
