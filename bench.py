@@ -108,8 +108,7 @@ def main():
         first[e] = f
         if e == 0:
             kb_host, vb_host = k, v
-    bins = synth.make_drafts_uniform(wl) if wl.draft[0] == "uniform" else \
-        np.clip(synth.make_drafts_uniform(wl) + synth.make_offsets_geometric(wl, wl.draft[1]), 0, sh.n_bins - 1)
+    bins = synth.make_drafts_uniform(wl)
     drafts = (sh.bin_base + bins).astype(np.int32)
     skip = synth.make_skip_mask(wl) if wl.skip_p > 0 else None
     t_plen = torch.full((B,), P, dtype=torch.int32, device=dev)
@@ -118,6 +117,21 @@ def main():
     t_skip = None if skip is None else torch.from_numpy(skip).to(dev)
     acc = make_accept_desc(wl.tau_tok, wl.tau_seq)
     stream = torch.cuda.current_stream(dev)
+    drafts_note = "uniform over the bins"
+    if wl.draft[0] == "geometric":
+        # drafts near the target's own choice: d_j = clip(v_j + offset_j), v_j = the target's greedy bin given
+        # d_0..d_{j-1}.  v_j is row j of target_bins, which depends on the earlier drafts only, so K
+        # untimed steps fix the drafts one position at a time (the benchmark may not call the oracle).
+        off = synth.make_offsets_geometric(wl, wl.draft[1])
+        out0 = None
+        for j in range(K):
+            out0 = ver.step(kc, vc, t_plen, t_first, t_drafts, acc, t_skip, want_aux=True, out=out0, stream=stream)
+            vj = out0["target_bins"][:, j].cpu().numpy()
+            live = vj >= 0
+            bins[live, j] = np.clip(vj[live] + off[live, j], 0, sh.n_bins - 1)
+            t_drafts[:, j] = torch.from_numpy((sh.bin_base + bins[:, j]).astype(np.int32)).to(dev)
+        drafts = (sh.bin_base + bins).astype(np.int32)
+        drafts_note = "target's own greedy bins (fixed position by position with K untimed device steps) + Geometric(%g) signed offsets" % wl.draft[1]
 
     if args.calibrate_copy:
         src = torch.empty(1 << 28, dtype=torch.float32, device=dev).normal_()
@@ -136,6 +150,15 @@ def main():
     torch.cuda.synchronize()
     ms = (time.perf_counter() - t0) * 1e3 / args.steps
     accepted = out["accepted_len"].cpu().tolist()
+    # acceptance does not change the work of a step: one time, several thresholds (paper Sec. 4.2: 15/30)
+    hist = {}
+    if wl.draft[0] == "geometric":
+        for tt, ts in ((0, 0), (1, 3), (2, 6), (4, 12), (2, 4), (15, 30)):
+            o2 = ver.step(kc, vc, t_plen, t_first, t_drafts, make_accept_desc(tt, ts), t_skip, want_aux=False, stream=stream)
+            al = o2["accepted_len"].cpu().numpy()
+            if skip is not None:
+                al = al[skip == 0]
+            hist["%d/%d" % (tt, ts)] = np.bincount(al, minlength=K + 1).tolist()
 
     # per-kernel durations: HIP events recorded by the library on the launch stream
     n_prof = max(1, min(args.steps, 32))
@@ -196,15 +219,17 @@ def main():
         "metric": "verify steps/s (7B-shaped decoder, K=7, bs=1)" if wl.name == "C1" else
                   "verify steps/s (%s)" % wl.name,
         "value": round(1000.0 / ms, 2), "unit": "verify steps/s", "n_gpus": 1, "steps": args.steps,
+        "episode_steps_per_s": round(B * 1000.0 / ms, 1), "draft_tokens_verified_per_s": round(active * K * 1000.0 / ms, 1),
         "warmup": args.warmup, "ms_per_step": round(ms, 4), "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": "%s: %d-layer d=%d decoder, prefix %d, batch %d, K=%d, thresholds %d/%d" %
                                (wl.name, sh.n_layers, sh.d_model, P, B, K, wl.tau_tok, wl.tau_seq),
-                   "prefix_kv": "drawn directly (no prefill)", "global_batch": B, "K": K},
+                   "prefix_kv": "drawn directly (no prefill)", "drafts": drafts_note, "global_batch": B, "K": K},
         "kernel_path": args.path,
         "hbm_frac_whole_step": round(total_bytes / (ms * 1e-3) / HBM_PEAK, 4),
         "algorithmic_bytes_per_step": total_bytes,
         "accepted_len": accepted[:8],
+        "accepted_len_histograms_by_threshold": hist or None,
         "weights_gen_s": round(t_gen, 1),
         "kernels": kernels,
         "roofline": roofline,
