@@ -128,6 +128,7 @@ struct FastScratch {
 };
 
 static hipError_t bat_prepare();
+static hipError_t bat_ns_prepare();
 
 static bool shape_ok(const heisd_model_desc *d) {
   return d && d->n_layers > 0 && d->d_model > 0 && d->n_heads > 0 && d->head_dim > 0 && d->d_ffn > 0 &&
@@ -693,7 +694,8 @@ static hipError_t bat_prepare() {
   if ((e = bat_prepare_mc<2>()) != hipSuccess) return e;
   if ((e = bat_prepare_mc<4>()) != hipSuccess) return e;
   if ((e = bat_prepare_mc<7>()) != hipSuccess) return e;
-  return bat_prepare_mc<8>();
+  if ((e = bat_prepare_mc<8>()) != hipSuccess) return e;
+  return bat_ns_prepare();
 }
 
 template <int MC>
@@ -704,9 +706,44 @@ static void bat_launch_mc(const BatGemm &g, int grid, hipStream_t st) {
     bat_gemm<MC, 3><<<dim3(grid), dim3(kBatThreads), bat_lds_bytes<MC>(), st>>>(g);
 }
 
+template <int MC, int NT, int KW>
+static hipError_t bat_ns_prepare_one() {
+  return hipFuncSetAttribute(reinterpret_cast<const void *>(&bat_gemm_ns<MC, NT, KW>),
+                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)bat_ns_lds_bytes<MC>());
+}
+static hipError_t bat_ns_prepare() {
+  hipError_t e;
+  if ((e = bat_ns_prepare_one<4, 2, 1>()) != hipSuccess) return e;
+  if ((e = bat_ns_prepare_one<4, 2, 2>()) != hipSuccess) return e;
+  if ((e = bat_ns_prepare_one<8, 2, 1>()) != hipSuccess) return e;
+  return bat_ns_prepare_one<8, 2, 2>();
+}
+
+// Gate/up + SwiGLU for up to 64 rows: six waves split the (gate, up) pairs - 6 pairs, or 3 pairs x 2
+// shares of the reduction - and share the activation fragments through LDS.  Fewer workgroups mean
+// less record traffic but fewer compute units pulling weights: 6 pairs per workgroup only if that
+// still gives three quarters of the compute units a workgroup.  (For the single-tile projections
+// this arrangement measured no better than bat_gemm: with one MFMA per B fragment the LDS reads
+// bound it, and 256 tiles make too few workgroups.)
+template <int MC>
+static void bat_ns_launch_mc(BatGemm g, int n_cu, hipStream_t st) {
+  const int kw = (g.n_units + kNsCompute - 1) / kNsCompute >= (3 * n_cu) / 4 ? 1 : 2;
+  const int nw = kNsCompute / kw;
+  g.NW = nw;
+  const int groups = (g.n_units + nw - 1) / nw;
+  const dim3 grid(groups < n_cu ? groups : n_cu), block(kBatThreads);
+  if (kw == 1) bat_gemm_ns<MC, 2, 1><<<grid, block, bat_ns_lds_bytes<MC>(), st>>>(g);
+  else bat_gemm_ns<MC, 2, 2><<<grid, block, bat_ns_lds_bytes<MC>(), st>>>(g);
+}
+
 // Wave arrangement for CT column tiles: MW groups of MC tiles (MC from the compiled set).
 static void bat_launch(BatGemm g, int n_cu, hipStream_t st) {
   const int CT = g.CT;
+  if (CT <= 8 && g.epi == FEPI_SWIGLU) {
+    if (CT <= 4) bat_ns_launch_mc<4>(g, n_cu, st);
+    else bat_ns_launch_mc<8>(g, n_cu, st);
+    return;
+  }
   const int MW = CT <= 8 ? 1 : (CT <= 16 ? 2 : (CT <= 32 ? 4 : 8));
   const int need = (CT + MW - 1) / MW < 8 ? (CT + MW - 1) / MW : 8;
   g.MW = MW;

@@ -42,7 +42,8 @@ struct BatGemm {
   const float *next_gain; // RESID_NORM: gain of the norm that consumes x next
   uint16_t *o_planes;     // RESID_NORM / SWIGLU: records [unit][CTS][16][16]
   float *ssq_out;         // RESID_NORM: [n_units][CTS*8] partial sums of squares of the new x
-  int MW;                 // waves across column tiles (1, 2, 4 or 8); the other 8/MW split k
+  int MW;                 // bat_gemm: waves across column tiles (1, 2, 4 or 8); the other 8/MW split k
+  int NW;                 // bat_gemm_ns: computing waves across weight tiles (6 or 3); set by the launcher
 };
 
 template <int MC>
@@ -63,6 +64,51 @@ __device__ __forceinline__ void bat_tile(const BatGemm &g, int wg, int nwg, int 
   const int seg = unit / g.seg_tiles;
   wbase = seg == 0 ? g.w[0] : (seg == 1 ? g.w[1] : g.w[2]);
   wrow0 = (unit - seg * g.seg_tiles) * 16;
+}
+
+// The projection's epilogue for one output pair: row m = 8*ct + jm, columns 2*c2, 2*c2+1 of unit
+// `unit`; (s0, s1) = the sums, (u0, u1) = the sums of the up tile (SwiGLU).  The 8 lanes c2 = 0..7 of
+// a row must call this together (they add up the row's partial sum of squares).
+__device__ __forceinline__ void bat_emit(const BatGemm &g, int unit, int ct, int jm, int c2, float s0, float s1, float u0,
+                                         float u1) {
+  const int i = 2 * c2;
+  const int m = ct * 8 + jm;
+  const bool live = m < g.M;
+  const float sc = g.inv_rms ? g.inv_rms[m] : 1.0f;
+  if (g.epi == FEPI_STORE_ROWS) {
+    if (live) *reinterpret_cast<float2 *>(g.out + (size_t)m * g.ldo + unit * 16 + i) = make_float2(s0 * sc, s1 * sc);
+    return;
+  }
+  float a0 = 0.f, a1 = 0.f;
+  if (g.epi == FEPI_SWIGLU) {
+    const float g0 = s0 * sc, g1 = s1 * sc;
+    if (live) {
+      a0 = g0 / (1.0f + expf(-g0)) * (u0 * sc);
+      a1 = g1 / (1.0f + expf(-g1)) * (u1 * sc);
+    }
+  } else {
+    if (live) {
+      float *xp = g.out + (size_t)m * g.ldo + unit * 16 + i;
+      const float2 xo = *reinterpret_cast<const float2 *>(xp);
+      a0 = xo.x + s0 * sc;
+      a1 = xo.y + s1 * sc;
+      *reinterpret_cast<float2 *>(xp) = make_float2(a0, a1);
+    }
+    float q = a0 * a0 + a1 * a1;          // over the tile's 16 columns: 8 adjacent lanes
+    q += __shfl_xor(q, 4, kWave);
+    q += __shfl_xor(q, 2, kWave);
+    q += __shfl_xor(q, 1, kWave);
+    if (c2 == 0) g.ssq_out[(size_t)unit * (g.CTS * 8) + m] = q;
+    const float2 gn = *reinterpret_cast<const float2 *>(g.next_gain + unit * 16 + i);
+    a0 *= gn.x;
+    a1 *= gn.y;
+  }
+  uint32_t h0, l0, h1, l1;
+  split_bf16(a0, h0, l0);
+  split_bf16(a1, h1, l1);
+  uint32_t *rec = reinterpret_cast<uint32_t *>(g.o_planes + ((size_t)unit * g.CTS + ct) * 256);
+  rec[(jm * 16 + i) / 2] = h0 | (h1 << 16);
+  rec[((jm + 8) * 16 + i) / 2] = l0 | (l1 << 16);
 }
 
 // First column tile of wave group mw in the block that starts at cb: groups that would run past
@@ -104,43 +150,7 @@ __device__ __forceinline__ void bat_epilogue(const BatGemm &g, int wg, int nwg, 
         u1 += cg.y + dg.y;
       }
     }
-    const int m = ct * 8 + jm;
-    const bool live = m < g.M;
-    const float sc = g.inv_rms ? g.inv_rms[m] : 1.0f;
-    if (g.epi == FEPI_STORE_ROWS) {
-      if (live) *reinterpret_cast<float2 *>(g.out + (size_t)m * g.ldo + unit * 16 + i) = make_float2(s0 * sc, s1 * sc);
-      continue;
-    }
-    float a0 = 0.f, a1 = 0.f;
-    if (g.epi == FEPI_SWIGLU) {
-      const float g0 = s0 * sc, g1 = s1 * sc;
-      if (live) {
-        a0 = g0 / (1.0f + expf(-g0)) * (u0 * sc);
-        a1 = g1 / (1.0f + expf(-g1)) * (u1 * sc);
-      }
-    } else {
-      if (live) {
-        float *xp = g.out + (size_t)m * g.ldo + unit * 16 + i;
-        const float2 xo = *reinterpret_cast<const float2 *>(xp);
-        a0 = xo.x + s0 * sc;
-        a1 = xo.y + s1 * sc;
-        *reinterpret_cast<float2 *>(xp) = make_float2(a0, a1);
-      }
-      float q = a0 * a0 + a1 * a1;          // over the tile's 16 columns: 8 adjacent lanes
-      q += __shfl_xor(q, 4, kWave);
-      q += __shfl_xor(q, 2, kWave);
-      q += __shfl_xor(q, 1, kWave);
-      if (c2 == 0) g.ssq_out[(size_t)unit * (g.CTS * 8) + m] = q;
-      const float2 gn = *reinterpret_cast<const float2 *>(g.next_gain + unit * 16 + i);
-      a0 *= gn.x;
-      a1 *= gn.y;
-    }
-    uint32_t h0, l0, h1, l1;
-    split_bf16(a0, h0, l0);
-    split_bf16(a1, h1, l1);
-    uint32_t *rec = reinterpret_cast<uint32_t *>(g.o_planes + ((size_t)unit * g.CTS + ct) * 256);
-    rec[(jm * 16 + i) / 2] = h0 | (h1 << 16);
-    rec[((jm + 8) * 16 + i) / 2] = l0 | (l1 << 16);
+    bat_emit(g, unit, ct, jm, c2, s0, s1, u0, u1);
   }
 }
 
@@ -240,6 +250,165 @@ __global__ __launch_bounds__(kBatThreads) __attribute__((amdgpu_waves_per_eu(2, 
         }
       }
     }
+  }
+}
+
+// ---- M <= 64 rows: the waves split the weight tiles and share the activation fragments through LDS ----
+// With few rows bat_gemm gives every wave its own part of the reduction, so every workgroup reads ALL
+// activation records once per pass (0.9 MB at M = 56 against 0.4 MB of weights): L2 traffic, not HBM,
+// bounds it.  Here kNsCompute waves of a workgroup multiply different weight tiles over the same
+// k-steps (arranged NW tiles x KW shares of the reduction), and the B fragments of those steps are
+// brought into LDS once per workgroup, double buffered in chunks of kNsSlots k-steps, by the other
+// two waves with direct global -> LDS transfers.  The split of roles matters: a wave's memory
+// operations complete in order, so a wave that streamed weights AND waited for B transfers would
+// drain its weight requests at every chunk; the computing waves meet the filling waves only at
+// workgroup barriers.  Record traffic drops with the number of workgroups, n_units/NW.  One unit
+// per computing wave and pass: a tile, or a (gate, up) pair.
+constexpr int kNsSlots = 8;
+constexpr int kNsCompute = 6;
+template <int MC>
+constexpr size_t bat_ns_lds_bytes() {
+  return (size_t)2 * kNsSlots * MC * 1024;        // two buffers; reused for the waves' accumulators at the end
+}
+
+template <int MC, int NT, int KW>
+__global__ __launch_bounds__(kBatThreads) __attribute__((amdgpu_waves_per_eu(2, 2))) void bat_gemm_ns(BatGemm g) {
+  constexpr int NW = kNsCompute / KW;
+  constexpr int S = kNsSlots / KW;                  // k-steps per chunk and share
+  constexpr int R = 16 / NT;                        // weight fragments in flight per tile
+  constexpr int NF = kBatWaves - kNsCompute;        // filling waves
+  static_assert(R % S == 0, "a ring revolution is a whole number of chunks");
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  const uint32_t smem_lds = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char *)smem;
+  const int wg = blockIdx.x, nwg = gridDim.x;
+  const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int lr = lane & 15, lg = lane >> 4;
+  const bool filler = wave >= kNsCompute;
+  const int nw = wave % NW, kw = filler ? 0 : wave / NW;
+  const int total = (g.Kd + 31) / 32;
+  const int ksw = (total + KW - 1) / KW;
+  const int ks0 = kw * ksw;
+  const int ns = max(0, min(ksw, total - ks0));
+  const int ks_last = min(ks0 + max(ns, 1) - 1, total - 1);
+  const int n_chunks = (ksw + S - 1) / S;
+  const int n_groups = (g.n_units + NW - 1) / NW;
+  const bool swiglu = g.epi == FEPI_SWIGLU;
+  const uint16_t *bsrc = g.b + (size_t)(lg >> 1) * g.CTS * 256 + lr * 16 + (lg & 1) * 8;     // + ks*bstep + ct*256
+  const size_t bstep = (size_t)2 * g.CTS * 256;
+  // filling wave f moves slots f, f+NF, ... of a chunk: slot = share*S + step
+  auto fill = [&](int c, int buf) __attribute__((always_inline)) {
+    for (int slot = wave - kNsCompute; slot < kNsSlots; slot += NF) {
+      const int skw = slot / S, j = c * S + slot % S;
+      const int s_ns = max(0, min(ksw, total - skw * ksw));
+      const int ks = j < s_ns ? skw * ksw + j : total;          // past the share: the all-zero k-step
+      const uint16_t *src = bsrc + (size_t)ks * bstep;
+#pragma unroll
+      for (int ct = 0; ct < MC; ++ct)
+        lds_dma16(src + ct * 256, __builtin_amdgcn_readfirstlane(smem_lds + (uint32_t)(((buf * kNsSlots + slot) * MC + ct) * 1024)));
+    }
+    wait_vmcnt<0>();
+  };
+
+  for (int grp = wg; grp < n_groups; grp += nwg) {
+    const int unit = grp * NW + nw;
+    const bool valid = !filler && unit < g.n_units;
+    const int ucl = unit < g.n_units ? unit : g.n_units - 1;     // surplus waves multiply a valid tile, results dropped
+    const uint16_t *wf[NT];
+#pragma unroll
+    for (int t = 0; t < NT; ++t) {
+      const uint16_t *wbase;
+      int wrow0;
+      if (swiglu) {
+        wbase = t ? g.w[1] : g.w[0];
+        wrow0 = ucl * 16;
+      } else {
+        const int seg = ucl / g.seg_tiles;
+        wbase = seg == 0 ? g.w[0] : (seg == 1 ? g.w[1] : g.w[2]);
+        wrow0 = (ucl - seg * g.seg_tiles) * 16;
+      }
+      wf[t] = fast_wfrag(wbase, wrow0, g.Kd, lane);
+    }
+    f32x4 acc[NT][MC];
+#pragma unroll
+    for (int t = 0; t < NT; ++t)
+#pragma unroll
+      for (int c = 0; c < MC; ++c) acc[t][c] = f32x4{0.f, 0.f, 0.f, 0.f};
+    if (filler) {
+      fill(0, 0);
+      lds_barrier();
+      for (int c = 0; c < n_chunks; ++c) {
+        if (c + 1 < n_chunks) fill(c + 1, (c & 1) ^ 1);
+        lds_barrier();
+      }
+    } else {
+      u32x4 A[R][NT];
+#pragma unroll
+      for (int u = 0; u < R; ++u)
+#pragma unroll
+        for (int t = 0; t < NT; ++t) A[u][t] = fast_ld_a(wf[t], g.Kd, min(ks0 + u, ks_last));
+      lds_barrier();                                  // chunk 0 is in LDS
+      for (int c0 = 0; c0 < n_chunks; c0 += R / S) {
+#pragma unroll
+        for (int cc = 0; cc < R / S; ++cc) {
+          const int c = c0 + cc;
+          if (c < n_chunks) {
+            const unsigned char *bl = smem + ((size_t)((c & 1) * kNsSlots + kw * S) * MC) * 1024 + lane * 16;
+#pragma unroll
+            for (int s = 0; s < S; ++s) {
+              const int u = cc * S + s;               // ring slot of step c*S + s
+              u32x4 Bf[MC];
+#pragma unroll
+              for (int ct = 0; ct < MC; ++ct) Bf[ct] = *reinterpret_cast<const u32x4 *>(bl + (size_t)(s * MC + ct) * 1024);
+#pragma unroll
+              for (int t = 0; t < NT; ++t) {
+#pragma unroll
+                for (int ct = 0; ct < MC; ++ct) acc[t][ct] = fast_mfma(A[u][t], Bf[ct], acc[t][ct]);
+                A[u][t] = fast_ld_a(wf[t], g.Kd, min(ks0 + c * S + s + R, ks_last));
+              }
+            }
+            lds_barrier();                            // chunk c+1 complete in LDS; everybody is done reading chunk c
+          }
+        }
+      }
+    }
+    // the shares of the reduction meet in LDS (the B buffers are free now); the wave with share 0 finishes the unit
+    float *red = reinterpret_cast<float *>(smem);
+    if (!filler) {
+#pragma unroll
+      for (int t = 0; t < NT; ++t)
+#pragma unroll
+        for (int ct = 0; ct < MC; ++ct)
+          *reinterpret_cast<f32x4 *>(red + ((size_t)((wave * NT + t) * MC + ct) * 64 + lane) * 4) = acc[t][ct];
+    }
+    lds_barrier();
+    if (kw == 0 && valid) {
+#pragma unroll
+      for (int ct = 0; ct < MC; ++ct) {
+        if (ct < g.CT) {
+          const int c2 = lane & 7, jm = lane >> 3;
+          const int i = 2 * c2;
+          const int l_hi = (i >> 2) * 16 + jm, r = i & 3;
+          float s0 = 0.f, s1 = 0.f, u0 = 0.f, u1 = 0.f;
+#pragma unroll
+          for (int kk = 0; kk < KW; ++kk) {
+            const float *p = red + ((size_t)(((kk * NW + nw) * NT) * MC + ct) * 64) * 4;
+            const float2 a = *reinterpret_cast<const float2 *>(p + l_hi * 4 + r);
+            const float2 b = *reinterpret_cast<const float2 *>(p + (l_hi + 8) * 4 + r);
+            s0 += a.x + b.x;
+            s1 += a.y + b.y;
+            if (NT == 2) {
+              const float *q = p + (size_t)MC * 256;
+              const float2 cg = *reinterpret_cast<const float2 *>(q + l_hi * 4 + r);
+              const float2 dg = *reinterpret_cast<const float2 *>(q + (l_hi + 8) * 4 + r);
+              u0 += cg.x + dg.x;
+              u1 += cg.y + dg.y;
+            }
+          }
+          bat_emit(g, unit, ct, jm, c2, s0, s1, u0, u1);
+        }
+      }
+    }
+    lds_barrier();                                    // the buffers are refilled by the next group
   }
 }
 

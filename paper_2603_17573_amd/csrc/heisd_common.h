@@ -34,6 +34,21 @@ __device__ __forceinline__ void lds_barrier() {
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
 }
 
+// One 16-byte-per-lane transfer global -> LDS that passes through no register: lane l's bytes land
+// at lds_addr + 16*l (lds_addr: LDS byte address, wave-uniform).  Completion is counted by vmcnt
+// like a load, in issue order with the wave's other vector memory operations.  Written as
+// assembly on purpose: the compiler would make every later LDS read wait for it.
+__device__ __forceinline__ void lds_dma16(const void *gptr, uint32_t lds_addr) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_addr), "v"(gptr) : "memory");
+}
+// s_waitcnt vmcnt(N) and nothing else, as a compiler-level memory barrier too: no load or store of
+// the surrounding code may be moved across it (the count is only right for the written order).
+template <int N>
+__device__ __forceinline__ void wait_vmcnt() {
+  static_assert(N >= 0 && N <= 63, "vmcnt range");
+  asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
+
 __device__ __forceinline__ float wave_sum(float v) {
 #pragma unroll
   for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, kWave);
