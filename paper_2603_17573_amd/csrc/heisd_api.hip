@@ -719,18 +719,19 @@ static hipError_t bat_ns_prepare() {
   return bat_ns_prepare_one<8, 2, 2>();
 }
 
-// Gate/up + SwiGLU for up to 64 rows: six waves split the (gate, up) pairs - 6 pairs, or 3 pairs x 2
+// Up to 64 rows, gate/up + SwiGLU: six waves split the (gate, up) pairs - 6 pairs, or 3 pairs x 2
 // shares of the reduction - and share the activation fragments through LDS.  Fewer workgroups mean
 // less record traffic but fewer compute units pulling weights: 6 pairs per workgroup only if that
-// still gives three quarters of the compute units a workgroup.  (For the single-tile projections
-// this arrangement measured no better than bat_gemm: with one MFMA per B fragment the LDS reads
-// bound it, and 256 tiles make too few workgroups.)
+// still gives three quarters of the compute units a workgroup.  (The kernel also takes plain
+// projections, two tiles per wave; measured at M = 56 that was slower than bat_gemm for QKV - 128
+// workgroups, 42 against 37 us - and O-proj and down have even fewer tiles, so they stay there.)
 template <int MC>
 static void bat_ns_launch_mc(BatGemm g, int n_cu, hipStream_t st) {
-  const int kw = (g.n_units + kNsCompute - 1) / kNsCompute >= (3 * n_cu) / 4 ? 1 : 2;
+  const int wunits = g.epi == FEPI_SWIGLU ? g.n_units : (g.n_units + 1) / 2;
+  const int kw = (wunits + kNsCompute - 1) / kNsCompute >= (3 * n_cu) / 4 ? 1 : 2;
   const int nw = kNsCompute / kw;
   g.NW = nw;
-  const int groups = (g.n_units + nw - 1) / nw;
+  const int groups = (wunits + nw - 1) / nw;
   const dim3 grid(groups < n_cu ? groups : n_cu), block(kBatThreads);
   if (kw == 1) bat_gemm_ns<MC, 2, 1><<<grid, block, bat_ns_lds_bytes<MC>(), st>>>(g);
   else bat_gemm_ns<MC, 2, 2><<<grid, block, bat_ns_lds_bytes<MC>(), st>>>(g);
