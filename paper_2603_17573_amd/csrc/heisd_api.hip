@@ -722,12 +722,12 @@ static hipError_t bat_ns_prepare() {
 // Up to 64 rows, gate/up + SwiGLU: six waves split the (gate, up) pairs - 6 pairs, or 3 pairs x 2
 // shares of the reduction - and share the activation fragments through LDS.  Fewer workgroups mean
 // less record traffic but fewer compute units pulling weights: 6 pairs per workgroup only if that
-// still gives three quarters of the compute units a workgroup.  (The kernel also takes plain
-// projections, two tiles per wave; measured at M = 56 that was slower than bat_gemm for QKV - 128
-// workgroups, 42 against 37 us - and O-proj and down have even fewer tiles, so they stay there.)
+// still gives three quarters of the compute units a workgroup.  (Tried for the plain projections
+// too: with one tile per wave the LDS reads bound it, with two tiles per wave QKV gets only 128
+// workgroups - 42 against 37 us at M = 56 - and O-proj and down have fewer tiles still.)
 template <int MC>
 static void bat_ns_launch_mc(BatGemm g, int n_cu, hipStream_t st) {
-  const int wunits = g.epi == FEPI_SWIGLU ? g.n_units : (g.n_units + 1) / 2;
+  const int wunits = g.n_units;
   const int kw = (wunits + kNsCompute - 1) / kNsCompute >= (3 * n_cu) / 4 ? 1 : 2;
   const int nw = kNsCompute / kw;
   g.NW = nw;

@@ -262,9 +262,8 @@ __global__ __launch_bounds__(kBatThreads) __attribute__((amdgpu_waves_per_eu(2, 
 // two waves with direct global -> LDS transfers.  The split of roles matters: a wave's memory
 // operations complete in order, so a wave that streamed weights AND waited for B transfers would
 // drain its weight requests at every chunk; the computing waves meet the filling waves only at
-// workgroup barriers.  Record traffic drops with the number of workgroups.  One unit per computing
-// wave and pass: a (gate, up) pair, or NT consecutive tiles of a plain projection - every B fragment
-// read from LDS feeds NT MFMAs.
+// workgroup barriers.  Record traffic drops with the number of workgroups, n_units/NW.  One unit
+// per computing wave and pass: a tile, or a (gate, up) pair.
 constexpr int kNsSlots = 8;
 constexpr int kNsCompute = 6;
 template <int MC>
@@ -292,10 +291,8 @@ __global__ __launch_bounds__(kBatThreads) __attribute__((amdgpu_waves_per_eu(2, 
   const int ns = max(0, min(ksw, total - ks0));
   const int ks_last = min(ks0 + max(ns, 1) - 1, total - 1);
   const int n_chunks = (ksw + S - 1) / S;
+  const int n_groups = (g.n_units + NW - 1) / NW;
   const bool swiglu = g.epi == FEPI_SWIGLU;
-  // a wave's unit: a (gate, up) pair, or NT consecutive tiles of a plain projection
-  const int n_wunits = swiglu ? g.n_units : (g.n_units + NT - 1) / NT;
-  const int n_groups = (n_wunits + NW - 1) / NW;
   const uint16_t *bsrc = g.b + (size_t)(lg >> 1) * g.CTS * 256 + lr * 16 + (lg & 1) * 8;     // + ks*bstep + ct*256
   const size_t bstep = (size_t)2 * g.CTS * 256;
   // filling wave f moves slots f, f+NF, ... of a chunk: slot = share*S + step
@@ -314,8 +311,8 @@ __global__ __launch_bounds__(kBatThreads) __attribute__((amdgpu_waves_per_eu(2, 
 
   for (int grp = wg; grp < n_groups; grp += nwg) {
     const int unit = grp * NW + nw;
-    const bool valid = !filler && unit < n_wunits;
-    const int ucl = unit < n_wunits ? unit : n_wunits - 1;       // surplus waves multiply a valid tile, results dropped
+    const bool valid = !filler && unit < g.n_units;
+    const int ucl = unit < g.n_units ? unit : g.n_units - 1;     // surplus waves multiply a valid tile, results dropped
     const uint16_t *wf[NT];
 #pragma unroll
     for (int t = 0; t < NT; ++t) {
@@ -325,10 +322,9 @@ __global__ __launch_bounds__(kBatThreads) __attribute__((amdgpu_waves_per_eu(2, 
         wbase = t ? g.w[1] : g.w[0];
         wrow0 = ucl * 16;
       } else {
-        const int tile = min(ucl * NT + t, g.n_units - 1);
-        const int seg = tile / g.seg_tiles;
+        const int seg = ucl / g.seg_tiles;
         wbase = seg == 0 ? g.w[0] : (seg == 1 ? g.w[1] : g.w[2]);
-        wrow0 = (tile - seg * g.seg_tiles) * 16;
+        wrow0 = (ucl - seg * g.seg_tiles) * 16;
       }
       wf[t] = fast_wfrag(wbase, wrow0, g.Kd, lane);
     }
@@ -408,12 +404,7 @@ __global__ __launch_bounds__(kBatThreads) __attribute__((amdgpu_waves_per_eu(2, 
               u1 += cg.y + dg.y;
             }
           }
-          if (swiglu) {
-            bat_emit(g, unit, ct, jm, c2, s0, s1, u0, u1);
-          } else {
-            bat_emit(g, unit * NT, ct, jm, c2, s0, s1, 0.f, 0.f);
-            if (NT == 2 && unit * NT + 1 < g.n_units) bat_emit(g, unit * NT + 1, ct, jm, c2, u0, u1, 0.f, 0.f);
-          }
+          bat_emit(g, unit, ct, jm, c2, s0, s1, u0, u1);
         }
       }
     }
