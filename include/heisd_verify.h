@@ -178,7 +178,8 @@ int heisd_verify_profile_read(heisd_verify_ctx *ctx, double *ms, int64_t *launch
 
 /*
  * Kernel-path selection, for tests and measurement.  AUTO (default) picks the fastest path
- * that covers the call: FAST for batch*K <= 8, BATCH above.  GENERIC forces the first any-M path
+ * that covers the call: FAST for batch*K <= 8 (when the model fits those kernels: d_model <= 4096),
+ * BATCH otherwise.  GENERIC forces the first any-M path
  * (activations converted and staged through LDS by every workgroup, one launch per phase);
  * BATCH forces the any-M path that exchanges pre-split bf16 activation records (waves arranged
  * over rows and over the reduction according to batch*K); FAST forces the batch*K <= 8 kernels

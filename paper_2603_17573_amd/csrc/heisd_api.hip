@@ -952,7 +952,7 @@ extern "C" int heisd_verify_step(heisd_verify_ctx *ctx, const heisd_kv_desc *kv,
     persist_launch(ctx, kv, draft_tokens, K, batch, skip_mask, logits, st);
   } else if (use_fast) {
     fast_forward(ctx, kv, draft_tokens, K, batch, skip_mask, logits, st, prof);
-  } else if (ctx->path == HEISD_PATH_BATCH || (ctx->path == HEISD_PATH_AUTO && M > 8)) {
+  } else if (ctx->path != HEISD_PATH_GENERIC) {          // BATCH, or AUTO when the M <= 8 kernels do not apply
     batch_forward(ctx, kv, draft_tokens, K, batch, skip_mask, logits, st, prof);
   } else {
     generic_forward(ctx, kv, draft_tokens, K, batch, skip_mask, logits, st, prof);

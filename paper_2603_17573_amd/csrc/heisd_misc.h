@@ -44,8 +44,6 @@ struct AcceptArgs {
 // ties, NaN never wins), then the acceptance rule of Sec. 4.2 walked group by group.
 // Integer work: bit-exact by construction.
 __global__ __launch_bounds__(256) void argmax_accept(AcceptArgs a) {
-  __shared__ float s_val[4];
-  __shared__ int s_idx[4];
   const int b = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int K = a.K;
   int32_t *tb = a.target_bins + (size_t)b * (K + 1);
@@ -59,11 +57,12 @@ __global__ __launch_bounds__(256) void argmax_accept(AcceptArgs a) {
     return;
   }
   if (tid == 0) tb[0] = a.first_pred[b];
-  for (int j = 0; j < K; ++j) {
+  // one wave per row: lanes stride over the bins, butterfly arg-max (lowest index wins ties)
+  for (int j = wave; j < K; j += 4) {
     const float *row = a.logits + ((size_t)b * K + j) * a.n_bins;
     float best = -INFINITY;
     int bi = 0x7FFFFFFF;
-    for (int t = tid; t < a.n_bins; t += 256) {
+    for (int t = lane; t < a.n_bins; t += kWave) {
       float v = row[t];
       if (v != v) v = -INFINITY;
       if (v > best || (v == best && t < bi)) { best = v; bi = t; }
@@ -74,15 +73,10 @@ __global__ __launch_bounds__(256) void argmax_accept(AcceptArgs a) {
       const int oi = __shfl_xor(bi, o, kWave);
       if (ov > best || (ov == best && oi < bi)) { best = ov; bi = oi; }
     }
-    if (lane == 0) { s_val[wave] = best; s_idx[wave] = bi; }
-    __syncthreads();
-    if (tid == 0) {
-      for (int w = 1; w < 4; ++w)
-        if (s_val[w] > best || (s_val[w] == best && s_idx[w] < bi)) { best = s_val[w]; bi = s_idx[w]; }
-      tb[j + 1] = (bi == 0x7FFFFFFF) ? 0 : bi;
-    }
-    __syncthreads();
+    if (lane == 0) tb[j + 1] = (bi == 0x7FFFFFFF) ? 0 : bi;
   }
+  __threadfence_block();
+  __syncthreads();          // thread 0 reads the rows' bins back from tb below
   if (tid != 0) return;
   // ---- acceptance: leading run of accepted groups ----
   const int32_t *dr = a.draft + (size_t)b * K;
