@@ -220,6 +220,32 @@ static void gemm_launch(GemmArgs a, int M, int epi, hipStream_t st) {
   }
 }
 
+// ---- any-M attention: workgroup size by the number of (episode, head) pairs ----------------
+
+template <int HD, int THREADS>
+static hipError_t attn_prepare_one(int cap) {
+  return hipFuncSetAttribute(reinterpret_cast<const void *>(&attn_verify<HD, THREADS>),
+                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)attn_lds_bytes(HD, cap, THREADS / 64));
+}
+static hipError_t attn_prepare(int hd, int cap) {
+  hipError_t e = hd == 128 ? attn_prepare_one<128, 256>(cap) : attn_prepare_one<64, 256>(cap);
+  if (e != hipSuccess) return e;
+  return hd == 128 ? attn_prepare_one<128, 512>(cap) : attn_prepare_one<64, 512>(cap);
+}
+static void attn_launch(const AttnArgs &a, int hd, int H, int batch, int cap, int n_cu, hipStream_t st) {
+  const bool big = H * batch < 2 * n_cu;       // few workgroups: 512 threads each hide more latency
+  const dim3 grid(H, batch);
+  if (big) {
+    const size_t lds = attn_lds_bytes(hd, cap, 8);
+    if (hd == 128) attn_verify<128, 512><<<grid, dim3(512), lds, st>>>(a);
+    else attn_verify<64, 512><<<grid, dim3(512), lds, st>>>(a);
+  } else {
+    const size_t lds = attn_lds_bytes(hd, cap, 4);
+    if (hd == 128) attn_verify<128, 256><<<grid, dim3(256), lds, st>>>(a);
+    else attn_verify<64, 256><<<grid, dim3(256), lds, st>>>(a);
+  }
+}
+
 // ---- weights in fragment order ------------------------------------------------------------
 
 static hipError_t pack_one(const void *src, int rows, int Kd, unsigned char *&cursor, const uint16_t *&out) {
@@ -566,13 +592,7 @@ extern "C" int heisd_verify_init(const heisd_model_desc *desc, heisd_verify_ctx 
   if (e == hipSuccess) e = gemm_prepare_mc<2>();
   if (e == hipSuccess) e = gemm_prepare_mc<4>();
   if (e == hipSuccess) e = gemm_prepare_mc<8>();
-  const int attn_lds = (int)attn_lds_bytes(desc->head_dim, desc->kv_capacity);
-  if (e == hipSuccess)
-    e = desc->head_dim == 128
-            ? hipFuncSetAttribute(reinterpret_cast<const void *>(&attn_verify<128>),
-                                  hipFuncAttributeMaxDynamicSharedMemorySize, attn_lds)
-            : hipFuncSetAttribute(reinterpret_cast<const void *>(&attn_verify<64>),
-                                  hipFuncAttributeMaxDynamicSharedMemorySize, attn_lds);
+  if (e == hipSuccess) e = attn_prepare(desc->head_dim, desc->kv_capacity);
   if (e != hipSuccess) {
     const int rc = fail(nullptr, HEISD_EHIP, "init: %s", hipGetErrorString(e));
     delete c;
@@ -777,7 +797,6 @@ static void batch_forward(heisd_verify_ctx *ctx, const heisd_kv_desc *kv, const 
     row_scales();
   }
   const size_t layer_stride = (size_t)batch * H * cap * HD;
-  const size_t attn_lds = attn_lds_bytes(HD, cap);
   BatGemm base{};
   base.CT = CT; base.CTS = CTS; base.M = M;
   for (int l = 0; l < d.n_layers; ++l) {
@@ -800,8 +819,7 @@ static void batch_forward(heisd_verify_ctx *ctx, const heisd_kv_desc *kv, const 
     a.K = K; a.H = H; a.cap = cap; a.d = dm; a.scale = 1.0f / std::sqrt((float)HD);
     {
       ProfScope ps(ctx, HEISD_KC_ATTN, st, prof);
-      if (HD == 128) attn_verify<128><<<dim3(H, batch), dim3(kAttnThreads), attn_lds, st>>>(a);
-      else attn_verify<64><<<dim3(H, batch), dim3(kAttnThreads), attn_lds, st>>>(a);
+      attn_launch(a, HD, H, batch, cap, ctx->n_cu, st);
     }
     // x += o . Wo^T; records of x * ffn gain, partial sums of squares
     g = base;
@@ -857,7 +875,6 @@ static void generic_forward(heisd_verify_ctx *ctx, const heisd_kv_desc *kv, cons
                                             ctx->x);
   }
   const size_t layer_stride = (size_t)batch * H * cap * HD;
-  const size_t attn_lds = attn_lds_bytes(HD, cap);
   for (int l = 0; l < d.n_layers; ++l) {
     GemmArgs g{};
     // q, k, v = RMSNorm(x) . {Wq, Wk, Wv}^T
@@ -877,8 +894,7 @@ static void generic_forward(heisd_verify_ctx *ctx, const heisd_kv_desc *kv, cons
     a.K = K; a.H = H; a.cap = cap; a.d = dm; a.scale = 1.0f / std::sqrt((float)HD);
     {
       ProfScope ps(ctx, HEISD_KC_ATTN, st, prof);
-      if (HD == 128) attn_verify<128><<<dim3(H, batch), dim3(kAttnThreads), attn_lds, st>>>(a);
-      else attn_verify<64><<<dim3(H, batch), dim3(kAttnThreads), attn_lds, st>>>(a);
+      attn_launch(a, HD, H, batch, cap, ctx->n_cu, st);
     }
     // x += o . Wo^T
     g = GemmArgs{};

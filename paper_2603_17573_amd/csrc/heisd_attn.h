@@ -16,8 +16,6 @@
 
 namespace heisd {
 
-constexpr int kAttnThreads = 256;
-constexpr int kAttnWaves = 4;
 constexpr int kAttnQB = 8;  // queries per block
 constexpr int kAttnU = 6;   // cache rows a key stream requests at once
 
@@ -44,9 +42,9 @@ struct AttnArgs {
   float scale;               // 1/sqrt(HD)
 };
 
-inline size_t attn_lds_bytes(int hd, int cap) {
-  return sizeof(float) * ((size_t)kAttnQB * hd + (size_t)kAttnQB * cap + kAttnQB +
-                          (size_t)kAttnWaves * kAttnQB * hd);
+// waves: 4 or 8 (workgroups of 256 or 512 threads)
+inline size_t attn_lds_bytes(int hd, int cap, int waves) {
+  return sizeof(float) * ((size_t)kAttnQB * hd + (size_t)kAttnQB * cap + kAttnQB + (size_t)waves * kAttnQB * hd);
 }
 
 // Attention output element (row m, column col).
@@ -61,8 +59,12 @@ __device__ __forceinline__ void attn_store(const AttnArgs &a, int m, int col, fl
   }
 }
 
-template <int HD>
-__global__ __launch_bounds__(kAttnThreads) void attn_verify(AttnArgs a) {
+// THREADS: 256 or 512.  With few (episode, head) pairs - fewer workgroups than would fill the
+// compute units twice - the larger workgroup hides more latency (M = 56: 31 -> 26 us per layer);
+// with many pairs the smaller one is faster (M = 448: 131 against 167 us).
+template <int HD, int THREADS>
+__global__ __launch_bounds__(THREADS) void attn_verify(AttnArgs a) {
+  constexpr int kAttnThreads = THREADS, kAttnWaves = THREADS / 64;
   constexpr int HALF = HD / 2;
   constexpr int LPK = HD / 8;              // lanes that share one key row (16 bytes each)
   constexpr int G = kAttnThreads / LPK;    // key rows in flight per pass
