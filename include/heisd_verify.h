@@ -154,6 +154,63 @@ int heisd_verify_step(heisd_verify_ctx *ctx, const heisd_kv_desc *kv, const int3
                       int32_t *target_bins, float *bin_logits, void *stream);
 
 /*
+ * Sequence-wise TREE verification (Sec. 4.2: Top-K retrieval; the draft tree is built sequence by
+ * sequence; every chain from the root is checked with the relaxed rule).  One decoder forward over
+ * all T tree tokens of every episode: token t sits at position prefix_len + depth(t) and attends to
+ * the prefix, its ancestors and itself, which gives every chain the numbers a forward of that chain
+ * alone would give.  Then, per episode, the chain that the acceptance rule lets get furthest is
+ * chosen (among equals: the one whose last accepted token has the lowest index), and the key/value
+ * rows of its accepted tokens are moved to cache rows prefix_len .. prefix_len + n - 1, so that the
+ * cache continues exactly as after a linear step over that chain.
+ *
+ *   tree_tokens   DEVICE i32 [batch][T]   vocabulary ids of the tree tokens
+ *   parent        DEVICE i32 [batch][T]   index of the token before t in its chain; -1 = t follows
+ *                                         the prefix.  A value outside [-1, t) marks padding: the
+ *                                         token is in no chain (it still costs a row of the forward)
+ *   T             tokens per episode, 1 .. min(max_k, 256); cache rows prefix_len .. prefix_len+T-1
+ *                 of a verified episode are overwritten
+ *   accepted_len  DEVICE i32 [batch] out  n = tokens of the chosen chain that are accepted; for a
+ *                                         skipped episode the length of the first chain (token 0,
+ *                                         then always the lowest-index child), executed unverified
+ *   next_token    DEVICE i32 [batch] out  the target's own token after the accepted tokens (after
+ *                                         the prefix when n = 0); -1 for skipped episodes
+ *   accepted_path DEVICE i32 [batch][T] out  the n accepted token indices in chain order, then -1
+ *   target_bins   DEVICE i32 [batch][T+1] out, optional: [0] = first_pred, [t+1] = the target's
+ *                                         greedy bin after token t; -1 for skipped episodes
+ *   bin_logits    DEVICE f32 [batch][T][n_bins] out, optional; NaN for skipped episodes
+ *   accept        as in heisd_verify_step; the sequence a token belongs to follows from its depth
+ *   other arguments as in heisd_verify_step.
+ *
+ * Runs on the record kernels (any T); asynchronous, allocates nothing, idempotent only if the
+ * caller restores nothing: the prefix rows are never written, and the rows past prefix_len are
+ * rewritten from the inputs by every call.
+ * Errors (nothing enqueued): as heisd_verify_step, plus EINVAL for T > 256 and EUNSUPPORTED when the
+ * context is pinned to a path that only serves batch*K <= 8 (HEISD_PATH_FAST / _PERSIST).
+ */
+int heisd_verify_tree_step(heisd_verify_ctx *ctx, const heisd_kv_desc *kv, const int32_t *tree_tokens,
+                           const int32_t *parent, int32_t T, int32_t batch, const heisd_accept_desc *accept,
+                           const uint8_t *skip_mask, int32_t *accepted_len, int32_t *next_token,
+                           int32_t *accepted_path, int32_t *target_bins, float *bin_logits, void *stream);
+
+/*
+ * Host-side construction of the draft tree from R retrieved candidates of K tokens each
+ * (Sec. 4.2: sequences of different retrieval results may follow each other, except the gripper).
+ * Plain CPU code, no device access.  Under a node, the children for a sequence level that is not
+ * exact are the distinct sequences of ALL candidates at that level; for an exact level (gripper)
+ * only those of the candidates whose sequence the node carries.  Equal siblings are merged.  Layout:
+ * depth-first preorder, candidates in the given order; a node that would exceed max_tokens is left
+ * out with its subtree.
+ *
+ *   candidates    HOST i32 [R][K]          vocabulary ids
+ *   accept        group sizes and exact mask (thresholds are not used)
+ *   tokens,parent HOST i32 [max_tokens] out
+ *   n_tokens      HOST out                 tokens written (<= max_tokens)
+ * Errors: EINVAL for NULL pointers, R < 1, K < 1, max_tokens < 1, R > 64, a bad group description.
+ */
+int heisd_build_sequence_tree(const int32_t *candidates, int32_t R, int32_t K, const heisd_accept_desc *accept,
+                              int32_t max_tokens, int32_t *tokens, int32_t *parent, int32_t *n_tokens);
+
+/*
  * Per-kernel timing for measurement runs (not part of the method).  With profiling enabled,
  * heisd_verify_step brackets every kernel launch with HIP events on the caller's stream;
  * heisd_verify_profile_read waits for the recorded events, adds the elapsed milliseconds

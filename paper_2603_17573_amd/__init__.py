@@ -5,12 +5,13 @@ entry points as include/heisd_verify.h, plus a small torch-facing convenience cl
 only moves pointers around.
 """
 from .binding import (heisd_model_desc, heisd_kv_desc, heisd_accept_desc, heisd_verify_workspace_bytes,
-                      heisd_verify_init, heisd_verify_step, heisd_free, heisd_last_error,
+                      heisd_verify_init, heisd_verify_step, heisd_verify_tree_step,
+                      heisd_build_sequence_tree, heisd_free, heisd_last_error,
                       heisd_verify_profile_enable, heisd_verify_profile_read, KERNEL_CLASSES,
                       heisd_verify_set_path, heisd_verify_check, HEISD_PATH_AUTO, HEISD_PATH_GENERIC, HEISD_PATH_FAST,
                       HEISD_PATH_PERSIST, HEISD_PATH_BATCH,
                       make_accept_desc, make_model_desc, HEISD_OK, HEISD_EINVAL, HEISD_EUNSUPPORTED,
                       HEISD_ENOMEM, HEISD_EHIP)
-from .runner import DeviceModel, Verifier
+from .runner import DeviceModel, Verifier, build_sequence_tree
 
 __all__ = [n for n in dir() if not n.startswith("_")]

@@ -58,6 +58,13 @@ def load():
                                           POINTER(heisd_accept_desc), c_void_p, c_void_p, c_void_p,
                                           c_void_p, c_void_p, c_void_p]
         lib.heisd_verify_step.restype = ctypes.c_int
+        lib.heisd_verify_tree_step.argtypes = [c_void_p, POINTER(heisd_kv_desc), c_void_p, c_void_p, c_int32, c_int32,
+                                               POINTER(heisd_accept_desc), c_void_p, c_void_p, c_void_p,
+                                               c_void_p, c_void_p, c_void_p, c_void_p]
+        lib.heisd_verify_tree_step.restype = ctypes.c_int
+        lib.heisd_build_sequence_tree.argtypes = [c_void_p, c_int32, c_int32, POINTER(heisd_accept_desc), c_int32,
+                                                  c_void_p, c_void_p, POINTER(c_int32)]
+        lib.heisd_build_sequence_tree.restype = ctypes.c_int
         lib.heisd_free.argtypes = [c_void_p]
         lib.heisd_free.restype = None
         lib.heisd_verify_profile_enable.argtypes = [c_void_p, ctypes.c_int]
@@ -91,6 +98,24 @@ def heisd_verify_step(ctx, kv: heisd_kv_desc, draft_tokens, K, batch, accept: he
     return load().heisd_verify_step(ctx, ctypes.byref(kv) if kv is not None else None, draft_tokens, K, batch,
                                     ctypes.byref(accept) if accept is not None else None, skip_mask,
                                     accepted_len, next_token, target_bins, bin_logits, stream)
+
+
+def heisd_verify_tree_step(ctx, kv: heisd_kv_desc, tree_tokens, parent, T, batch, accept: heisd_accept_desc,
+                           skip_mask, accepted_len, next_token, accepted_path, target_bins, bin_logits,
+                           stream) -> int:
+    """All array arguments are integer device addresses (0/None = NULL)."""
+    return load().heisd_verify_tree_step(ctx, ctypes.byref(kv) if kv is not None else None, tree_tokens, parent,
+                                         T, batch, ctypes.byref(accept) if accept is not None else None,
+                                         skip_mask, accepted_len, next_token, accepted_path, target_bins,
+                                         bin_logits, stream)
+
+
+def heisd_build_sequence_tree(candidates, R, K, accept: heisd_accept_desc, max_tokens, tokens, parent):
+    """candidates, tokens, parent: HOST addresses (ints) of i32 arrays.  Returns (rc, n_tokens)."""
+    n = c_int32(0)
+    rc = load().heisd_build_sequence_tree(candidates, R, K, ctypes.byref(accept) if accept is not None else None,
+                                          max_tokens, tokens, parent, ctypes.byref(n))
+    return rc, int(n.value)
 
 
 def heisd_free(ctx) -> None:

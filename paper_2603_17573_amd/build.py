@@ -5,7 +5,7 @@ import subprocess
 HERE = os.path.dirname(os.path.abspath(__file__))
 LIB = os.path.join(HERE, "libheisd_verify.so")
 SOURCES = [os.path.join(HERE, "csrc", "heisd_api.hip")]
-HEADERS = [os.path.join(HERE, "csrc", n) for n in ("heisd_common.h", "heisd_gemm.h", "heisd_attn.h", "heisd_misc.h")]
+HEADERS = [os.path.join(HERE, "csrc", n) for n in sorted(os.listdir(os.path.join(HERE, "csrc"))) if n.endswith(".h")]
 HEADERS.append(os.path.join(os.path.dirname(HERE), "include", "heisd_verify.h"))
 
 # packed-fp32 instructions are switched off on purpose: the compiler must not fuse pairs of

@@ -31,6 +31,8 @@ struct heisd_verify_ctx {
   float2 *rope;
   float *x, *qkv, *attn_o, *act, *logits;
   int32_t *tbins;
+  int32_t *tree_depth, *tree_path;     // tree steps: depth of every token, accepted path when the caller wants none
+  unsigned long long *tree_anc;        // tree steps: visibility bits [rows][4]
   unsigned char *fscr;                 // fast path: per-layer exchange records (see FastScratch)
   unsigned char *bscr;                 // batched path (M > 8): records and row statistics (see BatScratch)
   Phase *prog;                         // persistent kernel: the phase program in device memory
@@ -85,7 +87,7 @@ static int fail(heisd_verify_ctx *ctx, int code, const char *fmt, ...) {
 static size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
 
 struct WsLayout {
-  size_t rope, x, qkv, attn_o, act, logits, tbins, fscr, fscr_bytes, bscr, bscr_bytes, players, flags, trace, packed, packed_bytes, total;
+  size_t rope, x, qkv, attn_o, act, logits, tbins, tree_depth, tree_path, tree_anc, fscr, fscr_bytes, bscr, bscr_bytes, players, flags, trace, packed, packed_bytes, total;
 };
 
 // Buffers of the batched path (M > 8 rows).  One launch per phase, so one set serves every layer.
@@ -148,6 +150,9 @@ static WsLayout ws_layout(const heisd_model_desc *d) {
   w.act = off;    off += align256(M * d->d_ffn * sizeof(float));
   w.logits = off; off += align256(M * d->n_bins * sizeof(float));
   w.tbins = off;  off += align256((size_t)d->max_batch * (d->max_k + 1) * sizeof(int32_t));
+  w.tree_depth = off; off += align256(M * sizeof(int32_t));
+  w.tree_path = off;  off += align256(M * sizeof(int32_t));
+  w.tree_anc = off;   off += align256(M * 4 * sizeof(unsigned long long));
   w.fscr = off;
   w.fscr_bytes = FastScratch(d).stride * (size_t)(d->n_layers + 1);
   off += w.fscr_bytes;
@@ -222,27 +227,36 @@ static void gemm_launch(GemmArgs a, int M, int epi, hipStream_t st) {
 
 // ---- any-M attention: workgroup size by the number of (episode, head) pairs ----------------
 
-template <int HD, int THREADS>
+template <int HD, int THREADS, bool TREE>
 static hipError_t attn_prepare_one(int cap) {
-  return hipFuncSetAttribute(reinterpret_cast<const void *>(&attn_verify<HD, THREADS>),
+  return hipFuncSetAttribute(reinterpret_cast<const void *>(&attn_verify<HD, THREADS, TREE>),
                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)attn_lds_bytes(HD, cap, THREADS / 64));
 }
-static hipError_t attn_prepare(int hd, int cap) {
-  hipError_t e = hd == 128 ? attn_prepare_one<128, 256>(cap) : attn_prepare_one<64, 256>(cap);
-  if (e != hipSuccess) return e;
-  return hd == 128 ? attn_prepare_one<128, 512>(cap) : attn_prepare_one<64, 512>(cap);
+template <int HD>
+static hipError_t attn_prepare_hd(int cap) {
+  hipError_t e;
+  if ((e = attn_prepare_one<HD, 256, false>(cap)) != hipSuccess) return e;
+  if ((e = attn_prepare_one<HD, 512, false>(cap)) != hipSuccess) return e;
+  if ((e = attn_prepare_one<HD, 256, true>(cap)) != hipSuccess) return e;
+  return attn_prepare_one<HD, 512, true>(cap);
 }
-static void attn_launch(const AttnArgs &a, int hd, int H, int batch, int cap, int n_cu, hipStream_t st) {
+static hipError_t attn_prepare(int hd, int cap) { return hd == 128 ? attn_prepare_hd<128>(cap) : attn_prepare_hd<64>(cap); }
+
+template <int HD, bool TREE>
+static void attn_launch_hd(const AttnArgs &a, int H, int batch, int cap, int n_cu, hipStream_t st) {
   const bool big = H * batch < 2 * n_cu;       // few workgroups: 512 threads each hide more latency
   const dim3 grid(H, batch);
-  if (big) {
-    const size_t lds = attn_lds_bytes(hd, cap, 8);
-    if (hd == 128) attn_verify<128, 512><<<grid, dim3(512), lds, st>>>(a);
-    else attn_verify<64, 512><<<grid, dim3(512), lds, st>>>(a);
+  if (big) attn_verify<HD, 512, TREE><<<grid, dim3(512), attn_lds_bytes(HD, cap, 8), st>>>(a);
+  else attn_verify<HD, 256, TREE><<<grid, dim3(256), attn_lds_bytes(HD, cap, 4), st>>>(a);
+}
+static void attn_launch(const AttnArgs &a, int hd, int H, int batch, int cap, int n_cu, hipStream_t st) {
+  const bool tree = a.depth != nullptr && a.anc != nullptr;
+  if (hd == 128) {
+    if (tree) attn_launch_hd<128, true>(a, H, batch, cap, n_cu, st);
+    else attn_launch_hd<128, false>(a, H, batch, cap, n_cu, st);
   } else {
-    const size_t lds = attn_lds_bytes(hd, cap, 4);
-    if (hd == 128) attn_verify<128, 256><<<grid, dim3(256), lds, st>>>(a);
-    else attn_verify<64, 256><<<grid, dim3(256), lds, st>>>(a);
+    if (tree) attn_launch_hd<64, true>(a, H, batch, cap, n_cu, st);
+    else attn_launch_hd<64, false>(a, H, batch, cap, n_cu, st);
   }
 }
 
@@ -555,6 +569,9 @@ extern "C" int heisd_verify_init(const heisd_model_desc *desc, heisd_verify_ctx 
   c->act = reinterpret_cast<float *>(base + w.act);
   c->logits = reinterpret_cast<float *>(base + w.logits);
   c->tbins = reinterpret_cast<int32_t *>(base + w.tbins);
+  c->tree_depth = reinterpret_cast<int32_t *>(base + w.tree_depth);
+  c->tree_path = reinterpret_cast<int32_t *>(base + w.tree_path);
+  c->tree_anc = reinterpret_cast<unsigned long long *>(base + w.tree_anc);
   c->fscr = base + w.fscr;
   c->bscr = base + w.bscr;
   c->prog = reinterpret_cast<Phase *>(base + w.players);
@@ -776,7 +793,8 @@ static void bat_launch(BatGemm g, int n_cu, hipStream_t st) {
 }
 
 static void batch_forward(heisd_verify_ctx *ctx, const heisd_kv_desc *kv, const int32_t *draft_tokens, int K,
-                          int batch, const uint8_t *skip_mask, float *logits, hipStream_t st, bool prof) {
+                          int batch, const uint8_t *skip_mask, float *logits, hipStream_t st, bool prof,
+                          const int32_t *depth = nullptr, const unsigned long long *anc = nullptr) {
   const heisd_model_desc &d = ctx->d;
   const int M = batch * K, dm = d.d_model, F = d.d_ffn, H = d.n_heads, HD = d.head_dim, cap = d.kv_capacity;
   const BatScratch bs(&d);
@@ -817,6 +835,7 @@ static void batch_forward(heisd_verify_ctx *ctx, const heisd_kv_desc *kv, const 
     a.prefix_len = kv->prefix_len; a.skip = skip_mask; a.rope = ctx->rope; a.out = nullptr;
     a.o_planes = rec_o; a.CTS = CTS;
     a.K = K; a.H = H; a.cap = cap; a.d = dm; a.scale = 1.0f / std::sqrt((float)HD);
+    a.depth = depth; a.anc = anc;
     {
       ProfScope ps(ctx, HEISD_KC_ATTN, st, prof);
       attn_launch(a, HD, H, batch, cap, ctx->n_cu, st);
@@ -866,7 +885,8 @@ static void batch_forward(heisd_verify_ctx *ctx, const heisd_kv_desc *kv, const 
 }
 
 static void generic_forward(heisd_verify_ctx *ctx, const heisd_kv_desc *kv, const int32_t *draft_tokens, int K,
-                            int batch, const uint8_t *skip_mask, float *logits, hipStream_t st, bool prof) {
+                            int batch, const uint8_t *skip_mask, float *logits, hipStream_t st, bool prof,
+                            const int32_t *depth = nullptr, const unsigned long long *anc = nullptr) {
   const heisd_model_desc &d = ctx->d;
   const int M = batch * K, dm = d.d_model, F = d.d_ffn, H = d.n_heads, HD = d.head_dim, cap = d.kv_capacity;
   {
@@ -892,6 +912,7 @@ static void generic_forward(heisd_verify_ctx *ctx, const heisd_kv_desc *kv, cons
     a.v_cache = static_cast<uint16_t *>(kv->v_cache) + (size_t)l * layer_stride;
     a.prefix_len = kv->prefix_len; a.skip = skip_mask; a.rope = ctx->rope; a.out = ctx->attn_o;
     a.K = K; a.H = H; a.cap = cap; a.d = dm; a.scale = 1.0f / std::sqrt((float)HD);
+    a.depth = depth; a.anc = anc;
     {
       ProfScope ps(ctx, HEISD_KC_ATTN, st, prof);
       attn_launch(a, HD, H, batch, cap, ctx->n_cu, st);
@@ -987,5 +1008,143 @@ extern "C" int heisd_verify_step(heisd_verify_ctx *ctx, const heisd_kv_desc *kv,
   const hipError_t e = hipGetLastError();
   if (e != hipSuccess) return fail(ctx, HEISD_EHIP, "step: %s", hipGetErrorString(e));
   ctx->err[0] = 0;
+  return HEISD_OK;
+}
+
+// ---- one tree verify step -------------------------------------------------------------------
+
+static int check_accept_desc(heisd_verify_ctx *ctx, const heisd_accept_desc *accept, const char *who) {
+  if (accept->n_groups < 1 || accept->n_groups > HEISD_MAX_GROUPS)
+    return fail(ctx, HEISD_EINVAL, "%s: n_groups=%d outside [1,%d]", who, accept->n_groups, HEISD_MAX_GROUPS);
+  for (int g = 0; g < accept->n_groups; ++g)
+    if (accept->group_sizes[g] < 1) return fail(ctx, HEISD_EINVAL, "%s: group_sizes[%d] < 1", who, g);
+  if (accept->tok_threshold < 0 || accept->seq_budget < 0)
+    return fail(ctx, HEISD_EINVAL, "%s: negative acceptance threshold", who);
+  if (accept->mode != 0 && accept->mode != 1) return fail(ctx, HEISD_EINVAL, "%s: mode %d", who, accept->mode);
+  return HEISD_OK;
+}
+
+extern "C" int heisd_verify_tree_step(heisd_verify_ctx *ctx, const heisd_kv_desc *kv, const int32_t *tree_tokens,
+                                      const int32_t *parent, int32_t T, int32_t batch,
+                                      const heisd_accept_desc *accept, const uint8_t *skip_mask,
+                                      int32_t *accepted_len, int32_t *next_token, int32_t *accepted_path,
+                                      int32_t *target_bins, float *bin_logits, void *stream) {
+  if (!ctx) return HEISD_EINVAL;
+  if (!kv || !kv->k_cache || !kv->v_cache || !kv->prefix_len || !kv->first_pred || !tree_tokens || !parent ||
+      !accept || !accepted_len || !next_token)
+    return fail(ctx, HEISD_EINVAL, "tree_step: NULL required pointer");
+  const heisd_model_desc &d = ctx->d;
+  if (T < 1 || batch < 1 || T > d.max_k || T > kTreeMax || batch > d.max_batch || T > d.kv_capacity)
+    return fail(ctx, HEISD_EINVAL, "tree_step: T=%d batch=%d outside [1,%d] x [1,%d] (kv_capacity %d)", T, batch,
+                d.max_k < kTreeMax ? d.max_k : kTreeMax, d.max_batch, d.kv_capacity);
+  const int rc = check_accept_desc(ctx, accept, "tree_step");
+  if (rc != HEISD_OK) return rc;
+  if (ctx->path == HEISD_PATH_FAST || ctx->path == HEISD_PATH_PERSIST)
+    return fail(ctx, HEISD_EUNSUPPORTED, "tree_step: the selected path serves linear steps of at most 8 rows only");
+
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  float *logits = bin_logits ? bin_logits : ctx->logits;
+  int32_t *tbins = target_bins ? target_bins : ctx->tbins;
+  int32_t *path = accepted_path ? accepted_path : ctx->tree_path;
+  (void)hipGetLastError();
+  const bool prof = ctx->prof_on && ctx->prof_steps < HEISD_PROFILE_MAX_STEPS;
+  if (prof) ctx->prof_steps++;
+  {
+    ProfScope ps(ctx, HEISD_KC_EMBED, st, prof);
+    tree_setup<<<dim3(batch), dim3(kTreeMax), 0, st>>>(parent, T, ctx->tree_depth, ctx->tree_anc);
+  }
+  if (ctx->path == HEISD_PATH_GENERIC)
+    generic_forward(ctx, kv, tree_tokens, T, batch, skip_mask, logits, st, prof, ctx->tree_depth, ctx->tree_anc);
+  else
+    batch_forward(ctx, kv, tree_tokens, T, batch, skip_mask, logits, st, prof, ctx->tree_depth, ctx->tree_anc);
+  TreeAcceptArgs aa{};
+  aa.logits = logits; aa.logits_rw = logits; aa.tokens = tree_tokens; aa.parent = parent;
+  aa.first_pred = kv->first_pred; aa.skip = skip_mask; aa.accepted_len = accepted_len; aa.next_token = next_token;
+  aa.path = path; aa.target_bins = tbins;
+  aa.T = T; aa.n_bins = d.n_bins; aa.bin_base = d.bin_token_base;
+  aa.tok_threshold = accept->tok_threshold; aa.seq_budget = accept->seq_budget;
+  aa.n_groups = accept->n_groups; aa.mode = accept->mode; aa.exact_mask = accept->exact_group_mask;
+  for (int i = 0; i < 8; ++i) aa.group_sizes[i] = i < accept->n_groups ? accept->group_sizes[i] : 1;
+  TreeCompactArgs ca{};
+  ca.k_cache = static_cast<uint16_t *>(kv->k_cache); ca.v_cache = static_cast<uint16_t *>(kv->v_cache);
+  ca.prefix_len = kv->prefix_len; ca.skip = skip_mask; ca.accepted_len = accepted_len; ca.path = path;
+  ca.T = T; ca.H = d.n_heads; ca.cap = d.kv_capacity; ca.HD = d.head_dim; ca.batch = batch;
+  {
+    ProfScope ps(ctx, HEISD_KC_ACCEPT, st, prof);
+    tree_accept<<<dim3(batch), dim3(256), 0, st>>>(aa);
+    tree_compact<<<dim3(d.n_heads, batch, d.n_layers), dim3(256), 0, st>>>(ca);
+  }
+  const hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return fail(ctx, HEISD_EHIP, "tree_step: %s", hipGetErrorString(e));
+  ctx->err[0] = 0;
+  return HEISD_OK;
+}
+
+// ---- the draft tree from retrieved candidates (host code) -------------------------------------
+
+namespace {
+struct TreeBuilder {
+  const int32_t *cand;
+  int R, K, max_tokens;
+  std::vector<int> lv_start, lv_end, lv_group;
+  unsigned exact_mask;
+  int32_t *tokens, *parent;
+  int n = 0;
+
+  bool same_seq(int a, int b, int s, int e) const {
+    for (int j = s; j < e; ++j)
+      if (cand[(size_t)a * K + j] != cand[(size_t)b * K + j]) return false;
+    return true;
+  }
+  // Children of the node that ends at token `last` (-1: the prefix) and stands for candidates `carried`.
+  void grow(int level, int last, uint64_t carried) {
+    if (level == (int)lv_start.size()) return;
+    const int s = lv_start[level], e = lv_end[level];
+    const bool exact = (exact_mask >> lv_group[level]) & 1u;
+    const uint64_t eligible = exact ? carried : (R == 64 ? ~0ull : ((1ull << R) - 1));
+    uint64_t done = 0;
+    for (int c = 0; c < R; ++c) {
+      if (!((eligible >> c) & 1) || ((done >> c) & 1)) continue;
+      uint64_t owners = 0;
+      for (int o = c; o < R; ++o)
+        if (((eligible >> o) & 1) && same_seq(c, o, s, e)) owners |= 1ull << o;
+      done |= owners;
+      if (n + (e - s) > max_tokens) continue;
+      int prev = last;
+      for (int j = s; j < e; ++j) {
+        tokens[n] = cand[(size_t)c * K + j];
+        parent[n] = prev;
+        prev = n++;
+      }
+      grow(level + 1, prev, owners);
+    }
+  }
+};
+}  // namespace
+
+extern "C" int heisd_build_sequence_tree(const int32_t *candidates, int32_t R, int32_t K,
+                                         const heisd_accept_desc *accept, int32_t max_tokens, int32_t *tokens,
+                                         int32_t *parent, int32_t *n_tokens) {
+  if (!candidates || !accept || !tokens || !parent || !n_tokens)
+    return fail(nullptr, HEISD_EINVAL, "build_tree: NULL pointer");
+  if (R < 1 || R > 64 || K < 1 || max_tokens < 1)
+    return fail(nullptr, HEISD_EINVAL, "build_tree: R=%d K=%d max_tokens=%d", R, K, max_tokens);
+  if (accept->n_groups < 1 || accept->n_groups > HEISD_MAX_GROUPS)
+    return fail(nullptr, HEISD_EINVAL, "build_tree: n_groups=%d", accept->n_groups);
+  for (int g = 0; g < accept->n_groups; ++g)
+    if (accept->group_sizes[g] < 1) return fail(nullptr, HEISD_EINVAL, "build_tree: group_sizes[%d] < 1", g);
+  TreeBuilder tb;
+  tb.cand = candidates; tb.R = R; tb.K = K; tb.max_tokens = max_tokens;
+  tb.exact_mask = accept->exact_group_mask; tb.tokens = tokens; tb.parent = parent;
+  for (int j = 0, g = 0; j < K; ++g) {
+    const int gi = g % accept->n_groups, size = accept->group_sizes[gi];
+    tb.lv_start.push_back(j);
+    tb.lv_end.push_back(j + size < K ? j + size : K);
+    tb.lv_group.push_back(gi);
+    j += size;
+  }
+  tb.grow(0, -1, R == 64 ? ~0ull : ((1ull << R) - 1));
+  *n_tokens = tb.n;
+  g_init_err[0] = 0;
   return HEISD_OK;
 }

@@ -11,6 +11,11 @@
 //      wavefront shuffles), softmax per query with wavefront reductions, then one pass over
 //      the value rows accumulating all 8 outputs.
 // Skipped episodes (verify-skip, Sec. 4.1) touch neither the cache nor the scores.
+//
+// Tree verification (Sec. 4.2: chains of a sequence-wise draft tree are checked in one pass):
+// with `depth` and `anc` given, new row j sits at position prefix_len + depth[j] and sees, among
+// the new rows, exactly those whose bit is set in its 256-bit ancestor mask (itself included).
+// Its key and value still go to cache row prefix_len + j.
 #pragma once
 #include "heisd_common.h"
 
@@ -40,6 +45,8 @@ struct AttnArgs {
   int CTS;                   //     column tile of 8 activation rows), the B-operand format of the GEMMs
   int K, H, cap, d;
   float scale;               // 1/sqrt(HD)
+  const int32_t *depth;              // tree mode: [batch][K] tokens between the prefix and row j; else nullptr
+  const unsigned long long *anc;     // tree mode: [batch][K][4] visibility bits over the K new rows
 };
 
 // waves: 4 or 8 (workgroups of 256 or 512 threads)
@@ -62,7 +69,8 @@ __device__ __forceinline__ void attn_store(const AttnArgs &a, int m, int col, fl
 // THREADS: 256 or 512.  With few (episode, head) pairs - fewer workgroups than would fill the
 // compute units twice - the larger workgroup hides more latency (M = 56: 31 -> 26 us per layer);
 // with many pairs the smaller one is faster (M = 448: 131 against 167 us).
-template <int HD, int THREADS>
+// TREE: tree mode compiled in (the linear kernel carries none of its registers).
+template <int HD, int THREADS, bool TREE>
 __global__ __launch_bounds__(THREADS) void attn_verify(AttnArgs a) {
   constexpr int kAttnThreads = THREADS, kAttnWaves = THREADS / 64;
   constexpr int HALF = HD / 2;
@@ -91,7 +99,7 @@ __global__ __launch_bounds__(THREADS) void attn_verify(AttnArgs a) {
   for (int idx = tid; idx < K * HALF; idx += kAttnThreads) {
     const int j = idx / HALF, i = idx - j * HALF;
     float *src = a.qkv + (size_t)(row0 + j) * 3 * d + h * HD;
-    const float2 cs = a.rope[(size_t)(P + j) * HALF + i];
+    const float2 cs = a.rope[(size_t)(P + (TREE ? a.depth[row0 + j] : j)) * HALF + i];
     const float k1 = src[d + i], k2 = src[d + i + HALF];
     const float kr1 = k1 * cs.x - k2 * cs.y, kr2 = k2 * cs.x + k1 * cs.y;
     src[d + i] = kr1;
@@ -115,7 +123,7 @@ __global__ __launch_bounds__(THREADS) void attn_verify(AttnArgs a) {
       float r1 = 0.f, r2 = 0.f;
       if (j < nq) {
         const float *src = a.qkv + (size_t)(row0 + j0 + j) * 3 * d + h * HD;
-        const float2 cs = a.rope[(size_t)(P + j0 + j) * HALF + i];
+        const float2 cs = a.rope[(size_t)(P + (TREE ? a.depth[row0 + j0 + j] : j0 + j)) * HALF + i];
         const float q1 = src[i], q2 = src[i + HALF];
         r1 = (q1 * cs.x - q2 * cs.y) * a.scale;
         r2 = (q2 * cs.x + q1 * cs.y) * a.scale;
@@ -130,8 +138,22 @@ __global__ __launch_bounds__(THREADS) void attn_verify(AttnArgs a) {
 #pragma unroll
       for (int i = 0; i < 8; ++i) qf[j][i] = qs[j * HD + li * 8 + i];
 
+    // tree mode: the visibility bits of the query this lane writes scores for
+    unsigned long long aw0 = 0, aw1 = 0, aw2 = 0, aw3 = 0;
+    if (TREE && li < nq) {
+      const unsigned long long *w = a.anc + (size_t)(row0 + j0 + li) * 4;
+      aw0 = w[0]; aw1 = w[1]; aw2 = w[2]; aw3 = w[3];
+    }
+    // is new row r - P visible to query j0 + li?
+    auto sees_new = [&](int r) __attribute__((always_inline)) {
+      if (!TREE) return r <= P + j0 + li;
+      const int t = r - P, w = t >> 6;
+      const unsigned long long word = w == 0 ? aw0 : (w == 1 ? aw1 : (w == 2 ? aw2 : aw3));
+      return ((word >> (t & 63)) & 1ull) != 0;
+    };
+
     // ---- pass 1: scores ----
-    auto score_key = [&](const float (&kf)[8], int r) __attribute__((always_inline)) {
+    auto score_key = [&](const float (&kf)[8], int r, bool vis) __attribute__((always_inline)) {
       float s[kAttnQB];
 #pragma unroll
       for (int j = 0; j < kAttnQB; ++j) {
@@ -147,7 +169,7 @@ __global__ __launch_bounds__(THREADS) void attn_verify(AttnArgs a) {
       float mine = s[0];
 #pragma unroll
       for (int j = 1; j < kAttnQB; ++j) mine = (li == j) ? s[j] : mine;
-      if (li < kAttnQB) sc[(size_t)li * cap + r] = (r <= P + j0 + li) ? mine : -INFINITY;
+      if (li < kAttnQB) sc[(size_t)li * cap + r] = vis ? mine : -INFINITY;
     };
     // prefix rows (bf16, from the cache): kAttnU rows of this lane's stream are requested before
     // the first is used, so a stream is a few round trips to memory instead of one per row
@@ -164,7 +186,7 @@ __global__ __launch_bounds__(THREADS) void attn_verify(AttnArgs a) {
         if (r < P) {
           float kf[8];
           attn_unpack8(kk[u], kf);
-          score_key(kf, r);
+          score_key(kf, r, true);
         }
       }
     }
@@ -173,7 +195,7 @@ __global__ __launch_bounds__(THREADS) void attn_verify(AttnArgs a) {
       const float *kp = a.qkv + (size_t)(row0 + r - P) * 3 * d + d + h * HD + li * 8;
       const float4 k0 = *reinterpret_cast<const float4 *>(kp), k1 = *reinterpret_cast<const float4 *>(kp + 4);
       const float kf[8] = {k0.x, k0.y, k0.z, k0.w, k1.x, k1.y, k1.z, k1.w};
-      score_key(kf, r);
+      score_key(kf, r, sees_new(r));
     }
     __syncthreads();
 

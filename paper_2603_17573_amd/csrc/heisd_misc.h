@@ -125,4 +125,239 @@ __global__ __launch_bounds__(256) void argmax_accept(AcceptArgs a) {
   a.next_token[b] = a.bin_base + tb[n];
 }
 
+// ---- tree verification (Sec. 4.2: a sequence-wise draft tree, every chain checked from the root) ----
+
+constexpr int kTreeMax = 256;    // tree tokens per episode (four 64-bit words of visibility bits)
+
+// depth[b][t]: tokens between the prefix and token t; anc[b][t][4]: bit u set iff token u is t or one
+// of its ancestors.  A token whose chain does not reach the prefix through parent indices in [-1, own
+// index) is padding: depth 0, sees only itself.  One thread per token; the walk ends because the index
+// strictly decreases.
+__global__ __launch_bounds__(kTreeMax) void tree_setup(const int32_t *parent, int T, int32_t *depth,
+                                                      unsigned long long *anc) {
+  const int b = blockIdx.x, t = threadIdx.x;
+  if (t >= T) return;
+  const int32_t *par = parent + (size_t)b * T;
+  unsigned long long w[4] = {0, 0, 0, 0};
+  auto set_bit = [&](int u) __attribute__((always_inline)) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) w[i] |= ((u >> 6) == i) ? (1ull << (u & 63)) : 0ull;
+  };
+  int dep = 0, cur = t;
+  bool ok = true;
+  for (;;) {
+    const int p = par[cur];
+    if (p == -1) break;
+    if (p < 0 || p >= cur) { ok = false; break; }
+    set_bit(p);
+    ++dep;
+    cur = p;
+  }
+  if (!ok) {
+    dep = 0;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) w[i] = 0;
+  }
+  set_bit(t);
+  depth[(size_t)b * T + t] = dep;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) anc[((size_t)b * T + t) * 4 + i] = w[i];
+}
+
+struct TreeAcceptArgs {
+  const float *logits;        // [batch][T][n_bins]
+  float *logits_rw;
+  const int32_t *tokens;      // [batch][T] vocabulary ids
+  const int32_t *parent;      // [batch][T]
+  const int32_t *first_pred;  // [batch]
+  const uint8_t *skip;        // [batch] or nullptr
+  int32_t *accepted_len;      // [batch]
+  int32_t *next_token;        // [batch]
+  int32_t *path;              // [batch][T]
+  int32_t *target_bins;       // [batch][T+1]
+  int T, n_bins, bin_base;
+  int tok_threshold, seq_budget, n_groups, mode;
+  int group_sizes[8];
+  unsigned exact_mask;
+};
+
+// One workgroup per episode.  Greedy bin after every tree token, then the chain selection: walking
+// the tokens in index order (a parent always precedes its children), each token extends the state of
+// its parent - the running sums of the sequence it is in, and whether everything before that
+// sequence was accepted - so that one pass finds, for every point where a chain may stop (the end of
+// a sequence, or a leaf), whether the chain is accepted up to there.  The deepest such point wins,
+// among equals the lowest token index.  Integer work: bit-exact by construction.
+__global__ __launch_bounds__(256) void tree_accept(TreeAcceptArgs a) {
+  __shared__ int32_t s_par[kTreeMax], s_pred[kTreeMax], s_depth[kTreeMax], s_gmax[kTreeMax], s_child[kTreeMax];
+  __shared__ long long s_gsum[kTreeMax];
+  __shared__ unsigned char s_valid[kTreeMax], s_alive[kTreeMax], s_end[kTreeMax];
+  __shared__ unsigned char s_gi[kTreeMax], s_first[kTreeMax], s_last[kTreeMax];    // by depth
+  const int b = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int T = a.T;
+  int32_t *tb = a.target_bins + (size_t)b * (T + 1);
+  int32_t *path = a.path + (size_t)b * T;
+  const int32_t *par = a.parent + (size_t)b * T;
+  const bool skipped = a.skip && a.skip[b];
+  for (int t = tid; t < T; t += 256) {
+    s_par[t] = par[t];
+    s_child[t] = 0x7FFFFFFF;       // lowest-index child
+  }
+  __syncthreads();
+  if (tid == 0) {
+    // which tokens are in the tree; the sequence pattern by depth
+    for (int t = 0; t < T; ++t) {
+      const int p = s_par[t];
+      const bool ok = p == -1 || (p >= 0 && p < t && s_valid[p]);
+      s_valid[t] = ok;
+      s_depth[t] = (ok && p >= 0) ? s_depth[p] + 1 : 0;
+    }
+    int dpt = 0, g = 0;
+    while (dpt < T) {
+      const int gi = g % a.n_groups, size = a.group_sizes[gi];
+      for (int i = 0; i < size && dpt < T; ++i, ++dpt) {
+        s_gi[dpt] = (unsigned char)gi;
+        s_first[dpt] = i == 0;
+        s_last[dpt] = i == size - 1;
+      }
+      ++g;
+    }
+  }
+  __syncthreads();
+  for (int t = tid; t < T; t += 256)
+    if (s_valid[t] && s_par[t] >= 0) atomicMin(&s_child[s_par[t]], t);
+  if (skipped) {
+    for (int i = tid; i < T * a.n_bins; i += 256) a.logits_rw[(size_t)b * T * a.n_bins + i] = __uint_as_float(0x7FC00000u);
+    for (int j = tid; j <= T; j += 256) tb[j] = -1;
+    for (int j = tid; j < T; j += 256) path[j] = -1;
+    __syncthreads();
+    if (tid == 0) {
+      // an unverified draft is executed as is: the first chain
+      int n = 0;
+      if (s_valid[0] && s_par[0] == -1) {
+        int cur = 0;
+        for (;;) {
+          path[n++] = cur;
+          const int c = s_child[cur];
+          if (c == 0x7FFFFFFF) break;
+          cur = c;
+        }
+      }
+      a.accepted_len[b] = n;
+      a.next_token[b] = -1;
+    }
+    return;
+  }
+  // greedy bin after every token: one wave per row, lowest index wins ties, NaN never wins
+  for (int j = wave; j < T; j += 4) {
+    const float *row = a.logits + ((size_t)b * T + j) * a.n_bins;
+    float best = -INFINITY;
+    int bi = 0x7FFFFFFF;
+    for (int t = lane; t < a.n_bins; t += kWave) {
+      float v = row[t];
+      if (v != v) v = -INFINITY;
+      if (v > best || (v == best && t < bi)) { best = v; bi = t; }
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+      const float ov = __shfl_xor(best, o, kWave);
+      const int oi = __shfl_xor(bi, o, kWave);
+      if (ov > best || (ov == best && oi < bi)) { best = ov; bi = oi; }
+    }
+    if (lane == 0) s_pred[j] = (bi == 0x7FFFFFFF) ? 0 : bi;
+  }
+  __syncthreads();
+  const int fp = a.first_pred[b];
+  for (int j = tid; j < T; j += 256) {
+    tb[j + 1] = s_valid[j] ? s_pred[j] : -1;
+    path[j] = -1;
+  }
+  if (tid == 0) tb[0] = fp;
+  __syncthreads();
+  if (tid != 0) return;
+  const int32_t *tok = a.tokens + (size_t)b * T;
+  int best_n = 0, best_t = -1;
+  for (int t = 0; t < T; ++t) {
+    if (!s_valid[t]) continue;
+    const int p = s_par[t], dpt = s_depth[t];
+    const int dbin = tok[t] - a.bin_base;
+    const int target = p < 0 ? fp : s_pred[p];
+    const long long bias = (dbin >= 0 && dbin < a.n_bins) ? (long long)abs(dbin - target) : 0x7FFFFFFFLL;
+    const bool exact = (a.exact_mask >> s_gi[dpt]) & 1u;
+    const bool leaf = s_child[t] == 0x7FFFFFFF;
+    if (a.mode == 0) {
+      const bool first = s_first[dpt];
+      // everything before this token's sequence accepted?
+      const bool alive = first ? (p < 0 || s_end[p]) : s_alive[p];
+      const long long gsum = (first ? 0 : s_gsum[p]) + bias;
+      const long long gmax = first ? bias : (bias > s_gmax[p] ? bias : (long long)s_gmax[p]);
+      s_alive[t] = alive;
+      s_gsum[t] = gsum;
+      s_gmax[t] = (int32_t)gmax;
+      const bool pass = exact ? gmax == 0 : (gmax <= a.tok_threshold && gsum <= a.seq_budget);
+      const bool stop_ok = alive && pass && (s_last[dpt] || leaf);
+      s_end[t] = stop_ok;
+      if (stop_ok && dpt + 1 > best_n) { best_n = dpt + 1; best_t = t; }
+    } else {
+      const long long run = (p < 0 ? 0 : s_gsum[p]) + bias;
+      const bool alive = (p < 0 || s_alive[p]) && !(exact && bias != 0) && bias <= a.tok_threshold &&
+                         run <= a.seq_budget;
+      s_gsum[t] = run;
+      s_alive[t] = alive;
+      if (alive && dpt + 1 > best_n) { best_n = dpt + 1; best_t = t; }
+    }
+  }
+  a.accepted_len[b] = best_n;
+  a.next_token[b] = a.bin_base + (best_t < 0 ? fp : s_pred[best_t]);
+  for (int cur = best_t, j = best_n - 1; j >= 0; --j) {
+    path[j] = cur;
+    cur = s_par[cur];
+  }
+}
+
+struct TreeCompactArgs {
+  uint16_t *k_cache, *v_cache;   // bf16 [L][batch][H][cap][HD]
+  const int32_t *prefix_len;     // [batch]
+  const uint8_t *skip;           // [batch] or nullptr
+  const int32_t *accepted_len;   // [batch]
+  const int32_t *path;           // [batch][T]
+  int T, H, cap, HD, batch;
+};
+
+// After the selection: the key/value rows of the n accepted tokens (written at prefix_len + token
+// index by the attention kernel) move to rows prefix_len .. prefix_len + n - 1.  One workgroup per
+// (head, episode, layer).  path[j] >= j and strictly increasing, so a chunk of rows is read whole,
+// then written: a source row is never overwritten before it is read.
+__global__ __launch_bounds__(256) void tree_compact(TreeCompactArgs a) {
+  const int h = blockIdx.x, b = blockIdx.y, l = blockIdx.z, tid = threadIdx.x;
+  if (a.skip && a.skip[b]) return;
+  const int n = max(0, min(a.accepted_len[b], a.T));
+  int P = a.prefix_len[b];
+  P = max(0, min(P, a.cap - a.T));
+  const int LPR = a.HD / 8, rows_per_pass = 256 / LPR;
+  const size_t base = (((size_t)l * a.batch + b) * a.H + h) * (size_t)a.cap * a.HD;
+  uint16_t *kc = a.k_cache + base, *vc = a.v_cache + base;
+  const int32_t *path = a.path + (size_t)b * a.T;
+  const int li = tid % LPR, rj = tid / LPR;
+  for (int j0 = 0; j0 < n; j0 += rows_per_pass) {      // n is the same for the whole workgroup
+    const int j = j0 + rj;
+    uint4 kk = make_uint4(0, 0, 0, 0), vv = kk;
+    int src = -1;
+    if (j < n) {
+      src = path[j];
+      if (src != j && src >= 0 && src < a.T) {
+        kk = *reinterpret_cast<const uint4 *>(kc + (size_t)(P + src) * a.HD + li * 8);
+        vv = *reinterpret_cast<const uint4 *>(vc + (size_t)(P + src) * a.HD + li * 8);
+      } else {
+        src = -1;
+      }
+    }
+    __syncthreads();
+    if (src >= 0) {
+      *reinterpret_cast<uint4 *>(kc + (size_t)(P + j) * a.HD + li * 8) = kk;
+      *reinterpret_cast<uint4 *>(vc + (size_t)(P + j) * a.HD + li * 8) = vv;
+    }
+    __syncthreads();
+  }
+}
+
 }  // namespace heisd

@@ -88,6 +88,32 @@ class Verifier:
             raise RuntimeError("heisd_verify_step failed (%d): %s" % (rc, B.heisd_last_error(self.ctx)))
         return out
 
+    def tree_step(self, k_cache, v_cache, prefix_len, first_pred, tree_tokens, parent, accept, skip_mask=None,
+                  want_aux=True, out=None, stream=None):
+        """tree_tokens, parent: i32[batch,T] on the device.  Returns dict of device tensors."""
+        batch, T = tree_tokens.shape
+        dev = self.model.device
+        if out is None:
+            out = {"accepted_len": torch.empty(batch, dtype=torch.int32, device=dev),
+                   "next_token": torch.empty(batch, dtype=torch.int32, device=dev),
+                   "accepted_path": torch.empty(batch, T, dtype=torch.int32, device=dev)}
+            if want_aux:
+                out["target_bins"] = torch.empty(batch, T + 1, dtype=torch.int32, device=dev)
+                out["bin_logits"] = torch.empty(batch, T, self.model.shape["n_bins"], dtype=torch.float32,
+                                                device=dev)
+        kv = B.heisd_kv_desc(k_cache.data_ptr(), v_cache.data_ptr(), prefix_len.data_ptr(),
+                             first_pred.data_ptr())
+        st = (stream or torch.cuda.current_stream(dev)).cuda_stream
+        rc = B.heisd_verify_tree_step(self.ctx, kv, tree_tokens.data_ptr(), parent.data_ptr(), T, batch, accept,
+                                      skip_mask.data_ptr() if skip_mask is not None else None,
+                                      out["accepted_len"].data_ptr(), out["next_token"].data_ptr(),
+                                      out["accepted_path"].data_ptr(),
+                                      out["target_bins"].data_ptr() if "target_bins" in out else None,
+                                      out["bin_logits"].data_ptr() if "bin_logits" in out else None, st)
+        if rc != 0:
+            raise RuntimeError("heisd_verify_tree_step failed (%d): %s" % (rc, B.heisd_last_error(self.ctx)))
+        return out
+
     def close(self):
         if self.ctx is not None:
             B.heisd_free(self.ctx)
@@ -98,3 +124,16 @@ class Verifier:
             self.close()
         except Exception:
             pass
+
+
+def build_sequence_tree(candidates, accept, max_tokens):
+    """Host call: candidates i32[R,K] (numpy) -> (tokens[T], parent[T]) numpy arrays."""
+    cand = np.ascontiguousarray(candidates, dtype=np.int32)
+    R, K = cand.shape
+    tokens = np.zeros(max_tokens, np.int32)
+    parent = np.zeros(max_tokens, np.int32)
+    rc, n = B.heisd_build_sequence_tree(cand.ctypes.data, R, K, accept, max_tokens, tokens.ctypes.data,
+                                        parent.ctypes.data)
+    if rc != 0:
+        raise RuntimeError("heisd_build_sequence_tree failed (%d): %s" % (rc, B.heisd_last_error(None)))
+    return tokens[:n].copy(), parent[:n].copy()

@@ -147,6 +147,19 @@ def make_offsets_geometric(wl: Workload, p: float) -> np.ndarray:
     return (mag * sign).astype(np.int32).reshape(wl.batch, wl.K)
 
 
+def make_candidate_offsets(wl: Workload, n_candidates: int, p: float) -> np.ndarray:
+    """Signed bin offsets i32[batch, n_candidates, K] for Top-K retrieval stand-ins: candidate r of an
+    episode is the target's own continuation plus these offsets (magnitude Geometric(p) on
+    {0,1,2,...}, fair sign), one independent stream per candidate."""
+    out = np.zeros((wl.batch, n_candidates, wl.K), np.int32)
+    for r in range(n_candidates):
+        u = rng.uniform_f64(wl.seed, "cand.mag.%d" % r, wl.batch * wl.K)
+        s = rng.uniform_f64(wl.seed, "cand.sign.%d" % r, wl.batch * wl.K)
+        mag = np.floor(np.log(u) / np.log1p(-p)).astype(np.int64)
+        out[:, r] = (mag * np.where(s < 0.5, -1, 1)).astype(np.int32).reshape(wl.batch, wl.K)
+    return out
+
+
 def make_skip_mask(wl: Workload) -> np.ndarray:
     """u8[batch]: 1 = this episode's drafts bypass verification (Bernoulli(skip_p))."""
     u = rng.uniform_f64(wl.seed, "skip", wl.batch)
