@@ -69,6 +69,9 @@ def main():
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run three plain 1 GiB device copies (reference kernel for HBM traffic counters)")
     ap.add_argument("--path", type=int, default=0, help="0 auto, 1 generic, 2 fast (launch per phase), 3 persistent")
+    ap.add_argument("--tree", type=int, default=0, metavar="R",
+                    help="time the TREE verify step instead: R retrieved candidates per episode, built into a "
+                         "sequence-wise draft tree (paper Sec. 4.2); 0 = the linear step")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs the verify step on ONE GPU (episodes would shard by batch "
@@ -78,7 +81,7 @@ def main():
     import numpy as np
     import torch
     import synth
-    from paper_2603_17573_amd import (DeviceModel, Verifier, make_accept_desc, binding,
+    from paper_2603_17573_amd import (DeviceModel, Verifier, make_accept_desc, binding, build_sequence_tree,
                                       heisd_verify_profile_enable, heisd_verify_profile_read)
     if not os.path.exists(binding.LIB_PATH):
         from paper_2603_17573_amd import build
@@ -88,12 +91,19 @@ def main():
     wl = synth.WORKLOADS[args.workload]
     sh = wl.shape
     B, K, P = wl.batch, wl.K, wl.prefix_len
-    cap = P + K
+    R = args.tree
+    # tree tokens per episode when all R candidates differ in every sequence (one 7-token action slice)
+    T = 3 * R + 3 * R * R + R * R if R else 0
+    if R and (K != 7 or T > 256):
+        print("bench.py: --tree needs a K=7 workload and at most 7 candidates", file=sys.stderr)
+        sys.exit(2)
+    rows = T if R else K                    # new rows per episode in one step
+    cap = P + rows
     t0 = time.time()
     weights = synth.make_weights(sh, wl.seed)
     t_gen = time.time() - t0
     dm = DeviceModel(sh, weights, dev)
-    ver = Verifier(dm, B, K, cap)
+    ver = Verifier(dm, B, rows, cap)
     from paper_2603_17573_amd import heisd_verify_set_path
     assert heisd_verify_set_path(ver.ctx, args.path) == 0
     # prefix K/V drawn directly (the benchmark may not call the oracle's prefill); same shapes,
@@ -118,20 +128,50 @@ def main():
     acc = make_accept_desc(wl.tau_tok, wl.tau_seq)
     stream = torch.cuda.current_stream(dev)
     drafts_note = "uniform over the bins"
-    if wl.draft[0] == "geometric":
-        # drafts near the target's own choice: d_j = clip(v_j + offset_j), v_j = the target's greedy bin given
-        # d_0..d_{j-1}.  v_j is row j of target_bins, which depends on the earlier drafts only, so K
-        # untimed steps fix the drafts one position at a time (the benchmark may not call the oracle).
-        off = synth.make_offsets_geometric(wl, wl.draft[1])
+
+    def teacher_forced(off):
+        """Bins d_j = clip(v_j + off_j), v_j = the target's greedy bin given d_0..d_{j-1}: v_j is row j of
+        target_bins, which depends on the earlier drafts only, so K untimed linear steps fix the drafts one
+        position at a time (the benchmark may not call the oracle)."""
+        b_ = synth.make_drafts_uniform(wl)
+        t_d = torch.from_numpy((sh.bin_base + b_).astype(np.int32)).to(dev)
         out0 = None
         for j in range(K):
-            out0 = ver.step(kc, vc, t_plen, t_first, t_drafts, acc, t_skip, want_aux=True, out=out0, stream=stream)
+            out0 = ver.step(kc, vc, t_plen, t_first, t_d, acc, t_skip, want_aux=True, out=out0, stream=stream)
             vj = out0["target_bins"][:, j].cpu().numpy()
             live = vj >= 0
-            bins[live, j] = np.clip(vj[live] + off[live, j], 0, sh.n_bins - 1)
-            t_drafts[:, j] = torch.from_numpy((sh.bin_base + bins[:, j]).astype(np.int32)).to(dev)
+            b_[live, j] = np.clip(vj[live] + off[live, j], 0, sh.n_bins - 1)
+            t_d[:, j] = torch.from_numpy((sh.bin_base + b_[:, j]).astype(np.int32)).to(dev)
+        return b_
+
+    if wl.draft[0] == "geometric" and not R:
+        bins = teacher_forced(synth.make_offsets_geometric(wl, wl.draft[1]))
         drafts = (sh.bin_base + bins).astype(np.int32)
-        drafts_note = "target's own greedy bins (fixed position by position with K untimed device steps) + Geometric(%g) signed offsets" % wl.draft[1]
+        t_drafts = torch.from_numpy(drafts).to(dev)
+        drafts_note = "target's own greedy bins (fixed position by position with K untimed device steps) + " \
+                      "Geometric(%g) signed offsets" % wl.draft[1]
+    t_tokens = t_parent = None
+    if R:
+        # stand-ins for Top-K retrieval: candidate r = the target's own continuation + seeded geometric offsets
+        p_geo = wl.draft[1] if wl.draft[0] == "geometric" else 0.5
+        coff = synth.make_candidate_offsets(wl, R, p_geo)
+        cands = sh.bin_base + np.stack([teacher_forced(coff[:, r]) for r in range(R)], axis=1).astype(np.int32)
+        drafts = cands[:, 0]
+        tokens = np.zeros((B, T), np.int32)
+        parent = np.full((B, T), -2, np.int32)
+        for e in range(B):
+            tok, par = build_sequence_tree(cands[e], acc, T)
+            tokens[e, :len(tok)], parent[e, :len(par)] = tok, par
+        t_tokens, t_parent = torch.from_numpy(tokens).to(dev), torch.from_numpy(parent).to(dev)
+        drafts_note = "%d candidates per episode, each the target's own greedy continuation (fixed position by " \
+                      "position with untimed device steps) + Geometric(%g) signed offsets, built into a " \
+                      "sequence-wise tree of up to %d tokens (padded)" % (R, p_geo, T)
+
+    def step(accept, want_aux=False, out=None):
+        if R:
+            return ver.tree_step(kc, vc, t_plen, t_first, t_tokens, t_parent, accept, t_skip, want_aux=want_aux,
+                                 out=out, stream=stream)
+        return ver.step(kc, vc, t_plen, t_first, t_drafts, accept, t_skip, want_aux=want_aux, out=out, stream=stream)
 
     if args.calibrate_copy:
         src = torch.empty(1 << 28, dtype=torch.float32, device=dev).normal_()
@@ -142,19 +182,19 @@ def main():
         del src, dst
     out = None
     for _ in range(args.warmup):
-        out = ver.step(kc, vc, t_plen, t_first, t_drafts, acc, t_skip, want_aux=False, out=out, stream=stream)
+        out = step(acc, out=out)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(args.steps):
-        out = ver.step(kc, vc, t_plen, t_first, t_drafts, acc, t_skip, want_aux=False, out=out, stream=stream)
+        out = step(acc, out=out)
     torch.cuda.synchronize()
     ms = (time.perf_counter() - t0) * 1e3 / args.steps
     accepted = out["accepted_len"].cpu().tolist()
     # acceptance does not change the work of a step: one time, several thresholds (paper Sec. 4.2: 15/30)
     hist = {}
-    if wl.draft[0] == "geometric":
+    if wl.draft[0] == "geometric" or R:
         for tt, ts in ((0, 0), (1, 3), (2, 6), (4, 12), (2, 4), (15, 30)):
-            o2 = ver.step(kc, vc, t_plen, t_first, t_drafts, make_accept_desc(tt, ts), t_skip, want_aux=False, stream=stream)
+            o2 = step(make_accept_desc(tt, ts))
             al = o2["accepted_len"].cpu().numpy()
             if skip is not None:
                 al = al[skip == 0]
@@ -164,12 +204,12 @@ def main():
     n_prof = max(1, min(args.steps, 32))
     heisd_verify_profile_enable(ver.ctx, True)
     for _ in range(n_prof):
-        ver.step(kc, vc, t_plen, t_first, t_drafts, acc, t_skip, want_aux=False, out=out, stream=stream)
+        step(acc, out=out)
     rc, prof = heisd_verify_profile_read(ver.ctx)
     heisd_verify_profile_enable(ver.ctx, False)
     assert rc == 0
     active = B if skip is None else int(B - skip.sum())
-    total_bytes, per_class = algorithmic_bytes(sh, B, K, P, active)
+    total_bytes, per_class = algorithmic_bytes(sh, B, rows, P, active)
     kernels = {}
     for kcls, (tot_ms, n) in prof.items():
         if n:
@@ -203,7 +243,11 @@ def main():
                 k1, v1, f1 = synth.make_prefix_kv_direct(wl, e % max(B, 1) if B > 1 else e, cap)
             d1 = drafts[e % B][None, :]
             t0 = time.perf_counter()
-            ref = oracle.verify_step(om, k1[:, None], v1[:, None], [P], np.array([f1], np.int32), d1, rule)
+            if R:
+                ref = oracle.verify_tree_step(om, k1[:, None], v1[:, None], [P], np.array([f1], np.int32),
+                                              tokens[e % B][None, :], parent[e % B][None, :], rule)
+            else:
+                ref = oracle.verify_step(om, k1[:, None], v1[:, None], [P], np.array([f1], np.int32), d1, rule)
             spent += time.perf_counter() - t0
             n_done += 1
             ref_acc.append(int(ref["accepted_len"][0]))
@@ -211,20 +255,23 @@ def main():
         cores = min(cores, os.cpu_count() or cores)
         # one verify step of the workload covers B episodes
         cpu = {"value": round(n_done / B / spent, 5), "unit": "verify steps/s", "cores": cores, "kind": "oracle",
-               "sample": "%d oracle verify steps over single episodes of %s (K=%d rows through all %d layers each), "
-                         "%.1f s of oracle time" % (n_done, wl.name, K, sh.n_layers, spent),
+               "sample": "%d oracle %sverify steps over single episodes of %s (%s through all %d layers), "
+                         "%.1f s of oracle time" % (n_done, "tree " if R else "", wl.name,
+                                                    "every chain of the tree on its own" if R else "K=%d rows" % K,
+                                                    sh.n_layers, spent),
                "oracle_accepted_len": ref_acc[:8]}
 
     line = {
-        "metric": "verify steps/s (7B-shaped decoder, K=7, bs=1)" if wl.name == "C1" else
-                  "verify steps/s (%s)" % wl.name,
+        "metric": ("tree verify steps/s (%s, %d candidates, %d tree tokens)" % (wl.name, R, T)) if R else
+                  ("verify steps/s (7B-shaped decoder, K=7, bs=1)" if wl.name == "C1" else
+                   "verify steps/s (%s)" % wl.name),
         "value": round(1000.0 / ms, 2), "unit": "verify steps/s", "n_gpus": 1, "steps": args.steps,
-        "episode_steps_per_s": round(B * 1000.0 / ms, 1), "draft_tokens_verified_per_s": round(active * K * 1000.0 / ms, 1),
+        "episode_steps_per_s": round(B * 1000.0 / ms, 1), "draft_tokens_verified_per_s": round(active * rows * 1000.0 / ms, 1),
         "warmup": args.warmup, "ms_per_step": round(ms, 4), "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": "%s: %d-layer d=%d decoder, prefix %d, batch %d, K=%d, thresholds %d/%d" %
                                (wl.name, sh.n_layers, sh.d_model, P, B, K, wl.tau_tok, wl.tau_seq),
-                   "prefix_kv": "drawn directly (no prefill)", "drafts": drafts_note, "global_batch": B, "K": K},
+                   "prefix_kv": "drawn directly (no prefill)", "drafts": drafts_note, "global_batch": B, "K": K, "tree_tokens": T or None},
         "kernel_path": args.path,
         "hbm_frac_whole_step": round(total_bytes / (ms * 1e-3) / HBM_PEAK, 4),
         "algorithmic_bytes_per_step": total_bytes,

@@ -211,6 +211,31 @@ int heisd_build_sequence_tree(const int32_t *candidates, int32_t R, int32_t K, c
                               int32_t max_tokens, int32_t *tokens, int32_t *parent, int32_t *n_tokens);
 
 /*
+ * Extend every episode's cached prefix by n_rows rows: the decoder forward over the new rows against
+ * the rows already cached, appending their keys and values, and the target's greedy action bin after
+ * the LAST new row (Eq. 2-1).  Two uses, both on the same kernels as the verify step:
+ *   - chunked prefill of the vision+text prefix (App. A.1: 256 visual tokens arrive as embeddings, the
+ *     prompt as token ids): one call per chunk of at most max_k rows; after the last chunk `next_bin`
+ *     is the `first_pred` the verify step expects;
+ *   - the autoregressive decode step the method falls back to when every candidate is rejected
+ *     (Sec. 4.2) and that speculative decoding replaces (Sec. 2.2, App. A.2): n_rows = 1, token_ids =
+ *     the token just produced; `next_bin` is the next action token's bin.
+ *
+ *   token_ids    DEVICE i32 [batch][n_rows]            vocabulary ids, or NULL
+ *   x_rows       DEVICE f32 [batch][n_rows][d_model]   input embeddings, or NULL; exactly one is given
+ *   next_bin     DEVICE i32 [batch] out                greedy bin after the last new row
+ *   last_logits  DEVICE f32 [batch][n_bins] out, optional (NULL ok)
+ * Cache rows prefix_len[b] .. prefix_len[b]+n_rows-1 are written; the library does not advance
+ * prefix_len (the caller adds n_rows).  kv->first_pred is not read.  Asynchronous, allocates nothing.
+ * Errors (nothing enqueued): EINVAL for NULL required pointers, both or neither input given, n_rows or
+ * batch outside [1, max_k] x [1, max_batch]; EUNSUPPORTED when the context is pinned to the <= 8-row
+ * kernels and the call has more rows or embeddings as input; EHIP.
+ */
+int heisd_prefill_chunk(heisd_verify_ctx *ctx, const heisd_kv_desc *kv, const int32_t *token_ids,
+                        const float *x_rows, int32_t n_rows, int32_t batch, int32_t *next_bin,
+                        float *last_logits, void *stream);
+
+/*
  * Per-kernel timing for measurement runs (not part of the method).  With profiling enabled,
  * heisd_verify_step brackets every kernel launch with HIP events on the caller's stream;
  * heisd_verify_profile_read waits for the recorded events, adds the elapsed milliseconds

@@ -65,6 +65,9 @@ def load():
         lib.heisd_build_sequence_tree.argtypes = [c_void_p, c_int32, c_int32, POINTER(heisd_accept_desc), c_int32,
                                                   c_void_p, c_void_p, POINTER(c_int32)]
         lib.heisd_build_sequence_tree.restype = ctypes.c_int
+        lib.heisd_prefill_chunk.argtypes = [c_void_p, POINTER(heisd_kv_desc), c_void_p, c_void_p, c_int32, c_int32,
+                                            c_void_p, c_void_p, c_void_p]
+        lib.heisd_prefill_chunk.restype = ctypes.c_int
         lib.heisd_free.argtypes = [c_void_p]
         lib.heisd_free.restype = None
         lib.heisd_verify_profile_enable.argtypes = [c_void_p, ctypes.c_int]
@@ -116,6 +119,13 @@ def heisd_build_sequence_tree(candidates, R, K, accept: heisd_accept_desc, max_t
     rc = load().heisd_build_sequence_tree(candidates, R, K, ctypes.byref(accept) if accept is not None else None,
                                           max_tokens, tokens, parent, ctypes.byref(n))
     return rc, int(n.value)
+
+
+def heisd_prefill_chunk(ctx, kv: heisd_kv_desc, token_ids, x_rows, n_rows, batch, next_bin, last_logits,
+                        stream) -> int:
+    """All array arguments are integer device addresses (0/None = NULL)."""
+    return load().heisd_prefill_chunk(ctx, ctypes.byref(kv) if kv is not None else None, token_ids, x_rows, n_rows,
+                                      batch, next_bin, last_logits, stream)
 
 
 def heisd_free(ctx) -> None:

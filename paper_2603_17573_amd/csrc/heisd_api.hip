@@ -227,36 +227,50 @@ static void gemm_launch(GemmArgs a, int M, int epi, hipStream_t st) {
 
 // ---- any-M attention: workgroup size by the number of (episode, head) pairs ----------------
 
-template <int HD, int THREADS, bool TREE>
+template <int HD, int THREADS, bool TREE, bool SPLIT>
 static hipError_t attn_prepare_one(int cap) {
-  return hipFuncSetAttribute(reinterpret_cast<const void *>(&attn_verify<HD, THREADS, TREE>),
+  return hipFuncSetAttribute(reinterpret_cast<const void *>(&attn_verify<HD, THREADS, TREE, SPLIT>),
                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)attn_lds_bytes(HD, cap, THREADS / 64));
 }
-template <int HD>
-static hipError_t attn_prepare_hd(int cap) {
-  hipError_t e;
-  if ((e = attn_prepare_one<HD, 256, false>(cap)) != hipSuccess) return e;
-  if ((e = attn_prepare_one<HD, 512, false>(cap)) != hipSuccess) return e;
-  if ((e = attn_prepare_one<HD, 256, true>(cap)) != hipSuccess) return e;
-  return attn_prepare_one<HD, 512, true>(cap);
-}
-static hipError_t attn_prepare(int hd, int cap) { return hd == 128 ? attn_prepare_hd<128>(cap) : attn_prepare_hd<64>(cap); }
-
 template <int HD, bool TREE>
-static void attn_launch_hd(const AttnArgs &a, int H, int batch, int cap, int n_cu, hipStream_t st) {
-  const bool big = H * batch < 2 * n_cu;       // few workgroups: 512 threads each hide more latency
-  const dim3 grid(H, batch);
-  if (big) attn_verify<HD, 512, TREE><<<grid, dim3(512), attn_lds_bytes(HD, cap, 8), st>>>(a);
-  else attn_verify<HD, 256, TREE><<<grid, dim3(256), attn_lds_bytes(HD, cap, 4), st>>>(a);
+static hipError_t attn_prepare_mode(int cap) {
+  hipError_t e;
+  if ((e = attn_prepare_one<HD, 256, TREE, false>(cap)) != hipSuccess) return e;
+  if ((e = attn_prepare_one<HD, 512, TREE, false>(cap)) != hipSuccess) return e;
+  if ((e = attn_prepare_one<HD, 256, TREE, true>(cap)) != hipSuccess) return e;
+  return attn_prepare_one<HD, 512, TREE, true>(cap);
+}
+static hipError_t attn_prepare(int hd, int cap) {
+  hipError_t e = hd == 128 ? attn_prepare_mode<128, false>(cap) : attn_prepare_mode<64, false>(cap);
+  if (e != hipSuccess) return e;
+  return hd == 128 ? attn_prepare_mode<128, true>(cap) : attn_prepare_mode<64, true>(cap);
+}
+
+// One workgroup per (head, episode) while an episode has at most 8 new rows (one block of queries);
+// otherwise the append runs as a launch of its own and every block of 8 queries gets a workgroup.
+template <int HD, bool TREE>
+static void attn_launch_mode(const AttnArgs &a, int H, int batch, int cap, int n_cu, hipStream_t st) {
+  const int nqb = (a.K + kAttnQB - 1) / kAttnQB;
+  const bool big = H * batch * nqb <= n_cu;          // at most one workgroup per compute unit: 512 threads each hide more latency
+  if (nqb == 1) {
+    const dim3 grid(H, batch);
+    if (big) attn_verify<HD, 512, TREE, false><<<grid, dim3(512), attn_lds_bytes(HD, cap, 8), st>>>(a);
+    else attn_verify<HD, 256, TREE, false><<<grid, dim3(256), attn_lds_bytes(HD, cap, 4), st>>>(a);
+    return;
+  }
+  attn_append<HD, TREE><<<dim3(H, batch, nqb), dim3(256), 0, st>>>(a);
+  const dim3 grid(H, batch, nqb);
+  if (big) attn_verify<HD, 512, TREE, true><<<grid, dim3(512), attn_lds_bytes(HD, cap, 8), st>>>(a);
+  else attn_verify<HD, 256, TREE, true><<<grid, dim3(256), attn_lds_bytes(HD, cap, 4), st>>>(a);
 }
 static void attn_launch(const AttnArgs &a, int hd, int H, int batch, int cap, int n_cu, hipStream_t st) {
   const bool tree = a.depth != nullptr && a.anc != nullptr;
   if (hd == 128) {
-    if (tree) attn_launch_hd<128, true>(a, H, batch, cap, n_cu, st);
-    else attn_launch_hd<128, false>(a, H, batch, cap, n_cu, st);
+    if (tree) attn_launch_mode<128, true>(a, H, batch, cap, n_cu, st);
+    else attn_launch_mode<128, false>(a, H, batch, cap, n_cu, st);
   } else {
-    if (tree) attn_launch_hd<64, true>(a, H, batch, cap, n_cu, st);
-    else attn_launch_hd<64, false>(a, H, batch, cap, n_cu, st);
+    if (tree) attn_launch_mode<64, true>(a, H, batch, cap, n_cu, st);
+    else attn_launch_mode<64, false>(a, H, batch, cap, n_cu, st);
   }
 }
 
@@ -794,7 +808,8 @@ static void bat_launch(BatGemm g, int n_cu, hipStream_t st) {
 
 static void batch_forward(heisd_verify_ctx *ctx, const heisd_kv_desc *kv, const int32_t *draft_tokens, int K,
                           int batch, const uint8_t *skip_mask, float *logits, hipStream_t st, bool prof,
-                          const int32_t *depth = nullptr, const unsigned long long *anc = nullptr) {
+                          const int32_t *depth = nullptr, const unsigned long long *anc = nullptr,
+                          const float *x_rows = nullptr) {
   const heisd_model_desc &d = ctx->d;
   const int M = batch * K, dm = d.d_model, F = d.d_ffn, H = d.n_heads, HD = d.head_dim, cap = d.kv_capacity;
   const BatScratch bs(&d);
@@ -810,7 +825,7 @@ static void batch_forward(heisd_verify_ctx *ctx, const heisd_kv_desc *kv, const 
   };
   {
     ProfScope ps(ctx, HEISD_KC_EMBED, st, prof);
-    bat_embed<<<dim3(dm / 16), dim3(64), 0, st>>>(draft_tokens, static_cast<const uint16_t *>(d.tok_emb), d.vocab, dm, M,
+    bat_embed<<<dim3(dm / 16), dim3(64), 0, st>>>(draft_tokens, x_rows, static_cast<const uint16_t *>(d.tok_emb), d.vocab, dm, M,
                                                   CT, CTS, ctx->attn_norm[0], ctx->x, rec_x, ssq);
     row_scales();
   }
@@ -886,13 +901,17 @@ static void batch_forward(heisd_verify_ctx *ctx, const heisd_kv_desc *kv, const 
 
 static void generic_forward(heisd_verify_ctx *ctx, const heisd_kv_desc *kv, const int32_t *draft_tokens, int K,
                             int batch, const uint8_t *skip_mask, float *logits, hipStream_t st, bool prof,
-                            const int32_t *depth = nullptr, const unsigned long long *anc = nullptr) {
+                            const int32_t *depth = nullptr, const unsigned long long *anc = nullptr,
+                            const float *x_rows = nullptr) {
   const heisd_model_desc &d = ctx->d;
   const int M = batch * K, dm = d.d_model, F = d.d_ffn, H = d.n_heads, HD = d.head_dim, cap = d.kv_capacity;
   {
     ProfScope ps(ctx, HEISD_KC_EMBED, st, prof);
-  embed_rows<<<dim3(M), dim3(256), 0, st>>>(draft_tokens, static_cast<const uint16_t *>(d.tok_emb), d.vocab, dm,
-                                            ctx->x);
+    if (x_rows)
+      (void)hipMemcpyAsync(ctx->x, x_rows, (size_t)M * dm * sizeof(float), hipMemcpyDeviceToDevice, st);
+    else
+      embed_rows<<<dim3(M), dim3(256), 0, st>>>(draft_tokens, static_cast<const uint16_t *>(d.tok_emb), d.vocab, dm,
+                                                ctx->x);
   }
   const size_t layer_stride = (size_t)batch * H * cap * HD;
   for (int l = 0; l < d.n_layers; ++l) {
@@ -1146,5 +1165,43 @@ extern "C" int heisd_build_sequence_tree(const int32_t *candidates, int32_t R, i
   tb.grow(0, -1, R == 64 ? ~0ull : ((1ull << R) - 1));
   *n_tokens = tb.n;
   g_init_err[0] = 0;
+  return HEISD_OK;
+}
+
+// ---- prefix extension: chunked prefill and the autoregressive decode step -----------------------
+
+extern "C" int heisd_prefill_chunk(heisd_verify_ctx *ctx, const heisd_kv_desc *kv, const int32_t *token_ids,
+                                   const float *x_rows, int32_t n_rows, int32_t batch, int32_t *next_bin,
+                                   float *last_logits, void *stream) {
+  if (!ctx) return HEISD_EINVAL;
+  if (!kv || !kv->k_cache || !kv->v_cache || !kv->prefix_len || !next_bin)
+    return fail(ctx, HEISD_EINVAL, "prefill_chunk: NULL required pointer");
+  if ((token_ids == nullptr) == (x_rows == nullptr))
+    return fail(ctx, HEISD_EINVAL, "prefill_chunk: exactly one of token_ids and x_rows must be given");
+  const heisd_model_desc &d = ctx->d;
+  if (n_rows < 1 || batch < 1 || n_rows > d.max_k || batch > d.max_batch || n_rows > d.kv_capacity)
+    return fail(ctx, HEISD_EINVAL, "prefill_chunk: n_rows=%d batch=%d outside [1,%d] x [1,%d] (kv_capacity %d)", n_rows,
+                batch, d.max_k, d.max_batch, d.kv_capacity);
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  const int M = batch * n_rows;
+  (void)hipGetLastError();
+  const bool prof = ctx->prof_on && ctx->prof_steps < HEISD_PROFILE_MAX_STEPS;
+  if (prof) ctx->prof_steps++;
+  const bool use_fast = ctx->fast_ok && M <= 8 && token_ids && ctx->path != HEISD_PATH_GENERIC && ctx->path != HEISD_PATH_BATCH;
+  if ((ctx->path == HEISD_PATH_FAST || ctx->path == HEISD_PATH_PERSIST) && !use_fast)
+    return fail(ctx, HEISD_EUNSUPPORTED, "prefill_chunk: the selected path serves token rows with batch*n_rows <= 8 only");
+  if (use_fast)
+    fast_forward(ctx, kv, token_ids, n_rows, batch, nullptr, ctx->logits, st, prof);
+  else if (ctx->path == HEISD_PATH_GENERIC)
+    generic_forward(ctx, kv, token_ids, n_rows, batch, nullptr, ctx->logits, st, prof, nullptr, nullptr, x_rows);
+  else
+    batch_forward(ctx, kv, token_ids, n_rows, batch, nullptr, ctx->logits, st, prof, nullptr, nullptr, x_rows);
+  {
+    ProfScope ps(ctx, HEISD_KC_ACCEPT, st, prof);
+    last_row_argmax<<<dim3(batch), dim3(64), 0, st>>>(ctx->logits, n_rows, d.n_bins, next_bin, last_logits);
+  }
+  const hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return fail(ctx, HEISD_EHIP, "prefill_chunk: %s", hipGetErrorString(e));
+  ctx->err[0] = 0;
   return HEISD_OK;
 }

@@ -51,7 +51,8 @@ struct AttnArgs {
 
 // waves: 4 or 8 (workgroups of 256 or 512 threads)
 inline size_t attn_lds_bytes(int hd, int cap, int waves) {
-  return sizeof(float) * ((size_t)kAttnQB * hd + (size_t)kAttnQB * cap + kAttnQB + (size_t)waves * kAttnQB * hd);
+  return sizeof(float) * ((size_t)kAttnQB * hd + (size_t)kAttnQB * cap + kAttnQB + (size_t)waves * kAttnQB * hd) +
+         kAttnQB * 4 * sizeof(unsigned long long);   // tree mode: visibility bits of the block's queries
 }
 
 // Attention output element (row m, column col).
@@ -66,37 +67,16 @@ __device__ __forceinline__ void attn_store(const AttnArgs &a, int m, int col, fl
   }
 }
 
-// THREADS: 256 or 512.  With few (episode, head) pairs - fewer workgroups than would fill the
-// compute units twice - the larger workgroup hides more latency (M = 56: 31 -> 26 us per layer);
-// with many pairs the smaller one is faster (M = 448: 131 against 167 us).
-// TREE: tree mode compiled in (the linear kernel carries none of its registers).
-template <int HD, int THREADS, bool TREE>
-__global__ __launch_bounds__(THREADS) void attn_verify(AttnArgs a) {
-  constexpr int kAttnThreads = THREADS, kAttnWaves = THREADS / 64;
+// RoPE on the new keys of (episode b, head h), in place in fp32, and the append of keys and values
+// (bf16) to the episode's cache rows P .. P+K-1.
+template <int HD, bool TREE>
+__device__ __forceinline__ void attn_append_rows(const AttnArgs &a, int b, int h, int P, int tid, int nthreads,
+                                                 int jb, int je) {
   constexpr int HALF = HD / 2;
-  constexpr int LPK = HD / 8;              // lanes that share one key row (16 bytes each)
-  constexpr int G = kAttnThreads / LPK;    // key rows in flight per pass
-  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-  float *qs = reinterpret_cast<float *>(smem);        // [QB][HD]
-  float *sc = qs + kAttnQB * HD;                       // [QB][cap]
-  float *inv_l = sc + (size_t)kAttnQB * a.cap;         // [QB]
-  float *ored = inv_l + kAttnQB;                       // [waves][QB][HD]
-
-  const int h = blockIdx.x, b = blockIdx.y;
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int K = a.K, d = a.d, cap = a.cap;
-  const int row0 = b * K;
-  if (a.skip && a.skip[b]) {
-    for (int idx = tid; idx < K * HD; idx += kAttnThreads) attn_store(a, row0 + idx / HD, h * HD + (idx % HD), 0.f);
-    return;
-  }
-  int P = a.prefix_len[b];
-  P = max(0, min(P, cap - K));  // never index past the cache, whatever the caller passed
-  uint16_t *kc = a.k_cache + ((size_t)(b * a.H + h) * cap) * HD;
-  uint16_t *vc = a.v_cache + ((size_t)(b * a.H + h) * cap) * HD;
-
-  // ---- RoPE on the new keys, append keys and values (bf16) ----
-  for (int idx = tid; idx < K * HALF; idx += kAttnThreads) {
+  const int K = a.K, d = a.d, row0 = b * K;
+  uint16_t *kc = a.k_cache + ((size_t)(b * a.H + h) * a.cap) * HD;
+  uint16_t *vc = a.v_cache + ((size_t)(b * a.H + h) * a.cap) * HD;
+  for (int idx = tid + jb * HALF; idx < je * HALF; idx += nthreads) {
     const int j = idx / HALF, i = idx - j * HALF;
     float *src = a.qkv + (size_t)(row0 + j) * 3 * d + h * HD;
     const float2 cs = a.rope[(size_t)(P + (TREE ? a.depth[row0 + j] : j)) * HALF + i];
@@ -111,11 +91,66 @@ __global__ __launch_bounds__(THREADS) void attn_verify(AttnArgs a) {
     vr[i] = (uint16_t)f32_to_bf16_bits(src[2 * d + i]);
     vr[i + HALF] = (uint16_t)f32_to_bf16_bits(src[2 * d + i + HALF]);
   }
-  __syncthreads();  // the rotated fp32 keys are read back below by other waves of this workgroup
+}
+
+// The append alone, one workgroup per (head, episode, 8 new rows): first half of a step whose attention
+// runs with one workgroup per block of 8 queries (attn_verify with SPLIT).
+template <int HD, bool TREE>
+__global__ __launch_bounds__(256) void attn_append(AttnArgs a) {
+  const int h = blockIdx.x, b = blockIdx.y;
+  if (a.skip && a.skip[b]) return;
+  int P = a.prefix_len[b];
+  P = max(0, min(P, a.cap - a.K));
+  const int jb = (int)blockIdx.z * kAttnQB;
+  attn_append_rows<HD, TREE>(a, b, h, P, threadIdx.x, 256, jb, min(a.K, jb + kAttnQB));
+}
+
+// THREADS: 256 or 512.  With few (episode, head) pairs - fewer workgroups than would fill the
+// compute units twice - the larger workgroup hides more latency (M = 56: 31 -> 26 us per layer);
+// with many pairs the smaller one is faster (M = 448: 131 against 167 us).
+// TREE: tree mode compiled in (the linear kernel carries none of its registers).
+// A workgroup serves one block of at most 8 queries of one (head, episode): blockIdx.z names the block.
+// SPLIT = false: the episode has a single block and the workgroup also rotates and appends the new keys
+// and values; SPLIT = true: several blocks per episode, the append ran as attn_append before.  With many
+// queries per episode and few episodes the blocks are what fills the chip (76 tree tokens, one episode:
+// 225 us per layer with one workgroup per head, 64 us with one per block).
+template <int HD, int THREADS, bool TREE, bool SPLIT>
+__global__ __launch_bounds__(THREADS) void attn_verify(AttnArgs a) {
+  constexpr int kAttnThreads = THREADS, kAttnWaves = THREADS / 64;
+  constexpr int HALF = HD / 2;
+  constexpr int LPK = HD / 8;              // lanes that share one key row (16 bytes each)
+  constexpr int G = kAttnThreads / LPK;    // key rows in flight per pass
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  float *qs = reinterpret_cast<float *>(smem);        // [QB][HD]
+  float *sc = qs + kAttnQB * HD;                       // [QB][cap]
+  float *inv_l = sc + (size_t)kAttnQB * a.cap;         // [QB]
+  float *ored = inv_l + kAttnQB;                       // [waves][QB][HD]
+  unsigned long long *amask = reinterpret_cast<unsigned long long *>(ored + (size_t)kAttnWaves * kAttnQB * HD);   // [QB][4]
+
+  const int h = blockIdx.x, b = blockIdx.y;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int K = a.K, d = a.d, cap = a.cap;
+  const int row0 = b * K;
+  const int jb = SPLIT ? (int)blockIdx.z * kAttnQB : 0, je = SPLIT ? min(K, jb + kAttnQB) : K;   // this workgroup's queries
+  if (a.skip && a.skip[b]) {
+    for (int idx = tid; idx < (je - jb) * HD; idx += kAttnThreads)
+      attn_store(a, row0 + jb + idx / HD, h * HD + (idx % HD), 0.f);
+    return;
+  }
+  int P = a.prefix_len[b];
+  P = max(0, min(P, cap - K));  // never index past the cache, whatever the caller passed
+  uint16_t *kc = a.k_cache + ((size_t)(b * a.H + h) * cap) * HD;
+  uint16_t *vc = a.v_cache + ((size_t)(b * a.H + h) * cap) * HD;
+
+  if (!SPLIT) {
+    attn_append_rows<HD, TREE>(a, b, h, P, tid, kAttnThreads, 0, K);
+    __syncthreads();  // the rotated fp32 keys are read back below by other waves of this workgroup
+  }
 
   const int li = tid % LPK;   // which 8 channels of a row this lane covers
   const int g = tid / LPK;    // which key stream this lane belongs to
-  for (int j0 = 0; j0 < K; j0 += kAttnQB) {
+  {                       // one block of at most 8 queries per workgroup
+    const int j0 = jb;
     const int nq = min(kAttnQB, K - j0);
     const int nkeys = P + j0 + nq;  // keys visible to the last query of the block
     for (int idx = tid; idx < kAttnQB * HALF; idx += kAttnThreads) {
@@ -131,6 +166,8 @@ __global__ __launch_bounds__(THREADS) void attn_verify(AttnArgs a) {
       qs[j * HD + i] = r1;
       qs[j * HD + i + HALF] = r2;
     }
+    if (TREE && tid < kAttnQB * 4)
+      amask[tid] = (tid >> 2) < nq ? a.anc[(size_t)(row0 + j0 + (tid >> 2)) * 4 + (tid & 3)] : 0ull;
     __syncthreads();
     float qf[kAttnQB][8];
 #pragma unroll
@@ -138,18 +175,11 @@ __global__ __launch_bounds__(THREADS) void attn_verify(AttnArgs a) {
 #pragma unroll
       for (int i = 0; i < 8; ++i) qf[j][i] = qs[j * HD + li * 8 + i];
 
-    // tree mode: the visibility bits of the query this lane writes scores for
-    unsigned long long aw0 = 0, aw1 = 0, aw2 = 0, aw3 = 0;
-    if (TREE && li < nq) {
-      const unsigned long long *w = a.anc + (size_t)(row0 + j0 + li) * 4;
-      aw0 = w[0]; aw1 = w[1]; aw2 = w[2]; aw3 = w[3];
-    }
-    // is new row r - P visible to query j0 + li?
+    // is new row r - P visible to query j0 + li?  (tree mode: the bits were put in LDS with the queries)
     auto sees_new = [&](int r) __attribute__((always_inline)) {
       if (!TREE) return r <= P + j0 + li;
-      const int t = r - P, w = t >> 6;
-      const unsigned long long word = w == 0 ? aw0 : (w == 1 ? aw1 : (w == 2 ? aw2 : aw3));
-      return ((word >> (t & 63)) & 1ull) != 0;
+      const int t = r - P;
+      return li < kAttnQB && ((amask[li * 4 + (t >> 6)] >> (t & 63)) & 1ull) != 0;
     };
 
     // ---- pass 1: scores ----

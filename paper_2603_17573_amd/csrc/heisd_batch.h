@@ -413,9 +413,12 @@ __global__ __launch_bounds__(kBatThreads) __attribute__((amdgpu_waves_per_eu(2, 
 }
 
 // ---- embedding: x rows (fp32), records of x*gain, partial sums of squares --------------------------
-// One 16-column tile per workgroup (64 threads); thread (c2, jm) walks the column tiles.
-__global__ __launch_bounds__(64) void bat_embed(const int32_t *ids, const uint16_t *emb, int vocab, int d, int M, int CT, int CTS,
-                                                const float *gain, float *x, uint16_t *planes, float *ssq_out) {
+// One 16-column tile per workgroup (64 threads); thread (c2, jm) walks the column tiles.  With `rows`
+// given the input rows are taken from there (fp32 [M][d]: visual tokens arrive as embeddings, App. A.1)
+// instead of being looked up.
+__global__ __launch_bounds__(64) void bat_embed(const int32_t *ids, const float *rows, const uint16_t *emb, int vocab, int d,
+                                                int M, int CT, int CTS, const float *gain, float *x, uint16_t *planes,
+                                                float *ssq_out) {
   const int tile = blockIdx.x, tid = threadIdx.x;
   const int c2 = tid & 7, jm = tid >> 3;
   const int col = tile * 16 + 2 * c2;
@@ -424,11 +427,17 @@ __global__ __launch_bounds__(64) void bat_embed(const int32_t *ids, const uint16
     const int m = ct * 8 + jm;
     float v0 = 0.f, v1 = 0.f;
     if (m < M) {
-      int id = ids[m];
-      id = max(0, min(id, vocab - 1));
-      const uint32_t pr = *reinterpret_cast<const uint32_t *>(emb + (size_t)id * d + col);
-      v0 = __uint_as_float(pr << 16);
-      v1 = __uint_as_float(pr & 0xFFFF0000u);
+      if (rows) {
+        const float2 r = *reinterpret_cast<const float2 *>(rows + (size_t)m * d + col);
+        v0 = r.x;
+        v1 = r.y;
+      } else {
+        int id = ids[m];
+        id = max(0, min(id, vocab - 1));
+        const uint32_t pr = *reinterpret_cast<const uint32_t *>(emb + (size_t)id * d + col);
+        v0 = __uint_as_float(pr << 16);
+        v1 = __uint_as_float(pr & 0xFFFF0000u);
+      }
       *reinterpret_cast<float2 *>(x + (size_t)m * d + col) = make_float2(v0, v1);
     }
     float q = v0 * v0 + v1 * v1;

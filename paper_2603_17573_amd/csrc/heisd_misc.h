@@ -125,6 +125,29 @@ __global__ __launch_bounds__(256) void argmax_accept(AcceptArgs a) {
   a.next_token[b] = a.bin_base + tb[n];
 }
 
+// Greedy bin after the LAST of the n new rows of every episode (Eq. 2-1: the target's own next token),
+// and optionally that row's logits.  One wave per episode.
+__global__ __launch_bounds__(64) void last_row_argmax(const float *logits, int n, int n_bins, int32_t *pred,
+                                                      float *last_logits) {
+  const int b = blockIdx.x, lane = threadIdx.x;
+  const float *row = logits + ((size_t)b * n + (n - 1)) * n_bins;
+  float best = -INFINITY;
+  int bi = 0x7FFFFFFF;
+  for (int t = lane; t < n_bins; t += kWave) {
+    float v = row[t];
+    if (last_logits) last_logits[(size_t)b * n_bins + t] = v;
+    if (v != v) v = -INFINITY;
+    if (v > best || (v == best && t < bi)) { best = v; bi = t; }
+  }
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) {
+    const float ov = __shfl_xor(best, o, kWave);
+    const int oi = __shfl_xor(bi, o, kWave);
+    if (ov > best || (ov == best && oi < bi)) { best = ov; bi = oi; }
+  }
+  if (lane == 0) pred[b] = (bi == 0x7FFFFFFF) ? 0 : bi;
+}
+
 // ---- tree verification (Sec. 4.2: a sequence-wise draft tree, every chain checked from the root) ----
 
 constexpr int kTreeMax = 256;    // tree tokens per episode (four 64-bit words of visibility bits)
@@ -181,36 +204,34 @@ struct TreeAcceptArgs {
   unsigned exact_mask;
 };
 
-// One workgroup per episode.  Greedy bin after every tree token, then the chain selection: walking
-// the tokens in index order (a parent always precedes its children), each token extends the state of
-// its parent - the running sums of the sequence it is in, and whether everything before that
-// sequence was accepted - so that one pass finds, for every point where a chain may stop (the end of
-// a sequence, or a leaf), whether the chain is accepted up to there.  The deepest such point wins,
-// among equals the lowest token index.  Integer work: bit-exact by construction.
+// One workgroup per episode, thread t for tree token t.  Greedy bin after every tree token, then the
+// chain selection level by level (all tokens of one depth at once; a parent is one level up): each
+// token extends the state of its parent - the running max and sum of the sequence it is in, and
+// whether everything before that sequence was accepted - so that for every point where a chain may
+// stop (the end of a sequence, or a leaf) it is known whether the chain is accepted up to there.  The
+// deepest such point wins, among equals the lowest token index.  Integer work: bit-exact by
+// construction.
 __global__ __launch_bounds__(256) void tree_accept(TreeAcceptArgs a) {
   __shared__ int32_t s_par[kTreeMax], s_pred[kTreeMax], s_depth[kTreeMax], s_gmax[kTreeMax], s_child[kTreeMax];
   __shared__ long long s_gsum[kTreeMax];
   __shared__ unsigned char s_valid[kTreeMax], s_alive[kTreeMax], s_end[kTreeMax];
   __shared__ unsigned char s_gi[kTreeMax], s_first[kTreeMax], s_last[kTreeMax];    // by depth
+  __shared__ int s_maxd;
+  __shared__ unsigned s_best;                                                      // (n << 16) | (0xFFFF - t)
   const int b = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int T = a.T;
   int32_t *tb = a.target_bins + (size_t)b * (T + 1);
   int32_t *path = a.path + (size_t)b * T;
   const int32_t *par = a.parent + (size_t)b * T;
   const bool skipped = a.skip && a.skip[b];
-  for (int t = tid; t < T; t += 256) {
-    s_par[t] = par[t];
-    s_child[t] = 0x7FFFFFFF;       // lowest-index child
+  if (tid < T) {
+    s_par[tid] = par[tid];
+    s_child[tid] = 0x7FFFFFFF;       // lowest-index child
   }
-  __syncthreads();
   if (tid == 0) {
-    // which tokens are in the tree; the sequence pattern by depth
-    for (int t = 0; t < T; ++t) {
-      const int p = s_par[t];
-      const bool ok = p == -1 || (p >= 0 && p < t && s_valid[p]);
-      s_valid[t] = ok;
-      s_depth[t] = (ok && p >= 0) ? s_depth[p] + 1 : 0;
-    }
+    s_maxd = 0;
+    s_best = 0;
+    // the sequence pattern by depth
     int dpt = 0, g = 0;
     while (dpt < T) {
       const int gi = g % a.n_groups, size = a.group_sizes[gi];
@@ -223,8 +244,28 @@ __global__ __launch_bounds__(256) void tree_accept(TreeAcceptArgs a) {
     }
   }
   __syncthreads();
-  for (int t = tid; t < T; t += 256)
-    if (s_valid[t] && s_par[t] >= 0) atomicMin(&s_child[s_par[t]], t);
+  // which tokens are in the tree, and how deep: walk up (the index strictly decreases)
+  int my_depth = 0;
+  bool my_valid = false;
+  if (tid < T) {
+    int cur = tid, dep = 0;
+    bool ok = true;
+    for (;;) {
+      const int p = s_par[cur];
+      if (p == -1) break;
+      if (p < 0 || p >= cur) { ok = false; break; }
+      ++dep;
+      cur = p;
+    }
+    my_valid = ok;
+    my_depth = ok ? dep : 0;
+    s_valid[tid] = ok;
+    s_depth[tid] = my_depth;
+    if (ok) {
+      atomicMax(&s_maxd, dep);
+      if (s_par[tid] >= 0) atomicMin(&s_child[s_par[tid]], tid);
+    }
+  }
   if (skipped) {
     for (int i = tid; i < T * a.n_bins; i += 256) a.logits_rw[(size_t)b * T * a.n_bins + i] = __uint_as_float(0x7FC00000u);
     for (int j = tid; j <= T; j += 256) tb[j] = -1;
@@ -267,45 +308,55 @@ __global__ __launch_bounds__(256) void tree_accept(TreeAcceptArgs a) {
   }
   __syncthreads();
   const int fp = a.first_pred[b];
-  for (int j = tid; j < T; j += 256) {
-    tb[j + 1] = s_valid[j] ? s_pred[j] : -1;
-    path[j] = -1;
+  if (tid < T) {
+    tb[tid + 1] = my_valid ? s_pred[tid] : -1;
+    path[tid] = -1;
   }
   if (tid == 0) tb[0] = fp;
-  __syncthreads();
-  if (tid != 0) return;
-  const int32_t *tok = a.tokens + (size_t)b * T;
-  int best_n = 0, best_t = -1;
-  for (int t = 0; t < T; ++t) {
-    if (!s_valid[t]) continue;
-    const int p = s_par[t], dpt = s_depth[t];
-    const int dbin = tok[t] - a.bin_base;
+  // this token's own bias
+  long long bias = 0;
+  bool exact = false, leaf = false;
+  int p = -1;
+  if (tid < T && my_valid) {
+    p = s_par[tid];
+    const int dbin = a.tokens[(size_t)b * T + tid] - a.bin_base;
     const int target = p < 0 ? fp : s_pred[p];
-    const long long bias = (dbin >= 0 && dbin < a.n_bins) ? (long long)abs(dbin - target) : 0x7FFFFFFFLL;
-    const bool exact = (a.exact_mask >> s_gi[dpt]) & 1u;
-    const bool leaf = s_child[t] == 0x7FFFFFFF;
-    if (a.mode == 0) {
-      const bool first = s_first[dpt];
-      // everything before this token's sequence accepted?
-      const bool alive = first ? (p < 0 || s_end[p]) : s_alive[p];
-      const long long gsum = (first ? 0 : s_gsum[p]) + bias;
-      const long long gmax = first ? bias : (bias > s_gmax[p] ? bias : (long long)s_gmax[p]);
-      s_alive[t] = alive;
-      s_gsum[t] = gsum;
-      s_gmax[t] = (int32_t)gmax;
-      const bool pass = exact ? gmax == 0 : (gmax <= a.tok_threshold && gsum <= a.seq_budget);
-      const bool stop_ok = alive && pass && (s_last[dpt] || leaf);
-      s_end[t] = stop_ok;
-      if (stop_ok && dpt + 1 > best_n) { best_n = dpt + 1; best_t = t; }
-    } else {
-      const long long run = (p < 0 ? 0 : s_gsum[p]) + bias;
-      const bool alive = (p < 0 || s_alive[p]) && !(exact && bias != 0) && bias <= a.tok_threshold &&
-                         run <= a.seq_budget;
-      s_gsum[t] = run;
-      s_alive[t] = alive;
-      if (alive && dpt + 1 > best_n) { best_n = dpt + 1; best_t = t; }
-    }
+    bias = (dbin >= 0 && dbin < a.n_bins) ? (long long)abs(dbin - target) : 0x7FFFFFFFLL;
+    exact = (a.exact_mask >> s_gi[my_depth]) & 1u;
+    leaf = s_child[tid] == 0x7FFFFFFF;
   }
+  const int maxd = s_maxd;
+  for (int lvl = 0; lvl <= maxd; ++lvl) {           // uniform trip count
+    if (tid < T && my_valid && my_depth == lvl) {
+      unsigned cand = 0;
+      if (a.mode == 0) {
+        const bool first = s_first[lvl];
+        // everything before this token's sequence accepted?
+        const bool alive = first ? (p < 0 || s_end[p]) : s_alive[p];
+        const long long gsum = (first ? 0 : s_gsum[p]) + bias;
+        const long long gmax = first ? bias : (bias > s_gmax[p] ? bias : (long long)s_gmax[p]);
+        s_alive[tid] = alive;
+        s_gsum[tid] = gsum;
+        s_gmax[tid] = (int32_t)gmax;
+        const bool pass = exact ? gmax == 0 : (gmax <= a.tok_threshold && gsum <= a.seq_budget);
+        const bool stop_ok = alive && pass && (s_last[lvl] || leaf);
+        s_end[tid] = stop_ok;
+        if (stop_ok) cand = ((unsigned)(lvl + 1) << 16) | (unsigned)(0xFFFF - tid);
+      } else {
+        const long long run = (p < 0 ? 0 : s_gsum[p]) + bias;
+        const bool alive = (p < 0 || s_alive[p]) && !(exact && bias != 0) && bias <= a.tok_threshold &&
+                           run <= a.seq_budget;
+        s_gsum[tid] = run;
+        s_alive[tid] = alive;
+        if (alive) cand = ((unsigned)(lvl + 1) << 16) | (unsigned)(0xFFFF - tid);
+      }
+      if (cand) atomicMax(&s_best, cand);
+    }
+    __syncthreads();
+  }
+  if (tid != 0) return;
+  const unsigned best = s_best;
+  const int best_n = (int)(best >> 16), best_t = best ? 0xFFFF - (int)(best & 0xFFFFu) : -1;
   a.accepted_len[b] = best_n;
   a.next_token[b] = a.bin_base + (best_t < 0 ? fp : s_pred[best_t]);
   for (int cur = best_t, j = best_n - 1; j >= 0; --j) {

@@ -114,6 +114,27 @@ class Verifier:
             raise RuntimeError("heisd_verify_tree_step failed (%d): %s" % (rc, B.heisd_last_error(self.ctx)))
         return out
 
+    def prefill_chunk(self, k_cache, v_cache, prefix_len, token_ids=None, x_rows=None, want_logits=False,
+                      out=None, stream=None):
+        """token_ids i32[batch,n] or x_rows f32[batch,n,d] on the device (exactly one).  Returns dict of
+        device tensors: next_bin i32[batch] (and last_logits f32[batch,n_bins])."""
+        src = token_ids if token_ids is not None else x_rows
+        batch, n = src.shape[0], src.shape[1]
+        dev = self.model.device
+        if out is None:
+            out = {"next_bin": torch.empty(batch, dtype=torch.int32, device=dev)}
+            if want_logits:
+                out["last_logits"] = torch.empty(batch, self.model.shape["n_bins"], dtype=torch.float32, device=dev)
+        kv = B.heisd_kv_desc(k_cache.data_ptr(), v_cache.data_ptr(), prefix_len.data_ptr(), None)
+        st = (stream or torch.cuda.current_stream(dev)).cuda_stream
+        rc = B.heisd_prefill_chunk(self.ctx, kv, token_ids.data_ptr() if token_ids is not None else None,
+                                   x_rows.data_ptr() if x_rows is not None else None, n, batch,
+                                   out["next_bin"].data_ptr(),
+                                   out["last_logits"].data_ptr() if "last_logits" in out else None, st)
+        if rc != 0:
+            raise RuntimeError("heisd_prefill_chunk failed (%d): %s" % (rc, B.heisd_last_error(self.ctx)))
+        return out
+
     def close(self):
         if self.ctx is not None:
             B.heisd_free(self.ctx)

@@ -114,3 +114,49 @@ def test_c3_full_size_batch16_k14_with_skips_sampled(big):
 
 def test_c4_full_size_batch64_sampled(big):
     _sampled_case(big, "C4")
+
+
+def _tree_case(big, name, R, p_geo, n_sample=None):
+    """Tree verification (Sec. 4.2) at the 7B shape: R candidates per episode = the oracle's own
+    continuation plus seeded geometric offsets, built into a sequence-wise tree by the library's host
+    builder; the GPU verifies every episode, the oracle (chain by chain) a sample of them."""
+    import paper_2603_17573_amd as P
+    from gpu_harness import run_gpu_tree_step, compare_tree_with_oracle, accept_desc_of
+    sh, weights, om, dm = big
+    wl = synth.WORKLOADS[name]
+    B, K = wl.batch, wl.K
+    eps = list(range(B)) if n_sample is None else sorted({0, B // 2, B - 1})[:n_sample]
+    rule = oracle.AcceptRule(wl.tau_tok, wl.tau_seq)
+    T_full = 3 * R + 3 * R * R + R * R
+    cap = wl.prefix_len + T_full
+    kb, vb, plen, first = direct_prefix_cache(wl, cap)
+    off = synth.make_candidate_offsets(wl, R, p_geo)
+    cands = np.zeros((B, R, K), np.int32)
+    cands[:] = synth.make_drafts_uniform(wl)[:, None, :]                 # episodes outside the sample: one chain
+    t0 = time.time()
+    kbs, vbs = np.ascontiguousarray(kb[:, eps]), np.ascontiguousarray(vb[:, eps])
+    for r in range(R):
+        cands[eps, r] = teacher_forced_drafts(om, wl, kbs, vbs, plen[eps], first[eps], off[eps, r])
+    print("%s: %d teacher-forced candidates for episodes %s in %.1f s" % (name, R, eps, time.time() - t0), flush=True)
+    tokens = np.zeros((B, T_full), np.int32)
+    parent = np.full((B, T_full), -2, np.int32)
+    for b in range(B):
+        tok, par = P.build_sequence_tree(sh.bin_base + cands[b], accept_desc_of(rule), T_full)
+        tokens[b, :len(tok)], parent[b, :len(par)] = tok, par
+    t0 = time.time()
+    ref = oracle.verify_tree_step(om, kbs, vbs, plen[eps], first[eps], tokens[eps], parent[eps], rule)
+    print("%s: oracle, %d chains, %.1f s" % (name, sum(len(oracle.tree_chains(parent[e])) for e in eps),
+                                             time.time() - t0), flush=True)
+    got = run_gpu_tree_step(sh, weights, kb, vb, plen, first, tokens, parent, rule, None, model=dm)
+    stats = compare_tree_with_oracle(got, ref, tokens, parent, rule, sh, kb, vb, plen, first, None, episodes=eps)
+    print(name, "tree R", R, "T", T_full, stats, got["accepted_len"].tolist(), ref["accepted_len"].tolist(), flush=True)
+    assert np.all((got["accepted_len"] >= 0) & (got["accepted_len"] <= K))
+    return got, ref
+
+
+def test_c1_full_size_top4_tree(big):
+    got, ref = _tree_case(big, "C1", 4, 0.5)
+
+
+def test_c2_full_size_top3_trees_sampled(big):
+    _tree_case(big, "C2", 3, 0.5, n_sample=2)
