@@ -59,6 +59,126 @@ def read_traffic(kclass):
     return None
 
 
+def run_aux_mode(args):
+    """--mode decode: the autoregressive decode step (Eq. 2-1; the fallback of Sec. 4.2 and the baseline
+    speculative decoding replaces): one new token per episode through heisd_prefill_chunk.
+    --mode prefill: the workload's whole prefix from an empty cache, visual rows as one chunk of
+    embeddings, prompt ids as a second chunk.  Same JSON schema as the verify line."""
+    import numpy as np
+    import torch
+    import synth
+    from paper_2603_17573_amd import (DeviceModel, Verifier, binding, heisd_verify_profile_enable,
+                                      heisd_verify_profile_read, heisd_verify_set_path)
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    dev = "cuda:0"
+    wl = synth.WORKLOADS[args.workload]
+    sh = wl.shape
+    B, P = wl.batch, wl.prefix_len
+    decode = args.mode == "decode"
+    chunks = [1] if decode else [c for c in (wl.n_visual, wl.n_text) if c]
+    cap = P + 1
+    weights = synth.make_weights(sh, wl.seed)
+    ver = Verifier(DeviceModel(sh, weights, dev), B, max(chunks), cap)
+    assert heisd_verify_set_path(ver.ctx, args.path) == 0
+    kc, vc = ver.new_cache(B)
+    stream = torch.cuda.current_stream(dev)
+    calls = []                                   # (prefix_len tensor, keyword arguments) per call of one step
+    if decode:
+        first = np.zeros(B, np.int32)
+        for e in range(B):
+            k, v, f = synth.make_prefix_kv_direct(wl, e, cap)
+            kc[:, e] = torch.from_numpy(k.view(np.int16)).to(dev).view(torch.bfloat16)
+            vc[:, e] = torch.from_numpy(v.view(np.int16)).to(dev).view(torch.bfloat16)
+            first[e] = f
+        ids = torch.from_numpy((sh.bin_base + first).astype(np.int32)[:, None]).to(dev).contiguous()
+        calls.append((torch.full((B,), P, dtype=torch.int32, device=dev), {"token_ids": ids}))
+    else:
+        inputs = [synth.make_prefix_inputs(wl, e) for e in range(B)]
+        if wl.n_visual:
+            x = np.stack([emb for emb, _ in inputs]).astype(np.float32)
+            calls.append((torch.zeros(B, dtype=torch.int32, device=dev), {"x_rows": torch.from_numpy(x).to(dev)}))
+        if wl.n_text:
+            t = np.stack([ids for _, ids in inputs]).astype(np.int32)
+            calls.append((torch.full((B,), wl.n_visual, dtype=torch.int32, device=dev),
+                          {"token_ids": torch.from_numpy(t).to(dev)}))
+    outs = [None] * len(calls)
+
+    def step():
+        for i, (pl, kw) in enumerate(calls):
+            outs[i] = ver.prefill_chunk(kc, vc, pl, out=outs[i], stream=stream, **kw)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / args.steps
+    n_prof = max(1, min(args.steps, 16))
+    heisd_verify_profile_enable(ver.ctx, True)
+    for _ in range(n_prof):
+        step()
+    rc, prof = heisd_verify_profile_read(ver.ctx)
+    heisd_verify_profile_enable(ver.ctx, False)
+    assert rc == 0
+    kernels = {k: {"avg_us": round(t / n * 1e3, 3), "launches_per_step": n / n_prof,
+                   "share_of_step": round(t / n_prof / ms, 4)} for k, (t, n) in prof.items() if n}
+    d, f, L = sh.d_model, sh.d_ffn, sh.n_layers
+    gemm_flops_per_row = 2.0 * (L * (4 * d * d + 3 * d * f) + sh.n_bins * d)
+    if decode:
+        total_bytes, per_class = algorithmic_bytes(sh, B, 1, P)
+        dom = max((k for k in kernels if k in per_class and k != "persist"), key=lambda k: prof[k][0])
+        dom_s = prof[dom][0] / prof[dom][1] * 1e-3
+        roofline = {"kernel": dom, "bound": "hbm", "achieved": round(per_class[dom] / dom_s / 1e9, 1),
+                    "peak": HBM_PEAK / 1e9, "unit": "GB/s", "frac": round(per_class[dom] / dom_s / HBM_PEAK, 4),
+                    "bytes_per_launch": per_class[dom], "avg_launch_us": round(dom_s * 1e6, 3), "traffic": None}
+        metric, value, unit = "autoregressive decode steps/s (%s)" % wl.name, 1000.0 / ms, "decode steps/s"
+    else:
+        # dense contraction: flops of the dominant projection class over the rows of a step, against the
+        # bf16 matrix-core peak (each fp32 activation is two bf16 operands, so the cores do twice these flops)
+        cls_w = {"qkv": 3 * d * d, "oproj": d * d, "gateup": 2 * d * f, "down": d * f}
+        dom = max((k for k in kernels if k in cls_w), key=lambda k: prof[k][0])
+        step_s = prof[dom][0] / n_prof * 1e-3
+        fl = 2.0 * cls_w[dom] * L * B * P
+        roofline = {"kernel": dom, "bound": "mfma", "achieved": round(fl / step_s / 1e12, 2), "peak": 2500.0,
+                    "unit": "TFLOP/s", "frac": round(fl / step_s / 2.5e15, 4),
+                    "flops_per_step": fl, "class_ms_per_step": round(step_s * 1e3, 3), "traffic": None}
+        metric, value, unit = "prefix tokens prefilled/s (%s)" % wl.name, B * P * 1000.0 / ms, "tokens/s"
+    cpu = None
+    if not args.no_cpu_baseline:
+        import oracle
+        from helpers import oracle_model, oracle_chunked_prefill, prefix_embeddings
+        om = oracle_model(sh, weights)
+        t0 = time.perf_counter()
+        if decode:
+            n_done, spent = 0, 0.0
+            k1, v1, f1 = synth.make_prefix_kv_direct(wl, 0, cap)
+            while spent < 10.0 and n_done < 64:
+                t1 = time.perf_counter()
+                oracle.forward_block(om, oracle.embed(om, np.array([[sh.bin_base + int(f1)]])), [P], k1[:, None], v1[:, None])
+                spent += time.perf_counter() - t1
+                n_done += 1
+            cpu = {"value": round(n_done / B / spent, 4), "unit": unit, "cores": min(int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1)), os.cpu_count() or 1),
+                   "kind": "oracle", "sample": "%d single-episode oracle decode forwards, %.1f s" % (n_done, spent)}
+        else:
+            oracle_chunked_prefill(om, prefix_embeddings(om, wl, 0), chunks, cap)
+            spent = time.perf_counter() - t0
+            cpu = {"value": round(P / spent, 2), "unit": unit, "cores": min(int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1)), os.cpu_count() or 1),
+                   "kind": "oracle", "sample": "one episode's %d-row prefix through the oracle in the same chunks, %.1f s" % (P, spent)}
+    line = {"metric": metric, "value": round(value, 2), "unit": unit, "n_gpus": 1, "steps": args.steps,
+            "warmup": args.warmup, "ms_per_step": round(ms, 4), "higher_is_better": True, "scaling": "weak",
+            "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+            "config": {"workload": "%s: %d-layer d=%d decoder, prefix %d, batch %d; %s" %
+                                   (wl.name, L, d, P, B, "one new token per episode on a full prefix cache" if decode
+                                    else "whole prefix from an empty cache in chunks of %s rows" % chunks),
+                       "global_batch": B},
+            "kernel_path": args.path, "gemm_tflops_whole_step": round(gemm_flops_per_row * B * sum(chunks) / (ms * 1e-3) / 1e12, 2),
+            "kernels": kernels, "roofline": roofline, "cpu_baseline": cpu}
+    print(json.dumps(line))
+    ver.close()
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -72,11 +192,21 @@ def main():
     ap.add_argument("--tree", type=int, default=0, metavar="R",
                     help="time the TREE verify step instead: R retrieved candidates per episode, built into a "
                          "sequence-wise draft tree (paper Sec. 4.2); 0 = the linear step")
+    ap.add_argument("--mode", default="verify", choices=["verify", "decode", "prefill"],
+                    help="verify (default): the verify step; decode: one autoregressive decode step; prefill: the "
+                         "workload's prefix from an empty cache, in chunks")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs the verify step on ONE GPU (episodes would shard by batch "
               "with no exchange); --gpus %d is not supported" % args.gpus, file=sys.stderr)
         sys.exit(2)
+
+    if args.mode != "verify":
+        from paper_2603_17573_amd import binding as _b
+        if not os.path.exists(_b.LIB_PATH):
+            from paper_2603_17573_amd import build
+            build.build(force=False)
+        return run_aux_mode(args)
 
     import numpy as np
     import torch

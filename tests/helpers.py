@@ -78,3 +78,25 @@ def teacher_forced_drafts(model, wl, kb, vb, prefix_len, first_pred, offsets):
         plen += 1
         v_cur = oracle.argmax_bins(out["logits"][:, 0, :]).astype(np.int64)
     return drafts
+
+
+def oracle_chunked_prefill(model: oracle.OracleModel, x_full: np.ndarray, chunks, capacity: int):
+    """The prefix of ONE episode through the oracle chunk by chunk, the cache rounded to bf16 between
+    chunks (the cache format is part of the boundary: later chunks read bf16 rows).  x_full: [P, d] fp64.
+    Returns (k_bits, v_bits) u16 [L][1][H][cap][hd] after the last chunk, and one record per chunk:
+    {"p", "n", "k_before", "v_before" (the cache the chunk started from), "k_new", "v_new" (its rows,
+    unrounded, [L][H][n][hd]), "logits" (last row), "next_bin"}."""
+    L, H, hd = model.n_layers, model.n_heads, model.head_dim
+    kb = np.zeros((L, 1, H, capacity, hd), np.uint16)
+    vb = np.zeros_like(kb)
+    p, steps = 0, []
+    for n in chunks:
+        out = oracle.forward_block(model, x_full[None, p:p + n], [p], kb, vb)
+        rec = {"p": p, "n": n, "k_before": kb.copy(), "v_before": vb.copy(), "k_new": out["k_new"][:, 0],
+               "v_new": out["v_new"][:, 0], "logits": out["logits"][0, -1],
+               "next_bin": int(oracle.argmax_bins(out["logits"][0, -1]))}
+        kb[:, 0, :, p:p + n, :] = synth.f32_to_bf16_bits(out["k_new"][:, 0].astype(np.float32))
+        vb[:, 0, :, p:p + n, :] = synth.f32_to_bf16_bits(out["v_new"][:, 0].astype(np.float32))
+        steps.append(rec)
+        p += n
+    return kb, vb, steps

@@ -160,3 +160,42 @@ def test_c1_full_size_top4_tree(big):
 
 def test_c2_full_size_top3_trees_sampled(big):
     _tree_case(big, "C2", 3, 0.5, n_sample=2)
+
+
+def test_c1_full_size_chunked_prefill_and_decode(big):
+    """The C1 prefix (256 visual rows as embeddings, then 20 prompt ids) through heisd_prefill_chunk in
+    the two chunks a caller would use, against the oracle run the same way: each chunk on the oracle's
+    cache bytes (new rows to the cache bar), the whole prefix on the GPU's own cache (outcome to the
+    logit bar); then one autoregressive decode step (Eq. 2-1) on the oracle's cache."""
+    import torch
+    from paper_2603_17573_amd import Verifier
+    from gpu_harness import _bits_to_dev
+    from helpers import oracle_chunked_prefill, prefix_embeddings
+    from test_gpu_prefill import gpu_chunked_prefill, check_chunks_in_isolation, check_logits
+    sh, weights, om, dm = big
+    wl = synth.WORKLOADS["C1"]
+    P, cap = wl.prefix_len, wl.prefix_len + 8
+    chunks = [wl.n_visual, wl.n_text]
+    t0 = time.time()
+    x = prefix_embeddings(om, wl, 0)
+    ref = oracle_chunked_prefill(om, x, chunks, cap)
+    print("oracle prefill of %d rows in %.1f s" % (P, time.time() - t0), flush=True)
+    ver = Verifier(dm, 1, max(chunks), cap)
+    worst = check_chunks_in_isolation(ver, wl, [0], [ref], cap)
+    kc, vc, out = gpu_chunked_prefill(ver, wl, [0], chunks, cap)
+    last = ref[2][-1]
+    err = check_logits(out["last_logits"][0], out["next_bin"][0], last["logits"], last["next_bin"])
+    print("prefill: worst new-row error %.3g of the scale; last-row logit error of the GPU's own chain %.3g of "
+          "the range" % (worst, err), flush=True)
+    nb = last["next_bin"]
+    o = oracle.forward_block(om, oracle.embed(om, np.array([[sh.bin_base + nb]])), [P], ref[0], ref[1])
+    kc, vc = _bits_to_dev(ref[0], "cuda:0"), _bits_to_dev(ref[1], "cuda:0")
+    ids = torch.tensor([[sh.bin_base + nb]], dtype=torch.int32, device="cuda")
+    plen = torch.full((1,), P, dtype=torch.int32, device="cuda")
+    got = ver.prefill_chunk(kc, vc, plen, token_ids=ids, want_logits=True)
+    torch.cuda.synchronize()
+    lo = o["logits"][0, 0]
+    err2 = check_logits(got["last_logits"].cpu().numpy()[0], int(got["next_bin"].cpu()[0]), lo,
+                        int(oracle.argmax_bins(lo)))
+    print("decode: logit error %.3g of the range" % err2, flush=True)
+    ver.close()
