@@ -179,6 +179,70 @@ def run_aux_mode(args):
     ver.close()
 
 
+def run_skip_mode(args):
+    """--mode skip: the verify-skip decision kernels (Sec. 4.1, Alg. 1) on synthetic trajectory features:
+    the offline stage over n = 300 trajectory points of d_model-wide features, and the per-episode
+    decision for 64 episodes."""
+    import numpy as np
+    import torch
+    import synth
+    import paper_2603_17573_amd as P
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    dev = "cuda:0"
+    d, n, B = synth.WORKLOADS[args.workload].shape.d_model, 300, 64
+    f = synth.normal_f32(7, "skip.feat", n * d).reshape(n, d)
+    f = np.cumsum(0.1 * f, axis=0, dtype=np.float32) + synth.normal_f32(7, "skip.base", d)      # a drifting trajectory
+    t_f = torch.from_numpy(np.ascontiguousarray(f)).to(dev)
+    work = torch.zeros(1, dtype=torch.int64, device=dev)
+    min_s = torch.zeros(1, device=dev)
+    o_dist = torch.zeros(1, dtype=torch.int32, device=dev)
+    skip = torch.zeros(B, dtype=torch.uint8, device=dev)
+    dist = torch.ones(B, dtype=torch.int32, device=dev)
+    st = torch.cuda.current_stream(dev).cuda_stream
+
+    def offline():
+        assert P.heisd_skip_offline(t_f.data_ptr(), n, d, 0.8, None, work.data_ptr(), min_s.data_ptr(), o_dist.data_ptr(), st) == 0
+
+    def decide():
+        assert P.heisd_skip_decide(t_f.data_ptr(), t_f[B:].data_ptr(), dist.data_ptr(), B, d, min_s.data_ptr(),
+                                   o_dist.data_ptr(), skip.data_ptr(), None, st) == 0
+
+    res = {}
+    for name, fn in (("offline", offline), ("decide", decide)):
+        for _ in range(args.warmup):
+            fn()
+        torch.cuda.synchronize()
+        ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        ev0.record()
+        for _ in range(args.steps):
+            fn()
+        ev1.record()
+        torch.cuda.synchronize()
+        res[name] = ev0.elapsed_time(ev1) / args.steps
+    pairs = n * n
+    flops = 6.0 * d * pairs                    # three multiply-adds per element of a pair
+    cpu = None
+    if not args.no_cpu_baseline:
+        import oracle
+        t0 = time.perf_counter()
+        oracle.offline_stage(f[:100], 0.8)
+        spent = time.perf_counter() - t0
+        cpu = {"value": round(1.0 / (spent * 9.0), 4), "unit": "offline stages/s", "cores": 1, "kind": "oracle",
+               "sample": "the oracle's double loop over the first 100 of the 300 points (1/9 of the pairs), %.1f s" % spent}
+    line = {"metric": "verify-skip offline stages/s (%d trajectory points, d=%d)" % (n, d), "value": round(1000.0 / res["offline"], 1),
+            "unit": "offline stages/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+            "ms_per_step": round(res["offline"], 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+            "dtype": "f32", "data": "synthetic",
+            "config": {"workload": "offline stage of Alg. 1 over %d synthetic trajectory points (random-walk features of width %d), "
+                                   "boundary T = 0.8; decision for %d episodes" % (n, d, B)},
+            "decide_us": round(res["decide"] * 1e3, 2),
+            "min_S": float(min_s.cpu()[0]), "O_dist": int(o_dist.cpu()[0]), "skipped": int(skip.sum().cpu()),
+            "roofline": {"kernel": "pair_similarity", "bound": "alu", "achieved": round(flops / (res["offline"] * 1e-3) / 1e12, 2),
+                         "peak": 157.3, "unit": "TFLOP/s", "frac": round(flops / (res["offline"] * 1e-3) / 157.3e12, 4), "traffic": None},
+            "cpu_baseline": cpu}
+    print(json.dumps(line))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -192,7 +256,7 @@ def main():
     ap.add_argument("--tree", type=int, default=0, metavar="R",
                     help="time the TREE verify step instead: R retrieved candidates per episode, built into a "
                          "sequence-wise draft tree (paper Sec. 4.2); 0 = the linear step")
-    ap.add_argument("--mode", default="verify", choices=["verify", "decode", "prefill"],
+    ap.add_argument("--mode", default="verify", choices=["verify", "decode", "prefill", "skip"],
                     help="verify (default): the verify step; decode: one autoregressive decode step; prefill: the "
                          "workload's prefix from an empty cache, in chunks")
     args = ap.parse_args()
@@ -206,7 +270,7 @@ def main():
         if not os.path.exists(_b.LIB_PATH):
             from paper_2603_17573_amd import build
             build.build(force=False)
-        return run_aux_mode(args)
+        return run_skip_mode(args) if args.mode == "skip" else run_aux_mode(args)
 
     import numpy as np
     import torch

@@ -236,6 +236,44 @@ int heisd_prefill_chunk(heisd_verify_ctx *ctx, const heisd_kv_desc *kv, const in
                         float *last_logits, void *stream);
 
 /*
+ * The verify-skip DECISION (Sec. 4.1, Alg. 1), which produces the skip mask heisd_verify_step consumes.
+ * The paper captures the input features of the final (`lm_head`) layer while a draft is verified,
+ * computes the feature similarity S of pairs of trajectory points, collects on historical trajectories
+ * the minimum acceptable similarity min_S with its point distance O_dist (offline stage), and on a new
+ * task skips the verification of points that are "excessively similar".  Similarity is the cosine; the
+ * readings of what the paper leaves open are stated per call.  fp32 throughout; all calls asynchronous
+ * on `stream`, none allocates.
+ *
+ * heisd_export_features: feat[b] = the final-norm hidden state (the LM head's input) of row row[b]
+ *   (NULL: the last row) of episode b in the MOST RECENT step of this context (heisd_verify_step,
+ *   heisd_verify_tree_step or heisd_prefill_chunk with the same rows_per_episode and batch).
+ *     row   DEVICE i32 [batch] or NULL;  feat  DEVICE f32 [batch][d_model] out, 16-byte aligned
+ * heisd_feature_similarity: S[i][j] = cosine(a[i], b[j]) (0 if a vector is all zero).
+ *     a DEVICE f32 [n][d], b DEVICE f32 [m][d], S DEVICE f32 [n][m] out; d a multiple of 4, 16-byte aligned
+ * heisd_skip_offline: offline stage of Alg. 1 over n trajectory points: the smallest S(feat[i], feat[i+dd])
+ *   that exceeds T, and its distance dd; among equal similarities the pair found first with i ascending,
+ *   then dd ascending.  No pair above T: min_s = +inf, o_dist = 0 (never skip).
+ *     S     DEVICE f32 [n][n] out, optional (the whole similarity matrix)
+ *     work  DEVICE, 8 bytes, 8-byte aligned (scratch);  min_s DEVICE f32 [1] out;  o_dist DEVICE i32 [1] out
+ * heisd_skip_decide: skip_mask[b] = 1 iff dist[b] <= *o_dist and cosine(feat_prev[b], feat_last[b]) >= *min_s,
+ *   where feat_last is the feature of the episode's last VERIFIED trajectory point, feat_prev that of the
+ *   verified point before it, and dist[b] how many points the current one lies after the last verified
+ *   one (features exist only for verified points, so the rule looks back).
+ *     feat_prev, feat_last DEVICE f32 [batch][d]; dist DEVICE i32 [batch]; min_s, o_dist DEVICE scalars;
+ *     skip_mask DEVICE u8 [batch] out; similarity DEVICE f32 [batch] out, optional
+ * The adaptive update of min_S / O_dist from task feedback (online stage) is scalar host logic and not
+ * part of this library.
+ * Errors: EINVAL (NULL / misaligned pointers, sizes out of range: at most 65535 points), EHIP.
+ */
+int heisd_export_features(heisd_verify_ctx *ctx, const int32_t *row, int32_t rows_per_episode, int32_t batch,
+                          float *feat, void *stream);
+int heisd_feature_similarity(const float *a, const float *b, int32_t n, int32_t m, int32_t d, float *S, void *stream);
+int heisd_skip_offline(const float *feat, int32_t n, int32_t d, float T, float *S, uint64_t *work, float *min_s,
+                       int32_t *o_dist, void *stream);
+int heisd_skip_decide(const float *feat_prev, const float *feat_last, const int32_t *dist, int32_t batch, int32_t d,
+                      const float *min_s, const int32_t *o_dist, uint8_t *skip_mask, float *similarity, void *stream);
+
+/*
  * Per-kernel timing for measurement runs (not part of the method).  With profiling enabled,
  * heisd_verify_step brackets every kernel launch with HIP events on the caller's stream;
  * heisd_verify_profile_read waits for the recorded events, adds the elapsed milliseconds

@@ -68,6 +68,16 @@ def load():
         lib.heisd_prefill_chunk.argtypes = [c_void_p, POINTER(heisd_kv_desc), c_void_p, c_void_p, c_int32, c_int32,
                                             c_void_p, c_void_p, c_void_p]
         lib.heisd_prefill_chunk.restype = ctypes.c_int
+        lib.heisd_export_features.argtypes = [c_void_p, c_void_p, c_int32, c_int32, c_void_p, c_void_p]
+        lib.heisd_export_features.restype = ctypes.c_int
+        lib.heisd_feature_similarity.argtypes = [c_void_p, c_void_p, c_int32, c_int32, c_int32, c_void_p, c_void_p]
+        lib.heisd_feature_similarity.restype = ctypes.c_int
+        lib.heisd_skip_offline.argtypes = [c_void_p, c_int32, c_int32, c_float, c_void_p, c_void_p, c_void_p, c_void_p,
+                                           c_void_p]
+        lib.heisd_skip_offline.restype = ctypes.c_int
+        lib.heisd_skip_decide.argtypes = [c_void_p, c_void_p, c_void_p, c_int32, c_int32, c_void_p, c_void_p, c_void_p,
+                                          c_void_p, c_void_p]
+        lib.heisd_skip_decide.restype = ctypes.c_int
         lib.heisd_free.argtypes = [c_void_p]
         lib.heisd_free.restype = None
         lib.heisd_verify_profile_enable.argtypes = [c_void_p, ctypes.c_int]
@@ -126,6 +136,22 @@ def heisd_prefill_chunk(ctx, kv: heisd_kv_desc, token_ids, x_rows, n_rows, batch
     """All array arguments are integer device addresses (0/None = NULL)."""
     return load().heisd_prefill_chunk(ctx, ctypes.byref(kv) if kv is not None else None, token_ids, x_rows, n_rows,
                                       batch, next_bin, last_logits, stream)
+
+
+def heisd_export_features(ctx, row, rows_per_episode, batch, feat, stream) -> int:
+    return load().heisd_export_features(ctx, row, rows_per_episode, batch, feat, stream)
+
+
+def heisd_feature_similarity(a, b, n, m, d, S, stream) -> int:
+    return load().heisd_feature_similarity(a, b, n, m, d, S, stream)
+
+
+def heisd_skip_offline(feat, n, d, T, S, work, min_s, o_dist, stream) -> int:
+    return load().heisd_skip_offline(feat, n, d, T, S, work, min_s, o_dist, stream)
+
+
+def heisd_skip_decide(feat_prev, feat_last, dist, batch, d, min_s, o_dist, skip_mask, similarity, stream) -> int:
+    return load().heisd_skip_decide(feat_prev, feat_last, dist, batch, d, min_s, o_dist, skip_mask, similarity, stream)
 
 
 def heisd_free(ctx) -> None:

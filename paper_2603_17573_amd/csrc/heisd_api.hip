@@ -17,6 +17,7 @@
 #include "heisd_batch.h"
 #include "heisd_gemm.h"
 #include "heisd_misc.h"
+#include "heisd_skip.h"
 
 using namespace heisd;
 
@@ -1203,5 +1204,81 @@ extern "C" int heisd_prefill_chunk(heisd_verify_ctx *ctx, const heisd_kv_desc *k
   const hipError_t e = hipGetLastError();
   if (e != hipSuccess) return fail(ctx, HEISD_EHIP, "prefill_chunk: %s", hipGetErrorString(e));
   ctx->err[0] = 0;
+  return HEISD_OK;
+}
+
+// ---- the verify-skip decision (Sec. 4.1, Alg. 1) ------------------------------------------------
+
+static bool aligned16(const void *p) { return ((uintptr_t)p & 15) == 0; }
+
+extern "C" int heisd_export_features(heisd_verify_ctx *ctx, const int32_t *row, int32_t rows_per_episode,
+                                     int32_t batch, float *feat, void *stream) {
+  if (!ctx) return HEISD_EINVAL;
+  if (!feat || !aligned16(feat)) return fail(ctx, HEISD_EINVAL, "export_features: NULL or misaligned output");
+  const heisd_model_desc &d = ctx->d;
+  if (rows_per_episode < 1 || batch < 1 || rows_per_episode > d.max_k || batch > d.max_batch)
+    return fail(ctx, HEISD_EINVAL, "export_features: rows_per_episode=%d batch=%d outside the context", rows_per_episode, batch);
+  if (d.d_model % 4) return fail(ctx, HEISD_EUNSUPPORTED, "export_features: d_model not a multiple of 4");
+  (void)hipGetLastError();
+  export_features<<<dim3(batch), dim3(256), 0, static_cast<hipStream_t>(stream)>>>(ctx->x, row, rows_per_episode, d.d_model,
+                                                                                   d.final_norm, d.rms_eps, feat);
+  const hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return fail(ctx, HEISD_EHIP, "export_features: %s", hipGetErrorString(e));
+  ctx->err[0] = 0;
+  return HEISD_OK;
+}
+
+static int similarity_launch(const float *a, const float *b, int n, int m, int d, float *S, float T,
+                             unsigned long long *key, hipStream_t st, const char *who) {
+  if (!a || !b || !aligned16(a) || !aligned16(b)) return fail(nullptr, HEISD_EINVAL, "%s: NULL or misaligned features", who);
+  if (n < 1 || m < 1 || d < 4 || d % 4 || n > 65535 || m > 65535)
+    return fail(nullptr, HEISD_EINVAL, "%s: n=%d m=%d d=%d (1..65535 points, d a multiple of 4)", who, n, m, d);
+  const long long pairs = (long long)n * m;
+  pair_similarity<<<dim3((unsigned)((pairs + 3) / 4)), dim3(256), 0, st>>>(a, b, n, m, d, S, T, key);
+  return HEISD_OK;
+}
+
+extern "C" int heisd_feature_similarity(const float *a, const float *b, int32_t n, int32_t m, int32_t d, float *S,
+                                        void *stream) {
+  if (!S) return fail(nullptr, HEISD_EINVAL, "feature_similarity: NULL output");
+  (void)hipGetLastError();
+  const int rc = similarity_launch(a, b, n, m, d, S, 0.f, nullptr, static_cast<hipStream_t>(stream), "feature_similarity");
+  if (rc != HEISD_OK) return rc;
+  const hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return fail(nullptr, HEISD_EHIP, "feature_similarity: %s", hipGetErrorString(e));
+  g_init_err[0] = 0;
+  return HEISD_OK;
+}
+
+extern "C" int heisd_skip_offline(const float *feat, int32_t n, int32_t d, float T, float *S, uint64_t *work,
+                                  float *min_s, int32_t *o_dist, void *stream) {
+  if (!work || !min_s || !o_dist || ((uintptr_t)work & 7)) return fail(nullptr, HEISD_EINVAL, "skip_offline: NULL or misaligned pointer");
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  (void)hipGetLastError();
+  if (!feat || !aligned16(feat) || n < 1 || n > 65535 || d < 4 || d % 4)
+    return fail(nullptr, HEISD_EINVAL, "skip_offline: n=%d d=%d (1..65535 points, d a multiple of 4) or bad pointer", n, d);
+  unsigned long long *key = reinterpret_cast<unsigned long long *>(work);
+  skip_key_init<<<dim3(1), dim3(1), 0, st>>>(key);
+  const int rc = similarity_launch(feat, feat, n, n, d, S, T, key, st, "skip_offline");
+  if (rc != HEISD_OK) return rc;
+  skip_key_decode<<<dim3(1), dim3(1), 0, st>>>(key, min_s, o_dist);
+  const hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return fail(nullptr, HEISD_EHIP, "skip_offline: %s", hipGetErrorString(e));
+  g_init_err[0] = 0;
+  return HEISD_OK;
+}
+
+extern "C" int heisd_skip_decide(const float *feat_prev, const float *feat_last, const int32_t *dist, int32_t batch,
+                                 int32_t d, const float *min_s, const int32_t *o_dist, uint8_t *skip_mask,
+                                 float *similarity, void *stream) {
+  if (!feat_prev || !feat_last || !dist || !min_s || !o_dist || !skip_mask || !aligned16(feat_prev) || !aligned16(feat_last))
+    return fail(nullptr, HEISD_EINVAL, "skip_decide: NULL or misaligned pointer");
+  if (batch < 1 || d < 4 || d % 4) return fail(nullptr, HEISD_EINVAL, "skip_decide: batch=%d d=%d", batch, d);
+  (void)hipGetLastError();
+  skip_decide<<<dim3(batch), dim3(64), 0, static_cast<hipStream_t>(stream)>>>(feat_prev, feat_last, dist, d, min_s, o_dist,
+                                                                              skip_mask, similarity);
+  const hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return fail(nullptr, HEISD_EHIP, "skip_decide: %s", hipGetErrorString(e));
+  g_init_err[0] = 0;
   return HEISD_OK;
 }

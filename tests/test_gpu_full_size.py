@@ -199,3 +199,48 @@ def test_c1_full_size_chunked_prefill_and_decode(big):
                         int(oracle.argmax_bins(lo)))
     print("decode: logit error %.3g of the range" % err2, flush=True)
     ver.close()
+
+
+def test_c1_full_size_exported_features_and_skip_decision(big):
+    """Sec. 4.1 at the 7B shape: the final-layer features of two verify steps (same prefix, different
+    drafts) against the oracle's, their similarity, and the decision made from them."""
+    import torch
+    import paper_2603_17573_amd as P
+    from gpu_harness import accept_desc_of, _bits_to_dev
+    sh, weights, om, dm = big
+    wl = synth.WORKLOADS["C1"]
+    cap = wl.prefix_len + wl.K
+    kb, vb, plen, first = direct_prefix_cache(wl, cap)
+    rule = oracle.AcceptRule(wl.tau_tok, wl.tau_seq)
+    d0 = (sh.bin_base + synth.make_drafts_uniform(wl)).astype(np.int32)
+    d1 = d0.copy()
+    d1[0, -1] = sh.bin_base + (d0[0, -1] - sh.bin_base + 1) % sh.n_bins          # a neighbouring last token
+    ver = P.Verifier(dm, 1, wl.K, cap)
+    dev = "cuda:0"
+    feats_gpu, feats_ref = [], []
+    for drafts in (d0, d1):
+        kc, vc = _bits_to_dev(kb, dev), _bits_to_dev(vb, dev)
+        ver.step(kc, vc, torch.from_numpy(plen).to(dev), torch.from_numpy(first).to(dev), torch.from_numpy(drafts).to(dev),
+                 accept_desc_of(rule))
+        f = torch.zeros((1, sh.d_model), device=dev)
+        assert P.heisd_export_features(ver.ctx, None, wl.K, 1, f.data_ptr(), None) == 0
+        torch.cuda.synchronize()
+        feats_gpu.append(f)
+        feats_ref.append(oracle.verify_step(om, kb, vb, plen, first, drafts, rule)["feat"][0, -1])
+    for g, r in zip(feats_gpu, feats_ref):
+        err = np.abs(g.cpu().numpy()[0] - r).max() / np.abs(r).max()
+        print("feature error %.3g of the largest feature" % err, flush=True)
+        assert err <= 1e-4
+    s_ref = oracle.cosine(feats_ref[0], feats_ref[1])
+    skip = torch.zeros(1, dtype=torch.uint8, device=dev)
+    sim = torch.zeros(1, device=dev)
+    one = torch.ones(1, dtype=torch.int32, device=dev)
+    for min_s in (s_ref - 0.01, s_ref + 0.01):
+        ms = torch.full((1,), float(min_s), device=dev)
+        assert P.heisd_skip_decide(feats_gpu[0].data_ptr(), feats_gpu[1].data_ptr(), one.data_ptr(), 1, sh.d_model,
+                                   ms.data_ptr(), one.data_ptr(), skip.data_ptr(), sim.data_ptr(), None) == 0
+        torch.cuda.synchronize()
+        assert abs(float(sim.cpu()[0]) - s_ref) <= 1e-4
+        assert int(skip.cpu()[0]) == int(oracle.skip_decision([feats_ref[0]], [feats_ref[1]], [1], min_s, 1)[0])
+    print("similarity of the two points: %.6f (oracle %.6f)" % (float(sim.cpu()[0]), s_ref), flush=True)
+    ver.close()
