@@ -274,6 +274,33 @@ int heisd_skip_decide(const float *feat_prev, const float *feat_last, const int3
                       const float *min_s, const int32_t *o_dist, uint8_t *skip_mask, float *similarity, void *stream);
 
 /*
+ * The retrieval branch's search (App. B; Sec. 4.2: Top-K instead of Top-1): every stored timestep is an
+ * L2-normalised embedding (4352-dim in the paper) with a payload (the action tokens that followed); a query
+ * embedding retrieves the K entries of highest cosine similarity, whose payloads become the draft
+ * candidates (heisd_build_sequence_tree takes them).  The paper searches an HNSW graph on the CPU
+ * (approximate); this call is the exact search, as one scan of the database in HBM.
+ *
+ *   db           DEVICE bf16 [n_vectors][d], row-major, rows L2-normalised by the caller (the similarity
+ *                is the plain dot product of the stored values with the query)
+ *   queries      DEVICE f32 [batch][d], 16-byte aligned
+ *   K            1 .. 64
+ *   payload      DEVICE i32 [n_vectors][payload_len], optional (then top_payload must be given too)
+ *   top_index    DEVICE i32 [batch][K] out   higher similarity first, equal similarities by lower index;
+ *                                            -1 past the end when n_vectors < K
+ *   top_score    DEVICE f32 [batch][K] out   (-inf where top_index is -1)
+ *   top_payload  DEVICE i32 [batch][K][payload_len] out, optional
+ *   workspace    DEVICE, 256-byte aligned, at least heisd_retrieve_workspace_bytes(n_vectors, batch, K):
+ *                all scores of every query, and the first selection round's winners
+ * Asynchronous on `stream`, allocates nothing.  d a multiple of 4, at most 8192; n_vectors < 2^31;
+ * batch at most 1024 (the database is streamed once per four queries).
+ * Errors: EINVAL, ENOMEM (workspace too small), EHIP.
+ */
+size_t heisd_retrieve_workspace_bytes(int64_t n_vectors, int32_t batch, int32_t K);
+int heisd_retrieve_topk(const void *db, int64_t n_vectors, int32_t d, const float *queries, int32_t batch, int32_t K,
+                        const int32_t *payload, int32_t payload_len, int32_t *top_index, float *top_score,
+                        int32_t *top_payload, void *workspace, size_t workspace_bytes, void *stream);
+
+/*
  * Per-kernel timing for measurement runs (not part of the method).  With profiling enabled,
  * heisd_verify_step brackets every kernel launch with HIP events on the caller's stream;
  * heisd_verify_profile_read waits for the recorded events, adds the elapsed milliseconds

@@ -78,6 +78,11 @@ def load():
         lib.heisd_skip_decide.argtypes = [c_void_p, c_void_p, c_void_p, c_int32, c_int32, c_void_p, c_void_p, c_void_p,
                                           c_void_p, c_void_p]
         lib.heisd_skip_decide.restype = ctypes.c_int
+        lib.heisd_retrieve_workspace_bytes.argtypes = [ctypes.c_int64, c_int32, c_int32]
+        lib.heisd_retrieve_workspace_bytes.restype = c_size_t
+        lib.heisd_retrieve_topk.argtypes = [c_void_p, ctypes.c_int64, c_int32, c_void_p, c_int32, c_int32, c_void_p,
+                                            c_int32, c_void_p, c_void_p, c_void_p, c_void_p, c_size_t, c_void_p]
+        lib.heisd_retrieve_topk.restype = ctypes.c_int
         lib.heisd_free.argtypes = [c_void_p]
         lib.heisd_free.restype = None
         lib.heisd_verify_profile_enable.argtypes = [c_void_p, ctypes.c_int]
@@ -152,6 +157,17 @@ def heisd_skip_offline(feat, n, d, T, S, work, min_s, o_dist, stream) -> int:
 
 def heisd_skip_decide(feat_prev, feat_last, dist, batch, d, min_s, o_dist, skip_mask, similarity, stream) -> int:
     return load().heisd_skip_decide(feat_prev, feat_last, dist, batch, d, min_s, o_dist, skip_mask, similarity, stream)
+
+
+def heisd_retrieve_workspace_bytes(n_vectors, batch, K) -> int:
+    return int(load().heisd_retrieve_workspace_bytes(n_vectors, batch, K))
+
+
+def heisd_retrieve_topk(db, n_vectors, d, queries, batch, K, payload, payload_len, top_index, top_score, top_payload,
+                        workspace, workspace_bytes, stream) -> int:
+    """All array arguments are integer device addresses (0/None = NULL)."""
+    return load().heisd_retrieve_topk(db, n_vectors, d, queries, batch, K, payload, payload_len, top_index, top_score,
+                                      top_payload, workspace, workspace_bytes, stream)
 
 
 def heisd_free(ctx) -> None:

@@ -18,6 +18,7 @@
 #include "heisd_gemm.h"
 #include "heisd_misc.h"
 #include "heisd_skip.h"
+#include "heisd_retrieve.h"
 
 using namespace heisd;
 
@@ -1279,6 +1280,95 @@ extern "C" int heisd_skip_decide(const float *feat_prev, const float *feat_last,
                                                                               skip_mask, similarity);
   const hipError_t e = hipGetLastError();
   if (e != hipSuccess) return fail(nullptr, HEISD_EHIP, "skip_decide: %s", hipGetErrorString(e));
+  g_init_err[0] = 0;
+  return HEISD_OK;
+}
+
+// ---- retrieval: exact cosine Top-K over the embedding database (App. B) -------------------------
+
+struct RetrieveLayout {
+  size_t scores, cand_val, cand_idx, total;
+  int n_chunks;
+  long long ld_scores;
+  RetrieveLayout(long long N, int batch, int K) {
+    n_chunks = (int)((N + kTopChunk - 1) / kTopChunk);
+    ld_scores = (N + 63) / 64 * 64;
+    size_t off = 0;
+    scores = off;   off += align256((size_t)batch * (size_t)ld_scores * sizeof(float));
+    cand_val = off; off += align256((size_t)batch * n_chunks * K * sizeof(float));
+    cand_idx = off; off += align256((size_t)batch * n_chunks * K * sizeof(int));
+    total = off;
+  }
+};
+
+static bool retrieve_args_ok(int64_t N, int32_t batch, int32_t K) {
+  return N >= 1 && N <= 0x7FFFFFFFLL && batch >= 1 && batch <= 1024 && K >= 1 && K <= kTopMaxK;
+}
+
+extern "C" size_t heisd_retrieve_workspace_bytes(int64_t n_vectors, int32_t batch, int32_t K) {
+  if (!retrieve_args_ok(n_vectors, batch, K)) return 0;
+  return RetrieveLayout(n_vectors, batch, K).total;
+}
+
+template <int NQ>
+static hipError_t retrieve_scores_launch(const uint16_t *db, long long N, int d, const float *q, float *scores,
+                                         long long ld, int n_cu, hipStream_t st) {
+  const int lds = NQ * d * (int)sizeof(float);
+  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&retrieve_scores<NQ>),
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+  if (e != hipSuccess) return e;
+  const long long pairs = (N + 1) / 2, want = (pairs + kScanThreads / 64 - 1) / (kScanThreads / 64);
+  const long long resident = (NQ <= 2 ? 4LL : 2LL) * n_cu;      // workgroups a compute unit holds at this LDS size
+  const int grid = (int)(want < resident ? want : resident);
+  retrieve_scores<NQ><<<dim3(grid), dim3(kScanThreads), lds, st>>>(db, N, d, q, scores, ld);
+  return hipGetLastError();
+}
+
+extern "C" int heisd_retrieve_topk(const void *db, int64_t n_vectors, int32_t d, const float *queries, int32_t batch,
+                                   int32_t K, const int32_t *payload, int32_t payload_len, int32_t *top_index,
+                                   float *top_score, int32_t *top_payload, void *workspace, size_t workspace_bytes,
+                                   void *stream) {
+  if (!db || !queries || !top_index || !top_score || !workspace)
+    return fail(nullptr, HEISD_EINVAL, "retrieve_topk: NULL required pointer");
+  if (!retrieve_args_ok(n_vectors, batch, K) || d < 4 || d % 4 || d > 8192)
+    return fail(nullptr, HEISD_EINVAL, "retrieve_topk: n_vectors=%lld batch=%d K=%d d=%d outside the supported range",
+                (long long)n_vectors, batch, K, d);
+  if ((payload != nullptr) != (top_payload != nullptr) || (payload && payload_len < 1))
+    return fail(nullptr, HEISD_EINVAL, "retrieve_topk: payload and top_payload go together, with payload_len >= 1");
+  if (((uintptr_t)db & 7) || !aligned16(queries) || ((uintptr_t)workspace & 255))
+    return fail(nullptr, HEISD_EINVAL, "retrieve_topk: misaligned pointer");
+  const RetrieveLayout lay(n_vectors, batch, K);
+  if (workspace_bytes < lay.total)
+    return fail(nullptr, HEISD_ENOMEM, "retrieve_topk: workspace %zu bytes < %zu needed", workspace_bytes, lay.total);
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  unsigned char *base = static_cast<unsigned char *>(workspace);
+  float *scores = reinterpret_cast<float *>(base + lay.scores);
+  float *cand_val = reinterpret_cast<float *>(base + lay.cand_val);
+  int *cand_idx = reinterpret_cast<int *>(base + lay.cand_idx);
+  int n_cu = 256, dev = 0;
+  hipDeviceProp_t prop;
+  if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess && prop.multiProcessorCount > 0)
+    n_cu = prop.multiProcessorCount;
+  (void)hipGetLastError();
+  const uint16_t *dbp = static_cast<const uint16_t *>(db);
+  hipError_t e = hipSuccess;
+  for (int q0 = 0; q0 < batch && e == hipSuccess; q0 += 4) {       // the database is streamed once per four queries
+    const int nq = batch - q0 < 4 ? batch - q0 : 4;
+    const float *qp = queries + (size_t)q0 * d;
+    float *sp = scores + (size_t)q0 * lay.ld_scores;
+    if (nq == 1) e = retrieve_scores_launch<1>(dbp, n_vectors, d, qp, sp, lay.ld_scores, n_cu, st);
+    else if (nq == 2) e = retrieve_scores_launch<2>(dbp, n_vectors, d, qp, sp, lay.ld_scores, n_cu, st);
+    else if (nq == 3) e = retrieve_scores_launch<3>(dbp, n_vectors, d, qp, sp, lay.ld_scores, n_cu, st);
+    else e = retrieve_scores_launch<4>(dbp, n_vectors, d, qp, sp, lay.ld_scores, n_cu, st);
+  }
+  if (e == hipSuccess) {
+    retrieve_top_chunks<<<dim3(lay.n_chunks, batch), dim3(256), 0, st>>>(scores, lay.ld_scores, n_vectors, K, cand_val,
+                                                                        cand_idx, lay.n_chunks);
+    retrieve_top_merge<<<dim3(batch), dim3(256), 0, st>>>(cand_val, cand_idx, lay.n_chunks * K, K, top_score, top_index,
+                                                         payload, payload_len, top_payload);
+    e = hipGetLastError();
+  }
+  if (e != hipSuccess) return fail(nullptr, HEISD_EHIP, "retrieve_topk: %s", hipGetErrorString(e));
   g_init_err[0] = 0;
   return HEISD_OK;
 }

@@ -72,8 +72,12 @@ WORKLOADS: Dict[str, Workload] = {
 def f32_to_bf16_bits(a: np.ndarray) -> np.ndarray:
     """Round-to-nearest-even fp32 -> bf16 bit patterns (storage format conversion only)."""
     u = np.ascontiguousarray(a, dtype=np.float32).view(np.uint32)
-    r = u + np.uint32(0x7FFF) + ((u >> np.uint32(16)) & np.uint32(1))
-    return (r >> np.uint32(16)).astype(np.uint16)
+    r = u >> np.uint32(16)
+    r &= np.uint32(1)
+    r += np.uint32(0x7FFF)
+    r += u
+    r >>= np.uint32(16)
+    return r.astype(np.uint16)
 
 
 def bf16_bits_to_f32(b: np.ndarray) -> np.ndarray:
@@ -158,6 +162,31 @@ def make_candidate_offsets(wl: Workload, n_candidates: int, p: float) -> np.ndar
         mag = np.floor(np.log(u) / np.log1p(-p)).astype(np.int64)
         out[:, r] = (mag * np.where(s < 0.5, -1, 1)).astype(np.int32).reshape(wl.batch, wl.K)
     return out
+
+
+def make_retrieval_db(n_vectors: int, dim: int, seed: int = 0, payload_len: int = 7, n_bins: int = 256):
+    """Stand-in for the retrieval database: n_vectors L2-normalised N(0,1) directions stored as bf16 bit
+    patterns u16 [n_vectors, dim], and a payload of action bins i32 [n_vectors, payload_len] (uniform)."""
+    db = np.empty((n_vectors, dim), np.uint16)
+    step = max(1, (1 << 26) // dim)
+    for s in range(0, n_vectors, step):
+        n = min(step, n_vectors - s)
+        v = rng.normal_f32(seed, "retrieval.db.%d" % s, n * dim).reshape(n, dim)
+        v /= np.sqrt(np.einsum("ij,ij->i", v, v, dtype=np.float64)).astype(np.float32)[:, None]
+        db[s:s + n] = f32_to_bf16_bits(v)
+    payload = rng.uniform_i32(seed, "retrieval.payload", n_vectors * payload_len, 0, n_bins).reshape(n_vectors, payload_len)
+    return db, payload
+
+
+def make_retrieval_queries(db_bits: np.ndarray, batch: int, noise: float, seed: int = 0) -> np.ndarray:
+    """Queries f32 [batch, dim]: a stored vector (rows spread over the database) plus N(0, noise^2/dim)
+    per component, L2-normalised - an observation close to one seen before."""
+    n, dim = db_bits.shape
+    rows = (np.arange(batch, dtype=np.int64) * 7919 + 13) % n
+    q = bf16_bits_to_f32(db_bits[rows]).astype(np.float64)
+    q += noise / np.sqrt(dim) * rng.normal_f64(seed, "retrieval.noise", batch * dim).reshape(batch, dim)
+    q /= np.sqrt((q * q).sum(axis=1, keepdims=True))
+    return q.astype(np.float32)
 
 
 def make_skip_mask(wl: Workload) -> np.ndarray:
