@@ -745,7 +745,10 @@ static hipError_t bat_prepare_mc() {
 static hipError_t bat_prepare() {
   hipError_t e;
   if ((e = bat_prepare_mc<2>()) != hipSuccess) return e;
+  if ((e = bat_prepare_mc<3>()) != hipSuccess) return e;
   if ((e = bat_prepare_mc<4>()) != hipSuccess) return e;
+  if ((e = bat_prepare_mc<5>()) != hipSuccess) return e;
+  if ((e = bat_prepare_mc<6>()) != hipSuccess) return e;
   if ((e = bat_prepare_mc<7>()) != hipSuccess) return e;
   if ((e = bat_prepare_mc<8>()) != hipSuccess) return e;
   return bat_ns_prepare();
@@ -802,10 +805,15 @@ static void bat_launch(BatGemm g, int n_cu, hipStream_t st) {
   const int need = (CT + MW - 1) / MW < 8 ? (CT + MW - 1) / MW : 8;
   g.MW = MW;
   const int grid = g.n_units < n_cu ? g.n_units : n_cu;
-  if (need <= 2) bat_launch_mc<2>(g, grid, st);
-  else if (need <= 4) bat_launch_mc<4>(g, grid, st);
-  else if (need <= 7) bat_launch_mc<7>(g, grid, st);
-  else bat_launch_mc<8>(g, grid, st);
+  switch (need) {                      // a wave group holds exactly the column tiles it needs
+    case 1: case 2: bat_launch_mc<2>(g, grid, st); break;
+    case 3: bat_launch_mc<3>(g, grid, st); break;
+    case 4: bat_launch_mc<4>(g, grid, st); break;
+    case 5: bat_launch_mc<5>(g, grid, st); break;
+    case 6: bat_launch_mc<6>(g, grid, st); break;
+    case 7: bat_launch_mc<7>(g, grid, st); break;
+    default: bat_launch_mc<8>(g, grid, st); break;
+  }
 }
 
 static void batch_forward(heisd_verify_ctx *ctx, const heisd_kv_desc *kv, const int32_t *draft_tokens, int K,

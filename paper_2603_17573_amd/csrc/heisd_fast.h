@@ -182,11 +182,28 @@ constexpr size_t kFastRedBytes = (size_t)kFastWaves * kMaxT * 64 * 16;
 constexpr size_t kFastLds = kFastRedBytes + 16 * sizeof(float);
 
 // 1/rms of each row from the producer's partial sums (fixed order: lanes stride, butterfly sum);
-// wave w computes row w.  Must be followed by a __syncthreads before scale_s is read.
-__device__ __forceinline__ void fast_row_scales(const FastGemm &g, float *scale_s, int wave, int lane) {
+// wave w computes row w.  In two halves: the partial sums are REQUESTED first thing in a phase,
+// ahead of the activation and weight fragments, and only summed after the first pass of matrix
+// products - a loop that waits for each partial sum in turn costs one memory round trip per 64 tiles
+// before the first weight is even requested (four round trips, about 3 us, at d_model = 4096).
+struct SsqPre {
+  float v[4];
+};
+__device__ __forceinline__ SsqPre fast_row_scales_issue(const FastGemm &g, int wave, int lane) {
+  SsqPre s;
+#pragma unroll
+  for (int u = 0; u < 4; ++u) {
+    const int p = lane + u * kWave;
+    s.v[u] = (g.ssq && p < g.n_ssq) ? g.ssq[(size_t)p * kSsqStride + wave] : 0.f;
+  }
+  return s;
+}
+// Must be followed by a workgroup barrier before scale_s is read.
+__device__ __forceinline__ void fast_row_scales_finish(const FastGemm &g, const SsqPre &s, float *scale_s, int wave,
+                                                       int lane) {
   if (g.ssq) {
-    float t = 0.f;
-    for (int p = lane; p < g.n_ssq; p += kWave) t += g.ssq[(size_t)p * kSsqStride + wave];
+    float t = ((s.v[0] + s.v[1]) + s.v[2]) + s.v[3];
+    for (int p = lane + 4 * kWave; p < g.n_ssq; p += kWave) t += g.ssq[(size_t)p * kSsqStride + wave];   // d_model > 4096 only
     t = wave_sum(t);
     if (lane == 0) scale_s[wave] = rsqrtf(t / (float)g.Kd + g.eps);
   } else if (lane == 0) {
@@ -297,11 +314,11 @@ __device__ __forceinline__ void fast_gemm_phase(const FastGemm &g, int wg, int n
   const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int lr = lane & 15, lg = lane >> 4;
   const int my_entries = fast_my_entries(g, wg, nwg);
-  fast_row_scales(g, scale_s, wave, lane);
   if (my_entries == 0) {
     lds_barrier();
     return;
   }
+  const SsqPre sp = fast_row_scales_issue(g, wave, lane);
   const int ks0 = wave * fast_ksw(g.Kd), ns = fast_steps(g.Kd, wave);
   Frag16 Bf;
 #pragma unroll
@@ -332,6 +349,7 @@ __device__ __forceinline__ void fast_gemm_phase(const FastGemm &g, int wg, int n
       }
     }
     lds_barrier();
+    if (e0 == 0) fast_row_scales_finish(g, sp, scale_s, wave, lane);
 #pragma unroll
     for (int t = 0; t < kMaxT; ++t)
       *reinterpret_cast<f32x4 *>(red + ((size_t)(wave * kMaxT + t) * 64 + lane) * 4) = acc[t];
@@ -351,11 +369,11 @@ __device__ __forceinline__ void fast_gemm_stream_phase(const FastGemm &g, int wg
   const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int lr = lane & 15, lg = lane >> 4;
   const int my_entries = fast_my_entries(g, wg, nwg);
-  fast_row_scales(g, scale_s, wave, lane);
   if (my_entries == 0) {
     lds_barrier();
     return;
   }
+  const SsqPre sp = fast_row_scales_issue(g, wave, lane);
   const int ksw = fast_ksw(g.Kd), ks0 = wave * ksw, ns = fast_steps(g.Kd, wave);
   // Steps past this wave's share are multiplied with zero records; their weight fragment is read
   // from the wave's own last step (a line it has just fetched), not from the next wave's share.
@@ -388,6 +406,7 @@ __device__ __forceinline__ void fast_gemm_stream_phase(const FastGemm &g, int wg
       }
     }
     lds_barrier();
+    if (e == 0) fast_row_scales_finish(g, sp, scale_s, wave, lane);
     *reinterpret_cast<f32x4 *>(red + ((size_t)(wave * kMaxT) * 64 + lane) * 4) = acc;
     lds_barrier();
     fast_epilogue(g, wg, nwg, e, 1, red, scale_s, ep);
