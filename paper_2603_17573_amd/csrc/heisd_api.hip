@@ -229,8 +229,11 @@ static void gemm_launch(GemmArgs a, int M, int epi, hipStream_t st) {
 
 // ---- any-M attention: workgroup size by the number of (episode, head) pairs ----------------
 
+constexpr size_t kLdsPerWorkgroup = 160 * 1024;
+
 template <int HD, int THREADS, bool TREE, bool SPLIT>
 static hipError_t attn_prepare_one(int cap) {
+  if (attn_lds_bytes(HD, cap, THREADS / 64) > kLdsPerWorkgroup) return hipSuccess;   // variant not used at this capacity
   return hipFuncSetAttribute(reinterpret_cast<const void *>(&attn_verify<HD, THREADS, TREE, SPLIT>),
                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)attn_lds_bytes(HD, cap, THREADS / 64));
 }
@@ -253,7 +256,8 @@ static hipError_t attn_prepare(int hd, int cap) {
 template <int HD, bool TREE>
 static void attn_launch_mode(const AttnArgs &a, int H, int batch, int cap, int n_cu, hipStream_t st) {
   const int nqb = (a.K + kAttnQB - 1) / kAttnQB;
-  const bool big = H * batch * nqb <= n_cu;          // at most one workgroup per compute unit: 512 threads each hide more latency
+  // at most one workgroup per compute unit: 512 threads each hide more latency (if their LDS fits)
+  const bool big = H * batch * nqb <= n_cu && attn_lds_bytes(HD, cap, 8) <= kLdsPerWorkgroup;
   if (nqb == 1) {
     const dim3 grid(H, batch);
     if (big) attn_verify<HD, 512, TREE, false><<<grid, dim3(512), attn_lds_bytes(HD, cap, 8), st>>>(a);

@@ -168,3 +168,25 @@ def test_step_argument_errors_enqueue_nothing():
     torch.cuda.synchronize()
     assert all(v in (0, 3, 6, 7) for v in acc.tolist())
     ver.close()
+
+
+@pytest.mark.parametrize("path", [0, 4])
+def test_largest_kv_capacity(path):
+    """kv_capacity 4096 (the largest the library takes) with a prefix that fills it: the attention
+    kernels' LDS score rows are at their longest."""
+    from gpu_harness import run_gpu_step, compare_with_oracle
+    _need_gpu()
+    cap, K = 4096, 7
+    wl = synth.Workload("cap4096", SMALL64, 0, cap - K, SMALL64.bin_base, batch=2, K=K, seed=61)
+    sh = wl.shape
+    weights = synth.make_weights(sh, wl.seed)
+    om = oracle_model(sh, weights)
+    k0, v0, f0 = zip(*[synth.make_prefix_kv_direct(wl, e, cap) for e in range(2)])
+    kb, vb = np.stack(k0, axis=1), np.stack(v0, axis=1)
+    plen, first = np.array([cap - K, 1234], np.int32), np.array(f0, np.int32)
+    drafts = (sh.bin_base + synth.make_drafts_uniform(wl)).astype(np.int32)
+    rule = oracle.AcceptRule(2, 6)
+    ref = oracle.verify_step(om, kb, vb, plen, first, drafts, rule)
+    got = run_gpu_step(sh, weights, kb, vb, plen, first, drafts, rule, None, path=path)
+    stats = compare_with_oracle(got, ref, drafts, rule, sh, kb, vb, plen, None)
+    print("cap 4096 path", path, stats, flush=True)
