@@ -100,6 +100,7 @@ struct BatScratch {
     const size_t M = (size_t)d->max_batch * d->max_k;
     CTS = (int)((M + 7) / 8);
     if (CTS < 8) CTS = 8;
+    if (CTS >= kWdCols) CTS = (CTS + kWdCols - 1) / kWdCols * kWdCols;     // the wide kernel reads whole blocks of column tiles
     const size_t kd = 2 * (((size_t)d->d_model + 31) / 32) + 2, kf = 2 * (((size_t)d->d_ffn + 31) / 32) + 2;   // + a zero k-step
     size_t off = 0;
     rec_x = off;   off += kd * CTS * 512;
@@ -755,6 +756,12 @@ static hipError_t bat_prepare() {
   if ((e = bat_prepare_mc<6>()) != hipSuccess) return e;
   if ((e = bat_prepare_mc<7>()) != hipSuccess) return e;
   if ((e = bat_prepare_mc<8>()) != hipSuccess) return e;
+  if ((e = hipFuncSetAttribute(reinterpret_cast<const void *>(&bat_gemm_wide<4>), hipFuncAttributeMaxDynamicSharedMemorySize,
+                               (int)kBatWideLds)) != hipSuccess)
+    return e;
+  if ((e = hipFuncSetAttribute(reinterpret_cast<const void *>(&bat_gemm_wide<2>), hipFuncAttributeMaxDynamicSharedMemorySize,
+                               (int)kBatWideLds)) != hipSuccess)
+    return e;
   return bat_ns_prepare();
 }
 
@@ -797,12 +804,27 @@ static void bat_ns_launch_mc(BatGemm g, int n_cu, hipStream_t st) {
   else bat_gemm_ns<MC, 2, 2><<<grid, block, bat_ns_lds_bytes<MC>(), st>>>(g);
 }
 
+constexpr int kWideMinCT = 24;       // column tiles (8 rows each) from which bat_gemm_wide takes over
+
 // Wave arrangement for CT column tiles: MW groups of MC tiles (MC from the compiled set).
 static void bat_launch(BatGemm g, int n_cu, hipStream_t st) {
   const int CT = g.CT;
   if (CT <= 8 && g.epi == FEPI_SWIGLU) {
     if (CT <= 4) bat_ns_launch_mc<4>(g, n_cu, st);
     else bat_ns_launch_mc<8>(g, n_cu, st);
+    return;
+  }
+  if (CT >= kWideMinCT) {                     // two-dimensional tiles, B fragments shared through LDS
+    const int n_blk = (CT + kWdCols - 1) / kWdCols;
+    const int per_unit = g.epi == FEPI_SWIGLU ? 2 : 1;        // weight tiles per unit
+    auto groups = [&](int nt) { const int upg = kWdNW * nt / per_unit; return (g.n_units + upg - 1) / upg; };
+    // 4 or 2 weight tiles per wave: whichever needs less time in whole rounds of workgroups over the
+    // compute units; a workgroup of the 4-tile variant takes about 1.55 times as long (measured).
+    auto cost = [&](int nt) { return (double)((groups(nt) * n_blk + n_cu - 1) / n_cu) * (nt == 4 ? 1.55 : 1.0); };
+    const int nt = cost(4) <= cost(2) ? 4 : 2;
+    const int grid = (groups(nt) + 7) / 8 * 8 * n_blk;
+    if (nt == 4) bat_gemm_wide<4><<<dim3(grid), dim3(kBatThreads), kBatWideLds, st>>>(g, n_blk);
+    else bat_gemm_wide<2><<<dim3(grid), dim3(kBatThreads), kBatWideLds, st>>>(g, n_blk);
     return;
   }
   const int MW = CT <= 8 ? 1 : (CT <= 16 ? 2 : (CT <= 32 ? 4 : 8));

@@ -68,13 +68,32 @@ __device__ __forceinline__ void bat_tile(const BatGemm &g, int wg, int nwg, int 
 
 // The projection's epilogue for one output pair: row m = 8*ct + jm, columns 2*c2, 2*c2+1 of unit
 // `unit`; (s0, s1) = the sums, (u0, u1) = the sums of the up tile (SwiGLU).  The 8 lanes c2 = 0..7 of
-// a row must call this together (they add up the row's partial sum of squares).
-__device__ __forceinline__ void bat_emit(const BatGemm &g, int unit, int ct, int jm, int c2, float s0, float s1, float u0,
-                                         float u1) {
+// a row must call this together (they add up the row's partial sum of squares).  In two halves, so
+// that a caller with many pairs can request everything they read before the first store (a load
+// after a store to memory the compiler cannot tell apart waits for that store).
+struct EmitPre {
+  float sc;       // 1/rms of the row (1 if the projection's input is not normalised)
+  float2 xo;      // RESID_NORM: the residual stream's old values
+  float2 gn;      // RESID_NORM: the next norm's gains
+};
+__device__ __forceinline__ EmitPre bat_emit_load(const BatGemm &g, int unit, int ct, int jm, int c2) {
+  const int i = 2 * c2, m = ct * 8 + jm;
+  EmitPre p;
+  p.sc = g.inv_rms ? g.inv_rms[m] : 1.0f;
+  p.xo = make_float2(0.f, 0.f);
+  p.gn = make_float2(0.f, 0.f);
+  if (g.epi == FEPI_RESID_NORM) {
+    if (m < g.M) p.xo = *reinterpret_cast<const float2 *>(g.out + (size_t)m * g.ldo + unit * 16 + i);
+    p.gn = *reinterpret_cast<const float2 *>(g.next_gain + unit * 16 + i);
+  }
+  return p;
+}
+__device__ __forceinline__ void bat_emit_apply(const BatGemm &g, int unit, int ct, int jm, int c2, float s0, float s1,
+                                               float u0, float u1, const EmitPre &pre) {
   const int i = 2 * c2;
   const int m = ct * 8 + jm;
   const bool live = m < g.M;
-  const float sc = g.inv_rms ? g.inv_rms[m] : 1.0f;
+  const float sc = pre.sc;
   if (g.epi == FEPI_STORE_ROWS) {
     if (live) *reinterpret_cast<float2 *>(g.out + (size_t)m * g.ldo + unit * 16 + i) = make_float2(s0 * sc, s1 * sc);
     return;
@@ -88,20 +107,17 @@ __device__ __forceinline__ void bat_emit(const BatGemm &g, int unit, int ct, int
     }
   } else {
     if (live) {
-      float *xp = g.out + (size_t)m * g.ldo + unit * 16 + i;
-      const float2 xo = *reinterpret_cast<const float2 *>(xp);
-      a0 = xo.x + s0 * sc;
-      a1 = xo.y + s1 * sc;
-      *reinterpret_cast<float2 *>(xp) = make_float2(a0, a1);
+      a0 = pre.xo.x + s0 * sc;
+      a1 = pre.xo.y + s1 * sc;
+      *reinterpret_cast<float2 *>(g.out + (size_t)m * g.ldo + unit * 16 + i) = make_float2(a0, a1);
     }
     float q = a0 * a0 + a1 * a1;          // over the tile's 16 columns: 8 adjacent lanes
     q += __shfl_xor(q, 4, kWave);
     q += __shfl_xor(q, 2, kWave);
     q += __shfl_xor(q, 1, kWave);
     if (c2 == 0) g.ssq_out[(size_t)unit * (g.CTS * 8) + m] = q;
-    const float2 gn = *reinterpret_cast<const float2 *>(g.next_gain + unit * 16 + i);
-    a0 *= gn.x;
-    a1 *= gn.y;
+    a0 *= pre.gn.x;
+    a1 *= pre.gn.y;
   }
   uint32_t h0, l0, h1, l1;
   split_bf16(a0, h0, l0);
@@ -109,6 +125,11 @@ __device__ __forceinline__ void bat_emit(const BatGemm &g, int unit, int ct, int
   uint32_t *rec = reinterpret_cast<uint32_t *>(g.o_planes + ((size_t)unit * g.CTS + ct) * 256);
   rec[(jm * 16 + i) / 2] = h0 | (h1 << 16);
   rec[((jm + 8) * 16 + i) / 2] = l0 | (l1 << 16);
+}
+__device__ __forceinline__ void bat_emit(const BatGemm &g, int unit, int ct, int jm, int c2, float s0, float s1, float u0,
+                                         float u1) {
+  const EmitPre pre = bat_emit_load(g, unit, ct, jm, c2);
+  bat_emit_apply(g, unit, ct, jm, c2, s0, s1, u0, u1, pre);
 }
 
 // First column tile of wave group mw in the block that starts at cb: groups that would run past
@@ -409,6 +430,171 @@ __global__ __launch_bounds__(kBatThreads) __attribute__((amdgpu_waves_per_eu(2, 
       }
     }
     lds_barrier();                                    // the buffers are refilled by the next group
+  }
+}
+
+// ---- M >= 128 rows: two-dimensional tiles, activation fragments shared through LDS -----------------
+// With many rows bat_gemm is bound by the vector-memory path of a compute unit: every wave fetches its
+// own activation fragments (8 KB per k-step against 3 KB of weights) and nothing is shared.  Here a
+// workgroup owns 12 weight tiles x 16 column tiles (192 weight rows x 128 activation rows): six
+// computing waves arranged 3 x 2, each 4 weight tiles x 8 column tiles (32 accumulator tiles), read
+// their B fragments from LDS, where two filling waves put every k-step's 16 column tiles once with
+// direct global -> LDS transfers: a ring of four chunks of 2 k-steps, three of them in flight (one
+// chunk ahead is not enough: a transfer's round trip is about as long as two chunks of products).  The weights still go
+// straight from global memory into the MFMA A layout.  Workgroups are numbered so that the row blocks
+// of one weight group run next to each other on one XCD and find its weights in that L2.
+constexpr int kWdMC = 8, kWdNW = 3, kWdMW = 2;
+constexpr int kWdS = 2, kWdNB = 4;                       // k-steps per chunk of B fragments, chunks resident in LDS
+constexpr int kWdRA = 4;                                 // k-steps of weight fragments requested ahead
+constexpr int kWdCompute = kWdNW * kWdMW;                // 6 of the 8 waves
+constexpr int kWdCols = kWdMW * kWdMC;                   // 16 column tiles per workgroup
+constexpr size_t kBatWideLds = (size_t)kWdNB * kWdS * kWdCols * 1024;  // 128 KB: four chunks of B fragments
+
+// NT: weight tiles per computing wave, 4 or 2 (2: half as many rows per workgroup, for projections with few tiles).
+template <int NT>
+__global__ __launch_bounds__(kBatThreads) __attribute__((amdgpu_waves_per_eu(2, 2))) void bat_gemm_wide(BatGemm g, int n_blk) {
+  constexpr int MC = kWdMC, S = kWdS;
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  const uint32_t smem_lds = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char *)smem;
+  const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int lr = lane & 15, lg = lane >> 4;
+  const bool filler = wave >= kWdCompute;
+  const int nwv = wave % kWdNW, mwv = filler ? 0 : wave / kWdNW;
+  const bool swiglu = g.epi == FEPI_SWIGLU;
+  const int upg = swiglu ? kWdNW * (NT / 2) : kWdNW * NT;          // units (tiles, or gate/up pairs) per workgroup
+  const int n_groups = (g.n_units + upg - 1) / upg;
+  // workgroup -> (weight group, row block): the row blocks of a group differ by 8 in the launch order
+  const int id = blockIdx.x, q = id >> 3;
+  const int blk = q % n_blk, grp = (q / n_blk) * 8 + (id & 7);
+  if (grp >= n_groups) return;
+  const int total = (g.Kd + 31) / 32;
+  const int n_chunks = (total + S - 1) / S;
+  const size_t bstep = (size_t)2 * g.CTS * 256;
+  // units of this wave's NT tiles (SwiGLU: tile t is matrix t & 1 of pair t >> 1)
+  int unit_of[NT];
+  const uint16_t *wf[NT];
+#pragma unroll
+  for (int t = 0; t < NT; ++t) {
+    const int u = swiglu ? grp * upg + nwv * (NT / 2) + (t >> 1) : grp * upg + nwv * NT + t;
+    unit_of[t] = u;
+    const int ucl = u < g.n_units ? u : g.n_units - 1;               // surplus tiles multiply a valid one, results dropped
+    const uint16_t *wbase;
+    int wrow0;
+    if (swiglu) {
+      wbase = (t & 1) ? g.w[1] : g.w[0];
+      wrow0 = ucl * 16;
+    } else {
+      const int seg = ucl / g.seg_tiles;
+      wbase = seg == 0 ? g.w[0] : (seg == 1 ? g.w[1] : g.w[2]);
+      wrow0 = (ucl - seg * g.seg_tiles) * 16;
+    }
+    wf[t] = fast_wfrag(wbase, wrow0, g.Kd, lane);
+  }
+  f32x4 acc[NT][MC];
+#pragma unroll
+  for (int t = 0; t < NT; ++t)
+#pragma unroll
+    for (int c = 0; c < MC; ++c) acc[t][c] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+  if (filler) {
+    // this lane's piece of the B fragment of (k-step ks, column tile blk*16 + ct): bsrc + ks*bstep + ct*256
+    const uint16_t *bsrc = g.b + ((size_t)(lg >> 1) * g.CTS + (size_t)blk * kWdCols) * 256 + lr * 16 + (lg & 1) * 8;
+    constexpr int NF = kBatWaves - kWdCompute;                    // 2 filling waves
+    constexpr int OPS = S * kWdCols / NF;                         // transfers per wave and chunk
+    // Chunks past the end are transferred too (from the all-zero k-step), so that the count of
+    // transfers in flight is the same at every wait.
+    auto fill = [&](int c) __attribute__((always_inline)) {
+      const int buf = c % kWdNB;
+#pragma unroll
+      for (int o = 0; o < OPS; ++o) {
+        const int op = o * NF + (wave - kWdCompute);
+        const int slot = op / kWdCols, ct = op % kWdCols;
+        const int ks = c * S + slot < total ? c * S + slot : total;
+        lds_dma16(bsrc + (size_t)ks * bstep + ct * 256,
+                  __builtin_amdgcn_readfirstlane(smem_lds + (uint32_t)(((buf * S + slot) * kWdCols + ct) * 1024)));
+      }
+    };
+#pragma unroll
+    for (int c = 0; c < kWdNB - 1; ++c) fill(c);
+    wait_vmcnt<(kWdNB - 2) * OPS>();                              // chunk 0 has arrived
+    lds_barrier();
+    for (int c = 0; c < n_chunks; ++c) {
+      fill(c + kWdNB - 1);                                        // into the buffer chunk c-1 was read from
+      wait_vmcnt<(kWdNB - 2) * OPS>();                            // chunk c+1 has arrived
+      lds_barrier();
+    }
+    wait_vmcnt<0>();                                              // nothing may land in LDS after the buffers change hands
+  } else {
+    u32x4 A[kWdRA][NT];
+#pragma unroll
+    for (int u = 0; u < kWdRA; ++u)
+#pragma unroll
+      for (int t = 0; t < NT; ++t) A[u][t] = fast_ld_a(wf[t], g.Kd, u);
+    lds_barrier();                                    // chunk 0 is in LDS
+    constexpr int CPR = kWdRA / S;                    // chunks per revolution of the weight ring
+    for (int c0 = 0; c0 < n_chunks; c0 += CPR) {
+#pragma unroll
+      for (int cc = 0; cc < CPR; ++cc) {
+        const int c = c0 + cc;
+        if (c < n_chunks) {                           // uniform over the workgroup
+          const unsigned char *bl = smem + ((size_t)((c % kWdNB) * S * kWdCols + mwv * MC)) * 1024 + lane * 16;
+#pragma unroll
+          for (int s = 0; s < S; ++s) {
+            const int u = cc * S + s;                 // ring slot of k-step c*S + s
+            u32x4 Bf[MC];
+#pragma unroll
+            for (int ct = 0; ct < MC; ++ct) Bf[ct] = *reinterpret_cast<const u32x4 *>(bl + (size_t)(s * kWdCols + ct) * 1024);
+#pragma unroll
+            for (int t = 0; t < NT; ++t) {
+#pragma unroll
+              for (int ct = 0; ct < MC; ++ct) acc[t][ct] = fast_mfma(A[u][t], Bf[ct], acc[t][ct]);
+              A[u][t] = fast_ld_a(wf[t], g.Kd, c * S + s + kWdRA);   // clamped into the matrix; met by zero records
+            }
+          }
+          lds_barrier();                              // chunk c+1 complete in LDS; everybody is done reading chunk c
+        }
+      }
+    }
+  }
+  lds_barrier();                                      // the B buffers are free: every wave turns its own tiles around in them
+  if (filler) return;
+  float *mine = reinterpret_cast<float *>(smem + (size_t)wave * (2 * MC * 1024));
+  const int c2 = lane & 7, jm = lane >> 3, i = 2 * c2;
+  const int l_hi = (i >> 2) * 16 + jm, r = i & 3;
+#pragma unroll
+  for (int h = 0; h < NT / 2; ++h) {                  // two tiles at a time: 16 KB of LDS per wave
+#pragma unroll
+    for (int tt = 0; tt < 2; ++tt)
+#pragma unroll
+      for (int ct = 0; ct < MC; ++ct)
+        *reinterpret_cast<f32x4 *>(mine + ((size_t)(tt * MC + ct) * 64 + lane) * 4) = acc[2 * h + tt][ct];
+#pragma unroll
+    for (int tt = 0; tt < 2; ++tt) {
+      if (swiglu && tt == 1) break;                   // a pair is emitted once, from its gate tile
+      const int unit = unit_of[2 * h + tt];
+      if (unit >= g.n_units) continue;                // uniform over the wave
+      const int ctg0 = blk * kWdCols + mwv * MC;
+      EmitPre pre[MC];                                // everything the tile's 8 column tiles read, requested before the first store
+#pragma unroll
+      for (int ct = 0; ct < MC; ++ct) pre[ct] = bat_emit_load(g, unit, min(ctg0 + ct, g.CT - 1), jm, c2);
+#pragma unroll
+      for (int ct = 0; ct < MC; ++ct) {
+        const int ctg = ctg0 + ct;
+        if (ctg >= g.CT) continue;                    // uniform over the wave
+        const float *p = mine + ((size_t)(tt * MC + ct) * 64) * 4;
+        const float2 a = *reinterpret_cast<const float2 *>(p + l_hi * 4 + r);
+        const float2 b = *reinterpret_cast<const float2 *>(p + (l_hi + 8) * 4 + r);
+        float u0 = 0.f, u1 = 0.f;
+        if (swiglu) {
+          const float *qq = p + (size_t)MC * 256;
+          const float2 cg = *reinterpret_cast<const float2 *>(qq + l_hi * 4 + r);
+          const float2 dg = *reinterpret_cast<const float2 *>(qq + (l_hi + 8) * 4 + r);
+          u0 = cg.x + dg.x;
+          u1 = cg.y + dg.y;
+        }
+        bat_emit_apply(g, unit, ctg, jm, c2, a.x + b.x, a.y + b.y, u0, u1, pre[ct]);
+      }
+    }
   }
 }
 
