@@ -804,7 +804,10 @@ static void bat_ns_launch_mc(BatGemm g, int n_cu, hipStream_t st) {
   else bat_gemm_ns<MC, 2, 2><<<grid, block, bat_ns_lds_bytes<MC>(), st>>>(g);
 }
 
-constexpr int kWideMinCT = 24;       // column tiles (8 rows each) from which bat_gemm_wide takes over
+// Column tiles (8 rows each) from which bat_gemm_wide takes over: gate/up, with its many weight tiles, as soon
+// as the rows no longer fit bat_gemm_ns (65 rows); the other projections from 185 rows (measured at 76, 115,
+// 224, 256, 360 and 448 rows).
+constexpr int kWideMinCT = 24, kWideMinCTGateUp = 9;
 
 // Wave arrangement for CT column tiles: MW groups of MC tiles (MC from the compiled set).
 static void bat_launch(BatGemm g, int n_cu, hipStream_t st) {
@@ -814,7 +817,7 @@ static void bat_launch(BatGemm g, int n_cu, hipStream_t st) {
     else bat_ns_launch_mc<8>(g, n_cu, st);
     return;
   }
-  if (CT >= kWideMinCT) {                     // two-dimensional tiles, B fragments shared through LDS
+  if (CT >= (g.epi == FEPI_SWIGLU ? kWideMinCTGateUp : kWideMinCT)) {      // two-dimensional tiles, B fragments shared through LDS
     const int n_blk = (CT + kWdCols - 1) / kWdCols;
     const int per_unit = g.epi == FEPI_SWIGLU ? 2 : 1;        // weight tiles per unit
     auto groups = [&](int nt) { const int upg = kWdNW * nt / per_unit; return (g.n_units + upg - 1) / upg; };
