@@ -705,7 +705,12 @@ template <int KC>
 __global__ __launch_bounds__(kFastThreads) void fast_gemm_kernel(FastGemm g) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   Frag16 A;
-  fast_gemm_phase(g, blockIdx.x, gridDim.x, smem, A, false);
+  // The first weight fragments are requested before anything else: the phase's loop over passes begins
+  // with a wait for every request made so far (the compiler cannot count requests across the loop's
+  // back edge), so whatever is requested after that wait starts one memory round trip late.
+  const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  fast_issue16(A, g, blockIdx.x, gridDim.x, 0, wave, lane & 15, lane >> 4);
+  fast_gemm_phase(g, blockIdx.x, gridDim.x, smem, A, true);
 }
 
 template <int KC>
