@@ -115,7 +115,9 @@ __global__ __launch_bounds__(256) void attn_append(AttnArgs a) {
 // queries per episode and few episodes the blocks are what fills the chip (76 tree tokens, one episode:
 // 225 us per layer with one workgroup per head, 64 us with one per block).
 template <int HD, int THREADS, bool TREE, bool SPLIT>
-__global__ __launch_bounds__(THREADS) void attn_verify(AttnArgs a) {
+// The 256-thread single-block variant is held to 128 registers (four waves per SIMD: 108 -> 98 us per layer
+// at 64 episodes); the same limit on the per-block variant measured slower (long prefixes: 72 -> 86 us).
+__global__ __launch_bounds__(THREADS) __attribute__((amdgpu_waves_per_eu((THREADS == 256 && !SPLIT) ? 4 : 2))) void attn_verify(AttnArgs a) {
   constexpr int kAttnThreads = THREADS, kAttnWaves = THREADS / 64;
   constexpr int HALF = HD / 2;
   constexpr int LPK = HD / 8;              // lanes that share one key row (16 bytes each)
