@@ -93,9 +93,11 @@ struct WsLayout {
 };
 
 // Buffers of the batched path (M > 8 rows).  One launch per phase, so one set serves every layer.
+constexpr int kSplitMax = 4;          // runs a reduction is cut into at most (bat_gemm_wide)
+
 struct BatScratch {
   int CTS;                         // column tiles allocated: those of max_batch*max_k rows, at least 8
-  size_t rec_x, rec_o, rec_act, ssq, inv_rms, total;
+  size_t rec_x, rec_o, rec_act, ssq, inv_rms, part, total;
   explicit BatScratch(const heisd_model_desc *d) {
     const size_t M = (size_t)d->max_batch * d->max_k;
     CTS = (int)((M + 7) / 8);
@@ -108,6 +110,8 @@ struct BatScratch {
     rec_act = off; off += kf * CTS * 512;
     ssq = off;     off += align256((size_t)(d->d_model / 16) * CTS * 8 * sizeof(float));
     inv_rms = off; off += align256((size_t)CTS * 8 * sizeof(float));
+    // sums of a split reduction (bat_gemm_wide): kSplitMax x (d_model / 16 units) x CTS x 64 lanes x float2
+    part = off;    off += CTS >= kWdCols ? (size_t)kSplitMax * (d->d_model / 16) * CTS * 512 : 0;
     total = align256(off);
   }
 };
@@ -756,12 +760,10 @@ static hipError_t bat_prepare() {
   if ((e = bat_prepare_mc<6>()) != hipSuccess) return e;
   if ((e = bat_prepare_mc<7>()) != hipSuccess) return e;
   if ((e = bat_prepare_mc<8>()) != hipSuccess) return e;
-  if ((e = hipFuncSetAttribute(reinterpret_cast<const void *>(&bat_gemm_wide<4>), hipFuncAttributeMaxDynamicSharedMemorySize,
-                               (int)kBatWideLds)) != hipSuccess)
-    return e;
-  if ((e = hipFuncSetAttribute(reinterpret_cast<const void *>(&bat_gemm_wide<2>), hipFuncAttributeMaxDynamicSharedMemorySize,
-                               (int)kBatWideLds)) != hipSuccess)
-    return e;
+  const void *wide[] = {reinterpret_cast<const void *>(&bat_gemm_wide<4, false>), reinterpret_cast<const void *>(&bat_gemm_wide<4, true>),
+                        reinterpret_cast<const void *>(&bat_gemm_wide<2, false>), reinterpret_cast<const void *>(&bat_gemm_wide<2, true>)};
+  for (const void *f : wide)
+    if ((e = hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kBatWideLds)) != hipSuccess) return e;
   return bat_ns_prepare();
 }
 
@@ -810,7 +812,8 @@ static void bat_ns_launch_mc(BatGemm g, int n_cu, hipStream_t st) {
 constexpr int kWideMinCT = 24, kWideMinCTGateUp = 9;
 
 // Wave arrangement for CT column tiles: MW groups of MC tiles (MC from the compiled set).
-static void bat_launch(BatGemm g, int n_cu, hipStream_t st) {
+// part: room for the sums of a split reduction (kSplitMax x n_units x CT x 512 bytes), or null.
+static void bat_launch(BatGemm g, int n_cu, hipStream_t st, float2 *part = nullptr) {
   const int CT = g.CT;
   if (CT <= 8 && g.epi == FEPI_SWIGLU) {
     if (CT <= 4) bat_ns_launch_mc<4>(g, n_cu, st);
@@ -820,14 +823,36 @@ static void bat_launch(BatGemm g, int n_cu, hipStream_t st) {
   if (CT >= (g.epi == FEPI_SWIGLU ? kWideMinCTGateUp : kWideMinCT)) {      // two-dimensional tiles, B fragments shared through LDS
     const int n_blk = (CT + kWdCols - 1) / kWdCols;
     const int per_unit = g.epi == FEPI_SWIGLU ? 2 : 1;        // weight tiles per unit
+    const int total = (g.Kd + 31) / 32, n_chunks = (total + kWdS - 1) / kWdS;
+    constexpr int CPR = kWdRA / kWdS;
     auto groups = [&](int nt) { const int upg = kWdNW * nt / per_unit; return (g.n_units + upg - 1) / upg; };
-    // 4 or 2 weight tiles per wave: whichever needs less time in whole rounds of workgroups over the
-    // compute units; a workgroup of the 4-tile variant takes about 1.55 times as long (measured).
-    auto cost = [&](int nt) { return (double)((groups(nt) * n_blk + n_cu - 1) / n_cu) * (nt == 4 ? 1.55 : 1.0); };
-    const int nt = cost(4) <= cost(2) ? 4 : 2;
-    const int grid = (groups(nt) + 7) / 8 * 8 * n_blk;
-    if (nt == 4) bat_gemm_wide<4><<<dim3(grid), dim3(kBatThreads), kBatWideLds, st>>>(g, n_blk);
-    else bat_gemm_wide<2><<<dim3(grid), dim3(kBatThreads), kBatWideLds, st>>>(g, n_blk);
+    // Estimated time in us of (nt weight tiles per wave, reduction in ks runs): whole rounds of workgroups
+    // over the compute units (one workgroup fills a unit's LDS), 0.42 us per k-step with 2 tiles per wave
+    // and 0.65 us with 4 (measured on the 7B shapes at 224 and 448 rows), a few us to start and end a
+    // workgroup; a split reduction adds the launch that sums the runs and what it moves (at 2 TB/s).
+    auto estimate = [&](int nt, int ks) {
+      const double rounds = (double)(((long)groups(nt) * n_blk * ks + n_cu - 1) / n_cu);
+      const double finish = ks > 1 ? 6.0 + 2.0 * ks * g.n_units * CT * 512.0 / 2.0e6 : 0.0;
+      return rounds * ((double)total / ks * (nt == 4 ? 0.65 : 0.42) + 4.0) + finish;
+    };
+    int nt = 4, ks = 1;
+    double best = estimate(4, 1);
+    for (int n : {4, 2})
+      for (int k : {1, 2, 4}) {
+        if (k > 1 && (!part || g.epi == FEPI_SWIGLU || n_chunks % (k * CPR) != 0 || k > kSplitMax)) continue;
+        const double e = estimate(n, k);
+        if (e < best) { best = e; nt = n; ks = k; }
+      }
+    const bool whole = (n_chunks / ks) % CPR == 0;            // see the kernel
+    const dim3 gr((groups(nt) + 7) / 8 * 8 * n_blk * ks), bl(kBatThreads);
+    if (nt == 4) {
+      if (whole) bat_gemm_wide<4, true><<<gr, bl, kBatWideLds, st>>>(g, n_blk, ks, part);
+      else bat_gemm_wide<4, false><<<gr, bl, kBatWideLds, st>>>(g, n_blk, ks, part);
+    } else {
+      if (whole) bat_gemm_wide<2, true><<<gr, bl, kBatWideLds, st>>>(g, n_blk, ks, part);
+      else bat_gemm_wide<2, false><<<gr, bl, kBatWideLds, st>>>(g, n_blk, ks, part);
+    }
+    if (ks > 1) bat_split_finish<<<dim3((g.n_units * CT + 3) / 4), dim3(256), 0, st>>>(g, ks, part);
     return;
   }
   const int MW = CT <= 8 ? 1 : (CT <= 16 ? 2 : (CT <= 32 ? 4 : 8));
@@ -857,6 +882,7 @@ static void batch_forward(heisd_verify_ctx *ctx, const heisd_kv_desc *kv, const 
   uint16_t *rec_o = reinterpret_cast<uint16_t *>(ctx->bscr + bs.rec_o);
   uint16_t *rec_act = reinterpret_cast<uint16_t *>(ctx->bscr + bs.rec_act);
   float *ssq = reinterpret_cast<float *>(ctx->bscr + bs.ssq);
+  float2 *part = CTS >= kWdCols ? reinterpret_cast<float2 *>(ctx->bscr + bs.part) : nullptr;
   float *inv_rms = reinterpret_cast<float *>(ctx->bscr + bs.inv_rms);
   auto row_scales = [&]() {
     bat_row_scales<<<dim3((CT * 8 + kBatWaves - 1) / kBatWaves), dim3(kBatThreads), 0, st>>>(ssq, dm / 16, CT * 8,
@@ -903,7 +929,7 @@ static void batch_forward(heisd_verify_ctx *ctx, const heisd_kv_desc *kv, const 
     g.next_gain = ctx->ffn_norm[l]; g.o_planes = rec_x; g.ssq_out = ssq;
     {
       ProfScope ps(ctx, HEISD_KC_OPROJ, st, prof);
-      bat_launch(g, ctx->n_cu, st);
+      bat_launch(g, ctx->n_cu, st, part);
       row_scales();
     }
     // a = silu(RMSNorm(x) . Wg^T) * (RMSNorm(x) . Wu^T), as records
@@ -924,7 +950,7 @@ static void batch_forward(heisd_verify_ctx *ctx, const heisd_kv_desc *kv, const 
     g.o_planes = rec_x; g.ssq_out = ssq;
     {
       ProfScope ps(ctx, HEISD_KC_DOWN, st, prof);
-      bat_launch(g, ctx->n_cu, st);
+      bat_launch(g, ctx->n_cu, st, part);
       row_scales();
     }
   }
@@ -935,7 +961,7 @@ static void batch_forward(heisd_verify_ctx *ctx, const heisd_kv_desc *kv, const 
   g.seg_tiles = d.n_bins / 16; g.n_units = d.n_bins / 16; g.Kd = dm;
   g.b = rec_x; g.inv_rms = inv_rms; g.out = logits; g.ldo = d.n_bins;
   ProfScope ps(ctx, HEISD_KC_LMHEAD, st, prof);
-  bat_launch(g, ctx->n_cu, st);
+  bat_launch(g, ctx->n_cu, st, part);
 }
 
 static void generic_forward(heisd_verify_ctx *ctx, const heisd_kv_desc *kv, const int32_t *draft_tokens, int K,

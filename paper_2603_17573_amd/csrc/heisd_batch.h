@@ -451,8 +451,13 @@ constexpr int kWdCols = kWdMW * kWdMC;                   // 16 column tiles per 
 constexpr size_t kBatWideLds = (size_t)kWdNB * kWdS * kWdCols * 1024;  // 128 KB: four chunks of B fragments
 
 // NT: weight tiles per computing wave, 4 or 2 (2: half as many rows per workgroup, for projections with few tiles).
-template <int NT>
-__global__ __launch_bounds__(kBatThreads) __attribute__((amdgpu_waves_per_eu(2, 2))) void bat_gemm_wide(BatGemm g, int n_blk) {
+// ksplit > 1: the reduction is cut into ksplit equal runs of chunks, one workgroup each; a workgroup then
+// stores its sums (part[split][unit][column tile][lane], the pair a lane would hand to the epilogue) and
+// bat_split_finish adds them in the order of the splits and applies the epilogue.  For projections with
+// so few weight tiles that one workgroup per tile group leaves most compute units idle (O-proj, down).
+template <int NT, bool WHOLE>
+__global__ __launch_bounds__(kBatThreads) __attribute__((amdgpu_waves_per_eu(2, 2))) void bat_gemm_wide(BatGemm g, int n_blk, int ksplit,
+                                                                                                          float2 *part) {
   constexpr int MC = kWdMC, S = kWdS;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   const uint32_t smem_lds = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char *)smem;
@@ -465,10 +470,12 @@ __global__ __launch_bounds__(kBatThreads) __attribute__((amdgpu_waves_per_eu(2, 
   const int n_groups = (g.n_units + upg - 1) / upg;
   // workgroup -> (weight group, row block): the row blocks of a group differ by 8 in the launch order
   const int id = blockIdx.x, q = id >> 3;
-  const int blk = q % n_blk, grp = (q / n_blk) * 8 + (id & 7);
+  const int inner = q % (n_blk * ksplit);
+  const int blk = inner % n_blk, split = inner / n_blk, grp = (q / (n_blk * ksplit)) * 8 + (id & 7);
   if (grp >= n_groups) return;
   const int total = (g.Kd + 31) / 32;
-  const int n_chunks = (total + S - 1) / S;
+  const int n_chunks = ((total + S - 1) / S) / ksplit;             // of this split (the host splits only what divides)
+  const int kbase = split * n_chunks * S;                          // its first k-step
   const size_t bstep = (size_t)2 * g.CTS * 256;
   // units of this wave's NT tiles (SwiGLU: tile t is matrix t & 1 of pair t >> 1)
   int unit_of[NT];
@@ -509,7 +516,8 @@ __global__ __launch_bounds__(kBatThreads) __attribute__((amdgpu_waves_per_eu(2, 
       for (int o = 0; o < OPS; ++o) {
         const int op = o * NF + (wave - kWdCompute);
         const int slot = op / kWdCols, ct = op % kWdCols;
-        const int ks = c * S + slot < total ? c * S + slot : total;
+        const int ksl = c * S + slot;
+        const int ks = (ksl < n_chunks * S && kbase + ksl < total) ? kbase + ksl : total;
         lds_dma16(bsrc + (size_t)ks * bstep + ct * 256,
                   __builtin_amdgcn_readfirstlane(smem_lds + (uint32_t)(((buf * S + slot) * kWdCols + ct) * 1024)));
       }
@@ -529,31 +537,34 @@ __global__ __launch_bounds__(kBatThreads) __attribute__((amdgpu_waves_per_eu(2, 
 #pragma unroll
     for (int u = 0; u < kWdRA; ++u)
 #pragma unroll
-      for (int t = 0; t < NT; ++t) A[u][t] = fast_ld_a(wf[t], g.Kd, u);
+      for (int t = 0; t < NT; ++t) A[u][t] = fast_ld_a(wf[t], g.Kd, kbase + u);
     lds_barrier();                                    // chunk 0 is in LDS
     constexpr int CPR = kWdRA / S;                    // chunks per revolution of the weight ring
-    for (int c0 = 0; c0 < n_chunks; c0 += CPR) {
+    auto chunk = [&](int c, int cc) __attribute__((always_inline)) {
+      const unsigned char *bl = smem + ((size_t)((c % kWdNB) * S * kWdCols + mwv * MC)) * 1024 + lane * 16;
 #pragma unroll
-      for (int cc = 0; cc < CPR; ++cc) {
-        const int c = c0 + cc;
-        if (c < n_chunks) {                           // uniform over the workgroup
-          const unsigned char *bl = smem + ((size_t)((c % kWdNB) * S * kWdCols + mwv * MC)) * 1024 + lane * 16;
+      for (int s = 0; s < S; ++s) {
+        const int u = cc * S + s;                     // ring slot of k-step c*S + s
+        u32x4 Bf[MC];
 #pragma unroll
-          for (int s = 0; s < S; ++s) {
-            const int u = cc * S + s;                 // ring slot of k-step c*S + s
-            u32x4 Bf[MC];
+        for (int ct = 0; ct < MC; ++ct) Bf[ct] = *reinterpret_cast<const u32x4 *>(bl + (size_t)(s * kWdCols + ct) * 1024);
 #pragma unroll
-            for (int ct = 0; ct < MC; ++ct) Bf[ct] = *reinterpret_cast<const u32x4 *>(bl + (size_t)(s * kWdCols + ct) * 1024);
+        for (int t = 0; t < NT; ++t) {
 #pragma unroll
-            for (int t = 0; t < NT; ++t) {
-#pragma unroll
-              for (int ct = 0; ct < MC; ++ct) acc[t][ct] = fast_mfma(A[u][t], Bf[ct], acc[t][ct]);
-              A[u][t] = fast_ld_a(wf[t], g.Kd, c * S + s + kWdRA);   // clamped into the matrix; met by zero records
-            }
-          }
-          lds_barrier();                              // chunk c+1 complete in LDS; everybody is done reading chunk c
+          for (int ct = 0; ct < MC; ++ct) acc[t][ct] = fast_mfma(A[u][t], Bf[ct], acc[t][ct]);
+          A[u][t] = fast_ld_a(wf[t], g.Kd, kbase + c * S + s + kWdRA);   // clamped into the matrix; never used past the end
         }
       }
+      lds_barrier();                                  // chunk c+1 complete in LDS; everybody is done reading chunk c
+    };
+    // WHOLE (the chunk count is a whole number of revolutions): no branch inside the loop, so the waits
+    // the compiler places before each weight fragment count every younger request of the ring; with a
+    // branch it can only count those of the current chunk, which halves the distance the weights are
+    // requested ahead.
+    for (int c0 = 0; c0 < n_chunks; c0 += CPR) {
+#pragma unroll
+      for (int cc = 0; cc < CPR; ++cc)
+        if (WHOLE || c0 + cc < n_chunks) chunk(c0 + cc, cc);   // uniform over the workgroup
     }
   }
   lds_barrier();                                      // the B buffers are free: every wave turns its own tiles around in them
@@ -574,6 +585,18 @@ __global__ __launch_bounds__(kBatThreads) __attribute__((amdgpu_waves_per_eu(2, 
       const int unit = unit_of[2 * h + tt];
       if (unit >= g.n_units) continue;                // uniform over the wave
       const int ctg0 = blk * kWdCols + mwv * MC;
+      if (ksplit > 1) {                               // uniform: the sums go to bat_split_finish
+#pragma unroll
+        for (int ct = 0; ct < MC; ++ct) {
+          const int ctg = ctg0 + ct;
+          if (ctg >= g.CT) continue;
+          const float *p = mine + ((size_t)(tt * MC + ct) * 64) * 4;
+          const float2 a = *reinterpret_cast<const float2 *>(p + l_hi * 4 + r);
+          const float2 b = *reinterpret_cast<const float2 *>(p + (l_hi + 8) * 4 + r);
+          part[(((size_t)split * g.n_units + unit) * g.CT + ctg) * 64 + lane] = make_float2(a.x + b.x, a.y + b.y);
+        }
+        continue;
+      }
       EmitPre pre[MC];                                // everything the tile's 8 column tiles read, requested before the first store
 #pragma unroll
       for (int ct = 0; ct < MC; ++ct) pre[ct] = bat_emit_load(g, unit, min(ctg0 + ct, g.CT - 1), jm, c2);
@@ -596,6 +619,24 @@ __global__ __launch_bounds__(kBatThreads) __attribute__((amdgpu_waves_per_eu(2, 
       }
     }
   }
+}
+
+// Second half of a split reduction: one wave per (column tile, unit); lane (jm, c2) adds the pair of every
+// split in the order of the splits and applies the projection's epilogue (not SwiGLU: never split).
+__global__ __launch_bounds__(256) void bat_split_finish(BatGemm g, int ksplit, const float2 *part) {
+  const int lane = threadIdx.x & 63;
+  const int tile = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (tile >= g.n_units * g.CT) return;               // uniform over the wave
+  const int ct = tile / g.n_units, unit = tile - ct * g.n_units;     // neighbouring waves: neighbouring columns of the same rows
+  const int c2 = lane & 7, jm = lane >> 3;
+  const EmitPre pre = bat_emit_load(g, unit, ct, jm, c2);
+  float2 s = part[((size_t)unit * g.CT + ct) * 64 + lane];
+  for (int k = 1; k < ksplit; ++k) {
+    const float2 v = part[(((size_t)k * g.n_units + unit) * g.CT + ct) * 64 + lane];
+    s.x += v.x;
+    s.y += v.y;
+  }
+  bat_emit_apply(g, unit, ct, jm, c2, s.x, s.y, 0.f, 0.f, pre);
 }
 
 // ---- embedding: x rows (fp32), records of x*gain, partial sums of squares --------------------------
