@@ -102,7 +102,9 @@ struct BatScratch {
     const size_t M = (size_t)d->max_batch * d->max_k;
     CTS = (int)((M + 7) / 8);
     if (CTS < 8) CTS = 8;
-    if (CTS >= kWdCols) CTS = (CTS + kWdCols - 1) / kWdCols * kWdCols;     // the wide kernel reads whole blocks of column tiles
+    // the wide kernel reads whole blocks of column tiles; one tile more keeps the distance between k-steps
+    // from being a multiple of 8 KB (with that, workloads that use a few of the tiles read from few channels)
+    if (CTS > 8) CTS = (CTS + kWdCols - 1) / kWdCols * kWdCols + 1;
     const size_t kd = 2 * (((size_t)d->d_model + 31) / 32) + 2, kf = 2 * (((size_t)d->d_ffn + 31) / 32) + 2;   // + a zero k-step
     size_t off = 0;
     rec_x = off;   off += kd * CTS * 512;
@@ -807,9 +809,10 @@ static void bat_ns_launch_mc(BatGemm g, int n_cu, hipStream_t st) {
 }
 
 // Column tiles (8 rows each) from which bat_gemm_wide takes over: gate/up, with its many weight tiles, as soon
-// as the rows no longer fit bat_gemm_ns (65 rows); the other projections from 185 rows (measured at 76, 115,
-// 224, 256, 360 and 448 rows).
-constexpr int kWideMinCT = 24, kWideMinCTGateUp = 9;
+// as the rows no longer fit bat_gemm_ns (65 rows), and so do the projections whose reduction may be split
+// (O-proj, down, LM head: few weight tiles, so one workgroup per tile group fills a fraction of the chip);
+// QKV from 185 rows (measured at 76, 115, 162, 176, 224, 256, 360 and 448 rows).
+constexpr int kWideMinCT = 24, kWideMinCTGateUp = 9, kWideMinCTSplit = 9;
 
 // Wave arrangement for CT column tiles: MW groups of MC tiles (MC from the compiled set).
 // part: room for the sums of a split reduction (kSplitMax x n_units x CT x 512 bytes), or null.
@@ -820,7 +823,7 @@ static void bat_launch(BatGemm g, int n_cu, hipStream_t st, float2 *part = nullp
     else bat_ns_launch_mc<8>(g, n_cu, st);
     return;
   }
-  if (CT >= (g.epi == FEPI_SWIGLU ? kWideMinCTGateUp : kWideMinCT)) {      // two-dimensional tiles, B fragments shared through LDS
+  if (CT >= (g.epi == FEPI_SWIGLU ? kWideMinCTGateUp : (part ? kWideMinCTSplit : kWideMinCT))) {      // two-dimensional tiles, B fragments shared through LDS
     const int n_blk = (CT + kWdCols - 1) / kWdCols;
     const int per_unit = g.epi == FEPI_SWIGLU ? 2 : 1;        // weight tiles per unit
     const int total = (g.Kd + 31) / 32, n_chunks = (total + kWdS - 1) / kWdS;

@@ -355,6 +355,7 @@ __global__ __launch_bounds__(kBatThreads) __attribute__((amdgpu_waves_per_eu(2, 
 #pragma unroll
       for (int c = 0; c < MC; ++c) acc[t][c] = f32x4{0.f, 0.f, 0.f, 0.f};
     if (filler) {
+      wait_vmcnt_all();                               // no wait of the compiler's between the transfers
       fill(0, 0);
       lds_barrier();
       for (int c = 0; c < n_chunks; ++c) {
@@ -504,6 +505,7 @@ __global__ __launch_bounds__(kBatThreads) __attribute__((amdgpu_waves_per_eu(2, 
     for (int c = 0; c < MC; ++c) acc[t][c] = f32x4{0.f, 0.f, 0.f, 0.f};
 
   if (filler) {
+    wait_vmcnt_all();                                 // no wait of the compiler's between the transfers
     // this lane's piece of the B fragment of (k-step ks, column tile blk*16 + ct): bsrc + ks*bstep + ct*256
     const uint16_t *bsrc = g.b + ((size_t)(lg >> 1) * g.CTS + (size_t)blk * kWdCols) * 256 + lr * 16 + (lg & 1) * 8;
     constexpr int NF = kBatWaves - kWdCompute;                    // 2 filling waves

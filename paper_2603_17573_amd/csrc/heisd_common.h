@@ -49,6 +49,17 @@ __device__ __forceinline__ void wait_vmcnt() {
   asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
 }
 
+// vmcnt(0) in the form the compiler's own wait placement reads.  A wave that is about to issue
+// lds_dma16 transfers calls this first: the compiler cannot see the transfers, and a wait it places
+// later for one of ITS OWN earlier loads (one it moved up from code both kinds of wave share, say)
+// would land between the transfers and wait for them too, one round trip per transfer.  After this
+// call it knows of nothing pending.
+__device__ __forceinline__ void wait_vmcnt_all() {
+  asm volatile("" ::: "memory");
+  __builtin_amdgcn_s_waitcnt(0x0F70);                 // vmcnt 0; expcnt and lgkmcnt left at their maxima
+  asm volatile("" ::: "memory");
+}
+
 __device__ __forceinline__ float wave_sum(float v) {
 #pragma unroll
   for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, kWave);

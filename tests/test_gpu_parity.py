@@ -100,6 +100,20 @@ def test_wave_arrangements_of_the_record_path(shape_name, B, K):
     run_case(wl, path=4)
 
 
+SPLIT = synth.ModelShape(n_layers=2, d_model=1024, n_heads=8, head_dim=128, d_ffn=2816, vocab=2048)
+
+
+@pytest.mark.parametrize("B,K", [(12, 9), (25, 8)])
+def test_split_reductions(B, K):
+    """108 and 200 rows (one ragged block of column tiles; two blocks, the second ragged) on a shape
+    whose O-proj and down have few weight tiles (64) and long enough reductions (32 and 88 k-steps)
+    that the dispatcher cuts them into 4 and 2 runs: every run's sums go through memory and a second
+    launch adds them and applies the residual epilogue."""
+    wl = synth.Workload("split_%dx%d" % (B, K), SPLIT, 4, 11, SPLIT.bin_base, batch=B, K=K,
+                        draft=("geometric", 0.5), seed=3 * B + K)
+    run_case(wl)
+
+
 def test_context_sized_for_more_rows_than_the_call_uses():
     """A context initialised for 12 episodes verifies 3 (the record stride is that of the context,
     the column-tile count that of the call), on the automatic path and on the <=8-row path."""
