@@ -93,11 +93,12 @@ struct WsLayout {
 };
 
 // Buffers of the batched path (M > 8 rows).  One launch per phase, so one set serves every layer.
-constexpr int kSplitMax = 4;          // runs a reduction is cut into at most (bat_gemm_wide)
+constexpr int kSplitMax = 16;         // runs a reduction is cut into at most (bat_gemm_wide)
 
 struct BatScratch {
   int CTS;                         // column tiles allocated: those of max_batch*max_k rows, at least 8
   size_t rec_x, rec_o, rec_act, ssq, inv_rms, part, total;
+  int part_tiles() const { return 4 * CTS > 128 ? 4 * CTS : 128; }   // 16 runs at up to 64 rows, 4 runs at any row count
   explicit BatScratch(const heisd_model_desc *d) {
     const size_t M = (size_t)d->max_batch * d->max_k;
     CTS = (int)((M + 7) / 8);
@@ -112,8 +113,9 @@ struct BatScratch {
     rec_act = off; off += kf * CTS * 512;
     ssq = off;     off += align256((size_t)(d->d_model / 16) * CTS * 8 * sizeof(float));
     inv_rms = off; off += align256((size_t)CTS * 8 * sizeof(float));
-    // sums of a split reduction (bat_gemm_wide): kSplitMax x (d_model / 16 units) x CTS x 64 lanes x float2
-    part = off;    off += CTS >= kWdCols ? (size_t)kSplitMax * (d->d_model / 16) * CTS * 512 : 0;
+    // sums of split reductions (bat_gemm_wide): up to 3*d_model/16 units (QKV) x part_tiles() column tiles
+    // (runs x tiles in use) x 64 lanes x float2
+    part = off;    off += (size_t)(3 * d->d_model / 16) * part_tiles() * 512;
     total = align256(off);
   }
 };
@@ -762,8 +764,10 @@ static hipError_t bat_prepare() {
   if ((e = bat_prepare_mc<6>()) != hipSuccess) return e;
   if ((e = bat_prepare_mc<7>()) != hipSuccess) return e;
   if ((e = bat_prepare_mc<8>()) != hipSuccess) return e;
-  const void *wide[] = {reinterpret_cast<const void *>(&bat_gemm_wide<4, false>), reinterpret_cast<const void *>(&bat_gemm_wide<4, true>),
-                        reinterpret_cast<const void *>(&bat_gemm_wide<2, false>), reinterpret_cast<const void *>(&bat_gemm_wide<2, true>)};
+  const void *wide[] = {reinterpret_cast<const void *>(&bat_gemm_wide<4, false, 2>), reinterpret_cast<const void *>(&bat_gemm_wide<4, true, 2>),
+                        reinterpret_cast<const void *>(&bat_gemm_wide<2, false, 2>), reinterpret_cast<const void *>(&bat_gemm_wide<2, true, 2>),
+                        reinterpret_cast<const void *>(&bat_gemm_wide<4, false, 1>), reinterpret_cast<const void *>(&bat_gemm_wide<4, true, 1>),
+                        reinterpret_cast<const void *>(&bat_gemm_wide<2, false, 1>), reinterpret_cast<const void *>(&bat_gemm_wide<2, true, 1>)};
   for (const void *f : wide)
     if ((e = hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kBatWideLds)) != hipSuccess) return e;
   return bat_ns_prepare();
@@ -808,54 +812,86 @@ static void bat_ns_launch_mc(BatGemm g, int n_cu, hipStream_t st) {
   else bat_gemm_ns<MC, 2, 2><<<grid, block, bat_ns_lds_bytes<MC>(), st>>>(g);
 }
 
-// Column tiles (8 rows each) from which bat_gemm_wide takes over: gate/up, with its many weight tiles, as soon
-// as the rows no longer fit bat_gemm_ns (65 rows), and so do the projections whose reduction may be split
-// (O-proj, down, LM head: few weight tiles, so one workgroup per tile group fills a fraction of the chip);
-// QKV from 185 rows (measured at 76, 115, 162, 176, 224, 256, 360 and 448 rows).
+// Column tiles (8 rows each) from which bat_gemm_wide takes over.  3 x 2 arrangement: from 65 rows for gate/up
+// (the rows no longer fit bat_gemm_ns) and for every projection whose reduction may be split; without room
+// for a split from 185 rows (measured at 76, 115, 162, 176, 224, 256, 360 and 448 rows).  6 x 1 arrangement
+// with split reductions, up to 64 rows: from 33 rows, and from 17 rows for projections with no more weight
+// tiles than compute units (measured at 22, 45 and 56 rows: QKV at 22 rows is the one case bat_gemm wins).
 constexpr int kWideMinCT = 24, kWideMinCTGateUp = 9, kWideMinCTSplit = 9;
+constexpr int kWide1MinCT = 5, kWide1MinCTFew = 3;
+
+// Room for the sums of split reductions: part holds up to `units` units x `tiles` column tiles (runs x tiles in use).
+struct SplitRoom {
+  float2 *part = nullptr;
+  int units = 0, tiles = 0;
+};
+
+// bat_gemm_wide in the arrangement MW (2: blocks of 16 column tiles, 1: blocks of 8), nt weight tiles per
+// wave and the reduction in ks runs.
+template <int MW>
+static void bat_wide_launch_t(const BatGemm &g, int nt, int ks, bool whole, int grid, int n_blk, float2 *part, hipStream_t st) {
+  const dim3 gr(grid), bl(kBatThreads);
+  if (nt == 4) {
+    if (whole) bat_gemm_wide<4, true, MW><<<gr, bl, kBatWideLds, st>>>(g, n_blk, ks, part);
+    else bat_gemm_wide<4, false, MW><<<gr, bl, kBatWideLds, st>>>(g, n_blk, ks, part);
+  } else {
+    if (whole) bat_gemm_wide<2, true, MW><<<gr, bl, kBatWideLds, st>>>(g, n_blk, ks, part);
+    else bat_gemm_wide<2, false, MW><<<gr, bl, kBatWideLds, st>>>(g, n_blk, ks, part);
+  }
+}
+
+static void bat_wide_launch(const BatGemm &g, int mw, int n_cu, hipStream_t st, const SplitRoom &room) {
+  const int CT = g.CT, cols = mw * kWdMC, nwv = kWdCompute / mw;
+  const int n_blk = (CT + cols - 1) / cols;
+  const int per_unit = g.epi == FEPI_SWIGLU ? 2 : 1;        // weight tiles per unit
+  const int total = (g.Kd + 31) / 32, n_chunks = (total + kWdS - 1) / kWdS;
+  constexpr int CPR = kWdRA / kWdS;
+  auto groups = [&](int nt) { const int upg = nwv * nt / per_unit; return (g.n_units + upg - 1) / upg; };
+  // Estimated time in us of (nt weight tiles per wave, reduction in ks runs): whole rounds of workgroups
+  // over the compute units (one workgroup fills a unit's LDS); per k-step 0.42 us with 2 tiles per wave
+  // and 0.65 us with 4 in the 3 x 2 arrangement (measured on the 7B shapes at 224 and 448 rows), 0.27 and
+  // 0.445 us in the 6 x 1 arrangement (fitted to 2..16 runs at 56 rows); a few us to start and end a
+  // workgroup; a split reduction adds the launch that sums the runs and what it moves (at 2 TB/s).
+  auto estimate = [&](int nt, int ks) {
+    const long wgs = (long)((groups(nt) + 7) / 8 * 8) * n_blk * ks;     // as launched: the surplus ones come last
+    const double rounds = (double)((wgs + n_cu - 1) / n_cu);
+    const int per = (n_chunks + ks - 1) / ks;
+    const double finish = ks > 1 ? 8.0 + 2.0 * ks * g.n_units * CT * 512.0 / 2.0e6 : 0.0;
+    const double per_step = mw == 2 ? (nt == 4 ? 0.65 : 0.42) : (nt == 4 ? 0.445 : 0.27);
+    return rounds * ((double)per * kWdS * per_step + (mw == 2 ? 4.0 : 8.0)) + finish;
+  };
+  const bool may_split = room.part && g.epi != FEPI_SWIGLU && g.n_units <= room.units;
+  int nt = 4, ks = 1;
+  double best = estimate(4, 1);
+  for (int n : {4, 2})
+    for (int k = 1; k <= kSplitMax; ++k) {
+      if (k > 1 && (!may_split || k * CT > room.tiles)) break;
+      if ((k - 1) * ((n_chunks + k - 1) / k) >= n_chunks) continue;      // the last run would be empty
+      const double e = estimate(n, k);
+      if (e < best) { best = e; nt = n; ks = k; }
+    }
+  const int per = (n_chunks + ks - 1) / ks;
+  const bool whole = per % CPR == 0 && n_chunks % per == 0;   // every run a whole number of ring revolutions (see the kernel)
+  const int grid = (groups(nt) + 7) / 8 * 8 * n_blk * ks;
+  if (mw == 2) bat_wide_launch_t<2>(g, nt, ks, whole, grid, n_blk, room.part, st);
+  else bat_wide_launch_t<1>(g, nt, ks, whole, grid, n_blk, room.part, st);
+  if (ks > 1) bat_split_finish<<<dim3((g.n_units * CT + 3) / 4), dim3(256), 0, st>>>(g, ks, room.part);
+}
 
 // Wave arrangement for CT column tiles: MW groups of MC tiles (MC from the compiled set).
-// part: room for the sums of a split reduction (kSplitMax x n_units x CT x 512 bytes), or null.
-static void bat_launch(BatGemm g, int n_cu, hipStream_t st, float2 *part = nullptr) {
+static void bat_launch(BatGemm g, int n_cu, hipStream_t st, const SplitRoom &room = SplitRoom()) {
   const int CT = g.CT;
   if (CT <= 8 && g.epi == FEPI_SWIGLU) {
     if (CT <= 4) bat_ns_launch_mc<4>(g, n_cu, st);
     else bat_ns_launch_mc<8>(g, n_cu, st);
     return;
   }
-  if (CT >= (g.epi == FEPI_SWIGLU ? kWideMinCTGateUp : (part ? kWideMinCTSplit : kWideMinCT))) {      // two-dimensional tiles, B fragments shared through LDS
-    const int n_blk = (CT + kWdCols - 1) / kWdCols;
-    const int per_unit = g.epi == FEPI_SWIGLU ? 2 : 1;        // weight tiles per unit
-    const int total = (g.Kd + 31) / 32, n_chunks = (total + kWdS - 1) / kWdS;
-    constexpr int CPR = kWdRA / kWdS;
-    auto groups = [&](int nt) { const int upg = kWdNW * nt / per_unit; return (g.n_units + upg - 1) / upg; };
-    // Estimated time in us of (nt weight tiles per wave, reduction in ks runs): whole rounds of workgroups
-    // over the compute units (one workgroup fills a unit's LDS), 0.42 us per k-step with 2 tiles per wave
-    // and 0.65 us with 4 (measured on the 7B shapes at 224 and 448 rows), a few us to start and end a
-    // workgroup; a split reduction adds the launch that sums the runs and what it moves (at 2 TB/s).
-    auto estimate = [&](int nt, int ks) {
-      const double rounds = (double)(((long)groups(nt) * n_blk * ks + n_cu - 1) / n_cu);
-      const double finish = ks > 1 ? 6.0 + 2.0 * ks * g.n_units * CT * 512.0 / 2.0e6 : 0.0;
-      return rounds * ((double)total / ks * (nt == 4 ? 0.65 : 0.42) + 4.0) + finish;
-    };
-    int nt = 4, ks = 1;
-    double best = estimate(4, 1);
-    for (int n : {4, 2})
-      for (int k : {1, 2, 4}) {
-        if (k > 1 && (!part || g.epi == FEPI_SWIGLU || n_chunks % (k * CPR) != 0 || k > kSplitMax)) continue;
-        const double e = estimate(n, k);
-        if (e < best) { best = e; nt = n; ks = k; }
-      }
-    const bool whole = (n_chunks / ks) % CPR == 0;            // see the kernel
-    const dim3 gr((groups(nt) + 7) / 8 * 8 * n_blk * ks), bl(kBatThreads);
-    if (nt == 4) {
-      if (whole) bat_gemm_wide<4, true><<<gr, bl, kBatWideLds, st>>>(g, n_blk, ks, part);
-      else bat_gemm_wide<4, false><<<gr, bl, kBatWideLds, st>>>(g, n_blk, ks, part);
-    } else {
-      if (whole) bat_gemm_wide<2, true><<<gr, bl, kBatWideLds, st>>>(g, n_blk, ks, part);
-      else bat_gemm_wide<2, false><<<gr, bl, kBatWideLds, st>>>(g, n_blk, ks, part);
-    }
-    if (ks > 1) bat_split_finish<<<dim3((g.n_units * CT + 3) / 4), dim3(256), 0, st>>>(g, ks, part);
+  if (CT <= 8 && room.part && (CT >= kWide1MinCT || (CT >= kWide1MinCTFew && g.n_units <= n_cu))) {
+    bat_wide_launch(g, 1, n_cu, st, room);                    // six waves across the weight tiles, 8 column tiles
+    return;
+  }
+  if (CT >= (g.epi == FEPI_SWIGLU ? kWideMinCTGateUp : (room.part ? kWideMinCTSplit : kWideMinCT))) {
+    bat_wide_launch(g, 2, n_cu, st, room);                    // 3 x 2 waves, 16 column tiles
     return;
   }
   const int MW = CT <= 8 ? 1 : (CT <= 16 ? 2 : (CT <= 32 ? 4 : 8));
@@ -885,7 +921,10 @@ static void batch_forward(heisd_verify_ctx *ctx, const heisd_kv_desc *kv, const 
   uint16_t *rec_o = reinterpret_cast<uint16_t *>(ctx->bscr + bs.rec_o);
   uint16_t *rec_act = reinterpret_cast<uint16_t *>(ctx->bscr + bs.rec_act);
   float *ssq = reinterpret_cast<float *>(ctx->bscr + bs.ssq);
-  float2 *part = CTS >= kWdCols ? reinterpret_cast<float2 *>(ctx->bscr + bs.part) : nullptr;
+  SplitRoom part;
+  part.part = reinterpret_cast<float2 *>(ctx->bscr + bs.part);
+  part.units = 3 * dm / 16;
+  part.tiles = bs.part_tiles();
   float *inv_rms = reinterpret_cast<float *>(ctx->bscr + bs.inv_rms);
   auto row_scales = [&]() {
     bat_row_scales<<<dim3((CT * 8 + kBatWaves - 1) / kBatWaves), dim3(kBatThreads), 0, st>>>(ssq, dm / 16, CT * 8,
@@ -909,7 +948,7 @@ static void batch_forward(heisd_verify_ctx *ctx, const heisd_kv_desc *kv, const 
     g.w[2] = ctx->pv[l];
     g.seg_tiles = dm / 16; g.n_units = 3 * dm / 16; g.Kd = dm;
     g.b = rec_x; g.inv_rms = inv_rms; g.out = ctx->qkv; g.ldo = 3 * dm;
-    { ProfScope ps(ctx, HEISD_KC_QKV, st, prof); bat_launch(g, ctx->n_cu, st); }
+    { ProfScope ps(ctx, HEISD_KC_QKV, st, prof); bat_launch(g, ctx->n_cu, st, part); }
     // RoPE + KV-append + attention; the output goes straight into records
     AttnArgs a{};
     a.qkv = ctx->qkv;

@@ -444,30 +444,35 @@ __global__ __launch_bounds__(kBatThreads) __attribute__((amdgpu_waves_per_eu(2, 
 // chunk ahead is not enough: a transfer's round trip is about as long as two chunks of products).  The weights still go
 // straight from global memory into the MFMA A layout.  Workgroups are numbered so that the row blocks
 // of one weight group run next to each other on one XCD and find its weights in that L2.
-constexpr int kWdMC = 8, kWdNW = 3, kWdMW = 2;
+// With MW = 1 the six computing waves all take different weight tiles of one block of 8 column tiles:
+// the arrangement for up to 64 rows.
+constexpr int kWdMC = 8;
 constexpr int kWdS = 2, kWdNB = 4;                       // k-steps per chunk of B fragments, chunks resident in LDS
 constexpr int kWdRA = 4;                                 // k-steps of weight fragments requested ahead
-constexpr int kWdCompute = kWdNW * kWdMW;                // 6 of the 8 waves
-constexpr int kWdCols = kWdMW * kWdMC;                   // 16 column tiles per workgroup
-constexpr size_t kBatWideLds = (size_t)kWdNB * kWdS * kWdCols * 1024;  // 128 KB: four chunks of B fragments
+constexpr int kWdCompute = 6;                            // of the 8 waves: 3 x 2 (weight tiles x column tiles) or 6 x 1
+constexpr int kWdCols = 2 * kWdMC;                       // 16 column tiles per workgroup in the 3 x 2 arrangement
+constexpr size_t kBatWideLds = (size_t)kWdNB * kWdS * kWdCols * 1024;  // 128 KB: four chunks of B fragments (3 x 2); at
+                                                         // the end 16 KB per computing wave to turn its tiles around
 
 // NT: weight tiles per computing wave, 4 or 2 (2: half as many rows per workgroup, for projections with few tiles).
 // ksplit > 1: the reduction is cut into ksplit equal runs of chunks, one workgroup each; a workgroup then
 // stores its sums (part[split][unit][column tile][lane], the pair a lane would hand to the epilogue) and
 // bat_split_finish adds them in the order of the splits and applies the epilogue.  For projections with
 // so few weight tiles that one workgroup per tile group leaves most compute units idle (O-proj, down).
-template <int NT, bool WHOLE>
+template <int NT, bool WHOLE, int MW>
 __global__ __launch_bounds__(kBatThreads) __attribute__((amdgpu_waves_per_eu(2, 2))) void bat_gemm_wide(BatGemm g, int n_blk, int ksplit,
                                                                                                           float2 *part) {
   constexpr int MC = kWdMC, S = kWdS;
+  constexpr int NWV = kWdCompute / MW, COLS = MW * MC;     // waves across weight tiles; column tiles per workgroup
+  static_assert(MW == 1 || MW == 2, "wave arrangements");
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   const uint32_t smem_lds = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char *)smem;
   const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int lr = lane & 15, lg = lane >> 4;
   const bool filler = wave >= kWdCompute;
-  const int nwv = wave % kWdNW, mwv = filler ? 0 : wave / kWdNW;
+  const int nwv = wave % NWV, mwv = filler ? 0 : wave / NWV;
   const bool swiglu = g.epi == FEPI_SWIGLU;
-  const int upg = swiglu ? kWdNW * (NT / 2) : kWdNW * NT;          // units (tiles, or gate/up pairs) per workgroup
+  const int upg = swiglu ? NWV * (NT / 2) : NWV * NT;          // units (tiles, or gate/up pairs) per workgroup
   const int n_groups = (g.n_units + upg - 1) / upg;
   // workgroup -> (weight group, row block): the row blocks of a group differ by 8 in the launch order
   const int id = blockIdx.x, q = id >> 3;
@@ -475,8 +480,9 @@ __global__ __launch_bounds__(kBatThreads) __attribute__((amdgpu_waves_per_eu(2, 
   const int blk = inner % n_blk, split = inner / n_blk, grp = (q / (n_blk * ksplit)) * 8 + (id & 7);
   if (grp >= n_groups) return;
   const int total = (g.Kd + 31) / 32;
-  const int n_chunks = ((total + S - 1) / S) / ksplit;             // of this split (the host splits only what divides)
-  const int kbase = split * n_chunks * S;                          // its first k-step
+  const int all_chunks = (total + S - 1) / S, per = (all_chunks + ksplit - 1) / ksplit;
+  const int n_chunks = max(0, min(per, all_chunks - split * per)); // of this split (the last one may be shorter)
+  const int kbase = split * per * S;                               // its first k-step
   const size_t bstep = (size_t)2 * g.CTS * 256;
   // units of this wave's NT tiles (SwiGLU: tile t is matrix t & 1 of pair t >> 1)
   int unit_of[NT];
@@ -507,9 +513,9 @@ __global__ __launch_bounds__(kBatThreads) __attribute__((amdgpu_waves_per_eu(2, 
   if (filler) {
     wait_vmcnt_all();                                 // no wait of the compiler's between the transfers
     // this lane's piece of the B fragment of (k-step ks, column tile blk*16 + ct): bsrc + ks*bstep + ct*256
-    const uint16_t *bsrc = g.b + ((size_t)(lg >> 1) * g.CTS + (size_t)blk * kWdCols) * 256 + lr * 16 + (lg & 1) * 8;
+    const uint16_t *bsrc = g.b + ((size_t)(lg >> 1) * g.CTS + (size_t)blk * COLS) * 256 + lr * 16 + (lg & 1) * 8;
     constexpr int NF = kBatWaves - kWdCompute;                    // 2 filling waves
-    constexpr int OPS = S * kWdCols / NF;                         // transfers per wave and chunk
+    constexpr int OPS = S * COLS / NF;                         // transfers per wave and chunk
     // Chunks past the end are transferred too (from the all-zero k-step), so that the count of
     // transfers in flight is the same at every wait.
     auto fill = [&](int c) __attribute__((always_inline)) {
@@ -517,11 +523,11 @@ __global__ __launch_bounds__(kBatThreads) __attribute__((amdgpu_waves_per_eu(2, 
 #pragma unroll
       for (int o = 0; o < OPS; ++o) {
         const int op = o * NF + (wave - kWdCompute);
-        const int slot = op / kWdCols, ct = op % kWdCols;
+        const int slot = op / COLS, ct = op % COLS;
         const int ksl = c * S + slot;
         const int ks = (ksl < n_chunks * S && kbase + ksl < total) ? kbase + ksl : total;
         lds_dma16(bsrc + (size_t)ks * bstep + ct * 256,
-                  __builtin_amdgcn_readfirstlane(smem_lds + (uint32_t)(((buf * S + slot) * kWdCols + ct) * 1024)));
+                  __builtin_amdgcn_readfirstlane(smem_lds + (uint32_t)(((buf * S + slot) * COLS + ct) * 1024)));
       }
     };
 #pragma unroll
@@ -543,13 +549,13 @@ __global__ __launch_bounds__(kBatThreads) __attribute__((amdgpu_waves_per_eu(2, 
     lds_barrier();                                    // chunk 0 is in LDS
     constexpr int CPR = kWdRA / S;                    // chunks per revolution of the weight ring
     auto chunk = [&](int c, int cc) __attribute__((always_inline)) {
-      const unsigned char *bl = smem + ((size_t)((c % kWdNB) * S * kWdCols + mwv * MC)) * 1024 + lane * 16;
+      const unsigned char *bl = smem + ((size_t)((c % kWdNB) * S * COLS + mwv * MC)) * 1024 + lane * 16;
 #pragma unroll
       for (int s = 0; s < S; ++s) {
         const int u = cc * S + s;                     // ring slot of k-step c*S + s
         u32x4 Bf[MC];
 #pragma unroll
-        for (int ct = 0; ct < MC; ++ct) Bf[ct] = *reinterpret_cast<const u32x4 *>(bl + (size_t)(s * kWdCols + ct) * 1024);
+        for (int ct = 0; ct < MC; ++ct) Bf[ct] = *reinterpret_cast<const u32x4 *>(bl + (size_t)(s * COLS + ct) * 1024);
 #pragma unroll
         for (int t = 0; t < NT; ++t) {
 #pragma unroll
@@ -586,7 +592,7 @@ __global__ __launch_bounds__(kBatThreads) __attribute__((amdgpu_waves_per_eu(2, 
       if (swiglu && tt == 1) break;                   // a pair is emitted once, from its gate tile
       const int unit = unit_of[2 * h + tt];
       if (unit >= g.n_units) continue;                // uniform over the wave
-      const int ctg0 = blk * kWdCols + mwv * MC;
+      const int ctg0 = blk * COLS + mwv * MC;
       if (ksplit > 1) {                               // uniform: the sums go to bat_split_finish
 #pragma unroll
         for (int ct = 0; ct < MC; ++ct) {
@@ -632,11 +638,20 @@ __global__ __launch_bounds__(256) void bat_split_finish(BatGemm g, int ksplit, c
   const int ct = tile / g.n_units, unit = tile - ct * g.n_units;     // neighbouring waves: neighbouring columns of the same rows
   const int c2 = lane & 7, jm = lane >> 3;
   const EmitPre pre = bat_emit_load(g, unit, ct, jm, c2);
-  float2 s = part[((size_t)unit * g.CT + ct) * 64 + lane];
-  for (int k = 1; k < ksplit; ++k) {
-    const float2 v = part[(((size_t)k * g.n_units + unit) * g.CT + ct) * 64 + lane];
-    s.x += v.x;
-    s.y += v.y;
+  // eight runs are requested together (one round trip, not one per run) and added in the order of the runs
+  const size_t run_stride = (size_t)g.n_units * g.CT * 64;
+  const float2 *mine = part + ((size_t)unit * g.CT + ct) * 64 + lane;
+  float2 s = make_float2(0.f, 0.f);
+  for (int k0 = 0; k0 < ksplit; k0 += 8) {
+    float2 v[8];
+#pragma unroll
+    for (int k = 0; k < 8; ++k) v[k] = mine[(size_t)min(k0 + k, ksplit - 1) * run_stride];
+#pragma unroll
+    for (int k = 0; k < 8; ++k)
+      if (k0 + k < ksplit) {
+        s.x += v[k].x;
+        s.y += v[k].y;
+      }
   }
   bat_emit_apply(g, unit, ct, jm, c2, s.x, s.y, 0.f, 0.f, pre);
 }
