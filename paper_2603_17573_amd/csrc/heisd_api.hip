@@ -879,6 +879,8 @@ static void bat_wide_launch(const BatGemm &g, int mw, int n_cu, hipStream_t st, 
 }
 
 // Wave arrangement for CT column tiles: MW groups of MC tiles (MC from the compiled set).
+// (Gate/up at up to 64 rows stays on bat_gemm_ns: on the 6 x 1 wide kernel, which cannot split it,
+// it measured 60 against 49 us at 56 rows.)
 static void bat_launch(BatGemm g, int n_cu, hipStream_t st, const SplitRoom &room = SplitRoom()) {
   const int CT = g.CT;
   if (CT <= 8 && g.epi == FEPI_SWIGLU) {
