@@ -22,7 +22,7 @@
 namespace heisd {
 
 constexpr int kAttnQB = 8;  // queries per block
-constexpr int kAttnU = 6;   // cache rows a key stream requests at once
+constexpr int kAttnU = 6;   // cache rows a value stream requests at once
 
 __device__ __forceinline__ void attn_unpack8(const uint4 v, float (&f)[8]) {
   const uint32_t w[4] = {v.x, v.y, v.z, v.w};
@@ -203,22 +203,57 @@ __global__ __launch_bounds__(THREADS) __attribute__((amdgpu_waves_per_eu((THREAD
       for (int j = 1; j < kAttnQB; ++j) mine = (li == j) ? s[j] : mine;
       if (li < kAttnQB) sc[(size_t)li * cap + r] = vis ? mine : -INFINITY;
     };
-    // prefix rows (bf16, from the cache): kAttnU rows of this lane's stream are requested before
-    // the first is used, so a stream is a few round trips to memory instead of one per row
-    for (int r0 = g; r0 < P; r0 += G * kAttnU) {
-      uint4 kk[kAttnU];
+    // prefix rows (bf16, from the cache) on the matrix cores: a tile of 16 keys is the A operand of
+    // v_mfma_f32_16x16x32_bf16 straight from the cache (lane l: key l%16, 8 consecutive channels), the
+    // block's queries are the B operand, each fp32 query as a bf16 head (columns 0-7) and a bf16 tail
+    // (columns 8-15), kept in registers for the whole pass; lane l then holds the scores of keys
+    // 4*(l/16)..+3 against column l%16, and head and tail columns are added with one exchange.  (With
+    // plain FMAs every key cost 64 of them plus a 32-step butterfly over the 16 lanes that share a row.)
+    {
+      constexpr int KS = HD / 32;
+      const int lr = lane & 15, lg = lane >> 4;
+      typedef unsigned int attn_u32x4 __attribute__((ext_vector_type(4)));
+      attn_u32x4 qb[KS];
 #pragma unroll
-      for (int u = 0; u < kAttnU; ++u) {
-        const int r = r0 + u * G;
-        kk[u] = r < P ? *reinterpret_cast<const uint4 *>(kc + (size_t)r * HD + li * 8) : make_uint4(0, 0, 0, 0);
+      for (int ks = 0; ks < KS; ++ks) {
+        uint32_t w[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const float x0 = qs[(lr & 7) * HD + ks * 32 + lg * 8 + 2 * i], x1 = qs[(lr & 7) * HD + ks * 32 + lg * 8 + 2 * i + 1];
+          uint32_t h0, l0, h1, l1;
+          split_bf16(x0, h0, l0);
+          split_bf16(x1, h1, l1);
+          w[i] = lr < 8 ? (h0 | (h1 << 16)) : (l0 | (l1 << 16));
+        }
+        qb[ks] = attn_u32x4{w[0], w[1], w[2], w[3]};
       }
+      constexpr int TU = 2;                           // tiles a wave requests before it uses the first
+      const int n_tiles = (P + 15) / 16;
+      for (int t0 = wave; t0 < n_tiles; t0 += kAttnWaves * TU) {
+        attn_u32x4 kf[TU][KS];
 #pragma unroll
-      for (int u = 0; u < kAttnU; ++u) {
-        const int r = r0 + u * G;
-        if (r < P) {
-          float kf[8];
-          attn_unpack8(kk[u], kf);
-          score_key(kf, r, true);
+        for (int u = 0; u < TU; ++u) {
+          const int r = min((t0 + u * kAttnWaves) * 16 + lr, P - 1);      // rows past the prefix repeat its last row
+#pragma unroll
+          for (int ks = 0; ks < KS; ++ks)
+            kf[u][ks] = *reinterpret_cast<const attn_u32x4 *>(kc + (size_t)r * HD + ks * 32 + lg * 8);
+        }
+#pragma unroll
+        for (int u = 0; u < TU; ++u) {
+          const int t = t0 + u * kAttnWaves;
+          if (t < n_tiles) {                          // uniform over the wave
+            f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks)
+              acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, kf[u][ks]), __builtin_bit_cast(bf16x8, qb[ks]),
+                                                            acc, 0, 0, 0);
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+              const float v = acc[i] + __shfl_xor(acc[i], 8, kWave);     // head column + tail column
+              const int r = t * 16 + lg * 4 + i;
+              if (lr < kAttnQB && r < P) sc[(size_t)lr * cap + r] = v;
+            }
+          }
         }
       }
     }
