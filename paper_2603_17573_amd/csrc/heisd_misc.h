@@ -288,23 +288,40 @@ __global__ __launch_bounds__(256) void tree_accept(TreeAcceptArgs a) {
     }
     return;
   }
-  // greedy bin after every token: one wave per row, lowest index wins ties, NaN never wins
-  for (int j = wave; j < T; j += 4) {
-    const float *row = a.logits + ((size_t)b * T + j) * a.n_bins;
-    float best = -INFINITY;
-    int bi = 0x7FFFFFFF;
+  // greedy bin after every token: one wave per row, lowest index wins ties, NaN never wins.  A wave takes
+  // kRows rows at a time and requests a slice of all of them before it compares anything: one row at a time
+  // is one memory round trip per row (76 rows: 19 per wave, 38 of the kernel's 48 us).
+  constexpr int kRows = 8;
+  for (int j0 = wave * kRows; j0 < T; j0 += 4 * kRows) {
+    float best[kRows];
+    int bi[kRows];
+#pragma unroll
+    for (int u = 0; u < kRows; ++u) {
+      best[u] = -INFINITY;
+      bi[u] = 0x7FFFFFFF;
+    }
     for (int t = lane; t < a.n_bins; t += kWave) {
-      float v = row[t];
-      if (v != v) v = -INFINITY;
-      if (v > best || (v == best && t < bi)) { best = v; bi = t; }
+      float v[kRows];
+#pragma unroll
+      for (int u = 0; u < kRows; ++u)
+        v[u] = a.logits[((size_t)b * T + min(j0 + u, T - 1)) * a.n_bins + t];
+#pragma unroll
+      for (int u = 0; u < kRows; ++u) {
+        float x = v[u];
+        if (x != x) x = -INFINITY;
+        if (x > best[u] || (x == best[u] && t < bi[u])) { best[u] = x; bi[u] = t; }
+      }
     }
 #pragma unroll
-    for (int o = 32; o > 0; o >>= 1) {
-      const float ov = __shfl_xor(best, o, kWave);
-      const int oi = __shfl_xor(bi, o, kWave);
-      if (ov > best || (ov == best && oi < bi)) { best = ov; bi = oi; }
+    for (int u = 0; u < kRows; ++u) {
+#pragma unroll
+      for (int o = 32; o > 0; o >>= 1) {
+        const float ov = __shfl_xor(best[u], o, kWave);
+        const int oi = __shfl_xor(bi[u], o, kWave);
+        if (ov > best[u] || (ov == best[u] && oi < bi[u])) { best[u] = ov; bi[u] = oi; }
+      }
+      if (lane == 0 && j0 + u < T) s_pred[j0 + u] = (bi[u] == 0x7FFFFFFF) ? 0 : bi[u];
     }
-    if (lane == 0) s_pred[j] = (bi == 0x7FFFFFFF) ? 0 : bi;
   }
   __syncthreads();
   const int fp = a.first_pred[b];
