@@ -114,6 +114,17 @@ def test_split_reductions(B, K):
     run_case(wl)
 
 
+@pytest.mark.parametrize("B,K", [(17, 1), (3, 8), (3, 11), (5, 8), (8, 8), (5, 13), (9, 8), (16, 8), (43, 3), (17, 8)])
+def test_row_counts_at_the_dispatch_boundaries(B, K):
+    """17, 24, 33, 40, 64, 65, 72, 128, 129 and 136 rows on the shape whose reductions get split: the row
+    counts on either side of the points where the launcher changes kernel or wave arrangement (6 x 1 wide
+    kernel from 17 and 33 rows, 3 x 2 from 65, a second block of column tiles from 129), with full and
+    ragged last column tiles."""
+    wl = synth.Workload("edge_%dx%d" % (B, K), SPLIT, 3, 7, SPLIT.bin_base, batch=B, K=K,
+                        draft=("geometric", 0.5), seed=5 * B + K)
+    run_case(wl)
+
+
 def test_context_sized_for_more_rows_than_the_call_uses():
     """A context initialised for 12 episodes verifies 3 (the record stride is that of the context,
     the column-tile count that of the call), on the automatic path and on the <=8-row path."""
