@@ -454,6 +454,64 @@ constexpr int kWdCols = 2 * kWdMC;                       // 16 column tiles per 
 constexpr size_t kBatWideLds = (size_t)kWdNB * kWdS * kWdCols * 1024;  // 128 KB: four chunks of B fragments (3 x 2); at
                                                          // the end 16 KB per computing wave to turn its tiles around
 
+// The end of a wide-GEMM wave: its NT x 8 accumulator tiles are turned around through `mine` (16 KB of LDS
+// of its own), two weight tiles at a time, so that a lane holds the pairs the epilogue works on; then the
+// projection's epilogue, or, in a split reduction, the store of the run's sums.  ctg0: first of the wave's 8
+// column tiles.
+template <int NT>
+__device__ __forceinline__ void bat_wide_finish_wave(const BatGemm &g, f32x4 (&acc)[NT][kWdMC], const int (&unit_of)[NT], float *mine,
+                                                     int ctg0, int lane, bool swiglu, int split, int ksplit, float2 *part) {
+  constexpr int MC = kWdMC;
+  const int c2 = lane & 7, jm = lane >> 3, i = 2 * c2;
+  const int l_hi = (i >> 2) * 16 + jm, r = i & 3;
+#pragma unroll
+  for (int h = 0; h < NT / 2; ++h) {                  // two tiles at a time: 16 KB of LDS per wave
+#pragma unroll
+    for (int tt = 0; tt < 2; ++tt)
+#pragma unroll
+      for (int ct = 0; ct < MC; ++ct)
+        *reinterpret_cast<f32x4 *>(mine + ((size_t)(tt * MC + ct) * 64 + lane) * 4) = acc[2 * h + tt][ct];
+#pragma unroll
+    for (int tt = 0; tt < 2; ++tt) {
+      if (swiglu && tt == 1) break;                   // a pair is emitted once, from its gate tile
+      const int unit = unit_of[2 * h + tt];
+      if (unit >= g.n_units) continue;                // uniform over the wave
+      if (ksplit > 1) {                               // uniform: the sums go to bat_split_finish
+#pragma unroll
+        for (int ct = 0; ct < MC; ++ct) {
+          const int ctg = ctg0 + ct;
+          if (ctg >= g.CT) continue;
+          const float *p = mine + ((size_t)(tt * MC + ct) * 64) * 4;
+          const float2 a = *reinterpret_cast<const float2 *>(p + l_hi * 4 + r);
+          const float2 b = *reinterpret_cast<const float2 *>(p + (l_hi + 8) * 4 + r);
+          part[(((size_t)split * g.n_units + unit) * g.CT + ctg) * 64 + lane] = make_float2(a.x + b.x, a.y + b.y);
+        }
+        continue;
+      }
+      EmitPre pre[MC];                                // everything the tile's 8 column tiles read, requested before the first store
+#pragma unroll
+      for (int ct = 0; ct < MC; ++ct) pre[ct] = bat_emit_load(g, unit, min(ctg0 + ct, g.CT - 1), jm, c2);
+#pragma unroll
+      for (int ct = 0; ct < MC; ++ct) {
+        const int ctg = ctg0 + ct;
+        if (ctg >= g.CT) continue;                    // uniform over the wave
+        const float *p = mine + ((size_t)(tt * MC + ct) * 64) * 4;
+        const float2 a = *reinterpret_cast<const float2 *>(p + l_hi * 4 + r);
+        const float2 b = *reinterpret_cast<const float2 *>(p + (l_hi + 8) * 4 + r);
+        float u0 = 0.f, u1 = 0.f;
+        if (swiglu) {
+          const float *qq = p + (size_t)MC * 256;
+          const float2 cg = *reinterpret_cast<const float2 *>(qq + l_hi * 4 + r);
+          const float2 dg = *reinterpret_cast<const float2 *>(qq + (l_hi + 8) * 4 + r);
+          u0 = cg.x + dg.x;
+          u1 = cg.y + dg.y;
+        }
+        bat_emit_apply(g, unit, ctg, jm, c2, a.x + b.x, a.y + b.y, u0, u1, pre[ct]);
+      }
+    }
+  }
+}
+
 // NT: weight tiles per computing wave, 4 or 2 (2: half as many rows per workgroup, for projections with few tiles).
 // ksplit > 1: the reduction is cut into ksplit equal runs of chunks, one workgroup each; a workgroup then
 // stores its sums (part[split][unit][column tile][lane], the pair a lane would hand to the epilogue) and
@@ -577,56 +635,8 @@ __global__ __launch_bounds__(kBatThreads) __attribute__((amdgpu_waves_per_eu(2, 
   }
   lds_barrier();                                      // the B buffers are free: every wave turns its own tiles around in them
   if (filler) return;
-  float *mine = reinterpret_cast<float *>(smem + (size_t)wave * (2 * MC * 1024));
-  const int c2 = lane & 7, jm = lane >> 3, i = 2 * c2;
-  const int l_hi = (i >> 2) * 16 + jm, r = i & 3;
-#pragma unroll
-  for (int h = 0; h < NT / 2; ++h) {                  // two tiles at a time: 16 KB of LDS per wave
-#pragma unroll
-    for (int tt = 0; tt < 2; ++tt)
-#pragma unroll
-      for (int ct = 0; ct < MC; ++ct)
-        *reinterpret_cast<f32x4 *>(mine + ((size_t)(tt * MC + ct) * 64 + lane) * 4) = acc[2 * h + tt][ct];
-#pragma unroll
-    for (int tt = 0; tt < 2; ++tt) {
-      if (swiglu && tt == 1) break;                   // a pair is emitted once, from its gate tile
-      const int unit = unit_of[2 * h + tt];
-      if (unit >= g.n_units) continue;                // uniform over the wave
-      const int ctg0 = blk * COLS + mwv * MC;
-      if (ksplit > 1) {                               // uniform: the sums go to bat_split_finish
-#pragma unroll
-        for (int ct = 0; ct < MC; ++ct) {
-          const int ctg = ctg0 + ct;
-          if (ctg >= g.CT) continue;
-          const float *p = mine + ((size_t)(tt * MC + ct) * 64) * 4;
-          const float2 a = *reinterpret_cast<const float2 *>(p + l_hi * 4 + r);
-          const float2 b = *reinterpret_cast<const float2 *>(p + (l_hi + 8) * 4 + r);
-          part[(((size_t)split * g.n_units + unit) * g.CT + ctg) * 64 + lane] = make_float2(a.x + b.x, a.y + b.y);
-        }
-        continue;
-      }
-      EmitPre pre[MC];                                // everything the tile's 8 column tiles read, requested before the first store
-#pragma unroll
-      for (int ct = 0; ct < MC; ++ct) pre[ct] = bat_emit_load(g, unit, min(ctg0 + ct, g.CT - 1), jm, c2);
-#pragma unroll
-      for (int ct = 0; ct < MC; ++ct) {
-        const int ctg = ctg0 + ct;
-        if (ctg >= g.CT) continue;                    // uniform over the wave
-        const float *p = mine + ((size_t)(tt * MC + ct) * 64) * 4;
-        const float2 a = *reinterpret_cast<const float2 *>(p + l_hi * 4 + r);
-        const float2 b = *reinterpret_cast<const float2 *>(p + (l_hi + 8) * 4 + r);
-        float u0 = 0.f, u1 = 0.f;
-        if (swiglu) {
-          const float *qq = p + (size_t)MC * 256;
-          const float2 cg = *reinterpret_cast<const float2 *>(qq + l_hi * 4 + r);
-          const float2 dg = *reinterpret_cast<const float2 *>(qq + (l_hi + 8) * 4 + r);
-          u0 = cg.x + dg.x;
-          u1 = cg.y + dg.y;
-        }
-        bat_emit_apply(g, unit, ctg, jm, c2, a.x + b.x, a.y + b.y, u0, u1, pre[ct]);
-      }
-    }
-  }
+  bat_wide_finish_wave<NT>(g, acc, unit_of, reinterpret_cast<float *>(smem + (size_t)wave * (2 * MC * 1024)), blk * COLS + mwv * MC,
+                           lane, swiglu, split, ksplit, part);
 }
 
 // Second half of a split reduction: one wave per (column tile, unit); lane (jm, c2) adds the pair of every
