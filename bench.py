@@ -62,8 +62,9 @@ def read_traffic(kclass):
 def run_aux_mode(args):
     """--mode decode: the autoregressive decode step (Eq. 2-1; the fallback of Sec. 4.2 and the baseline
     speculative decoding replaces): one new token per episode through heisd_prefill_chunk.
-    --mode prefill: the workload's whole prefix from an empty cache, visual rows as one chunk of
-    embeddings, prompt ids as a second chunk.  Same JSON schema as the verify line."""
+    --mode prefill: the workload's whole prefix from an empty cache in one chunk, visual rows as
+    embeddings and prompt rows as token ids in the same call (--prefill-chunks 2: the visual rows as one
+    chunk, the prompt ids as a second: two passes over the weights).  Same JSON schema as the verify line."""
     import numpy as np
     import torch
     import synth
@@ -75,7 +76,8 @@ def run_aux_mode(args):
     sh = wl.shape
     B, P = wl.batch, wl.prefix_len
     decode = args.mode == "decode"
-    chunks = [1] if decode else [c for c in (wl.n_visual, wl.n_text) if c]
+    one_chunk = not decode and args.prefill_chunks == 1 and wl.n_visual and wl.n_text
+    chunks = [1] if decode else ([P] if one_chunk else [c for c in (wl.n_visual, wl.n_text) if c])
     cap = P + 1
     weights = synth.make_weights(sh, wl.seed)
     ver = Verifier(DeviceModel(sh, weights, dev), B, max(chunks), cap)
@@ -94,10 +96,18 @@ def run_aux_mode(args):
         calls.append((torch.full((B,), P, dtype=torch.int32, device=dev), {"token_ids": ids}))
     else:
         inputs = [synth.make_prefix_inputs(wl, e) for e in range(B)]
-        if wl.n_visual:
+        if one_chunk:
+            x = np.zeros((B, P, sh.d_model), np.float32)
+            t = np.full((B, P), -1, np.int32)                 # -1: the row takes its embedding
+            for e, (emb, ids) in enumerate(inputs):
+                x[e, :wl.n_visual] = emb
+                t[e, wl.n_visual:] = ids
+            calls.append((torch.zeros(B, dtype=torch.int32, device=dev),
+                          {"x_rows": torch.from_numpy(x).to(dev), "token_ids": torch.from_numpy(t).to(dev)}))
+        elif wl.n_visual:
             x = np.stack([emb for emb, _ in inputs]).astype(np.float32)
             calls.append((torch.zeros(B, dtype=torch.int32, device=dev), {"x_rows": torch.from_numpy(x).to(dev)}))
-        if wl.n_text:
+        if wl.n_text and not one_chunk:
             t = np.stack([ids for _, ids in inputs]).astype(np.int32)
             calls.append((torch.full((B,), wl.n_visual, dtype=torch.int32, device=dev),
                           {"token_ids": torch.from_numpy(t).to(dev)}))
@@ -322,6 +332,8 @@ def main():
     ap.add_argument("--tree", type=int, default=0, metavar="R",
                     help="time the TREE verify step instead: R retrieved candidates per episode, built into a "
                          "sequence-wise draft tree (paper Sec. 4.2); 0 = the linear step")
+    ap.add_argument("--prefill-chunks", type=int, default=1, choices=[1, 2],
+                    help="--mode prefill: 1 = visual embeddings and prompt ids in one call (default), 2 = one call each")
     ap.add_argument("--mode", default="verify", choices=["verify", "decode", "prefill", "skip", "retrieve"],
                     help="verify (default): the verify step; decode: one autoregressive decode step; prefill: the "
                          "workload's prefix from an empty cache, in chunks")

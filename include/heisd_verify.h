@@ -50,7 +50,7 @@ typedef struct {
   float rms_eps;          /* RMSNorm epsilon                                               */
   float rope_base;        /* rotary base (rotate-half pairing, absolute positions)         */
   int32_t max_batch;      /* largest `batch` a step may pass                               */
-  int32_t max_k;          /* largest `K` a step may pass                                   */
+  int32_t max_k;          /* largest `K` a step may pass (<= 1024; tree steps: <= 256)     */
   int32_t kv_capacity;    /* rows per (layer, episode, head) in the caller's KV cache      */
   const void *tok_emb;    /* DEVICE bf16 [vocab, d_model]                                  */
   const void *const *wq, *const *wk, *const *wv, *const *wo;    /* HOST tables of DEVICE bf16 [d_model, d_model] */
@@ -120,7 +120,7 @@ size_t heisd_verify_workspace_bytes(const heisd_model_desc *desc);
  * with heisd_free.  Not thread-safe; one step in flight per context.
  * Errors: EINVAL (NULL pointers, non-positive sizes, d_model != n_heads*head_dim,
  * bins outside the vocabulary), EUNSUPPORTED (head_dim not 64 or 128, d_model or d_ffn
- * or n_bins not a multiple of 16, max_k > 256, kv_capacity > 4096), ENOMEM (workspace too
+ * or n_bins not a multiple of 16, max_k > 1024, kv_capacity > 4096), ENOMEM (workspace too
  * small), EHIP.
  */
 int heisd_verify_init(const heisd_model_desc *desc, heisd_verify_ctx **out);
@@ -222,12 +222,15 @@ int heisd_build_sequence_tree(const int32_t *candidates, int32_t R, int32_t K, c
  *     the token just produced; `next_bin` is the next action token's bin.
  *
  *   token_ids    DEVICE i32 [batch][n_rows]            vocabulary ids, or NULL
- *   x_rows       DEVICE f32 [batch][n_rows][d_model]   input embeddings, or NULL; exactly one is given
+ *   x_rows       DEVICE f32 [batch][n_rows][d_model]   input embeddings, or NULL.  One of the two, or both:
+ *                with both, a row whose token id is negative takes its embedding from x_rows and every other
+ *                row is looked up, so that visual and prompt rows can share a chunk (one pass over the
+ *                weights instead of two)
  *   next_bin     DEVICE i32 [batch] out                greedy bin after the last new row
  *   last_logits  DEVICE f32 [batch][n_bins] out, optional (NULL ok)
  * Cache rows prefix_len[b] .. prefix_len[b]+n_rows-1 are written; the library does not advance
  * prefix_len (the caller adds n_rows).  kv->first_pred is not read.  Asynchronous, allocates nothing.
- * Errors (nothing enqueued): EINVAL for NULL required pointers, both or neither input given, n_rows or
+ * Errors (nothing enqueued): EINVAL for NULL required pointers, neither input given, n_rows or
  * batch outside [1, max_k] x [1, max_batch]; EUNSUPPORTED when the context is pinned to the <= 8-row
  * kernels and the call has more rows or embeddings as input; EHIP.
  */

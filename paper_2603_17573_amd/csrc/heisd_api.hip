@@ -566,7 +566,7 @@ extern "C" int heisd_verify_init(const heisd_model_desc *desc, heisd_verify_ctx 
     return fail(nullptr, HEISD_EUNSUPPORTED, "init: head_dim %d (64 or 128 supported)", desc->head_dim);
   if (desc->d_model % 16 || desc->d_ffn % 16 || desc->n_bins % 16)
     return fail(nullptr, HEISD_EUNSUPPORTED, "init: d_model, d_ffn and n_bins must be multiples of 16");
-  if (desc->max_k > 256) return fail(nullptr, HEISD_EUNSUPPORTED, "init: max_k %d > 256", desc->max_k);
+  if (desc->max_k > 1024) return fail(nullptr, HEISD_EUNSUPPORTED, "init: max_k %d > 1024", desc->max_k);
   if (desc->kv_capacity > 4096)
     return fail(nullptr, HEISD_EUNSUPPORTED, "init: kv_capacity %d > 4096", desc->kv_capacity);
   if (((uintptr_t)desc->workspace & 255) != 0) return fail(nullptr, HEISD_EINVAL, "init: workspace not 256-byte aligned");
@@ -1016,11 +1016,11 @@ static void generic_forward(heisd_verify_ctx *ctx, const heisd_kv_desc *kv, cons
   const int M = batch * K, dm = d.d_model, F = d.d_ffn, H = d.n_heads, HD = d.head_dim, cap = d.kv_capacity;
   {
     ProfScope ps(ctx, HEISD_KC_EMBED, st, prof);
-    if (x_rows)
+    if (x_rows && !draft_tokens)
       (void)hipMemcpyAsync(ctx->x, x_rows, (size_t)M * dm * sizeof(float), hipMemcpyDeviceToDevice, st);
     else
       embed_rows<<<dim3(M), dim3(256), 0, st>>>(draft_tokens, static_cast<const uint16_t *>(d.tok_emb), d.vocab, dm,
-                                                ctx->x);
+                                                ctx->x, x_rows);
   }
   const size_t layer_stride = (size_t)batch * H * cap * HD;
   for (int l = 0; l < d.n_layers; ++l) {
@@ -1285,8 +1285,8 @@ extern "C" int heisd_prefill_chunk(heisd_verify_ctx *ctx, const heisd_kv_desc *k
   if (!ctx) return HEISD_EINVAL;
   if (!kv || !kv->k_cache || !kv->v_cache || !kv->prefix_len || !next_bin)
     return fail(ctx, HEISD_EINVAL, "prefill_chunk: NULL required pointer");
-  if ((token_ids == nullptr) == (x_rows == nullptr))
-    return fail(ctx, HEISD_EINVAL, "prefill_chunk: exactly one of token_ids and x_rows must be given");
+  if (!token_ids && !x_rows)
+    return fail(ctx, HEISD_EINVAL, "prefill_chunk: token_ids, x_rows or both must be given");
   const heisd_model_desc &d = ctx->d;
   if (n_rows < 1 || batch < 1 || n_rows > d.max_k || batch > d.max_batch || n_rows > d.kv_capacity)
     return fail(ctx, HEISD_EINVAL, "prefill_chunk: n_rows=%d batch=%d outside [1,%d] x [1,%d] (kv_capacity %d)", n_rows,
@@ -1296,7 +1296,7 @@ extern "C" int heisd_prefill_chunk(heisd_verify_ctx *ctx, const heisd_kv_desc *k
   (void)hipGetLastError();
   const bool prof = ctx->prof_on && ctx->prof_steps < HEISD_PROFILE_MAX_STEPS;
   if (prof) ctx->prof_steps++;
-  const bool use_fast = ctx->fast_ok && M <= 8 && token_ids && ctx->path != HEISD_PATH_GENERIC && ctx->path != HEISD_PATH_BATCH;
+  const bool use_fast = ctx->fast_ok && M <= 8 && token_ids && !x_rows && ctx->path != HEISD_PATH_GENERIC && ctx->path != HEISD_PATH_BATCH;
   if ((ctx->path == HEISD_PATH_FAST || ctx->path == HEISD_PATH_PERSIST) && !use_fast)
     return fail(ctx, HEISD_EUNSUPPORTED, "prefill_chunk: the selected path serves token rows with batch*n_rows <= 8 only");
   if (use_fast)

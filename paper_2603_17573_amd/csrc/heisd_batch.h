@@ -669,7 +669,8 @@ __global__ __launch_bounds__(256) void bat_split_finish(BatGemm g, int ksplit, c
 // ---- embedding: x rows (fp32), records of x*gain, partial sums of squares --------------------------
 // One 16-column tile per workgroup (64 threads); thread (c2, jm) walks the column tiles.  With `rows`
 // given the input rows are taken from there (fp32 [M][d]: visual tokens arrive as embeddings, App. A.1)
-// instead of being looked up.
+// instead of being looked up; with both `ids` and `rows`, row m is looked up if ids[m] >= 0 and taken from
+// `rows` otherwise.
 __global__ __launch_bounds__(64) void bat_embed(const int32_t *ids, const float *rows, const uint16_t *emb, int vocab, int d,
                                                 int M, int CT, int CTS, const float *gain, float *x, uint16_t *planes,
                                                 float *ssq_out) {
@@ -681,7 +682,7 @@ __global__ __launch_bounds__(64) void bat_embed(const int32_t *ids, const float 
     const int m = ct * 8 + jm;
     float v0 = 0.f, v1 = 0.f;
     if (m < M) {
-      if (rows) {
+      if (rows && (!ids || ids[m] < 0)) {           // both given: a negative id takes the row's embedding
         const float2 r = *reinterpret_cast<const float2 *>(rows + (size_t)m * d + col);
         v0 = r.x;
         v1 = r.y;

@@ -6,10 +6,16 @@
 namespace heisd {
 
 // x[m][:] = E[clamp(id[m])][:]  (token embeddings e_t of Eq. 2-2), bf16 -> fp32.
+// With `rows` (fp32 [M][d]) a row whose id is negative is copied from there instead.
 __global__ __launch_bounds__(256) void embed_rows(const int32_t *ids, const uint16_t *emb, int vocab,
-                                                 int d, float *x) {
+                                                 int d, float *x, const float *rows = nullptr) {
   const int m = blockIdx.x;
   int id = ids[m];
+  if (rows && id < 0) {                               // uniform over the workgroup
+    for (int k = threadIdx.x * 4; k < d; k += 256 * 4)
+      *reinterpret_cast<float4 *>(x + (size_t)m * d + k) = *reinterpret_cast<const float4 *>(rows + (size_t)m * d + k);
+    return;
+  }
   id = max(0, min(id, vocab - 1));
   const uint16_t *src = emb + (size_t)id * d;
   for (int k = threadIdx.x * 8; k < d; k += 256 * 8) {

@@ -116,8 +116,9 @@ class Verifier:
 
     def prefill_chunk(self, k_cache, v_cache, prefix_len, token_ids=None, x_rows=None, want_logits=False,
                       out=None, stream=None):
-        """token_ids i32[batch,n] or x_rows f32[batch,n,d] on the device (exactly one).  Returns dict of
-        device tensors: next_bin i32[batch] (and last_logits f32[batch,n_bins])."""
+        """token_ids i32[batch,n], x_rows f32[batch,n,d] on the device, or both (then a row whose id is
+        negative takes its embedding from x_rows).  Returns dict of device tensors: next_bin i32[batch]
+        (and last_logits f32[batch,n_bins])."""
         src = token_ids if token_ids is not None else x_rows
         batch, n = src.shape[0], src.shape[1]
         dev = self.model.device

@@ -40,9 +40,18 @@ def chunk_inputs(wl, episodes, p, n, dev="cuda:0"):
     if p + n <= wl.n_visual:
         x = np.stack([emb[p:p + n] for emb, _ in inputs]).astype(np.float32)
         return {"x_rows": torch.from_numpy(x).to(dev)}
-    assert p >= wl.n_visual, "a chunk may not straddle the visual/text boundary"
-    ids = np.stack([t[p - wl.n_visual:p - wl.n_visual + n] for _, t in inputs]).astype(np.int32)
-    return {"token_ids": torch.from_numpy(ids).to(dev)}
+    if p >= wl.n_visual:
+        ids = np.stack([t[p - wl.n_visual:p - wl.n_visual + n] for _, t in inputs]).astype(np.int32)
+        return {"token_ids": torch.from_numpy(ids).to(dev)}
+    # the chunk straddles the boundary: both inputs, id -1 marks a row that takes its embedding; the
+    # embedding rows of the looked-up tokens are NaN (they must not be read)
+    nv = wl.n_visual - p
+    x = np.full((len(inputs), n, wl.shape.d_model), np.nan, np.float32)
+    ids = np.full((len(inputs), n), -1, np.int32)
+    for i, (emb, t) in enumerate(inputs):
+        x[i, :nv] = emb[p:]
+        ids[i, nv:] = t[:n - nv]
+    return {"x_rows": torch.from_numpy(x).to(dev), "token_ids": torch.from_numpy(ids).to(dev)}
 
 
 def gpu_chunked_prefill(ver, wl, episodes, chunks, cap, dev="cuda:0"):
@@ -136,9 +145,26 @@ def test_visual_rows_as_embeddings_then_text_ids_two_episodes():
     run_prefill_case(wl, [16, 14, 11])
 
 
+@pytest.mark.parametrize("path", [0, 1, 4])
+def test_visual_and_text_rows_in_one_chunk(path):
+    """Both inputs in one call: the rows with token id -1 take their embeddings, the others are looked
+    up (their embedding rows are NaN in the test).  The whole prefix as one chunk, and a split that
+    leaves the boundary inside the second chunk."""
+    wl = synth.Workload("pf_mixed", MID, 30, 11, MID.bin_base, batch=2, K=7, seed=53)
+    run_prefill_case(wl, [41], path=path)
+    run_prefill_case(wl, [20, 21], path=path)
+
+
 def test_chunk_of_256_rows():
     wl = synth.Workload("pf_256", SMALL64, 256, 20, SMALL64.bin_base, batch=1, K=7, seed=43)
     run_prefill_case(wl, [256, 20])
+
+
+def test_whole_prefix_of_276_rows_as_one_chunk():
+    """The paper's prefix shape (256 visual + 20 prompt rows) in a single call: more than 256 rows per
+    episode, embeddings and token ids mixed."""
+    wl = synth.Workload("pf_276", SMALL64, 256, 20, SMALL64.bin_base, batch=1, K=7, seed=44)
+    run_prefill_case(wl, [276])
 
 
 def test_autoregressive_decode_steps():
@@ -201,8 +227,7 @@ def test_prefill_argument_errors():
     def call(tok=ids.data_ptr(), rows=None, n=16, batch=2, out=nb.data_ptr()):
         return B.heisd_prefill_chunk(ver.ctx, kv, tok, rows, n, batch, out, None, None)
 
-    assert call(rows=x.data_ptr()) == B.HEISD_EINVAL            # both inputs
-    assert call(tok=None) == B.HEISD_EINVAL                     # neither
+    assert call(tok=None) == B.HEISD_EINVAL                     # neither input
     assert call(n=17) == B.HEISD_EINVAL and call(n=0) == B.HEISD_EINVAL and call(batch=3) == B.HEISD_EINVAL
     assert call(out=None) == B.HEISD_EINVAL
     assert B.heisd_verify_set_path(ver.ctx, B.HEISD_PATH_FAST) == 0
@@ -211,6 +236,7 @@ def test_prefill_argument_errors():
     torch.cuda.synchronize()
     assert nb.tolist() == [-7, -7]
     assert call() == B.HEISD_OK and call(tok=None, rows=x.data_ptr()) == B.HEISD_OK
+    assert call(rows=x.data_ptr()) == B.HEISD_OK                # both inputs: ids >= 0 are looked up
     torch.cuda.synchronize()
     assert all(0 <= v < 256 for v in nb.tolist())
     ver.close()
