@@ -755,6 +755,18 @@ static hipError_t bat_prepare_mc() {
                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)bat_lds_bytes<MC>());
 }
 
+template <int MC>
+static void bat_wide_variants(std::vector<const void *> &v) {
+  v.push_back(reinterpret_cast<const void *>(&bat_gemm_wide<4, false, 2, MC>));
+  v.push_back(reinterpret_cast<const void *>(&bat_gemm_wide<4, true, 2, MC>));
+  v.push_back(reinterpret_cast<const void *>(&bat_gemm_wide<2, false, 2, MC>));
+  v.push_back(reinterpret_cast<const void *>(&bat_gemm_wide<2, true, 2, MC>));
+  v.push_back(reinterpret_cast<const void *>(&bat_gemm_wide<4, false, 1, MC>));
+  v.push_back(reinterpret_cast<const void *>(&bat_gemm_wide<4, true, 1, MC>));
+  v.push_back(reinterpret_cast<const void *>(&bat_gemm_wide<2, false, 1, MC>));
+  v.push_back(reinterpret_cast<const void *>(&bat_gemm_wide<2, true, 1, MC>));
+}
+
 static hipError_t bat_prepare() {
   hipError_t e;
   if ((e = bat_prepare_mc<2>()) != hipSuccess) return e;
@@ -764,10 +776,11 @@ static hipError_t bat_prepare() {
   if ((e = bat_prepare_mc<6>()) != hipSuccess) return e;
   if ((e = bat_prepare_mc<7>()) != hipSuccess) return e;
   if ((e = bat_prepare_mc<8>()) != hipSuccess) return e;
-  const void *wide[] = {reinterpret_cast<const void *>(&bat_gemm_wide<4, false, 2>), reinterpret_cast<const void *>(&bat_gemm_wide<4, true, 2>),
-                        reinterpret_cast<const void *>(&bat_gemm_wide<2, false, 2>), reinterpret_cast<const void *>(&bat_gemm_wide<2, true, 2>),
-                        reinterpret_cast<const void *>(&bat_gemm_wide<4, false, 1>), reinterpret_cast<const void *>(&bat_gemm_wide<4, true, 1>),
-                        reinterpret_cast<const void *>(&bat_gemm_wide<2, false, 1>), reinterpret_cast<const void *>(&bat_gemm_wide<2, true, 1>)};
+  std::vector<const void *> wide;
+  bat_wide_variants<5>(wide);
+  bat_wide_variants<6>(wide);
+  bat_wide_variants<7>(wide);
+  bat_wide_variants<8>(wide);
   for (const void *f : wide)
     if ((e = hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kBatWideLds)) != hipSuccess) return e;
   return bat_ns_prepare();
@@ -828,20 +841,41 @@ struct SplitRoom {
 
 // bat_gemm_wide in the arrangement MW (2: blocks of 16 column tiles, 1: blocks of 8), nt weight tiles per
 // wave and the reduction in ks runs.
-template <int MW>
+template <int MW, int MC>
 static void bat_wide_launch_t(const BatGemm &g, int nt, int ks, bool whole, int grid, int n_blk, float2 *part, hipStream_t st) {
   const dim3 gr(grid), bl(kBatThreads);
   if (nt == 4) {
-    if (whole) bat_gemm_wide<4, true, MW><<<gr, bl, kBatWideLds, st>>>(g, n_blk, ks, part);
-    else bat_gemm_wide<4, false, MW><<<gr, bl, kBatWideLds, st>>>(g, n_blk, ks, part);
+    if (whole) bat_gemm_wide<4, true, MW, MC><<<gr, bl, kBatWideLds, st>>>(g, n_blk, ks, part);
+    else bat_gemm_wide<4, false, MW, MC><<<gr, bl, kBatWideLds, st>>>(g, n_blk, ks, part);
   } else {
-    if (whole) bat_gemm_wide<2, true, MW><<<gr, bl, kBatWideLds, st>>>(g, n_blk, ks, part);
-    else bat_gemm_wide<2, false, MW><<<gr, bl, kBatWideLds, st>>>(g, n_blk, ks, part);
+    if (whole) bat_gemm_wide<2, true, MW, MC><<<gr, bl, kBatWideLds, st>>>(g, n_blk, ks, part);
+    else bat_gemm_wide<2, false, MW, MC><<<gr, bl, kBatWideLds, st>>>(g, n_blk, ks, part);
+  }
+}
+template <int MW>
+static void bat_wide_launch_mc(int mc, const BatGemm &g, int nt, int ks, bool whole, int grid, int n_blk, float2 *part, hipStream_t st) {
+  switch (mc) {
+    case 5: bat_wide_launch_t<MW, 5>(g, nt, ks, whole, grid, n_blk, part, st); break;
+    case 6: bat_wide_launch_t<MW, 6>(g, nt, ks, whole, grid, n_blk, part, st); break;
+    case 7: bat_wide_launch_t<MW, 7>(g, nt, ks, whole, grid, n_blk, part, st); break;
+    default: bat_wide_launch_t<MW, 8>(g, nt, ks, whole, grid, n_blk, part, st); break;
   }
 }
 
 static void bat_wide_launch(const BatGemm &g, int mw, int n_cu, hipStream_t st, const SplitRoom &room) {
-  const int CT = g.CT, cols = mw * kWdMC, nwv = kWdCompute / mw;
+  const int CT = g.CT, nwv = kWdCompute / mw;
+  // column tiles per wave: 8, or fewer (down to 5) if the blocks then hold fewer padding tiles and no more
+  // tiles in all than blocks of 8 per wave would (the records are allocated for those)
+  int mc = kWdMC;
+  {
+    const int pad8 = (CT + mw * kWdMC - 1) / (mw * kWdMC) * (mw * kWdMC);
+    int best = pad8;
+    for (int m = kWdMC - 1; m >= 5; --m) {
+      const int padded = (CT + mw * m - 1) / (mw * m) * (mw * m);
+      if (padded < best) { best = padded; mc = m; }
+    }
+  }
+  const int cols = mw * mc;
   const int n_blk = (CT + cols - 1) / cols;
   const int per_unit = g.epi == FEPI_SWIGLU ? 2 : 1;        // weight tiles per unit
   const int total = (g.Kd + 31) / 32, n_chunks = (total + kWdS - 1) / kWdS;
@@ -873,8 +907,8 @@ static void bat_wide_launch(const BatGemm &g, int mw, int n_cu, hipStream_t st, 
   const int per = (n_chunks + ks - 1) / ks;
   const bool whole = per % CPR == 0 && n_chunks % per == 0;   // every run a whole number of ring revolutions (see the kernel)
   const int grid = (groups(nt) + 7) / 8 * 8 * n_blk * ks;
-  if (mw == 2) bat_wide_launch_t<2>(g, nt, ks, whole, grid, n_blk, room.part, st);
-  else bat_wide_launch_t<1>(g, nt, ks, whole, grid, n_blk, room.part, st);
+  if (mw == 2) bat_wide_launch_mc<2>(mc, g, nt, ks, whole, grid, n_blk, room.part, st);
+  else bat_wide_launch_mc<1>(mc, g, nt, ks, whole, grid, n_blk, room.part, st);
   if (ks > 1) bat_split_finish<<<dim3((g.n_units * CT + 3) / 4), dim3(256), 0, st>>>(g, ks, room.part);
 }
 

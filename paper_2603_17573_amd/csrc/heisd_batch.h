@@ -445,7 +445,9 @@ __global__ __launch_bounds__(kBatThreads) __attribute__((amdgpu_waves_per_eu(2, 
 // straight from global memory into the MFMA A layout.  Workgroups are numbered so that the row blocks
 // of one weight group run next to each other on one XCD and find its weights in that L2.
 // With MW = 1 the six computing waves all take different weight tiles of one block of 8 column tiles:
-// the arrangement for up to 64 rows.
+// the arrangement for up to 64 rows.  MC, the column tiles per wave, is 8 unless fewer leave less padding:
+// 448 rows are 56 column tiles, 4 blocks of 2 x 7 instead of 4 blocks of 2 x 8 (an eighth fewer products
+// and transfers); 56 rows are one block of 7.
 constexpr int kWdMC = 8;
 constexpr int kWdS = 2, kWdNB = 4;                       // k-steps per chunk of B fragments, chunks resident in LDS
 constexpr int kWdRA = 4;                                 // k-steps of weight fragments requested ahead
@@ -455,13 +457,12 @@ constexpr size_t kBatWideLds = (size_t)kWdNB * kWdS * kWdCols * 1024;  // 128 KB
                                                          // the end 16 KB per computing wave to turn its tiles around
 
 // The end of a wide-GEMM wave: its NT x 8 accumulator tiles are turned around through `mine` (16 KB of LDS
-// of its own), two weight tiles at a time, so that a lane holds the pairs the epilogue works on; then the
-// projection's epilogue, or, in a split reduction, the store of the run's sums.  ctg0: first of the wave's 8
+// of its own: room for 2 x 8 tiles), two weight tiles at a time, so that a lane holds the pairs the epilogue works on; then the
+// projection's epilogue, or, in a split reduction, the store of the run's sums.  ctg0: first of the wave's MC
 // column tiles.
-template <int NT>
-__device__ __forceinline__ void bat_wide_finish_wave(const BatGemm &g, f32x4 (&acc)[NT][kWdMC], const int (&unit_of)[NT], float *mine,
+template <int NT, int MC>
+__device__ __forceinline__ void bat_wide_finish_wave(const BatGemm &g, f32x4 (&acc)[NT][MC], const int (&unit_of)[NT], float *mine,
                                                      int ctg0, int lane, bool swiglu, int split, int ksplit, float2 *part) {
-  constexpr int MC = kWdMC;
   const int c2 = lane & 7, jm = lane >> 3, i = 2 * c2;
   const int l_hi = (i >> 2) * 16 + jm, r = i & 3;
 #pragma unroll
@@ -517,10 +518,11 @@ __device__ __forceinline__ void bat_wide_finish_wave(const BatGemm &g, f32x4 (&a
 // stores its sums (part[split][unit][column tile][lane], the pair a lane would hand to the epilogue) and
 // bat_split_finish adds them in the order of the splits and applies the epilogue.  For projections with
 // so few weight tiles that one workgroup per tile group leaves most compute units idle (O-proj, down).
-template <int NT, bool WHOLE, int MW>
+template <int NT, bool WHOLE, int MW, int MC>
 __global__ __launch_bounds__(kBatThreads) __attribute__((amdgpu_waves_per_eu(2, 2))) void bat_gemm_wide(BatGemm g, int n_blk, int ksplit,
                                                                                                           float2 *part) {
-  constexpr int MC = kWdMC, S = kWdS;
+  constexpr int S = kWdS;
+  static_assert(MC >= 5 && MC <= kWdMC && (S * MW * MC) % (kBatWaves - kWdCompute) == 0, "column tiles per wave");
   constexpr int NWV = kWdCompute / MW, COLS = MW * MC;     // waves across weight tiles; column tiles per workgroup
   static_assert(MW == 1 || MW == 2, "wave arrangements");
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
@@ -635,7 +637,7 @@ __global__ __launch_bounds__(kBatThreads) __attribute__((amdgpu_waves_per_eu(2, 
   }
   lds_barrier();                                      // the B buffers are free: every wave turns its own tiles around in them
   if (filler) return;
-  bat_wide_finish_wave<NT>(g, acc, unit_of, reinterpret_cast<float *>(smem + (size_t)wave * (2 * MC * 1024)), blk * COLS + mwv * MC,
+  bat_wide_finish_wave<NT, MC>(g, acc, unit_of, reinterpret_cast<float *>(smem + (size_t)wave * (2 * kWdMC * 1024)), blk * COLS + mwv * MC,
                            lane, swiglu, split, ksplit, part);
 }
 
