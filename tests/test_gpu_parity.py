@@ -161,6 +161,25 @@ def test_idempotent_and_deterministic():
         assert np.array_equal(a[k], b[k], equal_nan=True), k
 
 
+@pytest.mark.parametrize("B,K", [(6, 7), (25, 8)])
+def test_split_reductions_are_deterministic(B, K):
+    """42 and 200 rows on the shape whose reductions are split: the runs' sums are added in the order of the
+    runs, whichever workgroup finishes first, so a step repeated on the same inputs gives the same bits."""
+    from gpu_harness import run_gpu_step
+    _need_gpu()
+    wl = synth.Workload("idem_split", SPLIT, 0, 30, SPLIT.bin_base, batch=B, K=K, seed=19)
+    weights = synth.make_weights(wl.shape, wl.seed)
+    cap = 30 + K + 2
+    k0, v0, f0 = zip(*[synth.make_prefix_kv_direct(wl, e, cap) for e in range(B)])
+    kb, vb = np.stack(k0, axis=1), np.stack(v0, axis=1)
+    drafts = (wl.shape.bin_base + synth.make_drafts_uniform(wl)).astype(np.int32)
+    rule = oracle.AcceptRule(2, 6)
+    a = run_gpu_step(wl.shape, weights, kb, vb, [30] * B, list(f0), drafts, rule, None, repeat=1)
+    b = run_gpu_step(wl.shape, weights, kb, vb, [30] * B, list(f0), drafts, rule, None, repeat=4)
+    for k in a:
+        assert np.array_equal(a[k], b[k], equal_nan=True), k
+
+
 def test_step_argument_errors_enqueue_nothing():
     from paper_2603_17573_amd import DeviceModel, Verifier, make_accept_desc, binding as B
     _need_gpu()
