@@ -285,11 +285,12 @@ __global__ __launch_bounds__(kBatThreads) __attribute__((amdgpu_waves_per_eu(2, 
 // drain its weight requests at every chunk; the computing waves meet the filling waves only at
 // workgroup barriers.  Record traffic drops with the number of workgroups, n_units/NW.  One unit
 // per computing wave and pass: a tile, or a (gate, up) pair.
-constexpr int kNsSlots = 8;
+constexpr int kNsSlots = 4;                       // k-steps (over all shares) per chunk
+constexpr int kNsBufs = 4;                        // chunks resident in LDS: three in flight while one is multiplied
 constexpr int kNsCompute = 6;
 template <int MC>
 constexpr size_t bat_ns_lds_bytes() {
-  return (size_t)2 * kNsSlots * MC * 1024;        // two buffers; reused for the waves' accumulators at the end
+  return (size_t)kNsBufs * kNsSlots * MC * 1024;  // the ring; reused for the waves' accumulators at the end
 }
 
 template <int MC, int NT, int KW>
@@ -316,9 +317,14 @@ __global__ __launch_bounds__(kBatThreads) __attribute__((amdgpu_waves_per_eu(2, 
   const bool swiglu = g.epi == FEPI_SWIGLU;
   const uint16_t *bsrc = g.b + (size_t)(lg >> 1) * g.CTS * 256 + lr * 16 + (lg & 1) * 8;     // + ks*bstep + ct*256
   const size_t bstep = (size_t)2 * g.CTS * 256;
-  // filling wave f moves slots f, f+NF, ... of a chunk: slot = share*S + step
-  auto fill = [&](int c, int buf) __attribute__((always_inline)) {
-    for (int slot = wave - kNsCompute; slot < kNsSlots; slot += NF) {
+  // filling wave f moves slots f, f+NF, ... of a chunk: slot = share*S + step.  Chunks past the end are moved
+  // too (from the all-zero k-step), so that the count of transfers in flight is the same at every wait.
+  constexpr int OPS = kNsSlots / NF * MC;           // transfers per filling wave and chunk
+  static_assert(kNsSlots % NF == 0 && sizeof(float) * kNsCompute * NT * MC * 256 <= bat_ns_lds_bytes<MC>(), "ring arithmetic");
+  auto fill = [&](int c) __attribute__((always_inline)) {
+    const int buf = c % kNsBufs;
+#pragma unroll 1
+    for (int slot = wave - kNsCompute; slot < kNsSlots; slot += NF) {     // rolled: unrolled it takes the registers the products need
       const int skw = slot / S, j = c * S + slot % S;
       const int s_ns = max(0, min(ksw, total - skw * ksw));
       const int ks = j < s_ns ? skw * ksw + j : total;          // past the share: the all-zero k-step
@@ -327,7 +333,6 @@ __global__ __launch_bounds__(kBatThreads) __attribute__((amdgpu_waves_per_eu(2, 
       for (int ct = 0; ct < MC; ++ct)
         lds_dma16(src + ct * 256, __builtin_amdgcn_readfirstlane(smem_lds + (uint32_t)(((buf * kNsSlots + slot) * MC + ct) * 1024)));
     }
-    wait_vmcnt<0>();
   };
 
   for (int grp = wg; grp < n_groups; grp += nwg) {
@@ -356,12 +361,16 @@ __global__ __launch_bounds__(kBatThreads) __attribute__((amdgpu_waves_per_eu(2, 
       for (int c = 0; c < MC; ++c) acc[t][c] = f32x4{0.f, 0.f, 0.f, 0.f};
     if (filler) {
       wait_vmcnt_all();                               // no wait of the compiler's between the transfers
-      fill(0, 0);
+#pragma unroll 1
+      for (int c = 0; c < kNsBufs - 1; ++c) fill(c);
+      wait_vmcnt<(kNsBufs - 2) * OPS>();              // chunk 0 has arrived
       lds_barrier();
       for (int c = 0; c < n_chunks; ++c) {
-        if (c + 1 < n_chunks) fill(c + 1, (c & 1) ^ 1);
+        fill(c + kNsBufs - 1);                        // into the buffer chunk c-1 was read from
+        wait_vmcnt<(kNsBufs - 2) * OPS>();            // chunk c+1 has arrived
         lds_barrier();
       }
+      wait_vmcnt<0>();                                // nothing may land in LDS after the buffers change hands
     } else {
       u32x4 A[R][NT];
 #pragma unroll
@@ -374,7 +383,7 @@ __global__ __launch_bounds__(kBatThreads) __attribute__((amdgpu_waves_per_eu(2, 
         for (int cc = 0; cc < R / S; ++cc) {
           const int c = c0 + cc;
           if (c < n_chunks) {
-            const unsigned char *bl = smem + ((size_t)((c & 1) * kNsSlots + kw * S) * MC) * 1024 + lane * 16;
+            const unsigned char *bl = smem + ((size_t)((c % kNsBufs) * kNsSlots + kw * S) * MC) * 1024 + lane * 16;
 #pragma unroll
             for (int s = 0; s < S; ++s) {
               const int u = cc * S + s;               // ring slot of step c*S + s
@@ -393,7 +402,8 @@ __global__ __launch_bounds__(kBatThreads) __attribute__((amdgpu_waves_per_eu(2, 
         }
       }
     }
-    // the shares of the reduction meet in LDS (the B buffers are free now); the wave with share 0 finishes the unit
+    lds_barrier();                                    // every transfer has landed: the ring is free
+    // the shares of the reduction meet in LDS; the wave with share 0 finishes the unit
     float *red = reinterpret_cast<float *>(smem);
     if (!filler) {
 #pragma unroll
