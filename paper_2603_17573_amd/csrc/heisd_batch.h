@@ -297,7 +297,7 @@ template <int MC, int NT, int KW>
 __global__ __launch_bounds__(kBatThreads) __attribute__((amdgpu_waves_per_eu(2, 2))) void bat_gemm_ns(BatGemm g) {
   constexpr int NW = kNsCompute / KW;
   constexpr int S = kNsSlots / KW;                  // k-steps per chunk and share
-  constexpr int R = 16 / NT;                        // weight fragments in flight per tile
+  constexpr int R = 8 / NT;                         // k-steps of weight fragments requested ahead (deeper measured slower)
   constexpr int NF = kBatWaves - kNsCompute;        // filling waves
   static_assert(R % S == 0, "a ring revolution is a whole number of chunks");
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
