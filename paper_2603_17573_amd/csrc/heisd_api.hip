@@ -973,7 +973,7 @@ static void batch_forward(heisd_verify_ctx *ctx, const heisd_kv_desc *kv, const 
   };
   {
     ProfScope ps(ctx, HEISD_KC_EMBED, st, prof);
-    bat_embed<<<dim3(dm / 16), dim3(64), 0, st>>>(draft_tokens, x_rows, static_cast<const uint16_t *>(d.tok_emb), d.vocab, dm, M,
+    bat_embed<<<dim3(dm / 16, (CT + 7) / 8), dim3(64), 0, st>>>(draft_tokens, x_rows, static_cast<const uint16_t *>(d.tok_emb), d.vocab, dm, M,
                                                   CT, CTS, ctx->attn_norm[0], ctx->x, rec_x, ssq);
     row_scales();
   }

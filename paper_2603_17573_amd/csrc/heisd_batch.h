@@ -679,7 +679,8 @@ __global__ __launch_bounds__(256) void bat_split_finish(BatGemm g, int ksplit, c
 }
 
 // ---- embedding: x rows (fp32), records of x*gain, partial sums of squares --------------------------
-// One 16-column tile per workgroup (64 threads); thread (c2, jm) walks the column tiles.  With `rows`
+// One 16-column tile per workgroup (64 threads); thread (c2, jm) walks the column tiles (those of its share
+// when the grid has a second dimension: with many rows one walk is a long chain of dependent gathers).  With `rows`
 // given the input rows are taken from there (fp32 [M][d]: visual tokens arrive as embeddings, App. A.1)
 // instead of being looked up; with both `ids` and `rows`, row m is looked up if ids[m] >= 0 and taken from
 // `rows` otherwise.
@@ -690,7 +691,7 @@ __global__ __launch_bounds__(64) void bat_embed(const int32_t *ids, const float 
   const int c2 = tid & 7, jm = tid >> 3;
   const int col = tile * 16 + 2 * c2;
   const float2 gn = *reinterpret_cast<const float2 *>(gain + col);
-  for (int ct = 0; ct < CT; ++ct) {
+  for (int ct = blockIdx.y; ct < CT; ct += gridDim.y) {       // the grid's second dimension shares the column tiles
     const int m = ct * 8 + jm;
     float v0 = 0.f, v1 = 0.f;
     if (m < M) {
