@@ -254,7 +254,7 @@ def run_skip_mode(args):
 
 
 def run_retrieve_mode(args):
-    """--mode retrieve: the retrieval branch's exact cosine Top-8 search (App. B) over a synthetic database
+    """--mode retrieve: the retrieval branch's exact cosine Top-8 search (App. C) over a synthetic database
     of the paper's size (273,465 embeddings of 4352 dimensions, bf16: 2.38 GB), one query per call."""
     import numpy as np
     import torch

@@ -1,5 +1,5 @@
-"""Plain fp64 CPU oracle of the retrieval branch's nearest-neighbour search (paper App. B: the
-retrieval database).
+"""Plain fp64 CPU oracle of the retrieval branch's nearest-neighbour search (paper App. C: the retrieval database,
+C.1 its construction, C.2 its performance).
 
 TEST INFRASTRUCTURE ONLY, like the rest of this package.
 

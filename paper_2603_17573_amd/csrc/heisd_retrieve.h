@@ -1,4 +1,4 @@
-// The retrieval branch's nearest-neighbour search (paper App. B): cosine Top-K of a query embedding
+// The retrieval branch's nearest-neighbour search (paper App. C: C.1 database construction, C.2 performance): cosine Top-K of a query embedding
 // over the database of L2-normalised embeddings, as an exact brute-force scan.  The database is read
 // once per group of up to four queries (2.4 GB at the paper's size: an HBM stream), the scores go to
 // a small buffer, and the K best per query are selected in two rounds.

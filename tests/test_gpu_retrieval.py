@@ -1,5 +1,6 @@
-"""heisd_retrieve_topk through the C ABI against the oracle's exact search (paper App. B: cosine Top-K
-over L2-normalised embeddings; Sec. 4.2: Top-K instead of Top-1), on seeded synthetic databases."""
+"""heisd_retrieve_topk through the C ABI against the oracle's exact search (paper App. C: C.1 database
+construction, C.2 performance - cosine Top-K over L2-normalised embeddings; Sec. 4.2: Top-K instead of
+Top-1), on seeded synthetic databases."""
 import time
 
 import numpy as np

@@ -33,7 +33,19 @@ EXAMPLES = load_examples()
 def test_hand_worked_examples(ex):
     name, tt, ts, skip, d, v, n_exp, next_exp = ex
     if skip:
-        pytest.skip("skip rows are decided in verify_step; covered in test_oracle_forward")
+        # A skipped episode never reaches accept_block: the line goes through the whole verify step
+        # on a small seeded model, whatever its targets would have been (Sec. 4.1 / Sec. 6.2).
+        import oracle
+        import synth
+        from helpers import oracle_model
+        sh = synth.ModelShape(1, 16, 2, 8, 24, 300)
+        m = oracle_model(sh, synth.make_weights(sh, seed=3))
+        kv = [[np.zeros((2, 0, 8))]]
+        out = oracle.verify_step(m, kv, kv, [0], [v[0]], sh.bin_base + np.array([d]),
+                                 AcceptRule(tok_threshold=tt, seq_budget=ts), skip_mask=[1])
+        assert int(out["accepted_len"][0]) == n_exp == len(d) and int(out["next_token"][0]) == next_exp == -1
+        assert np.all(out["target_bins"][0] == -1)
+        return
     n, nb = accept_block(d, v, AcceptRule(tok_threshold=tt, seq_budget=ts))
     assert (n, nb) == (n_exp, next_exp)
 

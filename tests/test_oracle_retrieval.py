@@ -1,4 +1,5 @@
-"""Pins of the retrieval oracle (paper App. B: cosine Top-K over L2-normalised embeddings)."""
+"""Pins of the retrieval oracle (paper App. C: C.1 database construction, C.2 performance - cosine Top-K
+over L2-normalised embeddings)."""
 import numpy as np
 
 import oracle
