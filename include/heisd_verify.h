@@ -24,7 +24,9 @@
 extern "C" {
 #endif
 
-/* Return codes: 0 on success, negative on failure.  On failure nothing was enqueued. */
+/* Return codes: 0 on success, negative on failure.  Argument errors (EINVAL, EUNSUPPORTED, ENOMEM)
+ * are found before anything is enqueued.  EHIP means the HIP runtime refused a launch: launches
+ * issued before the refused one stay enqueued, and the call's outputs are undefined. */
 #define HEISD_OK 0
 #define HEISD_EINVAL (-1)        /* NULL / out-of-range argument, inconsistent shapes        */
 #define HEISD_EUNSUPPORTED (-2)  /* shape the compiled kernels do not cover                   */
@@ -277,8 +279,8 @@ int heisd_skip_decide(const float *feat_prev, const float *feat_last, const int3
                       const float *min_s, const int32_t *o_dist, uint8_t *skip_mask, float *similarity, void *stream);
 
 /*
- * The retrieval branch's search (App. B; Sec. 4.2: Top-K instead of Top-1): every stored timestep is an
- * L2-normalised embedding (4352-dim in the paper) with a payload (the action tokens that followed); a query
+ * The retrieval branch's search (App. C: C.1 database construction, C.2 performance; Sec. 4.2: Top-K
+ * instead of Top-1): every stored timestep is an L2-normalised embedding (4352-dim in the paper) with a payload (the action tokens that followed); a query
  * embedding retrieves the K entries of highest cosine similarity, whose payloads become the draft
  * candidates (heisd_build_sequence_tree takes them).  The paper searches an HNSW graph on the CPU
  * (approximate); this call is the exact search, as one scan of the database in HBM.
@@ -349,6 +351,17 @@ int heisd_verify_profile_read(heisd_verify_ctx *ctx, double *ms, int64_t *launch
 #define HEISD_PATH_BATCH 4
 int heisd_verify_check(heisd_verify_ctx *ctx);
 int heisd_verify_set_path(heisd_verify_ctx *ctx, int path);
+
+/*
+ * Measurement aid for the persistent kernel (not part of the method): with enable != 0 every later
+ * persistent step records, for each phase of its program, device timestamps (100 MHz counter) of
+ * workgroup 0: [0] phase entered, [1] inputs seen (grid barrier passed), [2] weights consumed,
+ * [3] outputs published; 8 slots per phase, the others unused.  With out != NULL (HOST array of
+ * max_entries values) the call synchronises the device, copies the record of the last persistent
+ * step and returns the number of values copied (n_phases * 8 at most); otherwise it returns OK.
+ * Errors: EINVAL (NULL ctx), EHIP.
+ */
+int heisd_debug_trace(heisd_verify_ctx *ctx, int enable, unsigned long long *out, int max_entries);
 
 /* Release the context (not the workspace, weights or caches: those are the caller's). NULL ok. */
 void heisd_free(heisd_verify_ctx *ctx);

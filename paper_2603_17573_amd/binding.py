@@ -93,6 +93,8 @@ def load():
         lib.heisd_verify_set_path.restype = ctypes.c_int
         lib.heisd_verify_check.argtypes = [c_void_p]
         lib.heisd_verify_check.restype = ctypes.c_int
+        lib.heisd_debug_trace.argtypes = [c_void_p, ctypes.c_int, c_void_p, ctypes.c_int]
+        lib.heisd_debug_trace.restype = ctypes.c_int
         lib.heisd_last_error.argtypes = [c_void_p]
         lib.heisd_last_error.restype = c_char_p
         _lib = lib
@@ -187,6 +189,15 @@ def heisd_verify_check(ctx) -> int:
 
 def heisd_verify_set_path(ctx, path: int) -> int:
     return load().heisd_verify_set_path(ctx, path)
+
+
+def heisd_debug_trace(ctx, enable: bool, max_entries: int = 0):
+    """Returns (rc, list of timestamps) - the list is empty unless max_entries > 0."""
+    if max_entries <= 0:
+        return load().heisd_debug_trace(ctx, 1 if enable else 0, None, 0), []
+    buf = (ctypes.c_ulonglong * max_entries)()
+    rc = load().heisd_debug_trace(ctx, 1 if enable else 0, buf, max_entries)
+    return rc, list(buf[:max(rc, 0)])
 
 
 KERNEL_CLASSES = ("embed", "qkv", "attn", "oproj", "gateup", "down", "lmhead", "accept", "persist")

@@ -8,6 +8,7 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <vector>
 
@@ -1145,11 +1146,11 @@ extern "C" int heisd_verify_step(heisd_verify_ctx *ctx, const heisd_kv_desc *kv,
   int32_t *tbins = target_bins ? target_bins : ctx->tbins;
   (void)hipGetLastError();
 
-  const bool prof = ctx->prof_on && ctx->prof_steps < HEISD_PROFILE_MAX_STEPS;
-  if (prof) ctx->prof_steps++;
   const bool use_fast = ctx->fast_ok && M <= 8 && ctx->path != HEISD_PATH_GENERIC;
   if ((ctx->path == HEISD_PATH_FAST || ctx->path == HEISD_PATH_PERSIST) && !use_fast)
     return fail(ctx, HEISD_EUNSUPPORTED, "step: this path needs batch*K <= 8 (got %d)", M);
+  const bool prof = ctx->prof_on && ctx->prof_steps < HEISD_PROFILE_MAX_STEPS;
+  if (prof) ctx->prof_steps++;
   const bool use_persist = use_fast && ctx->persist_ok && ctx->path == HEISD_PATH_PERSIST;   // AUTO: launch per phase
   if (use_persist) {
     ProfScope ps(ctx, HEISD_KC_PERSIST, st, prof);
@@ -1333,11 +1334,11 @@ extern "C" int heisd_prefill_chunk(heisd_verify_ctx *ctx, const heisd_kv_desc *k
   hipStream_t st = static_cast<hipStream_t>(stream);
   const int M = batch * n_rows;
   (void)hipGetLastError();
-  const bool prof = ctx->prof_on && ctx->prof_steps < HEISD_PROFILE_MAX_STEPS;
-  if (prof) ctx->prof_steps++;
   const bool use_fast = ctx->fast_ok && M <= 8 && token_ids && !x_rows && ctx->path != HEISD_PATH_GENERIC && ctx->path != HEISD_PATH_BATCH;
   if ((ctx->path == HEISD_PATH_FAST || ctx->path == HEISD_PATH_PERSIST) && !use_fast)
     return fail(ctx, HEISD_EUNSUPPORTED, "prefill_chunk: the selected path serves token rows with batch*n_rows <= 8 only");
+  const bool prof = ctx->prof_on && ctx->prof_steps < HEISD_PROFILE_MAX_STEPS;
+  if (prof) ctx->prof_steps++;
   if (use_fast)
     fast_forward(ctx, kv, token_ids, n_rows, batch, nullptr, ctx->logits, st, prof);
   else if (ctx->path == HEISD_PATH_GENERIC)
@@ -1430,7 +1431,7 @@ extern "C" int heisd_skip_decide(const float *feat_prev, const float *feat_last,
   return HEISD_OK;
 }
 
-// ---- retrieval: exact cosine Top-K over the embedding database (App. B) -------------------------
+// ---- retrieval: exact cosine Top-K over the embedding database (App. C) -------------------------
 
 struct RetrieveLayout {
   size_t scores, cand_val, cand_idx, total;
@@ -1456,13 +1457,50 @@ extern "C" size_t heisd_retrieve_workspace_bytes(int64_t n_vectors, int32_t batc
   return RetrieveLayout(n_vectors, batch, K).total;
 }
 
+// What the retrieval calls need to know about the current device, found once per device: the number of
+// compute units, and the scan kernels' LDS limit raised to the largest query block they may be given.
+constexpr int kRetrieveMaxD = 8192;
+constexpr int kRetrieveMaxDevices = 64;
+
+struct RetrieveDevice {
+  bool ready = false;
+  int n_cu = 256;
+};
+static RetrieveDevice g_retrieve_dev[kRetrieveMaxDevices];
+static std::mutex g_retrieve_mutex;
+
+template <int NQ>
+static hipError_t retrieve_scores_prepare() {
+  return hipFuncSetAttribute(reinterpret_cast<const void *>(&retrieve_scores<NQ>),
+                             hipFuncAttributeMaxDynamicSharedMemorySize, NQ * kRetrieveMaxD * (int)sizeof(float));
+}
+
+// The current device's entry (set up on the first call made with that device current); nullptr + *err on failure.
+static const RetrieveDevice *retrieve_device(hipError_t *err) {
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e == hipSuccess && (dev < 0 || dev >= kRetrieveMaxDevices)) e = hipErrorInvalidDevice;
+  if (e != hipSuccess) { *err = e; return nullptr; }
+  std::lock_guard<std::mutex> lock(g_retrieve_mutex);
+  RetrieveDevice &rd = g_retrieve_dev[dev];
+  if (!rd.ready) {
+    hipDeviceProp_t prop;
+    e = hipGetDeviceProperties(&prop, dev);
+    if (e == hipSuccess && prop.multiProcessorCount > 0) rd.n_cu = prop.multiProcessorCount;
+    if (e == hipSuccess) e = retrieve_scores_prepare<1>();
+    if (e == hipSuccess) e = retrieve_scores_prepare<2>();
+    if (e == hipSuccess) e = retrieve_scores_prepare<3>();
+    if (e == hipSuccess) e = retrieve_scores_prepare<4>();
+    if (e != hipSuccess) { *err = e; return nullptr; }
+    rd.ready = true;
+  }
+  return &rd;
+}
+
 template <int NQ>
 static hipError_t retrieve_scores_launch(const uint16_t *db, long long N, int d, const float *q, float *scores,
                                          long long ld, int n_cu, hipStream_t st) {
   const int lds = NQ * d * (int)sizeof(float);
-  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&retrieve_scores<NQ>),
-                                     hipFuncAttributeMaxDynamicSharedMemorySize, lds);
-  if (e != hipSuccess) return e;
   const long long pairs = (N + 1) / 2, want = (pairs + kScanThreads / 64 - 1) / (kScanThreads / 64);
   const long long resident = (NQ <= 2 ? 4LL : 2LL) * n_cu;      // workgroups a compute unit holds at this LDS size
   const int grid = (int)(want < resident ? want : resident);
@@ -1470,31 +1508,27 @@ static hipError_t retrieve_scores_launch(const uint16_t *db, long long N, int d,
   return hipGetLastError();
 }
 
-extern "C" int heisd_retrieve_topk(const void *db, int64_t n_vectors, int32_t d, const float *queries, int32_t batch,
-                                   int32_t K, const int32_t *payload, int32_t payload_len, int32_t *top_index,
-                                   float *top_score, int32_t *top_payload, void *workspace, size_t workspace_bytes,
-                                   void *stream) {
-  if (!db || !queries || !top_index || !top_score || !workspace)
-    return fail(nullptr, HEISD_EINVAL, "retrieve_topk: NULL required pointer");
-  if (!retrieve_args_ok(n_vectors, batch, K) || d < 4 || d % 4 || d > 8192)
-    return fail(nullptr, HEISD_EINVAL, "retrieve_topk: n_vectors=%lld batch=%d K=%d d=%d outside the supported range",
+static int retrieve_check_args(const void *db, int64_t n_vectors, int32_t d, const float *queries, int32_t batch, int32_t K,
+                               const int32_t *payload, int32_t payload_len, const int32_t *top_index, const float *top_score,
+                               const int32_t *top_payload, const char *who) {
+  if (!db || !queries || !top_index || !top_score) return fail(nullptr, HEISD_EINVAL, "%s: NULL required pointer", who);
+  if (!retrieve_args_ok(n_vectors, batch, K) || d < 4 || d % 4 || d > kRetrieveMaxD)
+    return fail(nullptr, HEISD_EINVAL, "%s: n_vectors=%lld batch=%d K=%d d=%d outside the supported range", who,
                 (long long)n_vectors, batch, K, d);
   if ((payload != nullptr) != (top_payload != nullptr) || (payload && payload_len < 1))
-    return fail(nullptr, HEISD_EINVAL, "retrieve_topk: payload and top_payload go together, with payload_len >= 1");
-  if (((uintptr_t)db & 7) || !aligned16(queries) || ((uintptr_t)workspace & 255))
-    return fail(nullptr, HEISD_EINVAL, "retrieve_topk: misaligned pointer");
-  const RetrieveLayout lay(n_vectors, batch, K);
-  if (workspace_bytes < lay.total)
-    return fail(nullptr, HEISD_ENOMEM, "retrieve_topk: workspace %zu bytes < %zu needed", workspace_bytes, lay.total);
-  hipStream_t st = static_cast<hipStream_t>(stream);
-  unsigned char *base = static_cast<unsigned char *>(workspace);
+    return fail(nullptr, HEISD_EINVAL, "%s: payload and top_payload go together, with payload_len >= 1", who);
+  if (((uintptr_t)db & 7) || !aligned16(queries)) return fail(nullptr, HEISD_EINVAL, "%s: misaligned pointer", who);
+  return HEISD_OK;
+}
+
+// The three launches of one search; `base` holds the buffers of `lay`.
+static int retrieve_enqueue(const RetrieveDevice *rd, const RetrieveLayout &lay, unsigned char *base, const void *db,
+                            int64_t n_vectors, int32_t d, const float *queries, int32_t batch, int32_t K,
+                            const int32_t *payload, int32_t payload_len, int32_t *top_index, float *top_score,
+                            int32_t *top_payload, hipStream_t st, const char *who) {
   float *scores = reinterpret_cast<float *>(base + lay.scores);
   float *cand_val = reinterpret_cast<float *>(base + lay.cand_val);
   int *cand_idx = reinterpret_cast<int *>(base + lay.cand_idx);
-  int n_cu = 256, dev = 0;
-  hipDeviceProp_t prop;
-  if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess && prop.multiProcessorCount > 0)
-    n_cu = prop.multiProcessorCount;
   (void)hipGetLastError();
   const uint16_t *dbp = static_cast<const uint16_t *>(db);
   hipError_t e = hipSuccess;
@@ -1502,10 +1536,10 @@ extern "C" int heisd_retrieve_topk(const void *db, int64_t n_vectors, int32_t d,
     const int nq = batch - q0 < 4 ? batch - q0 : 4;
     const float *qp = queries + (size_t)q0 * d;
     float *sp = scores + (size_t)q0 * lay.ld_scores;
-    if (nq == 1) e = retrieve_scores_launch<1>(dbp, n_vectors, d, qp, sp, lay.ld_scores, n_cu, st);
-    else if (nq == 2) e = retrieve_scores_launch<2>(dbp, n_vectors, d, qp, sp, lay.ld_scores, n_cu, st);
-    else if (nq == 3) e = retrieve_scores_launch<3>(dbp, n_vectors, d, qp, sp, lay.ld_scores, n_cu, st);
-    else e = retrieve_scores_launch<4>(dbp, n_vectors, d, qp, sp, lay.ld_scores, n_cu, st);
+    if (nq == 1) e = retrieve_scores_launch<1>(dbp, n_vectors, d, qp, sp, lay.ld_scores, rd->n_cu, st);
+    else if (nq == 2) e = retrieve_scores_launch<2>(dbp, n_vectors, d, qp, sp, lay.ld_scores, rd->n_cu, st);
+    else if (nq == 3) e = retrieve_scores_launch<3>(dbp, n_vectors, d, qp, sp, lay.ld_scores, rd->n_cu, st);
+    else e = retrieve_scores_launch<4>(dbp, n_vectors, d, qp, sp, lay.ld_scores, rd->n_cu, st);
   }
   if (e == hipSuccess) {
     retrieve_top_chunks<<<dim3(lay.n_chunks, batch), dim3(256), 0, st>>>(scores, lay.ld_scores, n_vectors, K, cand_val,
@@ -1514,7 +1548,26 @@ extern "C" int heisd_retrieve_topk(const void *db, int64_t n_vectors, int32_t d,
                                                          payload, payload_len, top_payload);
     e = hipGetLastError();
   }
-  if (e != hipSuccess) return fail(nullptr, HEISD_EHIP, "retrieve_topk: %s", hipGetErrorString(e));
+  if (e != hipSuccess) return fail(nullptr, HEISD_EHIP, "%s: %s", who, hipGetErrorString(e));
   g_init_err[0] = 0;
   return HEISD_OK;
+}
+
+extern "C" int heisd_retrieve_topk(const void *db, int64_t n_vectors, int32_t d, const float *queries, int32_t batch,
+                                   int32_t K, const int32_t *payload, int32_t payload_len, int32_t *top_index,
+                                   float *top_score, int32_t *top_payload, void *workspace, size_t workspace_bytes,
+                                   void *stream) {
+  const char *who = "retrieve_topk";
+  const int rc = retrieve_check_args(db, n_vectors, d, queries, batch, K, payload, payload_len, top_index, top_score,
+                                     top_payload, who);
+  if (rc != HEISD_OK) return rc;
+  if (!workspace || ((uintptr_t)workspace & 255)) return fail(nullptr, HEISD_EINVAL, "%s: NULL or misaligned workspace", who);
+  const RetrieveLayout lay(n_vectors, batch, K);
+  if (workspace_bytes < lay.total)
+    return fail(nullptr, HEISD_ENOMEM, "%s: workspace %zu bytes < %zu needed", who, workspace_bytes, lay.total);
+  hipError_t e = hipSuccess;
+  const RetrieveDevice *rd = retrieve_device(&e);
+  if (!rd) return fail(nullptr, HEISD_EHIP, "%s: %s", who, hipGetErrorString(e));
+  return retrieve_enqueue(rd, lay, static_cast<unsigned char *>(workspace), db, n_vectors, d, queries, batch, K, payload,
+                          payload_len, top_index, top_score, top_payload, static_cast<hipStream_t>(stream), who);
 }
