@@ -306,6 +306,27 @@ int heisd_retrieve_topk(const void *db, int64_t n_vectors, int32_t d, const floa
                         int32_t *top_payload, void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * heisd_retrieve_topk for callers that cannot allocate device memory and have no workspace to hand over:
+ * code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments,
+ * kernels and results, but the scores and the first selection round's winners live in a static array
+ * inside the library, heisd_retrieve_static_bytes() = 8 MiB per GPU (every GPU the library runs on
+ * holds its own copy until the process ends).  The call allocates and frees nothing.  A search that
+ * needs more scratch than that - heisd_retrieve_workspace_bytes(n_vectors, batch, K) is the amount; the
+ * paper-sized database fits with up to 7 queries - fails with ENOMEM and enqueues nothing: use
+ * heisd_retrieve_topk then.
+ * All calls on one GPU share that GPU's array: two calls that may overlap in time (different streams,
+ * different host threads) race and both results are undefined; calls on one stream are safe.  Nothing
+ * in the array has to start cleared: every call writes what it reads.  The first call on a device
+ * looks up the array's address and the device's properties (no allocation); make it outside graph
+ * capture.
+ * Errors: EINVAL, ENOMEM (search larger than the static array), EHIP.
+ */
+size_t heisd_retrieve_static_bytes(void);
+int heisd_retrieve_topk_static(const void *db, int64_t n_vectors, int32_t d, const float *queries, int32_t batch,
+                               int32_t K, const int32_t *payload, int32_t payload_len, int32_t *top_index,
+                               float *top_score, int32_t *top_payload, void *stream);
+
+/*
  * Per-kernel timing for measurement runs (not part of the method).  With profiling enabled,
  * heisd_verify_step brackets every kernel launch with HIP events on the caller's stream;
  * heisd_verify_profile_read waits for the recorded events, adds the elapsed milliseconds

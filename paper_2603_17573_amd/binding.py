@@ -83,6 +83,11 @@ def load():
         lib.heisd_retrieve_topk.argtypes = [c_void_p, ctypes.c_int64, c_int32, c_void_p, c_int32, c_int32, c_void_p,
                                             c_int32, c_void_p, c_void_p, c_void_p, c_void_p, c_size_t, c_void_p]
         lib.heisd_retrieve_topk.restype = ctypes.c_int
+        lib.heisd_retrieve_static_bytes.argtypes = []
+        lib.heisd_retrieve_static_bytes.restype = c_size_t
+        lib.heisd_retrieve_topk_static.argtypes = [c_void_p, ctypes.c_int64, c_int32, c_void_p, c_int32, c_int32,
+                                                   c_void_p, c_int32, c_void_p, c_void_p, c_void_p, c_void_p]
+        lib.heisd_retrieve_topk_static.restype = ctypes.c_int
         lib.heisd_free.argtypes = [c_void_p]
         lib.heisd_free.restype = None
         lib.heisd_verify_profile_enable.argtypes = [c_void_p, ctypes.c_int]
@@ -170,6 +175,17 @@ def heisd_retrieve_topk(db, n_vectors, d, queries, batch, K, payload, payload_le
     """All array arguments are integer device addresses (0/None = NULL)."""
     return load().heisd_retrieve_topk(db, n_vectors, d, queries, batch, K, payload, payload_len, top_index, top_score,
                                       top_payload, workspace, workspace_bytes, stream)
+
+
+def heisd_retrieve_static_bytes() -> int:
+    return int(load().heisd_retrieve_static_bytes())
+
+
+def heisd_retrieve_topk_static(db, n_vectors, d, queries, batch, K, payload, payload_len, top_index, top_score,
+                               top_payload, stream) -> int:
+    """All array arguments are integer device addresses (0/None = NULL)."""
+    return load().heisd_retrieve_topk_static(db, n_vectors, d, queries, batch, K, payload, payload_len, top_index,
+                                             top_score, top_payload, stream)
 
 
 def heisd_free(ctx) -> None:

@@ -1458,13 +1458,20 @@ extern "C" size_t heisd_retrieve_workspace_bytes(int64_t n_vectors, int32_t batc
 }
 
 // What the retrieval calls need to know about the current device, found once per device: the number of
-// compute units, and the scan kernels' LDS limit raised to the largest query block they may be given.
+// compute units, the scan kernels' LDS limit raised to the largest query block they may be given, and the
+// address of this device's copy of the static scratch array (see heisd_retrieve_topk_static).
+constexpr size_t kRetrieveStaticBytes = (size_t)8 << 20;
 constexpr int kRetrieveMaxD = 8192;
 constexpr int kRetrieveMaxDevices = 64;
+
+// Scratch of heisd_retrieve_topk_static: scores and first-round winners, laid out by RetrieveLayout.  In
+// host code this name is only a handle for hipGetSymbolAddress; the device address is kept per device.
+static __device__ __align__(256) unsigned char retrieve_static_scratch[kRetrieveStaticBytes];
 
 struct RetrieveDevice {
   bool ready = false;
   int n_cu = 256;
+  unsigned char *scratch = nullptr;
 };
 static RetrieveDevice g_retrieve_dev[kRetrieveMaxDevices];
 static std::mutex g_retrieve_mutex;
@@ -1491,7 +1498,11 @@ static const RetrieveDevice *retrieve_device(hipError_t *err) {
     if (e == hipSuccess) e = retrieve_scores_prepare<2>();
     if (e == hipSuccess) e = retrieve_scores_prepare<3>();
     if (e == hipSuccess) e = retrieve_scores_prepare<4>();
+    void *p = nullptr;
+    if (e == hipSuccess) e = hipGetSymbolAddress(&p, HIP_SYMBOL(retrieve_static_scratch));
+    if (e == hipSuccess && !p) e = hipErrorInvalidSymbol;
     if (e != hipSuccess) { *err = e; return nullptr; }
+    rd.scratch = static_cast<unsigned char *>(p);
     rd.ready = true;
   }
   return &rd;
@@ -1570,4 +1581,27 @@ extern "C" int heisd_retrieve_topk(const void *db, int64_t n_vectors, int32_t d,
   if (!rd) return fail(nullptr, HEISD_EHIP, "%s: %s", who, hipGetErrorString(e));
   return retrieve_enqueue(rd, lay, static_cast<unsigned char *>(workspace), db, n_vectors, d, queries, batch, K, payload,
                           payload_len, top_index, top_score, top_payload, static_cast<hipStream_t>(stream), who);
+}
+
+extern "C" size_t heisd_retrieve_static_bytes(void) { return kRetrieveStaticBytes; }
+
+extern "C" int heisd_retrieve_topk_static(const void *db, int64_t n_vectors, int32_t d, const float *queries,
+                                          int32_t batch, int32_t K, const int32_t *payload, int32_t payload_len,
+                                          int32_t *top_index, float *top_score, int32_t *top_payload, void *stream) {
+  const char *who = "retrieve_topk_static";
+  const int rc = retrieve_check_args(db, n_vectors, d, queries, batch, K, payload, payload_len, top_index, top_score,
+                                     top_payload, who);
+  if (rc != HEISD_OK) return rc;
+  const RetrieveLayout lay(n_vectors, batch, K);
+  if (lay.total > kRetrieveStaticBytes)
+    return fail(nullptr, HEISD_ENOMEM, "%s: this search needs %zu bytes of scratch, the static array holds %zu "
+                "(use heisd_retrieve_topk with a workspace)", who, lay.total, kRetrieveStaticBytes);
+  hipError_t e = hipSuccess;
+  const RetrieveDevice *rd = retrieve_device(&e);
+  if (!rd) return fail(nullptr, HEISD_EHIP, "%s: %s", who, hipGetErrorString(e));
+  // rd->scratch is the device address of this GPU's copy of the array; every buffer in it is written
+  // before it is read within one call (all scores below n_vectors, K winners per chunk), so nothing
+  // of an earlier call's contents is ever seen and nothing has to be cleared.
+  return retrieve_enqueue(rd, lay, rd->scratch, db, n_vectors, d, queries, batch, K, payload, payload_len, top_index,
+                          top_score, top_payload, static_cast<hipStream_t>(stream), who);
 }
