@@ -375,14 +375,29 @@ int heisd_verify_set_path(heisd_verify_ctx *ctx, int path);
 
 /*
  * Measurement aid for the persistent kernel (not part of the method): with enable != 0 every later
- * persistent step records, for each phase of its program, device timestamps (100 MHz counter) of
- * workgroup 0: [0] phase entered, [1] inputs seen (grid barrier passed), [2] weights consumed,
- * [3] outputs published; 8 slots per phase, the others unused.  With out != NULL (HOST array of
- * max_entries values) the call synchronises the device, copies the record of the last persistent
- * step and returns the number of values copied (n_phases * 8 at most); otherwise it returns OK.
+ * persistent step records device timestamps (100 MHz counter) of every workgroup in every phase of its
+ * program, as [phase][workgroup][8]: [0] phase entered, [1] inputs seen (grid barrier passed),
+ * [2] weights consumed, [3] outputs published, [4] and [5] epilogue begun and ended (GEMM phases);
+ * the other slots are unused.  One workgroup runs per compute unit.  With out != NULL (HOST array of
+ * max_entries values) the call synchronises the device, copies the record of the last persistent step
+ * and returns the number of values copied (phases * workgroups * 8 at most); otherwise it returns OK.
  * Errors: EINVAL (NULL ctx), EHIP.
  */
 int heisd_debug_trace(heisd_verify_ctx *ctx, int enable, unsigned long long *out, int max_entries);
+
+/*
+ * Measurement aid for the persistent kernel: what a phase requests across the grid barrier that ends it.
+ *   0 (default)  the first 12 k-steps of every wave's first weight tile of the next GEMM phase are handed
+ *                over through LDS, started as soon as the phase's own outputs have been stored (the
+ *                O-projection's at the end of the attention phase); the rest of that tile is requested
+ *                into registers before the wait
+ *   1            as 0, but the O-projection's hand-over starts at the end of the QKV phase
+ *   2            no LDS hand-over: the whole first tile is requested into registers before the wait
+ *   3            nothing is requested before the wait
+ * Synchronises the device and rewrites the phase program.  Results are identical in every mode.
+ * Errors: EINVAL (NULL ctx, unknown mode), EUNSUPPORTED (no persistent kernel for this context), EHIP.
+ */
+int heisd_verify_set_handover(heisd_verify_ctx *ctx, int mode);
 
 /* Release the context (not the workspace, weights or caches: those are the caller's). NULL ok. */
 void heisd_free(heisd_verify_ctx *ctx);

@@ -98,6 +98,8 @@ def load():
         lib.heisd_verify_set_path.restype = ctypes.c_int
         lib.heisd_verify_check.argtypes = [c_void_p]
         lib.heisd_verify_check.restype = ctypes.c_int
+        lib.heisd_verify_set_handover.argtypes = [c_void_p, ctypes.c_int]
+        lib.heisd_verify_set_handover.restype = ctypes.c_int
         lib.heisd_debug_trace.argtypes = [c_void_p, ctypes.c_int, c_void_p, ctypes.c_int]
         lib.heisd_debug_trace.restype = ctypes.c_int
         lib.heisd_last_error.argtypes = [c_void_p]
@@ -205,6 +207,10 @@ def heisd_verify_check(ctx) -> int:
 
 def heisd_verify_set_path(ctx, path: int) -> int:
     return load().heisd_verify_set_path(ctx, path)
+
+
+def heisd_verify_set_handover(ctx, mode: int) -> int:
+    return load().heisd_verify_set_handover(ctx, mode)
 
 
 def heisd_debug_trace(ctx, enable: bool, max_entries: int = 0):

@@ -43,6 +43,7 @@ struct heisd_verify_ctx {
   unsigned *flags, *dev_err;           // persistent kernel: barrier flags [n_cu][16], error word
   unsigned epoch = 0;                  // last barrier epoch handed out
   bool persist_ok = false;
+  int handover_mode = 0;               // persistent kernel: what crosses a grid barrier (see persist_build_program)
   unsigned long long *trace = nullptr; // device buffer [n_phases][8] when tracing is on
   bool trace_on = false;
   int n_cu = 256;
@@ -173,7 +174,7 @@ static WsLayout ws_layout(const heisd_model_desc *d) {
   off += w.bscr_bytes;
   w.players = off; off += align256((size_t)(5 * d->n_layers + 2) * sizeof(Phase));
   w.flags = off;   off += align256((size_t)(1024 + 1) * kFlagStride * sizeof(unsigned));
-  w.trace = off;   off += align256((size_t)(5 * d->n_layers + 2) * 8 * sizeof(unsigned long long));
+  w.trace = off;   off += align256((size_t)(5 * d->n_layers + 2) * 1024 * 8 * sizeof(unsigned long long));   // [phase][workgroup][8]
   w.packed = off;
   const size_t per_layer = 4 * align256(fast_packed_elems(d->d_model, d->d_model) * 2) +
                            2 * align256(fast_packed_elems(d->d_ffn, d->d_model) * 2) +
@@ -478,15 +479,15 @@ static const void *persist_pick(const heisd_verify_ctx *c) {
                               : reinterpret_cast<const void *>(&persist_forward<64>);
 }
 
-static size_t persist_lds(const heisd_verify_ctx *c) {
-  const size_t a = fast_attn_lds(c->d.head_dim, c->d.kv_capacity);
-  return a > kFastLds ? a : kFastLds;
-}
+static size_t persist_lds(const heisd_verify_ctx *) { return kPersistLds; }
 
 // The persistent kernel needs every workgroup resident at once: one per compute unit.
 static hipError_t persist_prepare(heisd_verify_ctx *c) {
   c->persist_ok = false;
   if (!c->fast_ok || c->n_cu > 1024) return hipSuccess;
+  // the attention units work in the LDS below the hand-over region, which holds the O-projection's first
+  // weight steps while they run
+  if (fast_attn_lds(c->d.head_dim, c->d.kv_capacity) > kPfOff) return hipSuccess;
   const void *fn = persist_pick(c);
   hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)persist_lds(c));
   if (e != hipSuccess) return e;
@@ -498,15 +499,25 @@ static hipError_t persist_prepare(heisd_verify_ctx *c) {
 }
 
 // The phase program of one step (everything that does not change from step to step).
+// ctx->handover_mode (heisd_verify_set_handover; default 0):
+//   0  every GEMM phase gets its first weight steps handed over in LDS by the phase before it (the
+//      O-projection by the attention phase, at its end) and requests the rest before the barrier
+//   1  as 0, but the O-projection's hand-over starts at the end of the QKV phase
+//   2  no LDS hand-over: the whole first tile is requested into registers before the barrier
+//   3  nothing is requested across a barrier
 static hipError_t persist_build_program(heisd_verify_ctx *ctx) {
   const heisd_model_desc &d = ctx->d;
   const int L = d.n_layers;
   const FastScratch fs(&d);
   const bool stream_down = d.d_ffn > kFastWaves * kKS * 32;
+  const int mode = ctx->handover_mode;
+  const bool lds = mode == 0 || mode == 1;
+  const int ft = (lds ? PHF_IN_LDS : 0) | (mode != 3 ? PHF_EARLY : 0);
+  auto nx = [&](int idx) { return lds ? idx : -1; };
   std::vector<Phase> prog;
   heisd_kv_desc no_kv{};
   Phase e{};
-  e.kind = PH_EMBED; e.next_gemm = 1;
+  e.kind = PH_EMBED; e.next_gemm = nx(1);
   e.g.next_gain = ctx->attn_norm[0]; e.g.out = ctx->x;
   e.g.o_planes = reinterpret_cast<uint16_t *>(ctx->fscr + fs.rec_x_a);
   e.g.ssq_out = reinterpret_cast<float *>(ctx->fscr + fs.ssq_a);
@@ -514,14 +525,14 @@ static hipError_t persist_build_program(heisd_verify_ctx *ctx) {
   for (int l = 0; l < L; ++l) {
     const FastLayerDescs D = fast_layer_descs(ctx, &no_kv, l, 1, 1, nullptr);
     const int base = 1 + 5 * l;
-    Phase q{}; q.kind = PH_GEMM; q.g = D.qkv; q.next_gemm = -1; prog.push_back(q);
-    Phase a{}; a.kind = PH_ATTN; a.layer = l; a.next_gemm = base + 2;
+    Phase q{}; q.kind = PH_GEMM; q.g = D.qkv; q.first_tile = ft; q.next_gemm = mode == 1 ? base + 2 : -1; prog.push_back(q);
+    Phase a{}; a.kind = PH_ATTN; a.layer = l; a.next_gemm = mode == 0 ? base + 2 : -1;
     a.g.b = reinterpret_cast<const uint16_t *>(D.attn.qkv); a.g.o_planes = D.attn.o_planes; prog.push_back(a);
-    Phase o{}; o.kind = PH_GEMM; o.g = D.oproj; o.next_gemm = base + 3; prog.push_back(o);
-    Phase g{}; g.kind = PH_GEMM; g.g = D.gateup; g.next_gemm = base + 4; prog.push_back(g);
-    Phase w{}; w.kind = stream_down ? PH_GEMM_STREAM : PH_GEMM; w.g = D.down; w.next_gemm = base + 5; prog.push_back(w);
+    Phase o{}; o.kind = PH_GEMM; o.g = D.oproj; o.first_tile = ft; o.next_gemm = nx(base + 3); prog.push_back(o);
+    Phase g{}; g.kind = PH_GEMM; g.g = D.gateup; g.first_tile = ft; g.next_gemm = nx(base + 4); prog.push_back(g);
+    Phase w{}; w.kind = stream_down ? PH_GEMM_STREAM : PH_GEMM; w.g = D.down; w.first_tile = ft; w.next_gemm = nx(base + 5); prog.push_back(w);
   }
-  Phase lm{}; lm.kind = PH_GEMM; lm.g = fast_lm_desc(ctx, 1, nullptr); lm.next_gemm = -1; prog.push_back(lm);
+  Phase lm{}; lm.kind = PH_GEMM; lm.g = fast_lm_desc(ctx, 1, nullptr); lm.first_tile = ft; lm.next_gemm = -1; prog.push_back(lm);
   ctx->n_phases = (int)prog.size();
   return hipMemcpy(ctx->prog, prog.data(), prog.size() * sizeof(Phase), hipMemcpyHostToDevice);
 }
@@ -663,14 +674,25 @@ extern "C" int heisd_verify_set_path(heisd_verify_ctx *ctx, int path) {
   return HEISD_OK;
 }
 
-// Measurement aid, not part of the public header: timestamps (100 MHz counter) of workgroup 0 at
-// phase start / weights consumed / epilogue done / barrier passed, for every phase of the last
-// persistent step.  enable != 0 switches recording on; out (HOST, n_phases*8 entries) may be NULL.
+extern "C" int heisd_verify_set_handover(heisd_verify_ctx *ctx, int mode) {
+  if (!ctx) return HEISD_EINVAL;
+  if (mode < 0 || mode > 3) return fail(ctx, HEISD_EINVAL, "set_handover: unknown mode %d", mode);
+  if (!ctx->persist_ok) return fail(ctx, HEISD_EUNSUPPORTED, "set_handover: the persistent kernel does not fit this device or shape");
+  if (hipDeviceSynchronize() != hipSuccess) return fail(ctx, HEISD_EHIP, "set_handover: device error");
+  ctx->handover_mode = mode;
+  const hipError_t e = persist_build_program(ctx);
+  if (e != hipSuccess) return fail(ctx, HEISD_EHIP, "set_handover: %s", hipGetErrorString(e));
+  return HEISD_OK;
+}
+
+// Measurement aid: timestamps (100 MHz counter) every workgroup of the persistent kernel takes in every
+// phase of a step, [phase][workgroup][8].  enable != 0 switches recording on; out (HOST) may be NULL.
 extern "C" int heisd_debug_trace(heisd_verify_ctx *ctx, int enable, unsigned long long *out, int max_entries) {
   if (!ctx) return HEISD_EINVAL;
   ctx->trace_on = enable != 0;
   if (out) {
-    const int n = ctx->n_phases * 8 < max_entries ? ctx->n_phases * 8 : max_entries;
+    const long long all = (long long)ctx->n_phases * ctx->n_cu * 8;
+    const int n = all < max_entries ? (int)all : max_entries;
     if (hipDeviceSynchronize() != hipSuccess ||
         hipMemcpy(out, ctx->trace, (size_t)n * sizeof(unsigned long long), hipMemcpyDeviceToHost) != hipSuccess)
       return HEISD_EHIP;

@@ -41,6 +41,13 @@ __device__ __forceinline__ void lds_barrier() {
 __device__ __forceinline__ void lds_dma16(const void *gptr, uint32_t lds_addr) {
   asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_addr), "v"(gptr) : "memory");
 }
+// The same transfer with the address split into a wave-uniform 64-bit base (scalar registers) and a
+// 32-bit per-lane byte offset: a run of transfers that differ only in the base costs no vector
+// address arithmetic.
+__device__ __forceinline__ void lds_dma16_s(const void *sbase, uint32_t lane_off, uint32_t lds_addr) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds_addr), "v"(lane_off), "s"(sbase)
+               : "memory");
+}
 // s_waitcnt vmcnt(N) and nothing else, as a compiler-level memory barrier too: no load or store of
 // the surrounding code may be moved across it (the count is only right for the written order).
 template <int N>

@@ -94,18 +94,22 @@ __device__ __forceinline__ int fast_steps(int Kd, int wave) {
 
 // Which weight tile is list entry `e` of workgroup `wg` (of `nwg`)?  Units are dealt round-robin,
 // so unit u always belongs to workgroup u % nwg.
+// (The three segment pointers are read unconditionally and then selected by value: a descriptor that
+// lives in a local variable stays in registers that way, whereas a load through a selected address
+// would force it onto the stack.)
 __device__ __forceinline__ bool fast_tile(const FastGemm &g, int wg, int nwg, int e, const uint16_t *&wbase,
                                           int &wrow0, int &unit) {
+  const uint16_t *const w0 = g.w[0], *const w1 = g.w[1], *const w2 = g.w[2];
   if (g.epi == FEPI_SWIGLU) {
     unit = wg + (e >> 1) * nwg;
-    wbase = (e & 1) ? g.w[1] : g.w[0];
+    wbase = (e & 1) ? w1 : w0;
     wrow0 = unit * 16;
     return unit < g.n_units;
   }
   unit = wg + e * nwg;
   const int u = unit < g.n_units ? unit : 0;
   const int seg = u / g.seg_tiles;
-  wbase = seg == 0 ? g.w[0] : (seg == 1 ? g.w[1] : g.w[2]);
+  wbase = seg == 0 ? w0 : (seg == 1 ? w1 : w2);
   wrow0 = (u - seg * g.seg_tiles) * 16;
   return unit < g.n_units;
 }
@@ -218,11 +222,11 @@ struct EpiPre {           // FEPI_RESID_NORM: this thread's residual and gain pa
 };
 // What thread `tid` will need in the epilogue of a pass over tile entries e0.. (its output is
 // element (jm, 2*c2..2*c2+1) of entry e0 + tid/64).
-__device__ __forceinline__ EpiPre fast_epilogue_preload(const FastGemm &g, int wg, int nwg, int e0, int n_tiles) {
+__device__ __forceinline__ EpiPre fast_epilogue_preload(const FastGemm &g, int wg, int nwg, int e0, int n_tiles, int tid) {
   EpiPre p;
   p.xo = make_float2(0.f, 0.f);
   p.gn = make_float2(0.f, 0.f);
-  const int tid = threadIdx.x, un = tid >> 6, jm = (tid >> 3) & 7, i = 2 * (tid & 7);
+  const int un = tid >> 6, jm = (tid >> 3) & 7, i = 2 * (tid & 7);
   if (g.epi == FEPI_RESID_NORM && un < n_tiles) {
     const uint16_t *wbase;
     int wrow0, unit;
@@ -234,10 +238,9 @@ __device__ __forceinline__ EpiPre fast_epilogue_preload(const FastGemm &g, int w
 }
 
 __device__ __forceinline__ void fast_epilogue(const FastGemm &g, int wg, int nwg, int e0, int n_tiles, const float *red,
-                                              const float *scale_s, const EpiPre &pre) {
+                                              const float *scale_s, const EpiPre &pre, int tid) {
   const int EPI = g.epi;
   const int UT = (EPI == FEPI_SWIGLU) ? 2 : 1;
-  const int tid = threadIdx.x;
   const int n_units_out = (n_tiles + UT - 1) / UT;
   if (tid < n_units_out * 64) {                 // n_units_out <= kMaxT < 8: one output pair per thread
     const int o = tid;
@@ -327,7 +330,7 @@ __device__ __forceinline__ void fast_gemm_phase(const FastGemm &g, int wg, int n
     f32x4 acc[kMaxT];
 #pragma unroll
     for (int t = 0; t < kMaxT; ++t) acc[t] = f32x4{0.f, 0.f, 0.f, 0.f};
-    const EpiPre ep = fast_epilogue_preload(g, wg, nwg, e0, min(kMaxT, my_entries - e0));
+    const EpiPre ep = fast_epilogue_preload(g, wg, nwg, e0, min(kMaxT, my_entries - e0), tid);
     if (!(pre && e0 == 0)) fast_issue16(A, g, wg, nwg, e0, wave, lr, lg);
 #pragma unroll
     for (int t = 0; t < kMaxT; ++t) {
@@ -354,7 +357,7 @@ __device__ __forceinline__ void fast_gemm_phase(const FastGemm &g, int wg, int n
     for (int t = 0; t < kMaxT; ++t)
       *reinterpret_cast<f32x4 *>(red + ((size_t)(wave * kMaxT + t) * 64 + lane) * 4) = acc[t];
     lds_barrier();
-    fast_epilogue(g, wg, nwg, e0, min(kMaxT, my_entries - e0), red, scale_s, ep);
+    fast_epilogue(g, wg, nwg, e0, min(kMaxT, my_entries - e0), red, scale_s, ep, tid);
     lds_barrier();
   }
 }
@@ -385,7 +388,7 @@ __device__ __forceinline__ void fast_gemm_stream_phase(const FastGemm &g, int wg
     const uint16_t *wf = fast_wfrag(wbase, wrow0, g.Kd, lane);
     f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
     Frag16 Bs;
-    const EpiPre ep = fast_epilogue_preload(g, wg, nwg, e, 1);
+    const EpiPre ep = fast_epilogue_preload(g, wg, nwg, e, 1, tid);
     if (!(pre && e == 0)) {
 #pragma unroll
       for (int s = 0; s < kKS; ++s) A.v[s] = fast_ld_a(wf, g.Kd, min(ks0 + s, ks_last));
@@ -409,7 +412,7 @@ __device__ __forceinline__ void fast_gemm_stream_phase(const FastGemm &g, int wg
     if (e == 0) fast_row_scales_finish(g, sp, scale_s, wave, lane);
     *reinterpret_cast<f32x4 *>(red + ((size_t)(wave * kMaxT) * 64 + lane) * 4) = acc;
     lds_barrier();
-    fast_epilogue(g, wg, nwg, e, 1, red, scale_s, ep);
+    fast_epilogue(g, wg, nwg, e, 1, red, scale_s, ep, tid);
     lds_barrier();
   }
 }
@@ -417,8 +420,7 @@ __device__ __forceinline__ void fast_gemm_stream_phase(const FastGemm &g, int wg
 // ---- embedding: x = E[id] (fp32, owner-private), plane records of x*gain, partial sums of squares ----
 // One 16-column tile per call; the first 64 threads of the workgroup work: thread (c2, m).
 __device__ __forceinline__ void fast_embed_tile(const int32_t *ids, const uint16_t *emb, int vocab, int d, int M, int tile,
-                                                const float *gain, float *x, uint16_t *planes, float *ssq_out) {
-  const int tid = threadIdx.x;
+                                                const float *gain, float *x, uint16_t *planes, float *ssq_out, int tid) {
   if (tid >= 64) return;
   const int c2 = tid & 7, m = tid >> 3;
   const int col = tile * 16 + 2 * c2;
@@ -482,9 +484,9 @@ struct AttnPre {
 // Request the first kAttnR prefix key and value rows of this lane's stream (no dependence on the
 // current step's activations: may be called before the grid barrier that publishes q/k/v).
 template <int HD>
-__device__ __forceinline__ void fast_attn_prefetch(const FastAttn &a, int b, int h, AttnPre &pre) {
+__device__ __forceinline__ void fast_attn_prefetch(const FastAttn &a, int b, int h, AttnPre &pre, int tid) {
   constexpr int LPK = HD / 8, G = kFastThreads / LPK;
-  const int tid = threadIdx.x, li = tid % LPK, g = tid / LPK;
+  const int li = tid % LPK, g = tid / LPK;
   int P = a.prefix_len[b];
   P = max(0, min(P, a.cap - a.K));
   const bool skip = a.skip && a.skip[b];
@@ -503,9 +505,15 @@ __device__ __forceinline__ void fast_attn_prefetch(const FastAttn &a, int b, int
 // `pre` holds the first kAttnR prefix rows of each stream.  The unit rotates the block's keys
 // 0..jq itself (fp32, LDS) and appends row jq to the cache; scores live in LDS; the softmax is a
 // workgroup reduction; only the stored cache rows are rounded to bf16.
-template <int HD>
+struct NoHook {
+  __device__ __forceinline__ void operator()() const {}
+};
+// `after_loads` is called once the unit's q/k/v records are in LDS (nothing of this step's activations
+// is requested after that point when the prefix fits the prefetched rows): the persistent kernel
+// starts bulk transfers there, behind which the unit's own loads must not queue.
+template <int HD, class Hook = NoHook>
 __device__ __forceinline__ void fast_attn_unit(const FastAttn &a, int b, int h, int jq, unsigned char *smem,
-                                               const AttnPre &pre) {
+                                               const AttnPre &pre, int tid, Hook after_loads = Hook()) {
   constexpr int HALF = HD / 2;
   constexpr int LPK = HD / 8;
   constexpr int G = kFastThreads / LPK;
@@ -516,7 +524,7 @@ __device__ __forceinline__ void fast_attn_unit(const FastAttn &a, int b, int h, 
   float *sc = vb + 8 * HD;                          // [cap]
   float *wred = sc + a.cap;                         // [32] per-wave partials
   float *ored = wred + 32;                          // [waves][HD]
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int lane = tid & 63, wave = tid >> 6;
   const int K = a.K, d = a.d, cap = a.cap;
   const int m = b * K + jq;                         // activation row of this query
   const int li = tid % LPK, g = tid / LPK;
@@ -527,6 +535,7 @@ __device__ __forceinline__ void fast_attn_unit(const FastAttn &a, int b, int h, 
       st_dev(rec + (m * 16 + (c & 15)) / 2, 0u);
       st_dev(rec + ((m + 8) * 16 + (c & 15)) / 2, 0u);
     }
+    after_loads();
     return;
   }
   int P = a.prefix_len[b];
@@ -562,6 +571,7 @@ __device__ __forceinline__ void fast_attn_unit(const FastAttn &a, int b, int h, 
     }
   }
   __syncthreads();
+  after_loads();
   float qf[8];
 #pragma unroll
   for (int i = 0; i < 8; ++i) qf[i] = qs[li * 8 + i];
@@ -725,13 +735,13 @@ __global__ __launch_bounds__(kFastThreads) void fast_attn_kernel(FastAttn a) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   AttnPre pre;
   const int b = blockIdx.y / a.K, jq = blockIdx.y - b * a.K;     // grid (H, batch*K)
-  fast_attn_prefetch<HD>(a, b, blockIdx.x, pre);
-  fast_attn_unit<HD>(a, b, blockIdx.x, jq, smem, pre);
+  fast_attn_prefetch<HD>(a, b, blockIdx.x, pre, threadIdx.x);
+  fast_attn_unit<HD>(a, b, blockIdx.x, jq, smem, pre, threadIdx.x);
 }
 
 __global__ __launch_bounds__(64) void fast_embed_kernel(const int32_t *ids, const uint16_t *emb, int vocab, int d, int M,
                                                        const float *gain, float *x, uint16_t *planes, float *ssq_out) {
-  fast_embed_tile(ids, emb, vocab, d, M, blockIdx.x, gain, x, planes, ssq_out);
+  fast_embed_tile(ids, emb, vocab, d, M, blockIdx.x, gain, x, planes, ssq_out, threadIdx.x);
 }
 
 }  // namespace heisd

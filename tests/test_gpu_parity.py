@@ -67,6 +67,57 @@ def test_small_row_counts_on_both_paths(path, shape_name, B, K, skip):
              plen_override=[41, 17][:B] if B > 1 else None)
 
 
+LONGF = synth.ModelShape(n_layers=2, d_model=512, n_heads=4, head_dim=128, d_ffn=4416, vocab=2048)
+
+
+@pytest.mark.parametrize("path", [2, 3])
+@pytest.mark.parametrize("B,K", [(1, 7), (2, 4)])
+def test_long_reduction_streams_its_activations(path, B, K):
+    """FFN width 4416 (138 k-steps, more than the 128 a workgroup's waves keep resident): the down
+    projection of the <=8-row kernels streams its activation fragments through a second ring, with a
+    ragged last round (18 steps per wave, the last wave 12)."""
+    wl = synth.Workload("longf_%dx%d" % (B, K), LONGF, 20, 9, LONGF.bin_base, batch=B, K=K,
+                        draft=("geometric", 0.5), seed=B * 5 + K)
+    run_case(wl, path=path)
+
+
+@pytest.mark.parametrize("mode", [1, 2, 3])
+def test_persistent_kernel_handover_modes_agree(mode):
+    """What the persistent kernel requests across its grid barriers changes when weights arrive, never
+    what is computed: every mode gives the bits of the default mode (two episodes, one skipped, so that
+    attention units without work hand over too)."""
+    import torch
+    import paper_2603_17573_amd as P
+    from gpu_harness import _bits_to_dev, _dev_to_bits, accept_desc_of
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    wl = synth.Workload("mid_ho", MID, 30, 11, MID.bin_base, batch=2, K=4, draft=("geometric", 0.5), seed=3)
+    weights = synth.make_weights(MID, wl.seed)
+    om = oracle_model(MID, weights)
+    cap = wl.prefix_len + wl.K
+    kb, vb, plen, first = oracle_prefix_cache(om, wl, cap)
+    drafts = (MID.bin_base + synth.make_drafts_uniform(wl)).astype(np.int32)
+    dm = P.DeviceModel(MID, weights)
+    ver = P.Verifier(dm, 2, 4, cap)
+    assert P.heisd_verify_set_path(ver.ctx, 3) == 0
+    dev = "cuda:0"
+    skip = torch.tensor([0, 1], dtype=torch.uint8, device=dev)
+    outs = []
+    for m in (0, mode):
+        assert P.heisd_verify_set_handover(ver.ctx, m) == 0
+        kc, vc = _bits_to_dev(kb, dev), _bits_to_dev(vb, dev)
+        out = ver.step(kc, vc, torch.from_numpy(plen).to(dev), torch.from_numpy(first).to(dev),
+                       torch.from_numpy(drafts).to(dev), accept_desc_of(oracle.AcceptRule(2, 6)), skip)
+        torch.cuda.synchronize()
+        assert P.heisd_verify_check(ver.ctx) == 0
+        outs.append(({k: v.cpu().numpy().copy() for k, v in out.items()}, _dev_to_bits(kc), _dev_to_bits(vc)))
+    for k in outs[0][0]:
+        assert np.array_equal(outs[0][0][k], outs[1][0][k], equal_nan=True), k
+    assert np.array_equal(outs[0][1], outs[1][1]) and np.array_equal(outs[0][2], outs[1][2])
+    assert P.heisd_verify_set_handover(ver.ctx, 7) == P.HEISD_EINVAL
+    ver.close()
+
+
 def test_mid_hd128_ragged_prefixes_geometric_drafts():
     wl = synth.Workload("mid_b3", MID, 50, 20, MID.bin_base, batch=3, K=7, draft=("geometric", 0.5), seed=11)
     got, ref, stats = run_case(wl, plen_override=[70, 33, 64])
