@@ -45,18 +45,87 @@ def algorithmic_bytes(sh, batch, K, P, active=None):
 
 
 def read_traffic(kclass):
-    """HBM traffic per launch of a kernel class, if a counter summary under profiles/ states it."""
+    """(HBM traffic per launch of a kernel class, where that figure comes from), if a counter summary under
+    profiles/ states it.  The figure is NOT measured in this run: hardware counters need rocprofv3 around
+    the process, so it is read back from the committed summary of such a run."""
     pdir = os.path.join(ROOT, "profiles")
     if not os.path.isdir(pdir):
-        return None
+        return None, None
     for fn in sorted(os.listdir(pdir)):
         if not fn.endswith((".md", ".txt")):
             continue
-        m = re.search(r"^traffic_bytes_per_launch\[%s\]:\s*([0-9.eE+]+)" % kclass,
-                      open(os.path.join(pdir, fn)).read(), flags=re.M)
+        text = open(os.path.join(pdir, fn)).read()
+        m = re.search(r"^traffic_bytes_per_launch\[%s\]:\s*([0-9.eE+]+)" % kclass, text, flags=re.M)
         if m:
-            return float(m.group(1))
-    return None
+            when = re.search(r"^recorded:\s*(.+)$", text, flags=re.M)
+            return float(m.group(1)), "profiles/%s (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of bench.py, %s; " \
+                                      "not measured in this run)" % (fn, when.group(1).strip() if when else "date not stated")
+    return None, None
+
+
+def run_readbw_mode(args):
+    """--mode readbw: what a kernel that only reads reaches on this chip with the access patterns of the
+    weight-streaming GEMMs (heisd_measure_read), and what an empty launch costs - the reference points of
+    the roofline accounting.  Every launch reads a different window of a 6 GiB buffer, sized like the
+    projection it stands for, so that nothing is served from the memory-side cache."""
+    import torch
+    from paper_2603_17573_amd import heisd_measure_read, heisd_measure_empty_launch, binding
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    dev = "cuda:0"
+    pool = torch.empty(6 << 30, dtype=torch.uint8, device=dev)
+    pool.view(torch.int32).random_(0, 1 << 30)
+    sink = torch.zeros(16, dtype=torch.int32, device=dev)
+    stream = torch.cuda.current_stream(dev).cuda_stream
+    reps = max(args.steps, 5)
+
+    def timed(win, pattern, ksteps, in_flight, wgs):
+        n_win = pool.numel() // win
+        def launch(r):
+            rc = heisd_measure_read(pool.data_ptr() + (r % n_win) * win, win, pattern, ksteps, in_flight, wgs,
+                                    sink.data_ptr(), stream)
+            assert rc == 0, binding.heisd_last_error(None)
+        for r in range(3):
+            launch(r)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for r in range(reps):
+            launch(3 + r)
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) * 1e3 / reps            # us per launch, launch overhead included
+
+    d, f = 4096, 11008
+    shapes = {"gateup": (2 * f * d * 2, d // 32), "qkv": (3 * d * d * 2, d // 32), "oproj": (d * d * 2, d // 32),
+              "down": (d * f * 2, f // 32)}
+    rows = []
+    for wgs in (128, 176, 256, 512, 1024, 2048):
+        for infl in (8, 16):
+            win = shapes["gateup"][0]
+            us = timed(win, 0, 0, infl, wgs)
+            rows.append({"pattern": "contiguous per wave", "window": "gateup (180 MB)", "in_flight_KB_per_wave": infl,
+                         "workgroups": wgs, "us": round(us, 2), "GBps": round(win / us / 1e3, 1)})
+    for name, (win, ks) in shapes.items():
+        for infl in (8, 16):
+            us = timed(win, 1, ks, infl, 256)
+            rows.append({"pattern": "fragment-ordered tiles", "window": "%s (%.1f MB, %d KB tiles)" % (name, win / 1e6, ks),
+                         "in_flight_KB_per_wave": infl, "workgroups": 256, "us": round(us, 2),
+                         "GBps": round(win / us / 1e3, 1)})
+    for r in range(20):
+        heisd_measure_empty_launch(256, stream)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for r in range(500):
+        heisd_measure_empty_launch(256, stream)
+    e1.record()
+    torch.cuda.synchronize()
+    empty_us = e0.elapsed_time(e1) * 1e3 / 500
+    best = max(r["GBps"] for r in rows)
+    print(json.dumps({"metric": "HBM read bandwidth of a read-only kernel (reference for the weight-streaming GEMMs)",
+                      "value": best, "unit": "GB/s", "n_gpus": 1, "steps": reps, "higher_is_better": True,
+                      "peak": HBM_PEAK / 1e9, "frac_of_peak": round(best * 1e9 / HBM_PEAK, 4),
+                      "empty_launch_us": round(empty_us, 3), "data": "synthetic", "rows": rows}))
 
 
 def run_aux_mode(args):
@@ -329,12 +398,15 @@ def main():
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run three plain 1 GiB device copies (reference kernel for HBM traffic counters)")
     ap.add_argument("--path", type=int, default=0, help="0 auto, 1 generic, 2 fast (launch per phase), 3 persistent")
+    ap.add_argument("--handover", type=int, default=0, choices=[0, 1, 2, 3],
+                    help="--path 3 only: what the persistent kernel requests across its grid barriers "
+                         "(heisd_verify_set_handover; 0 = default)")
     ap.add_argument("--tree", type=int, default=0, metavar="R",
                     help="time the TREE verify step instead: R retrieved candidates per episode, built into a "
                          "sequence-wise draft tree (paper Sec. 4.2); 0 = the linear step")
     ap.add_argument("--prefill-chunks", type=int, default=1, choices=[1, 2],
                     help="--mode prefill: 1 = visual embeddings and prompt ids in one call (default), 2 = one call each")
-    ap.add_argument("--mode", default="verify", choices=["verify", "decode", "prefill", "skip", "retrieve"],
+    ap.add_argument("--mode", default="verify", choices=["verify", "decode", "prefill", "skip", "retrieve", "readbw"],
                     help="verify (default): the verify step; decode: one autoregressive decode step; prefill: the "
                          "workload's prefix from an empty cache, in chunks")
     args = ap.parse_args()
@@ -350,6 +422,8 @@ def main():
             build.build(force=False)
         if args.mode == "retrieve":
             return run_retrieve_mode(args)
+        if args.mode == "readbw":
+            return run_readbw_mode(args)
         return run_skip_mode(args) if args.mode == "skip" else run_aux_mode(args)
 
     import numpy as np
@@ -378,8 +452,10 @@ def main():
     t_gen = time.time() - t0
     dm = DeviceModel(sh, weights, dev)
     ver = Verifier(dm, B, rows, cap)
-    from paper_2603_17573_amd import heisd_verify_set_path
+    from paper_2603_17573_amd import heisd_verify_set_path, heisd_verify_set_handover
     assert heisd_verify_set_path(ver.ctx, args.path) == 0
+    if args.path == 3 and args.handover:
+        assert heisd_verify_set_handover(ver.ctx, args.handover) == 0
     # prefix K/V drawn directly (the benchmark may not call the oracle's prefill); same shapes,
     # same bytes, same launch configuration as a prefilled cache
     kc, vc = ver.new_cache(B)
@@ -494,21 +570,24 @@ def main():
                 kernels[kcls]["GBps"] = round(per_class[kcls] / (avg * 1e-3) / 1e9, 1)
     dom = max((k for k in kernels if k in per_class), key=lambda k: prof[k][0])
     dom_avg_s = prof[dom][0] / prof[dom][1] * 1e-3
-    achieved = per_class[dom] / dom_avg_s
-    roofline = {"kernel": dom, "bound": "hbm", "achieved": round(achieved / 1e9, 1), "peak": HBM_PEAK / 1e9,
-                "unit": "GB/s", "frac": round(achieved / HBM_PEAK, 4),
-                "bytes_per_launch": per_class[dom], "avg_launch_us": round(dom_avg_s * 1e6, 3),
-                "traffic": read_traffic(dom)}
     # What the instrument adds: a bracket's two events cost time the timed steps do not spend.  The brackets
     # of a profiled step add up to more than a timed step; the surplus per bracket, taken off the dominant
-    # kernel's bracket, is its duration as it runs in the timed region (the figure the rocprofv3 summaries show).
+    # kernel's bracket, is the kernel's duration as it runs in the timed region - the figure the rocprofv3
+    # summaries under profiles/ show - and `achieved` / `frac` follow from that duration.  The raw bracket
+    # is reported beside it.
     brackets = sum(n for _, n in prof.values()) / n_prof
     surplus_us = (sum(t for t, _ in prof.values()) / n_prof - ms) * 1e3 / brackets
-    if 0.0 < surplus_us < dom_avg_s * 1e6:
-        in_step_s = dom_avg_s - surplus_us * 1e-6
-        roofline.update({"event_bracket_surplus_us": round(surplus_us, 3),
-                         "avg_launch_us_in_timed_region": round(in_step_s * 1e6, 3),
-                         "frac_in_timed_region": round(per_class[dom] / in_step_s / HBM_PEAK, 4)})
+    if not 0.0 < surplus_us < dom_avg_s * 1e6:
+        surplus_us = 0.0
+    kernel_s = dom_avg_s - surplus_us * 1e-6
+    achieved = per_class[dom] / kernel_s
+    traffic, traffic_source = read_traffic(dom)
+    roofline = {"kernel": dom, "bound": "hbm", "achieved": round(achieved / 1e9, 1), "peak": HBM_PEAK / 1e9,
+                "unit": "GB/s", "frac": round(achieved / HBM_PEAK, 4),
+                "bytes_per_launch": per_class[dom], "avg_launch_us": round(kernel_s * 1e6, 3),
+                "traffic": traffic, "traffic_source": traffic_source,
+                "event_bracket_us": round(dom_avg_s * 1e6, 3), "event_bracket_surplus_us": round(surplus_us, 3),
+                "frac_of_event_bracket": round(per_class[dom] / dom_avg_s / HBM_PEAK, 4)}
 
     cpu = None
     if not args.no_cpu_baseline:
@@ -556,7 +635,7 @@ def main():
         "config": {"workload": "%s: %d-layer d=%d decoder, prefix %d, batch %d, K=%d, thresholds %d/%d" %
                                (wl.name, sh.n_layers, sh.d_model, P, B, K, wl.tau_tok, wl.tau_seq),
                    "prefix_kv": "drawn directly (no prefill)", "drafts": drafts_note, "global_batch": B, "K": K, "tree_tokens": T or None},
-        "kernel_path": args.path,
+        "kernel_path": args.path, "handover_mode": args.handover if args.path == 3 else None,
         "hbm_frac_whole_step": round(total_bytes / (ms * 1e-3) / HBM_PEAK, 4),
         "algorithmic_bytes_per_step": total_bytes,
         "accepted_len": accepted[:8],

@@ -399,6 +399,22 @@ int heisd_debug_trace(heisd_verify_ctx *ctx, int enable, unsigned long long *out
  */
 int heisd_verify_set_handover(heisd_verify_ctx *ctx, int mode);
 
+/*
+ * Reference measurements behind the roofline accounting (not part of the method): one launch of a kernel
+ * that only reads `bytes` of device memory, in the access pattern of the weight-streaming GEMMs, and an
+ * empty launch.  The caller times them (events, or rocprofv3 around the process).
+ *   pattern 0   every wave reads one contiguous span (bytes / waves), `in_flight` KB per wave requested ahead
+ *   pattern 1   the fragment-ordered weight copy as the <= 8-row GEMMs walk it: tiles of `ksteps` KB
+ *               (ksteps = reduction length / 32), dealt round-robin to the workgroups, the 8 waves of a
+ *               workgroup an eighth of a tile's k-steps each, `in_flight` KB per wave requested ahead
+ *   in_flight   8 or 16;  workgroups: grid size (512 threads each; 256 = one per compute unit)
+ *   sink        DEVICE u32 [1], never written in practice (keeps the loads alive)
+ * Asynchronous on `stream`, allocates nothing.  Errors: EINVAL, EHIP.
+ */
+int heisd_measure_read(const void *buf, size_t bytes, int32_t pattern, int32_t ksteps, int32_t in_flight,
+                       int32_t workgroups, uint32_t *sink, void *stream);
+int heisd_measure_empty_launch(int32_t workgroups, void *stream);
+
 /* Release the context (not the workspace, weights or caches: those are the caller's). NULL ok. */
 void heisd_free(heisd_verify_ctx *ctx);
 

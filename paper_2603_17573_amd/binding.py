@@ -98,6 +98,10 @@ def load():
         lib.heisd_verify_set_path.restype = ctypes.c_int
         lib.heisd_verify_check.argtypes = [c_void_p]
         lib.heisd_verify_check.restype = ctypes.c_int
+        lib.heisd_measure_read.argtypes = [c_void_p, c_size_t, c_int32, c_int32, c_int32, c_int32, c_void_p, c_void_p]
+        lib.heisd_measure_read.restype = ctypes.c_int
+        lib.heisd_measure_empty_launch.argtypes = [c_int32, c_void_p]
+        lib.heisd_measure_empty_launch.restype = ctypes.c_int
         lib.heisd_verify_set_handover.argtypes = [c_void_p, ctypes.c_int]
         lib.heisd_verify_set_handover.restype = ctypes.c_int
         lib.heisd_debug_trace.argtypes = [c_void_p, ctypes.c_int, c_void_p, ctypes.c_int]
@@ -207,6 +211,14 @@ def heisd_verify_check(ctx) -> int:
 
 def heisd_verify_set_path(ctx, path: int) -> int:
     return load().heisd_verify_set_path(ctx, path)
+
+
+def heisd_measure_read(buf, nbytes, pattern, ksteps, in_flight, workgroups, sink, stream) -> int:
+    return load().heisd_measure_read(buf, nbytes, pattern, ksteps, in_flight, workgroups, sink, stream)
+
+
+def heisd_measure_empty_launch(workgroups, stream) -> int:
+    return load().heisd_measure_empty_launch(workgroups, stream)
 
 
 def heisd_verify_set_handover(ctx, mode: int) -> int:

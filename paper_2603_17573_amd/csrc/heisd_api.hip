@@ -20,6 +20,7 @@
 #include "heisd_misc.h"
 #include "heisd_skip.h"
 #include "heisd_retrieve.h"
+#include "heisd_measure.h"
 
 using namespace heisd;
 
@@ -1626,4 +1627,40 @@ extern "C" int heisd_retrieve_topk_static(const void *db, int64_t n_vectors, int
   // of an earlier call's contents is ever seen and nothing has to be cleared.
   return retrieve_enqueue(rd, lay, rd->scratch, db, n_vectors, d, queries, batch, K, payload, payload_len, top_index,
                           top_score, top_payload, static_cast<hipStream_t>(stream), who);
+}
+
+// ---- reference measurements (not part of the method) ---------------------------------------------
+
+extern "C" int heisd_measure_read(const void *buf, size_t bytes, int32_t pattern, int32_t ksteps, int32_t in_flight,
+                                  int32_t workgroups, uint32_t *sink, void *stream) {
+  if (!buf || !sink || ((uintptr_t)buf & 15)) return fail(nullptr, HEISD_EINVAL, "measure_read: NULL or misaligned pointer");
+  if ((pattern != 0 && pattern != 1) || (in_flight != 8 && in_flight != 16) || workgroups < 1 || workgroups > 65535)
+    return fail(nullptr, HEISD_EINVAL, "measure_read: pattern %d in_flight %d workgroups %d", pattern, in_flight, workgroups);
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  (void)hipGetLastError();
+  const mu32x4 *p = static_cast<const mu32x4 *>(buf);
+  if (pattern == 0) {
+    const size_t n_vec = bytes / 16;
+    if (n_vec < (size_t)workgroups * 8 * 64 * in_flight) return fail(nullptr, HEISD_EINVAL, "measure_read: buffer too small for this grid");
+    if (in_flight == 8) measure_read_contiguous<8><<<dim3(workgroups), dim3(kMeasureThreads), 0, st>>>(p, n_vec, sink);
+    else measure_read_contiguous<16><<<dim3(workgroups), dim3(kMeasureThreads), 0, st>>>(p, n_vec, sink);
+  } else {
+    if (ksteps < 8 || ksteps > 65536) return fail(nullptr, HEISD_EINVAL, "measure_read: ksteps %d", ksteps);
+    const size_t n_tiles = bytes / ((size_t)ksteps * 1024);
+    if (n_tiles < 1 || n_tiles > 0x7FFFFFFF) return fail(nullptr, HEISD_EINVAL, "measure_read: buffer holds no whole tile");
+    if (in_flight == 8) measure_read_tiles<8><<<dim3(workgroups), dim3(kMeasureThreads), 0, st>>>(p, (int)n_tiles, ksteps, sink);
+    else measure_read_tiles<16><<<dim3(workgroups), dim3(kMeasureThreads), 0, st>>>(p, (int)n_tiles, ksteps, sink);
+  }
+  const hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return fail(nullptr, HEISD_EHIP, "measure_read: %s", hipGetErrorString(e));
+  return HEISD_OK;
+}
+
+extern "C" int heisd_measure_empty_launch(int32_t workgroups, void *stream) {
+  if (workgroups < 1 || workgroups > 65535) return fail(nullptr, HEISD_EINVAL, "measure_empty_launch: workgroups %d", workgroups);
+  (void)hipGetLastError();
+  measure_empty<<<dim3(workgroups), dim3(kMeasureThreads), 0, static_cast<hipStream_t>(stream)>>>();
+  const hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return fail(nullptr, HEISD_EHIP, "measure_empty_launch: %s", hipGetErrorString(e));
+  return HEISD_OK;
 }
