@@ -99,18 +99,20 @@ def run_readbw_mode(args):
     shapes = {"gateup": (2 * f * d * 2, d // 32), "qkv": (3 * d * d * 2, d // 32), "oproj": (d * d * 2, d // 32),
               "down": (d * f * 2, f // 32)}
     rows = []
-    for wgs in (128, 176, 256, 512, 1024, 2048):
+    for wgs in (128, 176, 256, 512, 1024):
         for infl in (8, 16):
             win = shapes["gateup"][0]
             us = timed(win, 0, 0, infl, wgs)
+            waves = wgs * 8
+            read = (win // 16 // waves // (64 * infl)) * (64 * infl) * waves * 16     # whole rounds per wave only
             rows.append({"pattern": "contiguous per wave", "window": "gateup (180 MB)", "in_flight_KB_per_wave": infl,
-                         "workgroups": wgs, "us": round(us, 2), "GBps": round(win / us / 1e3, 1)})
+                         "workgroups": wgs, "bytes_read": read, "us": round(us, 2), "GBps": round(read / us / 1e3, 1)})
     for name, (win, ks) in shapes.items():
         for infl in (8, 16):
             us = timed(win, 1, ks, infl, 256)
             rows.append({"pattern": "fragment-ordered tiles", "window": "%s (%.1f MB, %d KB tiles)" % (name, win / 1e6, ks),
-                         "in_flight_KB_per_wave": infl, "workgroups": 256, "us": round(us, 2),
-                         "GBps": round(win / us / 1e3, 1)})
+                         "in_flight_KB_per_wave": infl, "workgroups": 256, "bytes_read": win // (ks * 1024) * ks * 1024,
+                         "us": round(us, 2), "GBps": round(win / us / 1e3, 1)})
     for r in range(20):
         heisd_measure_empty_launch(256, stream)
     torch.cuda.synchronize()

@@ -41,7 +41,8 @@ struct heisd_verify_ctx {
   unsigned char *bscr;                 // batched path (M > 8): records and row statistics (see BatScratch)
   Phase *prog;                         // persistent kernel: the phase program in device memory
   int n_phases = 0;
-  unsigned *flags, *dev_err;           // persistent kernel: barrier flags [n_cu][16], error word
+  unsigned *flags, *dev_err;           // persistent kernel: barrier flags [n_cu], error word
+  unsigned *lm_done = nullptr;         // fused LM head + acceptance: arrival counter of its workgroups
   unsigned epoch = 0;                  // last barrier epoch handed out
   bool persist_ok = false;
   int handover_mode = 0;               // persistent kernel: what crosses a grid barrier (see persist_build_program)
@@ -174,7 +175,7 @@ static WsLayout ws_layout(const heisd_model_desc *d) {
   w.bscr_bytes = BatScratch(d).total;
   off += w.bscr_bytes;
   w.players = off; off += align256((size_t)(5 * d->n_layers + 2) * sizeof(Phase));
-  w.flags = off;   off += align256((size_t)(1024 + 1) * kFlagStride * sizeof(unsigned));
+  w.flags = off;   off += align256((size_t)(1024 + 64) * sizeof(unsigned));   // barrier flags, error word, LM-head arrival counter
   w.trace = off;   off += align256((size_t)(5 * d->n_layers + 2) * 1024 * 8 * sizeof(unsigned long long));   // [phase][workgroup][8]
   w.packed = off;
   const size_t per_layer = 4 * align256(fast_packed_elems(d->d_model, d->d_model) * 2) +
@@ -335,7 +336,8 @@ static hipError_t fast_prepare(int hd, int cap) {
                        reinterpret_cast<const void *>(&fast_gemm_kernel<HEISD_KC_GATEUP>),
                        reinterpret_cast<const void *>(&fast_gemm_kernel<HEISD_KC_DOWN>),
                        reinterpret_cast<const void *>(&fast_gemm_kernel<HEISD_KC_LMHEAD>),
-                       reinterpret_cast<const void *>(&fast_gemm_stream_kernel<HEISD_KC_DOWN>)};
+                       reinterpret_cast<const void *>(&fast_gemm_stream_kernel<HEISD_KC_DOWN>),
+                       reinterpret_cast<const void *>(&fast_lmhead_accept_kernel)};
   for (const void *f : fns)
     if ((e = hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, lds)) != hipSuccess) return e;
   const int alds = (int)fast_attn_lds(hd, cap);
@@ -424,8 +426,10 @@ static FastLayerDescs fast_layer_descs(const heisd_verify_ctx *ctx, const heisd_
 }
 
 // The decoder forward for M <= 8 rows, one launch per phase; leaves the bin logits in `logits`.
+// With `accept` the LM-head launch also takes the greedy bins and runs the acceptance scan.
 static void fast_forward(heisd_verify_ctx *ctx, const heisd_kv_desc *kv, const int32_t *draft_tokens, int K,
-                         int batch, const uint8_t *skip_mask, float *logits, hipStream_t st, bool prof) {
+                         int batch, const uint8_t *skip_mask, float *logits, hipStream_t st, bool prof,
+                         const AcceptArgs *accept = nullptr) {
   const heisd_model_desc &d = ctx->d;
   const int M = batch * K, dm = d.d_model, H = d.n_heads, HD = d.head_dim, cap = d.kv_capacity;
   const int ncu = ctx->n_cu;
@@ -469,7 +473,10 @@ static void fast_forward(heisd_verify_ctx *ctx, const heisd_kv_desc *kv, const i
   }
   {
     ProfScope ps(ctx, HEISD_KC_LMHEAD, st, prof);
-    fast_gemm_kernel<HEISD_KC_LMHEAD><<<grid_for(lm.n_units), dim3(kFastThreads), kFastLds, st>>>(lm);
+    if (accept)
+      fast_lmhead_accept_kernel<<<grid_for(lm.n_units), dim3(kFastThreads), kFastLds, st>>>(lm, *accept, batch, ctx->lm_done);
+    else
+      fast_gemm_kernel<HEISD_KC_LMHEAD><<<grid_for(lm.n_units), dim3(kFastThreads), kFastLds, st>>>(lm);
   }
 }
 
@@ -618,7 +625,8 @@ extern "C" int heisd_verify_init(const heisd_model_desc *desc, heisd_verify_ctx 
   c->bscr = base + w.bscr;
   c->prog = reinterpret_cast<Phase *>(base + w.players);
   c->flags = reinterpret_cast<unsigned *>(base + w.flags);
-  c->dev_err = c->flags + 1024 * kFlagStride;
+  c->dev_err = c->flags + 1024;
+  c->lm_done = c->flags + 1024 + 16;
   c->trace = reinterpret_cast<unsigned long long *>(base + w.trace);
   c->fast_ok = desc->d_model <= kFastWaves * kKS * 32;
   c->path = HEISD_PATH_AUTO;
@@ -641,7 +649,7 @@ extern "C" int heisd_verify_init(const heisd_model_desc *desc, heisd_verify_ctx 
     if (e == hipSuccess) e = hipGetDeviceProperties(&prop, dev);
     if (e == hipSuccess) c->n_cu = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
   }
-  if (e == hipSuccess) e = hipMemset(base + w.flags, 0, (size_t)(1024 + 1) * kFlagStride * sizeof(unsigned));
+  if (e == hipSuccess) e = hipMemset(base + w.flags, 0, (size_t)(1024 + 64) * sizeof(unsigned));
   if (e == hipSuccess) e = pack_all(c, base + w.packed);
   if (e == hipSuccess) e = fast_prepare(desc->head_dim, desc->kv_capacity);
   if (e == hipSuccess) e = persist_prepare(c);
@@ -1175,16 +1183,6 @@ extern "C" int heisd_verify_step(heisd_verify_ctx *ctx, const heisd_kv_desc *kv,
   const bool prof = ctx->prof_on && ctx->prof_steps < HEISD_PROFILE_MAX_STEPS;
   if (prof) ctx->prof_steps++;
   const bool use_persist = use_fast && ctx->persist_ok && ctx->path == HEISD_PATH_PERSIST;   // AUTO: launch per phase
-  if (use_persist) {
-    ProfScope ps(ctx, HEISD_KC_PERSIST, st, prof);
-    persist_launch(ctx, kv, draft_tokens, K, batch, skip_mask, logits, st);
-  } else if (use_fast) {
-    fast_forward(ctx, kv, draft_tokens, K, batch, skip_mask, logits, st, prof);
-  } else if (ctx->path != HEISD_PATH_GENERIC) {          // BATCH, or AUTO when the M <= 8 kernels do not apply
-    batch_forward(ctx, kv, draft_tokens, K, batch, skip_mask, logits, st, prof);
-  } else {
-    generic_forward(ctx, kv, draft_tokens, K, batch, skip_mask, logits, st, prof);
-  }
   AcceptArgs aa{};
   aa.logits = logits; aa.logits_rw = logits; aa.draft = draft_tokens; aa.first_pred = kv->first_pred;
   aa.skip = skip_mask; aa.accepted_len = accepted_len; aa.next_token = next_token; aa.target_bins = tbins;
@@ -1192,7 +1190,19 @@ extern "C" int heisd_verify_step(heisd_verify_ctx *ctx, const heisd_kv_desc *kv,
   aa.tok_threshold = accept->tok_threshold; aa.seq_budget = accept->seq_budget;
   aa.n_groups = accept->n_groups; aa.mode = accept->mode; aa.exact_mask = accept->exact_group_mask;
   for (int i = 0; i < 8; ++i) aa.group_sizes[i] = i < accept->n_groups ? accept->group_sizes[i] : 1;
-  {
+  bool accept_done = false;
+  if (use_persist) {
+    ProfScope ps(ctx, HEISD_KC_PERSIST, st, prof);
+    persist_launch(ctx, kv, draft_tokens, K, batch, skip_mask, logits, st);
+  } else if (use_fast) {
+    fast_forward(ctx, kv, draft_tokens, K, batch, skip_mask, logits, st, prof, &aa);   // acceptance inside the LM-head launch
+    accept_done = true;
+  } else if (ctx->path != HEISD_PATH_GENERIC) {          // BATCH, or AUTO when the M <= 8 kernels do not apply
+    batch_forward(ctx, kv, draft_tokens, K, batch, skip_mask, logits, st, prof);
+  } else {
+    generic_forward(ctx, kv, draft_tokens, K, batch, skip_mask, logits, st, prof);
+  }
+  if (!accept_done) {
     ProfScope ps(ctx, HEISD_KC_ACCEPT, st, prof);
     argmax_accept<<<dim3(batch), dim3(256), 0, st>>>(aa);
   }

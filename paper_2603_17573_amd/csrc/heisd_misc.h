@@ -2,6 +2,7 @@
 // and the sequence-wise relaxed acceptance scan.
 #pragma once
 #include "heisd_common.h"
+#include "heisd_fast.h"
 
 namespace heisd {
 
@@ -46,16 +47,17 @@ struct AcceptArgs {
   unsigned exact_mask;
 };
 
-// One workgroup per episode.  Greedy bin per position (Eq. 2-1: argmax; lowest index on
-// ties, NaN never wins), then the acceptance rule of Sec. 4.2 walked group by group.
-// Integer work: bit-exact by construction.
-__global__ __launch_bounds__(256) void argmax_accept(AcceptArgs a) {
-  const int b = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+// Episode b, by one workgroup of NT threads (all of them call this; it holds a workgroup barrier).
+// Greedy bin per position (Eq. 2-1: argmax; lowest index on ties, NaN never wins), then the
+// acceptance rule of Sec. 4.2 walked group by group.  Integer work: bit-exact by construction.
+template <int NT>
+__device__ __forceinline__ void accept_episode(const AcceptArgs &a, int b, int tid) {
+  const int lane = tid & 63, wave = tid >> 6;
   const int K = a.K;
   int32_t *tb = a.target_bins + (size_t)b * (K + 1);
   if (a.skip && a.skip[b]) {
-    for (int i = tid; i < K * a.n_bins; i += 256) a.logits_rw[(size_t)b * K * a.n_bins + i] = __uint_as_float(0x7FC00000u);
-    for (int j = tid; j <= K; j += 256) tb[j] = -1;
+    for (int i = tid; i < K * a.n_bins; i += NT) a.logits_rw[(size_t)b * K * a.n_bins + i] = __uint_as_float(0x7FC00000u);
+    for (int j = tid; j <= K; j += NT) tb[j] = -1;
     if (tid == 0) {
       a.accepted_len[b] = K;   // an unverified draft is executed as is
       a.next_token[b] = -1;
@@ -64,7 +66,7 @@ __global__ __launch_bounds__(256) void argmax_accept(AcceptArgs a) {
   }
   if (tid == 0) tb[0] = a.first_pred[b];
   // one wave per row: lanes stride over the bins, butterfly arg-max (lowest index wins ties)
-  for (int j = wave; j < K; j += 4) {
+  for (int j = wave; j < K; j += NT / 64) {
     const float *row = a.logits + ((size_t)b * K + j) * a.n_bins;
     float best = -INFINITY;
     int bi = 0x7FFFFFFF;
@@ -129,6 +131,32 @@ __global__ __launch_bounds__(256) void argmax_accept(AcceptArgs a) {
   }
   a.accepted_len[b] = n;
   a.next_token[b] = a.bin_base + tb[n];
+}
+
+// One workgroup per episode.
+__global__ __launch_bounds__(256) void argmax_accept(AcceptArgs a) { accept_episode<256>(a, blockIdx.x, threadIdx.x); }
+
+// The LM-head slice of the <= 8-row kernels with the greedy bins and the acceptance scan in the same
+// launch: the workgroup that finishes its logit tiles last (a wrapping device-scope counter tells it)
+// judges every episode (K4/K5 in one launch with the GEMM).  The logits are written with device-scope stores and each workgroup waits for
+// its own before it counts itself, so the last one reads complete rows.
+__global__ __launch_bounds__(kFastThreads) void fast_lmhead_accept_kernel(FastGemm g, AcceptArgs a, int batch,
+                                                                          unsigned *done_counter) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  __shared__ int s_last;
+  Frag16 A;
+  const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  fast_issue16(A, g, blockIdx.x, gridDim.x, 0, wave, lane & 15, lane >> 4);
+  fast_gemm_phase(g, blockIdx.x, gridDim.x, smem, A, true);
+  __builtin_amdgcn_s_waitcnt(0);                       // this wave's logit stores have reached memory
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    const unsigned old = atomicInc(done_counter, gridDim.x - 1);      // wraps to 0 with the last arrival: no reset
+    s_last = old == gridDim.x - 1 ? 1 : 0;
+  }
+  __syncthreads();
+  if (!s_last) return;
+  for (int b = 0; b < batch; ++b) accept_episode<kFastThreads>(a, b, threadIdx.x);
 }
 
 // Greedy bin after the LAST of the n new rows of every episode (Eq. 2-1: the target's own next token),
