@@ -403,6 +403,9 @@ def main():
     ap.add_argument("--handover", type=int, default=0, choices=[0, 1, 2, 3],
                     help="--path 3 only: what the persistent kernel requests across its grid barriers "
                          "(heisd_verify_set_handover; 0 = default)")
+    ap.add_argument("--persist-trace", action="store_true",
+                    help="--path 3 only: after the timed steps, record one step's device timestamps of every workgroup "
+                         "in every phase (heisd_debug_trace) and add their summary to the JSON line")
     ap.add_argument("--tree", type=int, default=0, metavar="R",
                     help="time the TREE verify step instead: R retrieved candidates per episode, built into a "
                          "sequence-wise draft tree (paper Sec. 4.2); 0 = the linear step")
@@ -552,6 +555,38 @@ def main():
                 al = al[skip == 0]
             hist["%d/%d" % (tt, ts)] = np.bincount(al, minlength=K + 1).tolist()
 
+    timeline = None
+    if args.persist_trace and args.path == 3 and not R:
+        from paper_2603_17573_amd import heisd_debug_trace
+        n_ph, n_wg = 5 * sh.n_layers + 2, torch.cuda.get_device_properties(0).multi_processor_count
+        heisd_debug_trace(ver.ctx, True)
+        for _ in range(3):
+            step(acc, out=out)
+        torch.cuda.synchronize()
+        got, buf = heisd_debug_trace(ver.ctx, False, n_ph * n_wg * 8)
+        assert got == n_ph * n_wg * 8, got
+        t = np.array(buf, dtype=np.int64).reshape(n_ph, n_wg, 8) / 100.0          # us (100 MHz counter)
+        names = ["embed"] + ["qkv", "attn", "oproj", "gateup", "down"] * sh.n_layers + ["lmhead"]
+        timeline = {"note": "us, means over layers 2.. of one step; per phase kind, relative to the first workgroup's "
+                            "pass of the barrier that opens the phase: when the last workgroup passed it, when the "
+                            "workgroups had consumed their weights (min / mean / max), when they had published their "
+                            "outputs (min / mean / max), and when the first and last workgroup passed the next barrier",
+                    "step_us": round(float(t[-1, :, 3].max() - t[0, :, 0].min()), 1), "phases": {}}
+        for nm in ("qkv", "attn", "oproj", "gateup", "down"):
+            rows_ = []
+            for i in range(11, n_ph - 1):
+                if names[i] != nm:
+                    continue
+                r0 = t[i, :, 1].min()
+                rows_.append([t[i, :, 1].max() - r0, t[i, :, 2].min() - r0, t[i, :, 2].mean() - r0, t[i, :, 2].max() - r0,
+                              t[i, :, 3].min() - r0, t[i, :, 3].mean() - r0, t[i, :, 3].max() - r0,
+                              t[i + 1, :, 1].min() - r0, t[i + 1, :, 1].max() - r0])
+            m = np.mean(rows_, axis=0)
+            timeline["phases"][nm] = {"last_release": round(float(m[0]), 2),
+                                      "consumed_min_mean_max": [round(float(x), 2) for x in m[1:4]],
+                                      "published_min_mean_max": [round(float(x), 2) for x in m[4:7]],
+                                      "next_release_first_last": [round(float(x), 2) for x in m[7:9]]}
+
     # per-kernel durations: HIP events recorded by the library on the launch stream
     n_prof = max(1, min(args.steps, 32))
     heisd_verify_profile_enable(ver.ctx, True)
@@ -644,6 +679,7 @@ def main():
         "accepted_len_histograms_by_threshold": hist or None,
         "weights_gen_s": round(t_gen, 1),
         "kernels": kernels,
+        "persistent_kernel_timeline": timeline,
         "roofline": roofline,
         "cpu_baseline": cpu,
     }

@@ -492,7 +492,7 @@ static size_t persist_lds(const heisd_verify_ctx *) { return kPersistLds; }
 // The persistent kernel needs every workgroup resident at once: one per compute unit.
 static hipError_t persist_prepare(heisd_verify_ctx *c) {
   c->persist_ok = false;
-  if (!c->fast_ok || c->n_cu > 1024) return hipSuccess;
+  if (!c->fast_ok || c->n_cu > 512) return hipSuccess;      // a barrier poll covers 512 flags
   // the attention units work in the LDS below the hand-over region, which holds the O-projection's first
   // weight steps while they run
   if (fast_attn_lds(c->d.head_dim, c->d.kv_capacity) > kPfOff) return hipSuccess;

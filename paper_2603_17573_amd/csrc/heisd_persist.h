@@ -177,14 +177,15 @@ __device__ __forceinline__ bool grid_wait(const PersistArgs &p, int nwg, unsigne
     const int lane = tid;
     int spins = 0;
     bool good = true;
+    const unsigned long long *f64 = reinterpret_cast<const unsigned long long *>(p.flags);
     while (true) {
       bool ok = true;
       for (int i = lane; 2 * i < nwg; i += kWave) {       // two flags per load
-        const unsigned long long f = __hip_atomic_load(reinterpret_cast<const unsigned long long *>(p.flags) + i,
-                                                       __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        const unsigned long long f = __hip_atomic_load(f64 + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         ok = ok && ((int)((unsigned)f - epoch) >= 0) && (2 * i + 1 >= nwg || (int)((unsigned)(f >> 32) - epoch) >= 0);
       }
       if (__all(ok)) break;
+      __builtin_amdgcn_s_sleep(8);      // 256 pollers at full rate slow the loads they wait for (1 % of the step)
       if (++spins > kSpinLimit ||
           ((spins & 255) == 0 && __hip_atomic_load(p.err, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0u)) {
         good = false;
