@@ -72,8 +72,11 @@ typedef struct {
  * prefix_len[b]+K-1 of every non-skipped episode b (the drafts' keys/values), so
  * that the caller's next step can start at prefix_len[b] + accepted_len[b]; rows
  * past that are garbage to be overwritten.  prefix_len[b] + K <= kv_capacity is the
- * caller's duty (device data cannot be checked without a sync; the kernels clamp
- * instead of faulting).
+ * caller's duty; device data cannot be checked on the host without a sync, so an episode
+ * that breaks it (or has a negative prefix_len) is left out of the step ON THE DEVICE:
+ * nothing of its cache is read or written, its accepted_len and next_token (next_bin
+ * of heisd_prefill_chunk) are -1, its target_bins -1, its logits NaN, the other episodes
+ * are unaffected, and heisd_verify_check reports it.
  * first_pred[b] is the target's greedy bin after the last prefix position, i.e.
  * a_hat_0 of Eq. 2-2, which depends on the prefix alone and is produced by whoever
  * filled the cache.
@@ -361,9 +364,11 @@ int heisd_verify_profile_read(heisd_verify_ctx *ctx, double *ms, int64_t *launch
  * make a larger step fail with EUNSUPPORTED.  Results of the paths agree to fp32 rounding.
  *
  * The persistent kernel spins at its grid barriers with a bound; if the bound expires (the
- * GPU was shared with work that kept some of its workgroups from running) it raises a device
- * error word and ends.  heisd_verify_check synchronises the device and returns EHIP if that
- * word is set (and clears it), else OK.
+ * GPU was shared with work that kept some of its workgroups from running) it raises a bit of the
+ * context's device error word and ends; its outputs are then undefined.  An episode whose new rows did
+ * not fit its cache raises another bit (see heisd_kv_desc).  heisd_verify_check synchronises the
+ * device, clears the word and returns EHIP for an expired barrier, EINVAL for an episode that did
+ * not fit, else OK (heisd_last_error says which).
  */
 #define HEISD_PATH_AUTO 0
 #define HEISD_PATH_GENERIC 1

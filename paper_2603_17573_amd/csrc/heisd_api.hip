@@ -718,7 +718,9 @@ extern "C" int heisd_verify_check(heisd_verify_ctx *ctx) {
     return fail(ctx, HEISD_EHIP, "check: device error");
   if (w != 0) {
     (void)hipMemset(ctx->dev_err, 0, sizeof(w));
-    return fail(ctx, HEISD_EHIP, "check: a grid barrier of the persistent kernel timed out");
+    if (w & kErrBarrier) return fail(ctx, HEISD_EHIP, "check: a grid barrier of the persistent kernel timed out");
+    return fail(ctx, HEISD_EINVAL, "check: an episode's new rows did not fit its cache (prefix_len + rows > kv_capacity, or "
+                "a negative prefix_len): it was left unverified, its cache untouched, its accepted_len / next_bin -1");
   }
   return HEISD_OK;
 }
@@ -1190,6 +1192,7 @@ extern "C" int heisd_verify_step(heisd_verify_ctx *ctx, const heisd_kv_desc *kv,
   aa.tok_threshold = accept->tok_threshold; aa.seq_budget = accept->seq_budget;
   aa.n_groups = accept->n_groups; aa.mode = accept->mode; aa.exact_mask = accept->exact_group_mask;
   for (int i = 0; i < 8; ++i) aa.group_sizes[i] = i < accept->n_groups ? accept->group_sizes[i] : 1;
+  aa.prefix_len = kv->prefix_len; aa.cap = cap; aa.err = ctx->dev_err;
   bool accept_done = false;
   if (use_persist) {
     ProfScope ps(ctx, HEISD_KC_PERSIST, st, prof);
@@ -1266,6 +1269,7 @@ extern "C" int heisd_verify_tree_step(heisd_verify_ctx *ctx, const heisd_kv_desc
   aa.tok_threshold = accept->tok_threshold; aa.seq_budget = accept->seq_budget;
   aa.n_groups = accept->n_groups; aa.mode = accept->mode; aa.exact_mask = accept->exact_group_mask;
   for (int i = 0; i < 8; ++i) aa.group_sizes[i] = i < accept->n_groups ? accept->group_sizes[i] : 1;
+  aa.prefix_len = kv->prefix_len; aa.cap = d.kv_capacity; aa.err = ctx->dev_err;
   TreeCompactArgs ca{};
   ca.k_cache = static_cast<uint16_t *>(kv->k_cache); ca.v_cache = static_cast<uint16_t *>(kv->v_cache);
   ca.prefix_len = kv->prefix_len; ca.skip = skip_mask; ca.accepted_len = accepted_len; ca.path = path;
@@ -1380,7 +1384,8 @@ extern "C" int heisd_prefill_chunk(heisd_verify_ctx *ctx, const heisd_kv_desc *k
     batch_forward(ctx, kv, token_ids, n_rows, batch, nullptr, ctx->logits, st, prof, nullptr, nullptr, x_rows);
   {
     ProfScope ps(ctx, HEISD_KC_ACCEPT, st, prof);
-    last_row_argmax<<<dim3(batch), dim3(64), 0, st>>>(ctx->logits, n_rows, d.n_bins, next_bin, last_logits);
+    last_row_argmax<<<dim3(batch), dim3(64), 0, st>>>(ctx->logits, n_rows, d.n_bins, next_bin, last_logits, kv->prefix_len,
+                                                      d.kv_capacity, ctx->dev_err);
   }
   const hipError_t e = hipGetLastError();
   if (e != hipSuccess) return fail(ctx, HEISD_EHIP, "prefill_chunk: %s", hipGetErrorString(e));

@@ -98,7 +98,7 @@ __device__ __forceinline__ void attn_append_rows(const AttnArgs &a, int b, int h
 template <int HD, bool TREE>
 __global__ __launch_bounds__(256) void attn_append(AttnArgs a) {
   const int h = blockIdx.x, b = blockIdx.y;
-  if (a.skip && a.skip[b]) return;
+  if (episode_sits_out(a.skip, a.prefix_len, b, a.K, a.cap)) return;
   int P = a.prefix_len[b];
   P = max(0, min(P, a.cap - a.K));
   const int jb = (int)blockIdx.z * kAttnQB;
@@ -134,7 +134,7 @@ __global__ __launch_bounds__(THREADS) __attribute__((amdgpu_waves_per_eu((THREAD
   const int K = a.K, d = a.d, cap = a.cap;
   const int row0 = b * K;
   const int jb = SPLIT ? (int)blockIdx.z * kAttnQB : 0, je = SPLIT ? min(K, jb + kAttnQB) : K;   // this workgroup's queries
-  if (a.skip && a.skip[b]) {
+  if (episode_sits_out(a.skip, a.prefix_len, b, K, cap)) {
     for (int idx = tid; idx < (je - jb) * HD; idx += kAttnThreads)
       attn_store(a, row0 + jb + idx / HD, h * HD + (idx % HD), 0.f);
     return;

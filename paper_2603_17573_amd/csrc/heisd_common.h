@@ -67,6 +67,20 @@ __device__ __forceinline__ void wait_vmcnt_all() {
   asm volatile("" ::: "memory");
 }
 
+// Does episode b sit this step out?  Either its verify-skip flag is set (Sec. 4.1), or its new rows
+// would not fit its cache (prefix_len[b] < 0 or prefix_len[b] + rows > capacity) - a caller's error
+// that the host cannot see.  Every kernel that touches per-episode state treats both alike: nothing
+// of the episode's cache is read or written.  The acceptance kernels tell them apart again and report
+// the second kind (accepted_len = -1, error word).
+__device__ __forceinline__ bool episode_overflows(const int32_t *prefix_len, int b, int rows, int cap) {
+  const int P = prefix_len[b];
+  return P < 0 || P > cap - rows;
+}
+__device__ __forceinline__ bool episode_sits_out(const uint8_t *skip, const int32_t *prefix_len, int b, int rows, int cap) {
+  return (skip && skip[b]) || episode_overflows(prefix_len, b, rows, cap);
+}
+constexpr unsigned kErrBarrier = 1u, kErrOverflow = 2u;      // bits of the device error word
+
 __device__ __forceinline__ float wave_sum(float v) {
 #pragma unroll
   for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, kWave);

@@ -489,7 +489,7 @@ __device__ __forceinline__ void fast_attn_prefetch(const FastAttn &a, int b, int
   const int li = tid % LPK, g = tid / LPK;
   int P = a.prefix_len[b];
   P = max(0, min(P, a.cap - a.K));
-  const bool skip = a.skip && a.skip[b];
+  const bool skip = episode_sits_out(a.skip, a.prefix_len, b, a.K, a.cap);
   const uint16_t *kc = a.k_cache + ((size_t)(b * a.H + h) * a.cap) * HD;
   const uint16_t *vc = a.v_cache + ((size_t)(b * a.H + h) * a.cap) * HD;
 #pragma unroll
@@ -528,7 +528,7 @@ __device__ __forceinline__ void fast_attn_unit(const FastAttn &a, int b, int h, 
   const int K = a.K, d = a.d, cap = a.cap;
   const int m = b * K + jq;                         // activation row of this query
   const int li = tid % LPK, g = tid / LPK;
-  if (a.skip && a.skip[b]) {
+  if (episode_sits_out(a.skip, a.prefix_len, b, K, cap)) {
     for (int c2 = tid; c2 < HALF; c2 += kFastThreads) {     // zero this row's slice of the records
       const int c = c2 * 2;
       uint32_t *rec = reinterpret_cast<uint32_t *>(a.o_planes + (size_t)(h * TPH + c / 16) * 256);

@@ -45,6 +45,9 @@ struct AcceptArgs {
   int tok_threshold, seq_budget, n_groups, mode;
   int group_sizes[8];
   unsigned exact_mask;
+  const int32_t *prefix_len;  // [batch]: an episode whose K new rows do not fit its cache was left unverified
+  int cap;
+  unsigned *err;              // device error word (kErrOverflow is raised for such an episode)
 };
 
 // Episode b, by one workgroup of NT threads (all of them call this; it holds a workgroup barrier).
@@ -55,12 +58,14 @@ __device__ __forceinline__ void accept_episode(const AcceptArgs &a, int b, int t
   const int lane = tid & 63, wave = tid >> 6;
   const int K = a.K;
   int32_t *tb = a.target_bins + (size_t)b * (K + 1);
-  if (a.skip && a.skip[b]) {
+  const bool overflow = episode_overflows(a.prefix_len, b, K, a.cap);
+  if (overflow || (a.skip && a.skip[b])) {
     for (int i = tid; i < K * a.n_bins; i += NT) a.logits_rw[(size_t)b * K * a.n_bins + i] = __uint_as_float(0x7FC00000u);
     for (int j = tid; j <= K; j += NT) tb[j] = -1;
     if (tid == 0) {
-      a.accepted_len[b] = K;   // an unverified draft is executed as is
+      a.accepted_len[b] = overflow ? -1 : K;   // an unverified draft is executed as is; no room in the cache: an error
       a.next_token[b] = -1;
+      if (overflow) atomicOr(a.err, kErrOverflow);
     }
     return;
   }
@@ -161,9 +166,21 @@ __global__ __launch_bounds__(kFastThreads) void fast_lmhead_accept_kernel(FastGe
 
 // Greedy bin after the LAST of the n new rows of every episode (Eq. 2-1: the target's own next token),
 // and optionally that row's logits.  One wave per episode.
+// An episode whose n new rows did not fit its cache was left out by the attention kernels: its
+// prediction is -1, its logits NaN, and the error word is raised.
 __global__ __launch_bounds__(64) void last_row_argmax(const float *logits, int n, int n_bins, int32_t *pred,
-                                                      float *last_logits) {
+                                                      float *last_logits, const int32_t *prefix_len, int cap,
+                                                      unsigned *err) {
   const int b = blockIdx.x, lane = threadIdx.x;
+  if (episode_overflows(prefix_len, b, n, cap)) {
+    if (last_logits)
+      for (int t = lane; t < n_bins; t += kWave) last_logits[(size_t)b * n_bins + t] = __uint_as_float(0x7FC00000u);
+    if (lane == 0) {
+      pred[b] = -1;
+      atomicOr(err, kErrOverflow);
+    }
+    return;
+  }
   const float *row = logits + ((size_t)b * n + (n - 1)) * n_bins;
   float best = -INFINITY;
   int bi = 0x7FFFFFFF;
@@ -236,6 +253,9 @@ struct TreeAcceptArgs {
   int tok_threshold, seq_budget, n_groups, mode;
   int group_sizes[8];
   unsigned exact_mask;
+  const int32_t *prefix_len;  // as in AcceptArgs
+  int cap;
+  unsigned *err;
 };
 
 // One workgroup per episode, thread t for tree token t.  Greedy bin after every tree token, then the
@@ -257,7 +277,8 @@ __global__ __launch_bounds__(256) void tree_accept(TreeAcceptArgs a) {
   int32_t *tb = a.target_bins + (size_t)b * (T + 1);
   int32_t *path = a.path + (size_t)b * T;
   const int32_t *par = a.parent + (size_t)b * T;
-  const bool skipped = a.skip && a.skip[b];
+  const bool overflow = episode_overflows(a.prefix_len, b, T, a.cap);
+  const bool skipped = overflow || (a.skip && a.skip[b]);
   if (tid < T) {
     s_par[tid] = par[tid];
     s_child[tid] = 0x7FFFFFFF;       // lowest-index child
@@ -317,8 +338,12 @@ __global__ __launch_bounds__(256) void tree_accept(TreeAcceptArgs a) {
           cur = c;
         }
       }
-      a.accepted_len[b] = n;
+      a.accepted_len[b] = overflow ? -1 : n;
       a.next_token[b] = -1;
+      if (overflow) {
+        for (int j = 0; j < n; ++j) path[j] = -1;
+        atomicOr(a.err, kErrOverflow);
+      }
     }
     return;
   }
@@ -431,7 +456,7 @@ struct TreeCompactArgs {
 // then written: a source row is never overwritten before it is read.
 __global__ __launch_bounds__(256) void tree_compact(TreeCompactArgs a) {
   const int h = blockIdx.x, b = blockIdx.y, l = blockIdx.z, tid = threadIdx.x;
-  if (a.skip && a.skip[b]) return;
+  if (episode_sits_out(a.skip, a.prefix_len, b, a.T, a.cap)) return;
   const int n = max(0, min(a.accepted_len[b], a.T));
   int P = a.prefix_len[b];
   P = max(0, min(P, a.cap - a.T));

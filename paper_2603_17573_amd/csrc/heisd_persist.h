@@ -187,12 +187,12 @@ __device__ __forceinline__ bool grid_wait(const PersistArgs &p, int nwg, unsigne
       if (__all(ok)) break;
       __builtin_amdgcn_s_sleep(8);      // 256 pollers at full rate slow the loads they wait for (1 % of the step)
       if (++spins > kSpinLimit ||
-          ((spins & 255) == 0 && __hip_atomic_load(p.err, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0u)) {
+          ((spins & 255) == 0 && (__hip_atomic_load(p.err, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) & kErrBarrier) != 0u)) {
         good = false;
         break;
       }
     }
-    if (!good && lane == 0) __hip_atomic_store(p.err, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (!good && lane == 0) __hip_atomic_fetch_or(p.err, kErrBarrier, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     if (lane == 0) s_ok = good ? 1 : 0;
   } else if (land_transfers && wave >= kPfWave0) {
     wait_vmcnt_all();

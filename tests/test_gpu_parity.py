@@ -118,6 +118,51 @@ def test_persistent_kernel_handover_modes_agree(mode):
     ver.close()
 
 
+@pytest.mark.parametrize("path,B,K", [(0, 2, 4), (3, 2, 4), (4, 3, 7), (1, 3, 7)])
+def test_episode_that_does_not_fit_its_cache_is_left_out(path, B, K):
+    """prefix_len + K > kv_capacity for one episode (the host cannot see it): that episode's cache is
+    untouched and its outputs say so, the other episodes still match the oracle, and
+    heisd_verify_check reports the episode."""
+    import torch
+    import paper_2603_17573_amd as P
+    from gpu_harness import _bits_to_dev, _dev_to_bits, accept_desc_of, compare_with_oracle
+    _need_gpu()
+    wl = synth.Workload("mid_ovf", MID, 20, 9, MID.bin_base, batch=B, K=K, seed=17 + B)
+    weights = synth.make_weights(MID, wl.seed)
+    om = oracle_model(MID, weights)
+    cap = wl.prefix_len + K
+    kb, vb, plen, first = oracle_prefix_cache(om, wl, cap)
+    plen_bad = plen.copy()
+    plen_bad[B - 1] = cap - K + 1                         # one row too many
+    drafts = (MID.bin_base + synth.make_drafts_uniform(wl)).astype(np.int32)
+    rule = oracle.AcceptRule(2, 6)
+    good = [b for b in range(B) if b != B - 1]
+    ref = oracle.verify_step(om, kb[:, good], vb[:, good], plen[good], first[good], drafts[good], rule)
+    dm = P.DeviceModel(MID, weights)
+    ver = P.Verifier(dm, B, K, cap)
+    assert P.heisd_verify_set_path(ver.ctx, path) == 0
+    dev = "cuda:0"
+    kc, vc = _bits_to_dev(kb, dev), _bits_to_dev(vb, dev)
+    out = ver.step(kc, vc, torch.from_numpy(plen_bad).to(dev), torch.from_numpy(first).to(dev),
+                   torch.from_numpy(drafts).to(dev), accept_desc_of(rule))
+    torch.cuda.synchronize()
+    got = {k: v.cpu().numpy() for k, v in out.items()}
+    got["k_cache"], got["v_cache"] = _dev_to_bits(kc), _dev_to_bits(vc)
+    assert got["accepted_len"][B - 1] == -1 and got["next_token"][B - 1] == -1
+    assert np.all(got["target_bins"][B - 1] == -1) and np.all(np.isnan(got["bin_logits"][B - 1]))
+    assert np.array_equal(got["k_cache"][:, B - 1], kb[:, B - 1]) and np.array_equal(got["v_cache"][:, B - 1], vb[:, B - 1])
+    compare_with_oracle(got, ref, drafts, rule, MID, kb, vb, plen, None, episodes=good)
+    assert P.heisd_verify_check(ver.ctx) == P.HEISD_EINVAL and "did not fit" in P.heisd_last_error(ver.ctx)
+    assert P.heisd_verify_check(ver.ctx) == 0             # the word is cleared by the check
+    # the same context still serves a step that fits
+    kc, vc = _bits_to_dev(kb, dev), _bits_to_dev(vb, dev)
+    out = ver.step(kc, vc, torch.from_numpy(plen).to(dev), torch.from_numpy(first).to(dev),
+                   torch.from_numpy(drafts).to(dev), accept_desc_of(rule))
+    torch.cuda.synchronize()
+    assert int(out["accepted_len"].cpu()[B - 1]) >= 0 and P.heisd_verify_check(ver.ctx) == 0
+    ver.close()
+
+
 def test_mid_hd128_ragged_prefixes_geometric_drafts():
     wl = synth.Workload("mid_b3", MID, 50, 20, MID.bin_base, batch=3, K=7, draft=("geometric", 0.5), seed=11)
     got, ref, stats = run_case(wl, plen_override=[70, 33, 64])
