@@ -570,7 +570,8 @@ def main():
         timeline = {"note": "us, means over layers 2.. of one step; per phase kind, relative to the first workgroup's "
                             "pass of the barrier that opens the phase: when the last workgroup passed it, when the "
                             "workgroups had consumed their weights (min / mean / max), when they had published their "
-                            "outputs (min / mean / max), and when the first and last workgroup passed the next barrier",
+                            "outputs (min / mean / max), when the first and last workgroup passed the next barrier, when their "
+                            "polls had seen every flag, and how long a workgroup then waited for its hand-over to land",
                     "step_us": round(float(t[-1, :, 3].max() - t[0, :, 0].min()), 1), "phases": {}}
         for nm in ("qkv", "attn", "oproj", "gateup", "down"):
             rows_ = []
@@ -580,12 +581,16 @@ def main():
                 r0 = t[i, :, 1].min()
                 rows_.append([t[i, :, 1].max() - r0, t[i, :, 2].min() - r0, t[i, :, 2].mean() - r0, t[i, :, 2].max() - r0,
                               t[i, :, 3].min() - r0, t[i, :, 3].mean() - r0, t[i, :, 3].max() - r0,
-                              t[i + 1, :, 1].min() - r0, t[i + 1, :, 1].max() - r0])
+                              t[i + 1, :, 1].min() - r0, t[i + 1, :, 1].max() - r0,
+                              t[i + 1, :, 6].min() - r0, t[i + 1, :, 6].max() - r0,
+                              (t[i + 1, :, 1] - t[i + 1, :, 6]).mean(), (t[i + 1, :, 1] - t[i + 1, :, 6]).max()])
             m = np.mean(rows_, axis=0)
             timeline["phases"][nm] = {"last_release": round(float(m[0]), 2),
                                       "consumed_min_mean_max": [round(float(x), 2) for x in m[1:4]],
                                       "published_min_mean_max": [round(float(x), 2) for x in m[4:7]],
-                                      "next_release_first_last": [round(float(x), 2) for x in m[7:9]]}
+                                      "next_release_first_last": [round(float(x), 2) for x in m[7:9]],
+                                      "next_polls_done_first_last": [round(float(x), 2) for x in m[9:11]],
+                                      "next_polls_done_to_release_mean_max": [round(float(x), 2) for x in m[11:13]]}
 
     # per-kernel durations: HIP events recorded by the library on the launch stream
     n_prof = max(1, min(args.steps, 32))

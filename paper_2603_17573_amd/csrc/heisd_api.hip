@@ -487,15 +487,13 @@ static const void *persist_pick(const heisd_verify_ctx *c) {
                               : reinterpret_cast<const void *>(&persist_forward<64>);
 }
 
-static size_t persist_lds(const heisd_verify_ctx *) { return kPersistLds; }
+static size_t persist_lds(const heisd_verify_ctx *c) { return persist_lds_bytes(c->d.head_dim, c->d.kv_capacity); }
 
 // The persistent kernel needs every workgroup resident at once: one per compute unit.
 static hipError_t persist_prepare(heisd_verify_ctx *c) {
   c->persist_ok = false;
   if (!c->fast_ok || c->n_cu > 512) return hipSuccess;      // a barrier poll covers 512 flags
-  // the attention units work in the LDS below the hand-over region, which holds the O-projection's first
-  // weight steps while they run
-  if (fast_attn_lds(c->d.head_dim, c->d.kv_capacity) > kPfOff) return hipSuccess;
+  if (persist_lds(c) > kLdsPerWorkgroup) return hipSuccess;
   const void *fn = persist_pick(c);
   hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)persist_lds(c));
   if (e != hipSuccess) return e;
@@ -513,14 +511,15 @@ static hipError_t persist_prepare(heisd_verify_ctx *c) {
 //   1  as 0, but the O-projection's hand-over starts at the end of the QKV phase
 //   2  no LDS hand-over: the whole first tile is requested into registers before the barrier
 //   3  nothing is requested across a barrier
+//   4  as 0, and the second weight tile is requested into registers before the barrier
 static hipError_t persist_build_program(heisd_verify_ctx *ctx) {
   const heisd_model_desc &d = ctx->d;
   const int L = d.n_layers;
   const FastScratch fs(&d);
   const bool stream_down = d.d_ffn > kFastWaves * kKS * 32;
   const int mode = ctx->handover_mode;
-  const bool lds = mode == 0 || mode == 1;
-  const int ft = (lds ? PHF_IN_LDS : 0) | (mode != 3 ? PHF_EARLY : 0);
+  const bool lds = mode == 0 || mode == 1 || mode == 4;
+  const int ft = (lds ? PHF_IN_LDS : 0) | (mode == 2 || mode == 4 ? PHF_EARLY : 0);
   auto nx = [&](int idx) { return lds ? idx : -1; };
   std::vector<Phase> prog;
   heisd_kv_desc no_kv{};
@@ -534,7 +533,7 @@ static hipError_t persist_build_program(heisd_verify_ctx *ctx) {
     const FastLayerDescs D = fast_layer_descs(ctx, &no_kv, l, 1, 1, nullptr);
     const int base = 1 + 5 * l;
     Phase q{}; q.kind = PH_GEMM; q.g = D.qkv; q.first_tile = ft; q.next_gemm = mode == 1 ? base + 2 : -1; prog.push_back(q);
-    Phase a{}; a.kind = PH_ATTN; a.layer = l; a.next_gemm = mode == 0 ? base + 2 : -1;
+    Phase a{}; a.kind = PH_ATTN; a.layer = l; a.next_gemm = mode == 0 || mode == 4 ? base + 2 : -1;
     a.g.b = reinterpret_cast<const uint16_t *>(D.attn.qkv); a.g.o_planes = D.attn.o_planes; prog.push_back(a);
     Phase o{}; o.kind = PH_GEMM; o.g = D.oproj; o.first_tile = ft; o.next_gemm = nx(base + 3); prog.push_back(o);
     Phase g{}; g.kind = PH_GEMM; g.g = D.gateup; g.first_tile = ft; g.next_gemm = nx(base + 4); prog.push_back(g);
@@ -685,7 +684,7 @@ extern "C" int heisd_verify_set_path(heisd_verify_ctx *ctx, int path) {
 
 extern "C" int heisd_verify_set_handover(heisd_verify_ctx *ctx, int mode) {
   if (!ctx) return HEISD_EINVAL;
-  if (mode < 0 || mode > 3) return fail(ctx, HEISD_EINVAL, "set_handover: unknown mode %d", mode);
+  if (mode < 0 || mode > 4) return fail(ctx, HEISD_EINVAL, "set_handover: unknown mode %d", mode);
   if (!ctx->persist_ok) return fail(ctx, HEISD_EUNSUPPORTED, "set_handover: the persistent kernel does not fit this device or shape");
   if (hipDeviceSynchronize() != hipSuccess) return fail(ctx, HEISD_EHIP, "set_handover: device error");
   ctx->handover_mode = mode;

@@ -30,16 +30,22 @@ namespace heisd {
 constexpr int kFlagStride = 1;           // flags are packed: a poll of all of them is 8 cache lines, not one per workgroup
 constexpr int kSpinLimit = 1 << 22;
 
-constexpr int kPF = 12;                         // k-steps of a wave's first weight tile handed over through LDS
+constexpr int kPF = kKS;                 // k-steps of a wave's first weight tile handed over through LDS: a whole ring
 constexpr int kPfWave0 = 6;              // waves kPfWave0 .. 7 issue the transfers (they never store in a GEMM epilogue)
-constexpr size_t kSyncOff = kFastRedBytes + 64;                      // 8 words: what each wave has published (see gemm_publish)
-constexpr size_t kIssuedOff = kFastRedBytes + 96;                    // 8 words: whose epilogue stores have been issued
-constexpr size_t kOkOff = kFastRedBytes + 128;                       // 1 word: outcome of the last grid wait
-constexpr size_t kPfOff = kFastRedBytes + 256;                       // after the reduction buffer, the row scales and those
-constexpr size_t kPersistLds = kPfOff + (size_t)kFastWaves * kPF * 1024;
+// LDS map.  The hand-over region (128 KB) and the reduction buffer share their bytes: a phase reads what was
+// handed over into registers when it starts and reduces through the same bytes when it ends, and the next
+// hand-over is started only after every storing wave has read its sums (p2_wait_stores_acked).  The attention
+// units work above both, so that the O-projection's hand-over may sit in LDS while they run.
+constexpr size_t kPfOff = 0;
+constexpr size_t kPfBytes = (size_t)kFastWaves * kPF * 1024;
+constexpr size_t kCtlOff = kPfBytes;                                 // 16 floats: the rows' 1/rms
+constexpr size_t kSyncOff = kCtlOff + 64;                            // 8 words: what each wave has published (see gemm_publish)
+constexpr size_t kOkOff = kCtlOff + 128;                             // 1 word: outcome of the last grid wait
+constexpr size_t kAttnOff = kCtlOff + 256;                           // the attention units' buffers (fast_attn_lds bytes)
+inline size_t persist_lds_bytes(int hd, int cap) { return kAttnOff + fast_attn_lds(hd, cap); }
+static_assert(kPfBytes >= kFastRedBytes, "the reduction buffer lies inside the hand-over region");
 static_assert(kMaxT <= kPfWave0, "the waves that issue transfers must not take part in epilogue stores");
-static_assert((kFastWaves / (kFastWaves - kPfWave0)) * kPF <= 63 && kFastWaves % (kFastWaves - kPfWave0) == 0,
-              "an issuing wave serves a whole number of wave shares and keeps at most 63 transfers outstanding");
+static_assert(kFastWaves % (kFastWaves - kPfWave0) == 0 && kPF <= 31, "an issuing wave serves a whole number of wave shares");
 
 enum { PHF_IN_LDS = 1,    // an earlier phase has handed steps 0 .. kPF-1 of every wave share over in LDS
        PHF_EARLY = 2 };   // the steps not handed over are requested before the wait at the barrier (not by wave 0)
@@ -102,21 +108,20 @@ __device__ __forceinline__ void grid_arrive(const PersistArgs &p, int wg, unsign
     __hip_atomic_store(&p.flags[wg * kFlagStride], epoch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
-// A compute unit serves its waves' vector memory operations in the order they were issued.  The 96
-// transfers of a hand-over take microseconds to drain, and epilogue stores issued behind them are
-// acknowledged only then (measured: 4-7 us from the last product to the published flag, against 0.4 us
-// for the attention phase, which hands nothing over).  So the storing waves say in LDS when their
-// epilogue's stores have been ISSUED, and the issuing waves start the hand-over after that.
-__device__ __forceinline__ void p2_stores_issued(unsigned char *smem, unsigned token, int tid) {
-  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  if ((tid & 63) == 0) reinterpret_cast<volatile unsigned *>(smem + kIssuedOff)[wave] = token;
-}
-__device__ __forceinline__ void p2_wait_stores_issued(unsigned char *smem, unsigned token, int tid) {
-  volatile unsigned *w = reinterpret_cast<volatile unsigned *>(smem + kIssuedOff);
+// A compute unit serves its waves' vector memory operations in the order they were issued, and the memory
+// system behind it is a queue too.  The 128 transfers of a hand-over take microseconds to drain, and
+// epilogue stores issued behind them - or merely while they are in flight - are acknowledged late
+// (measured: 4-7 us from the last product to the published flag with the hand-over in front of the stores,
+// 2-4 us with the hand-over started once the stores were issued, against 0.4 us for a phase that hands
+// nothing over).  So the hand-over starts when the workgroup's stores have been ACKNOWLEDGED: every wave
+// says so in LDS (gemm_publish, attn_publish), and the issuing waves wait for those words.  (Waiting for
+// the flag's acknowledgement as well measured slower again: the hand-over then starts too late.)
+__device__ __forceinline__ void p2_wait_stores_acked(unsigned char *smem, unsigned token, int tid, int n_waves) {
+  volatile unsigned *w = reinterpret_cast<volatile unsigned *>(smem + kSyncOff);
   const int lane = tid & 63;
   for (int spins = 0; spins < kSpinLimit; ++spins) {
     const unsigned v = w[lane & 7];                  // (read unconditionally: a load through a selected address
-    if (__all(lane >= kPfWave0 || v == token)) break;   //  would put `token` on the stack)
+    if (__all(lane >= n_waves || v == token)) break;    //  would put `token` on the stack)
   }
 }
 
@@ -130,10 +135,8 @@ __device__ __forceinline__ void gemm_publish(const PersistArgs &p, int wg, unsig
   if (wave >= kPfWave0) return;
   volatile unsigned *sync_s = reinterpret_cast<volatile unsigned *>(smem + kSyncOff);
   wait_vmcnt_all();
-  if (wave != 0) {
-    if (lane == 0) sync_s[wave] = token;
-    return;
-  }
+  if (lane == 0) sync_s[wave] = token;
+  if (wave != 0) return;
   for (int spins = 0; spins < kSpinLimit; ++spins) {
     const unsigned v = sync_s[lane & 7];
     if (__all(lane == 0 || lane >= kPfWave0 || v == token)) break;
@@ -152,9 +155,12 @@ __device__ __forceinline__ void attn_publish(const PersistArgs &p, int wg, int n
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
   volatile unsigned *sync_s = reinterpret_cast<volatile unsigned *>(smem + kSyncOff);
   wait_vmcnt_all();
+  if (lane == 0) sync_s[wave] = token;
   if (wave != 0) {
-    if (lane == 0) sync_s[wave] = token;
-    p2_handover_issue(p, ng, wg, nwg, pf_lds);          // waves kPfWave0.. only
+    if (wave >= kPfWave0) {
+      p2_wait_stores_acked(smem, token, tid, kFastWaves);
+      p2_handover_issue(p, ng, wg, nwg, pf_lds);
+    }
     return;
   }
   for (int spins = 0; spins < kSpinLimit; ++spins) {
@@ -192,6 +198,8 @@ __device__ __forceinline__ bool grid_wait(const PersistArgs &p, int nwg, unsigne
         break;
       }
     }
+    if (p.trace && lane == 0)      // slot 6: the polls have seen every flag (slot 1, taken after this function, includes
+      p.trace[((size_t)(epoch - p.epoch0) * gridDim.x + blockIdx.x) * 8 + 6] = wall_clock64();   // the transfers' landing)
     if (!good && lane == 0) __hip_atomic_fetch_or(p.err, kErrBarrier, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     if (lane == 0) s_ok = good ? 1 : 0;
   } else if (land_transfers && wave >= kPfWave0) {
@@ -331,6 +339,7 @@ __device__ __forceinline__ void p2_handover_issue(const PersistArgs &p, int ng, 
 #pragma unroll 1
   for (int i = 0; i < SH; ++i) {
     const int w = (wave - kPfWave0) * SH + i;
+    if ((i + 1) * kPF > 63) wait_vmcnt<63 - kPF>();            // a wave keeps at most 63 memory operations outstanding
 #pragma unroll
     for (int s = 0; s < kPF; ++s) {
       const int ks = __builtin_amdgcn_readfirstlane(p2_a_step(Kd, stream, w, s));
@@ -352,7 +361,7 @@ __device__ __forceinline__ bool p2_gemm_phase(const PersistArgs &p, int ph, int 
   const FastGemm g = phase_gemm(p, ph);
   const int ng = p2_phase(p, ph)->next_gemm;
   float *red = reinterpret_cast<float *>(smem);
-  float *scale_s = reinterpret_cast<float *>(smem + kFastRedBytes);
+  float *scale_s = reinterpret_cast<float *>(smem + kCtlOff);
   const u32x4 *pf = reinterpret_cast<const u32x4 *>(smem + kPfOff);
   const uint32_t pf_lds = p2_lds_addr(smem) + (uint32_t)kPfOff;
   const int tid = p2_tid(), lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -363,10 +372,12 @@ __device__ __forceinline__ bool p2_gemm_phase(const PersistArgs &p, int ph, int 
   Frag16 A;
   const int ft = p2_phase(p, ph)->first_tile;
   const bool in_lds = (ft & PHF_IN_LDS) != 0, early = (ft & PHF_EARLY) != 0;
-  if (my_entries > 0 && wave != 0 && early) {     // the polling wave keeps nothing in flight
+  // The first request into the register ring: the first tile - or, when that one was handed over in LDS, the
+  // second, so that weights stream while the activation fragments are still on their way.
+  const uint16_t *tb_ring = in_lds ? (my_entries > 1 ? p2_tile_base(g, wg, nwg, 1) : nullptr) : tb0;
+  if (my_entries > 0 && wave != 0 && early && tb_ring) {     // the polling wave keeps nothing in flight
 #pragma unroll
-    for (int s = 0; s < kKS; ++s)
-      if (s >= kPF || !in_lds) A.v[s] = p2_ld_a(tb0, p2_a_step(g.Kd, false, wave, s), a_off);
+    for (int s = 0; s < kKS; ++s) A.v[s] = p2_ld_a(tb_ring, p2_a_step(g.Kd, false, wave, s), a_off);
   }
   if (!grid_wait(p, nwg, wait_epoch, true, smem)) return false;
   p2_stamp(p, wg, ph, 1);
@@ -375,18 +386,18 @@ __device__ __forceinline__ bool p2_gemm_phase(const PersistArgs &p, int ph, int 
     gemm_publish(p, wg, wait_epoch + 1, smem, tid);
     return true;
   }
-  if (wave == 0 || !early) {
+  const bool ring_now = (wave == 0 || !early) && tb_ring;
+  if (ring_now && !in_lds) {
 #pragma unroll
-    for (int s = 0; s < kKS; ++s)
-      if (s >= kPF || !in_lds) A.v[s] = p2_ld_a(tb0, p2_a_step(g.Kd, false, wave, s), a_off);
+    for (int s = 0; s < kKS; ++s) A.v[s] = p2_ld_a(tb_ring, p2_a_step(g.Kd, false, wave, s), a_off);
   }
   const SsqPre sp = fast_row_scales_issue(g, wave, lane);
   Frag16 Bf;
 #pragma unroll
   for (int s = 0; s < kKS; ++s) Bf.v[s] = p2_ld_b(g.b, g.Kd, ks0, s, ns, b_off);
-  if (in_lds) {
+  if (ring_now && in_lds) {                                  // behind the activation fragments, which are needed first
 #pragma unroll
-    for (int s = 0; s < kPF; ++s) A.v[s] = pf[(wave * kPF + s) * 64 + lane];
+    for (int s = 0; s < kKS; ++s) A.v[s] = p2_ld_a(tb_ring, p2_a_step(g.Kd, false, wave, s), a_off);
   }
   for (int e0 = 0; e0 < my_entries; e0 += kMaxT) {
     f32x4 acc[kMaxT];
@@ -401,7 +412,13 @@ __device__ __forceinline__ bool p2_gemm_phase(const PersistArgs &p, int ph, int 
     }
 #pragma unroll
     for (int t = 0; t < kMaxT; ++t) {
-      if (e0 + t < my_entries) {
+      if (t == 0 && e0 == 0 && in_lds) {
+#pragma unroll
+        for (int s = 0; s < kKS; ++s) {
+          acc[0] = fast_mfma(pf[(wave * kPF + s) * 64 + lane], Bf.v[s], acc[0]);
+          if ((s & 1) == 1) __builtin_amdgcn_sched_barrier(0);     // two fragments out of LDS at a time, not all sixteen
+        }
+      } else if (e0 + t < my_entries) {
         if (t + 1 < kMaxT && e0 + t + 1 < my_entries) {
           const uint16_t *tb = p2_tile_base(g, wg, nwg, e0 + t + 1);
 #pragma unroll
@@ -431,12 +448,11 @@ __device__ __forceinline__ bool p2_gemm_phase(const PersistArgs &p, int ph, int 
     } else if (wave >= kPfWave0) {
       // last pass: the weights are consumed and the hand-over region is free.  From here to the next
       // phase's barrier the issuing waves and the storing waves go separate ways (no workgroup barrier).
-      p2_wait_stores_issued(smem, wait_epoch + 1, tid);
+      p2_wait_stores_acked(smem, wait_epoch + 1, tid, kPfWave0);
       p2_handover_issue(p, ng, wg, nwg, pf_lds);
     } else {
       p2_stamp(p, wg, ph, 4);
       fast_epilogue(g, wg, nwg, e0, min(kMaxT, my_entries - e0), red, scale_s, ep, tid);
-      p2_stores_issued(smem, wait_epoch + 1, tid);
       p2_stamp(p, wg, ph, 5);
     }
   }
@@ -450,7 +466,7 @@ __device__ __forceinline__ bool p2_gemm_stream_phase(const PersistArgs &p, int p
   const FastGemm g = phase_gemm(p, ph);
   const int ng = p2_phase(p, ph)->next_gemm;
   float *red = reinterpret_cast<float *>(smem);
-  float *scale_s = reinterpret_cast<float *>(smem + kFastRedBytes);
+  float *scale_s = reinterpret_cast<float *>(smem + kCtlOff);
   const u32x4 *pf = reinterpret_cast<const u32x4 *>(smem + kPfOff);
   const uint32_t pf_lds = p2_lds_addr(smem) + (uint32_t)kPfOff;
   const int tid = p2_tid(), lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -517,12 +533,11 @@ __device__ __forceinline__ bool p2_gemm_stream_phase(const PersistArgs &p, int p
       fast_epilogue(g, wg, nwg, e, 1, red, scale_s, ep, tid);
       lds_barrier();
     } else if (wave >= kPfWave0) {                    // as in p2_gemm_phase: no workgroup barrier from here on
-      p2_wait_stores_issued(smem, wait_epoch + 1, tid);
+      p2_wait_stores_acked(smem, wait_epoch + 1, tid, kPfWave0);
       p2_handover_issue(p, ng, wg, nwg, pf_lds);
     } else {
       p2_stamp(p, wg, ph, 4);
       fast_epilogue(g, wg, nwg, e, 1, red, scale_s, ep, tid);
-      p2_stores_issued(smem, wait_epoch + 1, tid);
       p2_stamp(p, wg, ph, 5);
     }
   }
@@ -539,7 +554,13 @@ __device__ __forceinline__ bool p2_attn_phase(const PersistArgs &p, int ph, int 
   at.qkv = reinterpret_cast<const float *>(P->g.b);
   at.k_cache = p.k_cache + (size_t)layer * p.kv_layer_stride;
   at.v_cache = p.v_cache + (size_t)layer * p.kv_layer_stride;
-  at.prefix_len = p.prefix_len; at.skip = p.skip; at.rope = p.rope;
+  at.prefix_len = p.prefix_len; at.rope = p.rope;
+  {   // the test of this pointer against NULL is made here, per phase: hoisted out of the loop over phases the
+      // outcome is one more value that lives across every phase body (it ended up in scratch)
+    const uint8_t *sk = p.skip;
+    asm volatile("" : "+s"(sk));
+    at.skip = sk;
+  }
   at.o_planes = P->g.o_planes;
   at.K = p.K; at.H = p.H; at.cap = p.cap; at.d = p.d; at.batch = p.batch; at.scale = p.scale;
   const int tid = p2_tid();
@@ -547,15 +568,17 @@ __device__ __forceinline__ bool p2_attn_phase(const PersistArgs &p, int ph, int 
   const bool have = attn_unit_of(p, wg, nwg, 0, ab, ah, aj);
   AttnPre pre;
   if (have) fast_attn_prefetch<HD>(at, ab, ah, pre, tid);       // cached rows: no dependence on this step's q/k/v
+  // (the polling wave included: leaving its rows for after the wait, so that its polls do not return behind
+  //  them, measured 0.3 % slower)
   if (!grid_wait(p, nwg, wait_epoch, false, smem)) return false;
   p2_stamp(p, wg, ph, 1);
   const int ng = P->next_gemm;
   const uint32_t pf_lds = p2_lds_addr(smem) + (uint32_t)kPfOff;
   if (have) {
-    fast_attn_unit<HD>(at, ab, ah, aj, smem, pre, tid);
+    fast_attn_unit<HD>(at, ab, ah, aj, smem + kAttnOff, pre, tid);
     for (int t = 1; attn_unit_of(p, wg, nwg, t, ab, ah, aj); ++t) {
       fast_attn_prefetch<HD>(at, ab, ah, pre, tid);
-      fast_attn_unit<HD>(at, ab, ah, aj, smem, pre, tid);
+      fast_attn_unit<HD>(at, ab, ah, aj, smem + kAttnOff, pre, tid);
     }
   }
   p2_stamp(p, wg, ph, 2);
@@ -570,7 +593,6 @@ __global__ __launch_bounds__(kFastThreads) void persist_forward(PersistArgs p) {
   const uint32_t pf_lds = p2_lds_addr(smem) + (uint32_t)kPfOff;
   if (threadIdx.x < kFastWaves) {      // the waves' words start at a value no phase of this launch publishes
     reinterpret_cast<volatile unsigned *>(smem + kSyncOff)[threadIdx.x] = p.epoch0;
-    reinterpret_cast<volatile unsigned *>(smem + kIssuedOff)[threadIdx.x] = p.epoch0;
   }
   lds_barrier();
   for (int ph = 0; ph < p.n_phases; ++ph) {
