@@ -545,7 +545,7 @@ static hipError_t persist_build_program(heisd_verify_ctx *ctx) {
 }
 
 static void persist_launch(heisd_verify_ctx *ctx, const heisd_kv_desc *kv, const int32_t *draft_tokens, int K,
-                           int batch, const uint8_t *skip_mask, float *logits, hipStream_t st) {
+                           int batch, const uint8_t *skip_mask, float *logits, const AcceptArgs &accept, hipStream_t st) {
   const heisd_model_desc &d = ctx->d;
   PersistArgs p{};
   p.prog = ctx->prog; p.n_phases = ctx->n_phases;
@@ -559,6 +559,7 @@ static void persist_launch(heisd_verify_ctx *ctx, const heisd_kv_desc *kv, const
   p.prefix_len = kv->prefix_len; p.skip = skip_mask; p.K = K; p.batch = batch; p.logits = logits;
   p.flags = ctx->flags; p.err = ctx->dev_err;
   p.trace = ctx->trace_on ? ctx->trace : nullptr;
+  p.acc = accept;
   p.epoch0 = ctx->epoch;
   ctx->epoch += persist_epochs(ctx->n_phases);
   const dim3 grid(ctx->n_cu), block(kFastThreads);
@@ -1152,6 +1153,57 @@ static void generic_forward(heisd_verify_ctx *ctx, const heisd_kv_desc *kv, cons
 
 // ---- one verify step ----------------------------------------------------------------------
 
+// The persistent kernel needs every compute unit of the device: two of them started at the same time from
+// two streams could each hold half of the chip and wait for the other half (until their bounded spins give
+// up).  The automatic path choice therefore takes the persistent kernel only when the last one launched
+// through this library on the device went to the same stream or has finished, and never on a stream that is
+// being captured (an event query is not allowed there); otherwise the step runs one launch per phase.
+// A context switched to HEISD_PATH_PERSIST by its caller skips the test: the caller then owns the device.
+constexpr int kMaxDevices = 64;
+struct PersistGuard {
+  std::mutex m;
+  hipEvent_t done = nullptr;      // recorded behind the last persistent launch
+  hipStream_t stream = nullptr;
+  bool valid = false;
+};
+static PersistGuard g_persist_guard[kMaxDevices];
+
+// Launch the persistent kernel if it may run now (or unconditionally with force); returns whether it was launched.
+static bool persist_try_launch(heisd_verify_ctx *ctx, bool force, const heisd_kv_desc *kv, const int32_t *draft_tokens,
+                               int K, int batch, const uint8_t *skip_mask, float *logits, const AcceptArgs &aa,
+                               hipStream_t st, bool prof) {
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) {
+    (void)hipGetLastError();
+    if (!force) return false;
+    ProfScope ps(ctx, HEISD_KC_PERSIST, st, prof);
+    persist_launch(ctx, kv, draft_tokens, K, batch, skip_mask, logits, aa, st);
+    return true;
+  }
+  PersistGuard &g = g_persist_guard[dev];
+  std::lock_guard<std::mutex> lock(g.m);
+  hipStreamCaptureStatus cs = hipStreamCaptureStatusNone;
+  const bool capturing = hipStreamIsCapturing(st, &cs) != hipSuccess || cs != hipStreamCaptureStatusNone;
+  if (!force) {
+    if (capturing) { (void)hipGetLastError(); return false; }
+    if (g.valid && g.stream != st && hipEventQuery(g.done) != hipSuccess) { (void)hipGetLastError(); return false; }
+    if (!g.done && hipEventCreateWithFlags(&g.done, hipEventDisableTiming) != hipSuccess) {
+      (void)hipGetLastError();
+      g.done = nullptr;
+      return false;
+    }
+  }
+  {
+    ProfScope ps(ctx, HEISD_KC_PERSIST, st, prof);
+    persist_launch(ctx, kv, draft_tokens, K, batch, skip_mask, logits, aa, st);
+  }
+  if (!capturing && g.done && hipEventRecord(g.done, st) == hipSuccess) {
+    g.stream = st;
+    g.valid = true;
+  }
+  return true;
+}
+
 extern "C" int heisd_verify_step(heisd_verify_ctx *ctx, const heisd_kv_desc *kv, const int32_t *draft_tokens,
                                  int32_t K, int32_t batch, const heisd_accept_desc *accept,
                                  const uint8_t *skip_mask, int32_t *accepted_len, int32_t *next_token,
@@ -1183,7 +1235,8 @@ extern "C" int heisd_verify_step(heisd_verify_ctx *ctx, const heisd_kv_desc *kv,
     return fail(ctx, HEISD_EUNSUPPORTED, "step: this path needs batch*K <= 8 (got %d)", M);
   const bool prof = ctx->prof_on && ctx->prof_steps < HEISD_PROFILE_MAX_STEPS;
   if (prof) ctx->prof_steps++;
-  const bool use_persist = use_fast && ctx->persist_ok && ctx->path == HEISD_PATH_PERSIST;   // AUTO: launch per phase
+  // AUTO takes the persistent kernel when it may run (see PersistGuard), else one launch per phase
+  const bool want_persist = use_fast && ctx->persist_ok && (ctx->path == HEISD_PATH_PERSIST || ctx->path == HEISD_PATH_AUTO);
   AcceptArgs aa{};
   aa.logits = logits; aa.logits_rw = logits; aa.draft = draft_tokens; aa.first_pred = kv->first_pred;
   aa.skip = skip_mask; aa.accepted_len = accepted_len; aa.next_token = next_token; aa.target_bins = tbins;
@@ -1192,10 +1245,13 @@ extern "C" int heisd_verify_step(heisd_verify_ctx *ctx, const heisd_kv_desc *kv,
   aa.n_groups = accept->n_groups; aa.mode = accept->mode; aa.exact_mask = accept->exact_group_mask;
   for (int i = 0; i < 8; ++i) aa.group_sizes[i] = i < accept->n_groups ? accept->group_sizes[i] : 1;
   aa.prefix_len = kv->prefix_len; aa.cap = cap; aa.err = ctx->dev_err;
-  bool accept_done = false;
-  if (use_persist) {
-    ProfScope ps(ctx, HEISD_KC_PERSIST, st, prof);
-    persist_launch(ctx, kv, draft_tokens, K, batch, skip_mask, logits, st);
+  bool accept_done = false, persisted = false;
+  if (want_persist) {
+    persisted = persist_try_launch(ctx, ctx->path == HEISD_PATH_PERSIST, kv, draft_tokens, K, batch, skip_mask, logits, aa,
+                                   st, prof);
+    accept_done = persisted;                             // acceptance at the end of the same launch
+  }
+  if (persisted) {
   } else if (use_fast) {
     fast_forward(ctx, kv, draft_tokens, K, batch, skip_mask, logits, st, prof, &aa);   // acceptance inside the LM-head launch
     accept_done = true;

@@ -24,6 +24,7 @@
 // at its next barrier.
 #pragma once
 #include "heisd_fast.h"
+#include "heisd_misc.h"
 
 namespace heisd {
 
@@ -81,6 +82,7 @@ struct PersistArgs {
   unsigned epoch0;                       // flags hold values <= epoch0 when the kernel starts
   unsigned *err;
   unsigned long long *trace;             // optional [n_phases][workgroups][8] timestamps (measurement aid)
+  AcceptArgs acc;                        // greedy bins + acceptance scan of the step (paper Sec. 4.2), run by workgroups 0 .. batch-1
 };
 
 // The thread index as a value the optimiser cannot trace back to the hardware register: what a phase
@@ -616,6 +618,13 @@ __global__ __launch_bounds__(kFastThreads) void persist_forward(PersistArgs p) {
     }
     if (!ok) return;
     p2_stamp(p, wg, ph, 3);
+  }
+  // Greedy bins and the acceptance scan: workgroup b judges episode b once every workgroup has published its
+  // part of the logits (the epoch after the last phase).  The logits were written with device-scope stores
+  // into lines nobody has read in this launch, so plain loads see them.
+  if (wg < p.batch) {
+    if (!grid_wait(p, nwg, p.epoch0 + (unsigned)p.n_phases, false, smem)) return;
+    accept_episode<kFastThreads>(p.acc, wg, p2_tid());
   }
 }
 
