@@ -592,44 +592,70 @@ def main():
                                       "next_polls_done_first_last": [round(float(x), 2) for x in m[9:11]],
                                       "next_polls_done_to_release_mean_max": [round(float(x), 2) for x in m[11:13]]}
 
-    # per-kernel durations: HIP events recorded by the library on the launch stream
-    n_prof = max(1, min(args.steps, 32))
-    heisd_verify_profile_enable(ver.ctx, True)
-    for _ in range(n_prof):
-        step(acc, out=out)
-    rc, prof = heisd_verify_profile_read(ver.ctx)
-    heisd_verify_profile_enable(ver.ctx, False)
-    assert rc == 0
     active = B if skip is None else int(B - skip.sum())
     total_bytes, per_class = algorithmic_bytes(sh, B, rows, P, active)
-    kernels = {}
-    for kcls, (tot_ms, n) in prof.items():
-        if n:
-            avg = tot_ms / n
-            kernels[kcls] = {"avg_us": round(avg * 1e3, 3), "launches_per_step": n / n_prof,
-                             "share_of_step": round(tot_ms / n_prof / ms, 4)}
-            if kcls in per_class:
-                kernels[kcls]["GBps"] = round(per_class[kcls] / (avg * 1e-3) / 1e9, 1)
-    dom = max((k for k in kernels if k in per_class), key=lambda k: prof[k][0])
-    dom_avg_s = prof[dom][0] / prof[dom][1] * 1e-3
-    # What the instrument adds: a bracket's two events cost time the timed steps do not spend.  The brackets
-    # of a profiled step add up to more than a timed step; the surplus per bracket, taken off the dominant
-    # kernel's bracket, is the kernel's duration as it runs in the timed region - the figure the rocprofv3
-    # summaries under profiles/ show - and `achieved` / `frac` follow from that duration.  The raw bracket
-    # is reported beside it.
-    brackets = sum(n for _, n in prof.values()) / n_prof
-    surplus_us = (sum(t for t, _ in prof.values()) / n_prof - ms) * 1e3 / brackets
-    if not 0.0 < surplus_us < dom_avg_s * 1e6:
-        surplus_us = 0.0
-    kernel_s = dom_avg_s - surplus_us * 1e-6
-    achieved = per_class[dom] / kernel_s
-    traffic, traffic_source = read_traffic(dom)
-    roofline = {"kernel": dom, "bound": "hbm", "achieved": round(achieved / 1e9, 1), "peak": HBM_PEAK / 1e9,
-                "unit": "GB/s", "frac": round(achieved / HBM_PEAK, 4),
-                "bytes_per_launch": per_class[dom], "avg_launch_us": round(kernel_s * 1e6, 3),
-                "traffic": traffic, "traffic_source": traffic_source,
-                "event_bracket_us": round(dom_avg_s * 1e6, 3), "event_bracket_surplus_us": round(surplus_us, 3),
-                "frac_of_event_bracket": round(per_class[dom] / dom_avg_s / HBM_PEAK, 4)}
+
+    def measure_kernels(ms):
+        """Per-kernel durations of the path now selected (HIP events recorded by the library on the launch
+        stream) and the roofline object of its dominant kernel; ms = that path's timed step."""
+        n_prof = max(1, min(args.steps, 32))
+        heisd_verify_profile_enable(ver.ctx, True)
+        for _ in range(n_prof):
+            step(acc, out=out)
+        rc, prof = heisd_verify_profile_read(ver.ctx)
+        heisd_verify_profile_enable(ver.ctx, False)
+        assert rc == 0
+        kernels = {}
+        for kcls, (tot_ms, n) in prof.items():
+            if n:
+                avg = tot_ms / n
+                kernels[kcls] = {"avg_us": round(avg * 1e3, 3), "launches_per_step": n / n_prof,
+                                 "share_of_step": round(tot_ms / n_prof / ms, 4)}
+                if kcls in per_class:
+                    kernels[kcls]["GBps"] = round(per_class[kcls] / (avg * 1e-3) / 1e9, 1)
+        dom = max((k for k in kernels if k in per_class), key=lambda k: prof[k][0])
+        dom_avg_s = prof[dom][0] / prof[dom][1] * 1e-3
+        # What the instrument adds: a bracket's two events cost time the timed steps do not spend.  The brackets
+        # of a profiled step add up to more than a timed step; the surplus per bracket, taken off the dominant
+        # kernel's bracket, is the kernel's duration as it runs in the timed region - the figure the rocprofv3
+        # summaries under profiles/ show - and `achieved` / `frac` follow from that duration.  The raw bracket
+        # is reported beside it.
+        brackets = sum(n for _, n in prof.values()) / n_prof
+        surplus_us = (sum(t for t, _ in prof.values()) / n_prof - ms) * 1e3 / brackets
+        if not 0.0 < surplus_us < dom_avg_s * 1e6:
+            surplus_us = 0.0
+        kernel_s = dom_avg_s - surplus_us * 1e-6
+        achieved = per_class[dom] / kernel_s
+        traffic, traffic_source = read_traffic(dom)
+        roofline = {"kernel": dom, "bound": "hbm", "achieved": round(achieved / 1e9, 1), "peak": HBM_PEAK / 1e9,
+                    "unit": "GB/s", "frac": round(achieved / HBM_PEAK, 4),
+                    "bytes_per_launch": per_class[dom], "avg_launch_us": round(kernel_s * 1e6, 3),
+                    "traffic": traffic, "traffic_source": traffic_source,
+                    "event_bracket_us": round(dom_avg_s * 1e6, 3), "event_bracket_surplus_us": round(surplus_us, 3),
+                    "frac_of_event_bracket": round(per_class[dom] / dom_avg_s / HBM_PEAK, 4)}
+        return kernels, roofline
+
+    kernels, roofline = measure_kernels(ms)
+
+    # the same step with one launch per phase (what the automatic choice falls back to when the persistent
+    # kernel may not run), for comparison: its step time and its dominant kernel
+    per_phase = None
+    if not R and B * rows <= 8 and args.path in (0, 3) and kernels.get("persist"):
+        assert heisd_verify_set_path(ver.ctx, 2) == 0
+        for _ in range(10):
+            out = step(acc, out=out)
+        torch.cuda.synchronize()
+        n2 = max(1, min(args.steps, 100))
+        t0 = time.perf_counter()
+        for _ in range(n2):
+            out = step(acc, out=out)
+        torch.cuda.synchronize()
+        ms2 = (time.perf_counter() - t0) * 1e3 / n2
+        k2, r2 = measure_kernels(ms2)
+        assert heisd_verify_set_path(ver.ctx, args.path) == 0
+        per_phase = {"kernel_path": 2, "ms_per_step": round(ms2, 4), "steps": n2,
+                     "hbm_frac_whole_step": round(total_bytes / (ms2 * 1e-3) / HBM_PEAK, 4),
+                     "kernels": k2, "roofline": r2}
 
     cpu = None
     if not args.no_cpu_baseline:
@@ -685,6 +711,7 @@ def main():
         "weights_gen_s": round(t_gen, 1),
         "kernels": kernels,
         "persistent_kernel_timeline": timeline,
+        "launch_per_phase": per_phase,
         "roofline": roofline,
         "cpu_baseline": cpu,
     }

@@ -354,14 +354,19 @@ int heisd_verify_profile_read(heisd_verify_ctx *ctx, double *ms, int64_t *launch
 
 /*
  * Kernel-path selection, for tests and measurement.  AUTO (default) picks the fastest path
- * that covers the call: FAST for batch*K <= 8 (when the model fits those kernels: d_model <= 4096),
- * BATCH otherwise.  GENERIC forces the first any-M path
+ * that covers the call.  For batch*K <= 8 (when the model fits those kernels: d_model <= 4096) that
+ * is PERSIST - if it fits the device, the stream is not being captured into a graph, and the last
+ * persistent kernel launched through this library on the device went to the same stream or has
+ * finished (two of them started together from two streams could each hold half of the compute units
+ * and wait for the other half) - and FAST otherwise; for more rows it is BATCH.  GENERIC forces the first any-M path
  * (activations converted and staged through LDS by every workgroup, one launch per phase);
  * BATCH forces the any-M path that exchanges pre-split bf16 activation records (waves arranged
  * over rows and over the reduction according to batch*K); FAST forces the batch*K <= 8 kernels
  * with one launch per phase; PERSIST forces the batch*K <= 8 persistent kernel (the whole decoder
- * forward in one launch, one workgroup per compute unit, grid barriers inside).  FAST and PERSIST
- * make a larger step fail with EUNSUPPORTED.  Results of the paths agree to fp32 rounding.
+ * forward and the acceptance scan in one launch, one workgroup per compute unit, grid barriers inside)
+ * without the test AUTO makes: the caller then sees to it that no two persistent kernels run at once.
+ * FAST and PERSIST make a larger step fail with EUNSUPPORTED.  Results of the paths agree to fp32
+ * rounding (FAST and PERSIST bit for bit).
  *
  * The persistent kernel spins at its grid barriers with a bound; if the bound expires (the
  * GPU was shared with work that kept some of its workgroups from running) it raises a bit of the
@@ -393,13 +398,14 @@ int heisd_debug_trace(heisd_verify_ctx *ctx, int enable, unsigned long long *out
 
 /*
  * Measurement aid for the persistent kernel: what a phase requests across the grid barrier that ends it.
- *   0 (default)  the first 12 k-steps of every wave's first weight tile of the next GEMM phase are handed
- *                over through LDS, started as soon as the phase's own outputs have been stored (the
- *                O-projection's at the end of the attention phase); the rest of that tile is requested
- *                into registers before the wait
+ *   0 (default)  the whole first weight tile of the next GEMM phase (16 k-steps of every wave: 128 KB per
+ *                workgroup) is handed over through LDS, started as soon as the phase's own stores have been
+ *                acknowledged (the O-projection's at the end of the attention phase); nothing else is
+ *                requested before the wait
  *   1            as 0, but the O-projection's hand-over starts at the end of the QKV phase
  *   2            no LDS hand-over: the whole first tile is requested into registers before the wait
  *   3            nothing is requested before the wait
+ *   4            as 0, and the second weight tile is requested into registers before the wait
  * Synchronises the device and rewrites the phase program.  Results are identical in every mode.
  * Errors: EINVAL (NULL ctx, unknown mode), EUNSUPPORTED (no persistent kernel for this context), EHIP.
  */

@@ -81,7 +81,26 @@ def test_long_reduction_streams_its_activations(path, B, K):
     run_case(wl, path=path)
 
 
-@pytest.mark.parametrize("mode", [1, 2, 3])
+def test_persistent_kernel_gives_the_bits_of_one_launch_per_phase():
+    """The persistent kernel runs the phase bodies of the <= 8-row kernels in the same order of additions: logits,
+    bins, accepted lengths and appended cache rows are equal bit for bit (two episodes with different prefix
+    lengths, K = 4)."""
+    from gpu_harness import run_gpu_step
+    _need_gpu()
+    wl = synth.Workload("mid_bits", MID, 30, 11, MID.bin_base, batch=2, K=4, draft=("geometric", 0.5), seed=5)
+    weights = synth.make_weights(MID, wl.seed)
+    cap = 48
+    k0, v0, f0 = zip(*[synth.make_prefix_kv_direct(wl, e, cap) for e in range(2)])
+    kb, vb = np.stack(k0, axis=1), np.stack(v0, axis=1)
+    drafts = (MID.bin_base + synth.make_drafts_uniform(wl)).astype(np.int32)
+    rule = oracle.AcceptRule(2, 6)
+    outs = [run_gpu_step(MID, weights, kb, vb, [41, 33], list(f0), drafts, rule, None, path=p) for p in (2, 3, 0)]
+    for k in outs[0]:
+        assert np.array_equal(outs[0][k], outs[1][k], equal_nan=True), k
+        assert np.array_equal(outs[0][k], outs[2][k], equal_nan=True), k
+
+
+@pytest.mark.parametrize("mode", [1, 2, 3, 4])
 def test_persistent_kernel_handover_modes_agree(mode):
     """What the persistent kernel requests across its grid barriers changes when weights arrive, never
     what is computed: every mode gives the bits of the default mode (two episodes, one skipped, so that
