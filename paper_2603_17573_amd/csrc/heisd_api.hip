@@ -45,6 +45,7 @@ struct heisd_verify_ctx {
   unsigned *lm_done = nullptr;         // fused LM head + acceptance: arrival counter of its workgroups
   unsigned epoch = 0;                  // last barrier epoch handed out
   bool persist_ok = false;
+  int *attn_prod = nullptr;            // persistent kernel: [n_heads][3 * head_dim / 16] producer workgroups of a head's q/k/v
   int handover_mode = 0;               // persistent kernel: what crosses a grid barrier (see persist_build_program)
   unsigned long long *trace = nullptr; // device buffer [n_phases][8] when tracing is on
   bool trace_on = false;
@@ -93,7 +94,7 @@ static int fail(heisd_verify_ctx *ctx, int code, const char *fmt, ...) {
 static size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
 
 struct WsLayout {
-  size_t rope, x, qkv, attn_o, act, logits, tbins, tree_depth, tree_path, tree_anc, fscr, fscr_bytes, bscr, bscr_bytes, players, flags, trace, packed, packed_bytes, total;
+  size_t rope, x, qkv, attn_o, act, logits, tbins, tree_depth, tree_path, tree_anc, fscr, fscr_bytes, bscr, bscr_bytes, players, attn_prod, flags, trace, packed, packed_bytes, total;
 };
 
 // Buffers of the batched path (M > 8 rows).  One launch per phase, so one set serves every layer.
@@ -175,6 +176,7 @@ static WsLayout ws_layout(const heisd_model_desc *d) {
   w.bscr_bytes = BatScratch(d).total;
   off += w.bscr_bytes;
   w.players = off; off += align256((size_t)(5 * d->n_layers + 2) * sizeof(Phase));
+  w.attn_prod = off; off += align256((size_t)d->n_heads * (3 * d->head_dim / 16) * sizeof(int));
   w.flags = off;   off += align256((size_t)(1024 + 64) * sizeof(unsigned));   // barrier flags, error word, LM-head arrival counter
   w.trace = off;   off += align256((size_t)(5 * d->n_layers + 2) * 1024 * 8 * sizeof(unsigned long long));   // [phase][workgroup][8]
   w.packed = off;
@@ -541,6 +543,14 @@ static hipError_t persist_build_program(heisd_verify_ctx *ctx) {
   }
   Phase lm{}; lm.kind = PH_GEMM; lm.g = fast_lm_desc(ctx, 1, nullptr); lm.first_tile = ft; lm.next_gemm = -1; prog.push_back(lm);
   ctx->n_phases = (int)prog.size();
+  // which workgroups produce head h's rows of q, k and v: QKV unit u (segment * d/16 + tile) runs on workgroup u % n_cu
+  const int tph = d.head_dim / 16, T = d.d_model / 16;
+  std::vector<int> prod((size_t)d.n_heads * 3 * tph);
+  for (int h = 0; h < d.n_heads; ++h)
+    for (int seg = 0; seg < 3; ++seg)
+      for (int c = 0; c < tph; ++c) prod[((size_t)h * 3 + seg) * tph + c] = (seg * T + h * tph + c) % ctx->n_cu;
+  const hipError_t ep = hipMemcpy(ctx->attn_prod, prod.data(), prod.size() * sizeof(int), hipMemcpyHostToDevice);
+  if (ep != hipSuccess) return ep;
   return hipMemcpy(ctx->prog, prog.data(), prog.size() * sizeof(Phase), hipMemcpyHostToDevice);
 }
 
@@ -559,6 +569,7 @@ static void persist_launch(heisd_verify_ctx *ctx, const heisd_kv_desc *kv, const
   p.prefix_len = kv->prefix_len; p.skip = skip_mask; p.K = K; p.batch = batch; p.logits = logits;
   p.flags = ctx->flags; p.err = ctx->dev_err;
   p.trace = ctx->trace_on ? ctx->trace : nullptr;
+  p.attn_prod = ctx->attn_prod; p.n_prod = 3 * d.head_dim / 16;
   p.acc = accept;
   p.epoch0 = ctx->epoch;
   ctx->epoch += persist_epochs(ctx->n_phases);
@@ -624,6 +635,7 @@ extern "C" int heisd_verify_init(const heisd_model_desc *desc, heisd_verify_ctx 
   c->fscr = base + w.fscr;
   c->bscr = base + w.bscr;
   c->prog = reinterpret_cast<Phase *>(base + w.players);
+  c->attn_prod = reinterpret_cast<int *>(base + w.attn_prod);
   c->flags = reinterpret_cast<unsigned *>(base + w.flags);
   c->dev_err = c->flags + 1024;
   c->lm_done = c->flags + 1024 + 16;

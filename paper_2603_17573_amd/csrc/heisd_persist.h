@@ -35,7 +35,7 @@ constexpr int kPF = kKS;                 // k-steps of a wave's first weight til
 constexpr int kPfWave0 = 6;              // waves kPfWave0 .. 7 issue the transfers (they never store in a GEMM epilogue)
 // LDS map.  The hand-over region (128 KB) and the reduction buffer share their bytes: a phase reads what was
 // handed over into registers when it starts and reduces through the same bytes when it ends, and the next
-// hand-over is started only after every storing wave has read its sums (p2_wait_stores_acked).  The attention
+// hand-over is started only after every storing wave has read its sums (p2_wait_words).  The attention
 // units work above both, so that the O-projection's hand-over may sit in LDS while they run.
 constexpr size_t kPfOff = 0;
 constexpr size_t kPfBytes = (size_t)kFastWaves * kPF * 1024;
@@ -82,6 +82,8 @@ struct PersistArgs {
   unsigned epoch0;                       // flags hold values <= epoch0 when the kernel starts
   unsigned *err;
   unsigned long long *trace;             // optional [n_phases][workgroups][8] timestamps (measurement aid)
+  const int *attn_prod;                  // [H][n_prod]: the workgroups that produce head h's q/k/v in a QKV phase
+  int n_prod;                            // 3 * head_dim / 16 (at most 64)
   AcceptArgs acc;                        // greedy bins + acceptance scan of the step (paper Sec. 4.2), run by workgroups 0 .. batch-1
 };
 
@@ -116,15 +118,21 @@ __device__ __forceinline__ void grid_arrive(const PersistArgs &p, int wg, unsign
 // (measured: 4-7 us from the last product to the published flag with the hand-over in front of the stores,
 // 2-4 us with the hand-over started once the stores were issued, against 0.4 us for a phase that hands
 // nothing over).  So the hand-over starts when the workgroup's stores have been ACKNOWLEDGED: every wave
-// says so in LDS (gemm_publish, attn_publish), and the issuing waves wait for those words.  (Waiting for
+// says so in LDS (gemm_publish, attn_publish), and the issuing waves wait for those words (p2_wait_words).  (Waiting for
 // the flag's acknowledgement as well measured slower again: the hand-over then starts too late.)
-__device__ __forceinline__ void p2_wait_stores_acked(unsigned char *smem, unsigned token, int tid, int n_waves) {
+// Spin (bounded) until the sync words of waves lo .. hi-1 have reached `token`.  The words are compared as
+// "this epoch or a later one": a workgroup without an attention unit passes no workgroup barrier between its
+// QKV and attention phases, so a wave may already have written the next phase's token when a slower wave
+// looks.  If the bound expires the error word is raised (every workgroup then leaves at its next barrier).
+__device__ __forceinline__ void p2_wait_words(const PersistArgs &p, unsigned char *smem, unsigned token, int tid, int lo,
+                                              int hi) {
   volatile unsigned *w = reinterpret_cast<volatile unsigned *>(smem + kSyncOff);
   const int lane = tid & 63;
   for (int spins = 0; spins < kSpinLimit; ++spins) {
     const unsigned v = w[lane & 7];                  // (read unconditionally: a load through a selected address
-    if (__all(lane >= n_waves || v == token)) break;    //  would put `token` on the stack)
+    if (__all(lane < lo || lane >= hi || (int)(v - token) >= 0)) return;   //  would put `token` on the stack)
   }
+  if (lane == 0) __hip_atomic_fetch_or(p.err, kErrBarrier, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
 // The same for the end of a GEMM phase, without a workgroup barrier: the transfer-issuing waves are still
@@ -139,10 +147,7 @@ __device__ __forceinline__ void gemm_publish(const PersistArgs &p, int wg, unsig
   wait_vmcnt_all();
   if (lane == 0) sync_s[wave] = token;
   if (wave != 0) return;
-  for (int spins = 0; spins < kSpinLimit; ++spins) {
-    const unsigned v = sync_s[lane & 7];
-    if (__all(lane == 0 || lane >= kPfWave0 || v == token)) break;
-  }
+  p2_wait_words(p, smem, token, tid, 1, kPfWave0);
   if (lane == 0)
     __hip_atomic_store(&p.flags[wg * kFlagStride], token, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
@@ -160,25 +165,23 @@ __device__ __forceinline__ void attn_publish(const PersistArgs &p, int wg, int n
   if (lane == 0) sync_s[wave] = token;
   if (wave != 0) {
     if (wave >= kPfWave0) {
-      p2_wait_stores_acked(smem, token, tid, kFastWaves);
+      p2_wait_words(p, smem, token, tid, 0, kFastWaves);
       p2_handover_issue(p, ng, wg, nwg, pf_lds);
     }
     return;
   }
-  for (int spins = 0; spins < kSpinLimit; ++spins) {
-    const unsigned v = sync_s[lane & 7];
-    if (__all(lane == 0 || lane >= kFastWaves || v == token)) break;
-  }
+  p2_wait_words(p, smem, token, tid, 1, kFastWaves);
   if (lane == 0)
     __hip_atomic_store(&p.flags[wg * kFlagStride], token, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
-// Wait until every workgroup has published `epoch`.  Wave 0 polls; the others meet it at the workgroup
+// Wait until every workgroup has published `epoch` - or, with `subset` (n_subset <= 64 workgroup indices), until
+// those workgroups have.  Wave 0 polls; the others meet it at the workgroup
 // barrier with their requested loads still in flight - except that with land_transfers the issuing
 // waves first wait for their global -> LDS transfers, so that after the barrier every wave may read
 // what was handed over.  Returns false if the wait gave up (error word raised) or an error was seen.
 __device__ __forceinline__ bool grid_wait(const PersistArgs &p, int nwg, unsigned epoch, bool land_transfers,
-                                          unsigned char *smem) {
+                                          unsigned char *smem, const int *subset = nullptr, int n_subset = 0) {
   volatile int &s_ok = *reinterpret_cast<volatile int *>(smem + kOkOff);
   const int tid = p2_tid(), wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   if (wave == 0) {
@@ -186,11 +189,19 @@ __device__ __forceinline__ bool grid_wait(const PersistArgs &p, int nwg, unsigne
     int spins = 0;
     bool good = true;
     const unsigned long long *f64 = reinterpret_cast<const unsigned long long *>(p.flags);
+    const int mine = (subset && lane < n_subset) ? subset[lane] : 0;      // one flag per lane
     while (true) {
       bool ok = true;
-      for (int i = lane; 2 * i < nwg; i += kWave) {       // two flags per load
-        const unsigned long long f = __hip_atomic_load(f64 + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        ok = ok && ((int)((unsigned)f - epoch) >= 0) && (2 * i + 1 >= nwg || (int)((unsigned)(f >> 32) - epoch) >= 0);
+      if (subset) {
+        if (lane < n_subset) {      // (the other lanes load nothing: 200 workgroups polling one spare word would queue on it)
+          const unsigned f = __hip_atomic_load(p.flags + mine * kFlagStride, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+          ok = (int)(f - epoch) >= 0;
+        }
+      } else {
+        for (int i = lane; 2 * i < nwg; i += kWave) {       // two flags per load
+          const unsigned long long f = __hip_atomic_load(f64 + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+          ok = ok && ((int)((unsigned)f - epoch) >= 0) && (2 * i + 1 >= nwg || (int)((unsigned)(f >> 32) - epoch) >= 0);
+        }
       }
       if (__all(ok)) break;
       __builtin_amdgcn_s_sleep(8);      // 256 pollers at full rate slow the loads they wait for (1 % of the step)
@@ -450,7 +461,7 @@ __device__ __forceinline__ bool p2_gemm_phase(const PersistArgs &p, int ph, int 
     } else if (wave >= kPfWave0) {
       // last pass: the weights are consumed and the hand-over region is free.  From here to the next
       // phase's barrier the issuing waves and the storing waves go separate ways (no workgroup barrier).
-      p2_wait_stores_acked(smem, wait_epoch + 1, tid, kPfWave0);
+      p2_wait_words(p, smem, wait_epoch + 1, tid, 0, kPfWave0);
       p2_handover_issue(p, ng, wg, nwg, pf_lds);
     } else {
       p2_stamp(p, wg, ph, 4);
@@ -535,7 +546,7 @@ __device__ __forceinline__ bool p2_gemm_stream_phase(const PersistArgs &p, int p
       fast_epilogue(g, wg, nwg, e, 1, red, scale_s, ep, tid);
       lds_barrier();
     } else if (wave >= kPfWave0) {                    // as in p2_gemm_phase: no workgroup barrier from here on
-      p2_wait_stores_acked(smem, wait_epoch + 1, tid, kPfWave0);
+      p2_wait_words(p, smem, wait_epoch + 1, tid, 0, kPfWave0);
       p2_handover_issue(p, ng, wg, nwg, pf_lds);
     } else {
       p2_stamp(p, wg, ph, 4);
@@ -572,7 +583,11 @@ __device__ __forceinline__ bool p2_attn_phase(const PersistArgs &p, int ph, int 
   if (have) fast_attn_prefetch<HD>(at, ab, ah, pre, tid);       // cached rows: no dependence on this step's q/k/v
   // (the polling wave included: leaving its rows for after the wait, so that its polls do not return behind
   //  them, measured 0.3 % slower)
-  if (!grid_wait(p, nwg, wait_epoch, false, smem)) return false;
+  // An attention unit needs the q/k/v of ONE head: it waits for the workgroups that own that head's rows of
+  // the QKV weights (p.attn_prod), not for all of them - neither for the last workgroup of the whole QKV phase
+  // nor for a poll of every flag.  A workgroup without a unit waits for nothing.  (What an early unit writes -
+  // output records, appended cache rows - is read only behind the next barrier, which is a full one.)
+  if (have && !grid_wait(p, nwg, wait_epoch, false, smem, p.attn_prod + ah * p.n_prod, p.n_prod)) return false;
   p2_stamp(p, wg, ph, 1);
   const int ng = P->next_gemm;
   const uint32_t pf_lds = p2_lds_addr(smem) + (uint32_t)kPfOff;
@@ -580,6 +595,7 @@ __device__ __forceinline__ bool p2_attn_phase(const PersistArgs &p, int ph, int 
     fast_attn_unit<HD>(at, ab, ah, aj, smem + kAttnOff, pre, tid);
     for (int t = 1; attn_unit_of(p, wg, nwg, t, ab, ah, aj); ++t) {
       fast_attn_prefetch<HD>(at, ab, ah, pre, tid);
+      if (!grid_wait(p, nwg, wait_epoch, false, smem, p.attn_prod + ah * p.n_prod, p.n_prod)) return false;
       fast_attn_unit<HD>(at, ab, ah, aj, smem + kAttnOff, pre, tid);
     }
   }
