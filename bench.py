@@ -573,6 +573,10 @@ def main():
                             "outputs (min / mean / max), when the first and last workgroup passed the next barrier, when their "
                             "polls had seen every flag, and how long a workgroup then waited for its hand-over to land",
                     "step_us": round(float(t[-1, :, 3].max() - t[0, :, 0].min()), 1), "phases": {}}
+        # slot 6 (polls done) is written only by workgroups that waited: one without an attention unit does not
+        waited = lambda ph_t: ph_t[:, 6] > 0
+        polled = lambda ph_t: ph_t[waited(ph_t), 6]
+        landing = lambda ph_t: ph_t[waited(ph_t), 1] - ph_t[waited(ph_t), 6]
         for nm in ("qkv", "attn", "oproj", "gateup", "down"):
             rows_ = []
             for i in range(11, n_ph - 1):
@@ -582,8 +586,8 @@ def main():
                 rows_.append([t[i, :, 1].max() - r0, t[i, :, 2].min() - r0, t[i, :, 2].mean() - r0, t[i, :, 2].max() - r0,
                               t[i, :, 3].min() - r0, t[i, :, 3].mean() - r0, t[i, :, 3].max() - r0,
                               t[i + 1, :, 1].min() - r0, t[i + 1, :, 1].max() - r0,
-                              t[i + 1, :, 6].min() - r0, t[i + 1, :, 6].max() - r0,
-                              (t[i + 1, :, 1] - t[i + 1, :, 6]).mean(), (t[i + 1, :, 1] - t[i + 1, :, 6]).max()])
+                              polled(t[i + 1]).min() - r0, polled(t[i + 1]).max() - r0,
+                              landing(t[i + 1]).mean(), landing(t[i + 1]).max()])
             m = np.mean(rows_, axis=0)
             timeline["phases"][nm] = {"last_release": round(float(m[0]), 2),
                                       "consumed_min_mean_max": [round(float(x), 2) for x in m[1:4]],

@@ -389,7 +389,8 @@ int heisd_verify_set_path(heisd_verify_ctx *ctx, int path);
  * program, as [phase][workgroup][8]: [0] phase entered, [1] inputs seen (grid barrier passed),
  * [2] weights consumed, [3] outputs published, [4] and [5] epilogue begun and ended (GEMM phases),
  * [6] the barrier's polls have seen every flag ([1] minus [6] is the wait for weights handed over in LDS);
- * slot 7 is unused.  One workgroup runs per compute unit.  With out != NULL (HOST array of
+ * slot 7 is unused, and a slot a workgroup does not pass in a phase reads 0 (switching recording on
+ * synchronises the device and clears the record).  One workgroup runs per compute unit.  With out != NULL (HOST array of
  * max_entries values) the call synchronises the device, copies the record of the last persistent step
  * and returns the number of values copied (phases * workgroups * 8 at most); otherwise it returns OK.
  * Errors: EINVAL (NULL ctx), EHIP.

@@ -710,6 +710,11 @@ extern "C" int heisd_verify_set_handover(heisd_verify_ctx *ctx, int mode) {
 // phase of a step, [phase][workgroup][8].  enable != 0 switches recording on; out (HOST) may be NULL.
 extern "C" int heisd_debug_trace(heisd_verify_ctx *ctx, int enable, unsigned long long *out, int max_entries) {
   if (!ctx) return HEISD_EINVAL;
+  if (enable && !ctx->trace_on) {      // slots a workgroup does not write in a phase read 0
+    if (hipDeviceSynchronize() != hipSuccess ||
+        hipMemset(ctx->trace, 0, (size_t)ctx->n_phases * ctx->n_cu * 8 * sizeof(unsigned long long)) != hipSuccess)
+      return HEISD_EHIP;
+  }
   ctx->trace_on = enable != 0;
   if (out) {
     const long long all = (long long)ctx->n_phases * ctx->n_cu * 8;
