@@ -209,7 +209,7 @@ def run_aux_mode(args):
     gemm_flops_per_row = 2.0 * (L * (4 * d * d + 3 * d * f) + sh.n_bins * d)
     if decode:
         total_bytes, per_class = algorithmic_bytes(sh, B, 1, P)
-        dom = max((k for k in kernels if k in per_class and k != "persist"), key=lambda k: prof[k][0])
+        dom = max((k for k in kernels if k in per_class), key=lambda k: prof[k][0])
         dom_s = prof[dom][0] / prof[dom][1] * 1e-3
         roofline = {"kernel": dom, "bound": "hbm", "achieved": round(per_class[dom] / dom_s / 1e9, 1),
                     "peak": HBM_PEAK / 1e9, "unit": "GB/s", "frac": round(per_class[dom] / dom_s / HBM_PEAK, 4),

@@ -638,7 +638,7 @@ __global__ __launch_bounds__(kFastThreads) void persist_forward(PersistArgs p) {
   // Greedy bins and the acceptance scan: workgroup b judges episode b once every workgroup has published its
   // part of the logits (the epoch after the last phase).  The logits were written with device-scope stores
   // into lines nobody has read in this launch, so plain loads see them.
-  if (wg < p.batch) {
+  if (wg < p.batch && p.acc.accepted_len) {      // (a prefill chunk or decode step has no drafts to judge)
     if (!grid_wait(p, nwg, p.epoch0 + (unsigned)p.n_phases, false, smem)) return;
     accept_episode<kFastThreads>(p.acc, wg, p2_tid());
   }
