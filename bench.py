@@ -400,7 +400,7 @@ def main():
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run three plain 1 GiB device copies (reference kernel for HBM traffic counters)")
     ap.add_argument("--path", type=int, default=0, help="0 auto, 1 generic, 2 fast (launch per phase), 3 persistent")
-    ap.add_argument("--handover", type=int, default=0, choices=[0, 1, 2, 3, 4],
+    ap.add_argument("--handover", type=int, default=0, choices=[0, 1, 2, 3, 4, 5],
                     help="--path 3 only: what the persistent kernel requests across its grid barriers "
                          "(heisd_verify_set_handover; 0 = default)")
     ap.add_argument("--persist-trace", action="store_true",

@@ -408,6 +408,9 @@ int heisd_debug_trace(heisd_verify_ctx *ctx, int enable, unsigned long long *out
  *   2            no LDS hand-over: the whole first tile is requested into registers before the wait
  *   3            nothing is requested before the wait
  *   4            as 0, and the second weight tile is requested into registers before the wait
+ *   5            as 0, with the QKV tiles dealt to the workgroups in their plain order (in mode 0, at d_model
+ *                4096 / head_dim 128 on a 256-unit device, a head's q, k and v rows are produced on the XCD
+ *                whose workgroups run that head's attention units)
  * Synchronises the device and rewrites the phase program.  Results are identical in every mode.
  * Errors: EINVAL (NULL ctx, unknown mode), EUNSUPPORTED (no persistent kernel for this context), EHIP.
  */

@@ -46,6 +46,7 @@ struct heisd_verify_ctx {
   unsigned epoch = 0;                  // last barrier epoch handed out
   bool persist_ok = false;
   int *attn_prod = nullptr;            // persistent kernel: [n_heads][3 * head_dim / 16] producer workgroups of a head's q/k/v
+  int qkv_xcd_heads = 0;               // persistent kernel: QKV tiles dealt so that a head is produced on the XCD that consumes it
   int handover_mode = 0;               // persistent kernel: what crosses a grid barrier (see persist_build_program)
   unsigned long long *trace = nullptr; // device buffer [n_phases][8] when tracing is on
   bool trace_on = false;
@@ -506,6 +507,10 @@ static hipError_t persist_prepare(heisd_verify_ctx *c) {
   return hipSuccess;
 }
 
+static bool qkv_xcd_eligible(const heisd_verify_ctx *c) {
+  return c->n_cu == 256 && c->d.d_model == 4096 && c->d.head_dim == 128;
+}
+
 // The phase program of one step (everything that does not change from step to step).
 // ctx->handover_mode (heisd_verify_set_handover; default 0):
 //   0  every GEMM phase gets its first weight steps handed over in LDS by the phase before it (the
@@ -514,13 +519,14 @@ static hipError_t persist_prepare(heisd_verify_ctx *c) {
 //   2  no LDS hand-over: the whole first tile is requested into registers before the barrier
 //   3  nothing is requested across a barrier
 //   4  as 0, and the second weight tile is requested into registers before the barrier
+//   5  as 0, with the QKV tiles dealt to the workgroups in their plain order (see fast_xcd_tile)
 static hipError_t persist_build_program(heisd_verify_ctx *ctx) {
   const heisd_model_desc &d = ctx->d;
   const int L = d.n_layers;
   const FastScratch fs(&d);
   const bool stream_down = d.d_ffn > kFastWaves * kKS * 32;
   const int mode = ctx->handover_mode;
-  const bool lds = mode == 0 || mode == 1 || mode == 4;
+  const bool lds = mode == 0 || mode == 1 || mode == 4 || mode == 5;
   const int ft = (lds ? PHF_IN_LDS : 0) | (mode == 2 || mode == 4 ? PHF_EARLY : 0);
   auto nx = [&](int idx) { return lds ? idx : -1; };
   std::vector<Phase> prog;
@@ -534,8 +540,8 @@ static hipError_t persist_build_program(heisd_verify_ctx *ctx) {
   for (int l = 0; l < L; ++l) {
     const FastLayerDescs D = fast_layer_descs(ctx, &no_kv, l, 1, 1, nullptr);
     const int base = 1 + 5 * l;
-    Phase q{}; q.kind = PH_GEMM; q.g = D.qkv; q.first_tile = ft; q.next_gemm = mode == 1 ? base + 2 : -1; prog.push_back(q);
-    Phase a{}; a.kind = PH_ATTN; a.layer = l; a.next_gemm = mode == 0 || mode == 4 ? base + 2 : -1;
+    Phase q{}; q.kind = PH_GEMM; q.g = D.qkv; q.g.xcd_heads = ctx->qkv_xcd_heads; q.first_tile = ft; q.next_gemm = mode == 1 ? base + 2 : -1; prog.push_back(q);
+    Phase a{}; a.kind = PH_ATTN; a.layer = l; a.next_gemm = mode == 0 || mode == 4 || mode == 5 ? base + 2 : -1;
     a.g.b = reinterpret_cast<const uint16_t *>(D.attn.qkv); a.g.o_planes = D.attn.o_planes; prog.push_back(a);
     Phase o{}; o.kind = PH_GEMM; o.g = D.oproj; o.first_tile = ft; o.next_gemm = nx(base + 3); prog.push_back(o);
     Phase g{}; g.kind = PH_GEMM; g.g = D.gateup; g.first_tile = ft; g.next_gemm = nx(base + 4); prog.push_back(g);
@@ -548,7 +554,11 @@ static hipError_t persist_build_program(heisd_verify_ctx *ctx) {
   std::vector<int> prod((size_t)d.n_heads * 3 * tph);
   for (int h = 0; h < d.n_heads; ++h)
     for (int seg = 0; seg < 3; ++seg)
-      for (int c = 0; c < tph; ++c) prod[((size_t)h * 3 + seg) * tph + c] = (seg * T + h * tph + c) % ctx->n_cu;
+      for (int c = 0; c < tph; ++c) {
+        int w = (seg * T + h * tph + c) % ctx->n_cu;
+        if (ctx->qkv_xcd_heads) w = 8 * (8 * (h / 8) + c) + h % 8;          // the inverse of fast_xcd_tile
+        prod[((size_t)h * 3 + seg) * tph + c] = w;
+      }
   const hipError_t ep = hipMemcpy(ctx->attn_prod, prod.data(), prod.size() * sizeof(int), hipMemcpyHostToDevice);
   if (ep != hipSuccess) return ep;
   return hipMemcpy(ctx->prog, prog.data(), prog.size() * sizeof(Phase), hipMemcpyHostToDevice);
@@ -661,6 +671,7 @@ extern "C" int heisd_verify_init(const heisd_model_desc *desc, heisd_verify_ctx 
     if (e == hipSuccess) e = hipGetDeviceProperties(&prop, dev);
     if (e == hipSuccess) c->n_cu = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
   }
+  c->qkv_xcd_heads = qkv_xcd_eligible(c) ? 1 : 0;
   if (e == hipSuccess) e = hipMemset(base + w.flags, 0, (size_t)(1024 + 64) * sizeof(unsigned));
   if (e == hipSuccess) e = pack_all(c, base + w.packed);
   if (e == hipSuccess) e = fast_prepare(desc->head_dim, desc->kv_capacity);
@@ -697,10 +708,11 @@ extern "C" int heisd_verify_set_path(heisd_verify_ctx *ctx, int path) {
 
 extern "C" int heisd_verify_set_handover(heisd_verify_ctx *ctx, int mode) {
   if (!ctx) return HEISD_EINVAL;
-  if (mode < 0 || mode > 4) return fail(ctx, HEISD_EINVAL, "set_handover: unknown mode %d", mode);
+  if (mode < 0 || mode > 5) return fail(ctx, HEISD_EINVAL, "set_handover: unknown mode %d", mode);
   if (!ctx->persist_ok) return fail(ctx, HEISD_EUNSUPPORTED, "set_handover: the persistent kernel does not fit this device or shape");
   if (hipDeviceSynchronize() != hipSuccess) return fail(ctx, HEISD_EHIP, "set_handover: device error");
   ctx->handover_mode = mode;
+  ctx->qkv_xcd_heads = qkv_xcd_eligible(ctx) && mode != 5 ? 1 : 0;
   const hipError_t e = persist_build_program(ctx);
   if (e != hipSuccess) return fail(ctx, HEISD_EHIP, "set_handover: %s", hipGetErrorString(e));
   return HEISD_OK;

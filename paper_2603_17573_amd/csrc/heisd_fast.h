@@ -73,7 +73,15 @@ struct FastGemm {
   const float *next_gain; // RESID_NORM: gain of the norm that consumes x next
   uint16_t *o_planes;     // RESID_NORM / SWIGLU: plane records [unit][16][16]
   float *ssq_out;         // RESID_NORM: [n_units][kSsqStride]
+  int xcd_heads;          // STORE_REC with seg_tiles == workgroups == 256 and 8 tiles per head (the QKV projection at
+                          // d_model 4096, head_dim 128): tiles are dealt so that the eight tiles of head h run on
+                          // workgroups of XCD h % 8, where that head's attention units run (see fast_xcd_tile)
 };
+
+// Workgroup w of 256 (XCD w % 8, since workgroup ids are dealt to the 8 XCDs round-robin) takes, in each segment,
+// tile 8 * head + c with head = w % 8 + 8 * (w / 64) and c = (w / 8) % 8: a head's q, k and v rows are then produced
+// on the XCD that consumes them, and the attention unit's first loads hit that XCD's L2.
+__host__ __device__ __forceinline__ int fast_xcd_tile(int w) { return 8 * ((w & 7) + 8 * (w >> 6)) + ((w >> 3) & 7); }
 
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 struct Frag16 {
@@ -107,6 +115,7 @@ __device__ __forceinline__ bool fast_tile(const FastGemm &g, int wg, int nwg, in
     return unit < g.n_units;
   }
   unit = wg + e * nwg;
+  if (g.xcd_heads && nwg == 256) unit = fast_xcd_tile(wg) + e * nwg;
   const int u = unit < g.n_units ? unit : 0;
   const int seg = u / g.seg_tiles;
   wbase = seg == 0 ? w0 : (seg == 1 ? w1 : w2);

@@ -276,6 +276,7 @@ __device__ __forceinline__ FastGemm phase_gemm(const PersistArgs &p, int ph) {
   g.next_gain = P->g.next_gain;
   g.o_planes = P->g.o_planes;
   g.ssq_out = P->g.ssq_out;
+  g.xcd_heads = P->g.xcd_heads;
   return g;
 }
 
@@ -343,7 +344,8 @@ __device__ __forceinline__ void p2_handover_issue(const PersistArgs &p, int ng, 
   // tile entry 0 of workgroup wg is unit wg: the gate tile of pair wg, or tile wg of the segmented matrix
   const int seg = epi == FEPI_SWIGLU ? 0 : wg / seg_tiles;
   const uint16_t *wbase = seg == 0 ? N->g.w[0] : (seg == 1 ? N->g.w[1] : N->g.w[2]);
-  const int tile = epi == FEPI_SWIGLU ? wg : wg - seg * seg_tiles;
+  int tile = epi == FEPI_SWIGLU ? wg : wg - seg * seg_tiles;
+  if (N->g.xcd_heads && nwg == 256) tile = fast_xcd_tile(wg);          // as fast_tile deals them
   const int total = (Kd + 31) / 32;
   const uint16_t *tbase = p2_scalar(wbase + (size_t)tile * (size_t)total * 512);      // k-step 0 of the tile, lane 0
   constexpr int SH = kFastWaves / (kFastWaves - kPfWave0);     // wave shares per issuing wave

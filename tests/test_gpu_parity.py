@@ -100,7 +100,7 @@ def test_persistent_kernel_gives_the_bits_of_one_launch_per_phase():
         assert np.array_equal(outs[0][k], outs[2][k], equal_nan=True), k
 
 
-@pytest.mark.parametrize("mode", [1, 2, 3, 4])
+@pytest.mark.parametrize("mode", [1, 2, 3, 4, 5])
 def test_persistent_kernel_handover_modes_agree(mode):
     """What the persistent kernel requests across its grid barriers changes when weights arrive, never
     what is computed: every mode gives the bits of the default mode (two episodes, one skipped, so that
