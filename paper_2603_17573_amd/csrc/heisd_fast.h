@@ -470,10 +470,11 @@ struct FastAttn {
   float scale;
 };
 
-constexpr int kAttnR = 10;   // prefix rows a key stream requests at once
+constexpr int kAttnR = 10;   // prefix rows a value stream requests at once
+constexpr int kAttnKT = 3;   // tiles of 16 prefix keys a wave requests at once (8 waves: 384 keys)
 
 inline size_t fast_attn_lds(int hd, int cap) {
-  return sizeof(float) * ((size_t)hd * (1 + 8 + 8) + (size_t)cap + 32 + (size_t)kFastWaves * hd);
+  return sizeof(float) * ((size_t)hd * (1 + 8 + 8) + (size_t)cap + 32 + (size_t)kFastWaves * hd + (size_t)hd) + 16;
 }
 
 __device__ __forceinline__ void unpack8(const uint4 v, float (&f)[8]) {
@@ -486,26 +487,38 @@ __device__ __forceinline__ void unpack8(const uint4 v, float (&f)[8]) {
 }
 
 struct AttnPre {
-  uint4 k[kAttnR];
+  u32x4 k[kAttnKT * 4];      // key tiles wave, wave + 8, ... as MFMA A fragments: [tile][k-step of 32 channels]
   uint4 v[kAttnR];
 };
 
-// Request the first kAttnR prefix key and value rows of this lane's stream (no dependence on the
-// current step's activations: may be called before the grid barrier that publishes q/k/v).
+// The cache stores a key as HD consecutive bf16: lane l's 16 bytes at channel 32 ks + 8 (l / 16) of key 16 t + l % 16
+// are its piece of the A operand of v_mfma_f32_16x16x32_bf16 for key tile t, k-step ks.
+template <int HD>
+__device__ __forceinline__ u32x4 fast_attn_key_frag(const uint16_t *kc, int tile, int ks, int P, int lane) {
+  const int r = 16 * tile + (lane & 15);
+  return r < P ? *reinterpret_cast<const u32x4 *>(kc + (size_t)r * HD + 32 * ks + 8 * (lane >> 4)) : u32x4{0u, 0u, 0u, 0u};
+}
+
+// Request the first kAttnKT key tiles of this wave and the first kAttnR value rows of this lane's stream (no
+// dependence on the current step's activations: may be called before the grid barrier that publishes q/k/v).
 template <int HD>
 __device__ __forceinline__ void fast_attn_prefetch(const FastAttn &a, int b, int h, AttnPre &pre, int tid) {
-  constexpr int LPK = HD / 8, G = kFastThreads / LPK;
+  constexpr int LPK = HD / 8, G = kFastThreads / LPK, KS = HD / 32;
   const int li = tid % LPK, g = tid / LPK;
   int P = a.prefix_len[b];
   P = max(0, min(P, a.cap - a.K));
   const bool skip = episode_sits_out(a.skip, a.prefix_len, b, a.K, a.cap);
   const uint16_t *kc = a.k_cache + ((size_t)(b * a.H + h) * a.cap) * HD;
   const uint16_t *vc = a.v_cache + ((size_t)(b * a.H + h) * a.cap) * HD;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), Pk = skip ? 0 : P;
+#pragma unroll
+  for (int tt = 0; tt < kAttnKT; ++tt)
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) pre.k[tt * KS + ks] = fast_attn_key_frag<HD>(kc, wave + 8 * tt, ks, Pk, tid & 63);
 #pragma unroll
   for (int u = 0; u < kAttnR; ++u) {
     const int r = u * G + g;
     const bool ok = !skip && r < P;
-    pre.k[u] = ok ? *reinterpret_cast<const uint4 *>(kc + (size_t)r * HD + li * 8) : make_uint4(0, 0, 0, 0);
     pre.v[u] = ok ? *reinterpret_cast<const uint4 *>(vc + (size_t)r * HD + li * 8) : make_uint4(0, 0, 0, 0);
   }
 }
@@ -513,7 +526,9 @@ __device__ __forceinline__ void fast_attn_prefetch(const FastAttn &a, int b, int
 // Query jq (< K <= 8) of episode b, head h: one workgroup.  512 threads = 512/(HD/8) key streams;
 // `pre` holds the first kAttnR prefix rows of each stream.  The unit rotates the block's keys
 // 0..jq itself (fp32, LDS) and appends row jq to the cache; scores live in LDS; the softmax is a
-// workgroup reduction; only the stored cache rows are rounded to bf16.
+// workgroup reduction; only the stored cache rows are rounded to bf16.  The unit's barriers order LDS
+// traffic only (lds_barrier): what the waves exchange goes through LDS, and a full barrier would also wait for
+// the acknowledgement of the appended cache rows and of the output records, on the unit's critical path.
 struct NoHook {
   __device__ __forceinline__ void operator()() const {}
 };
@@ -533,6 +548,9 @@ __device__ __forceinline__ void fast_attn_unit(const FastAttn &a, int b, int h, 
   float *sc = vb + 8 * HD;                          // [cap]
   float *wred = sc + a.cap;                         // [32] per-wave partials
   float *ored = wred + 32;                          // [waves][HD]
+  uint16_t *qh = reinterpret_cast<uint16_t *>((reinterpret_cast<uintptr_t>(ored + kFastWaves * HD) + 15) & ~(uintptr_t)15);
+                                                                         // [HD] bf16 head of the query (16-byte aligned) ...
+  uint16_t *ql = qh + HD;                                                // [HD] ... and bf16 tail
   const int lane = tid & 63, wave = tid >> 6;
   const int K = a.K, d = a.d, cap = a.cap;
   const int m = b * K + jq;                         // activation row of this query
@@ -569,8 +587,14 @@ __device__ __forceinline__ void fast_attn_unit(const FastAttn &a, int b, int h, 
     vb[j * HD + i + HALF] = v2;
     if (j == jq) {
       const float q1 = qa[0], q2 = qb[0];
-      qs[i] = (q1 * cs.x - q2 * cs.y) * a.scale;
-      qs[i + HALF] = (q2 * cs.x + q1 * cs.y) * a.scale;
+      const float r1 = (q1 * cs.x - q2 * cs.y) * a.scale, r2 = (q2 * cs.x + q1 * cs.y) * a.scale;
+      qs[i] = r1;
+      qs[i + HALF] = r2;
+      uint32_t h1, l1, h2, l2;
+      split_bf16(r1, h1, l1);
+      split_bf16(r2, h2, l2);
+      qh[i] = (uint16_t)h1; ql[i] = (uint16_t)l1;
+      qh[i + HALF] = (uint16_t)h2; ql[i + HALF] = (uint16_t)l2;
       uint16_t *kr = kc + (size_t)(P + j) * HD;
       kr[i] = (uint16_t)f32_to_bf16_bits(kr1);
       kr[i + HALF] = (uint16_t)f32_to_bf16_bits(kr2);
@@ -579,7 +603,7 @@ __device__ __forceinline__ void fast_attn_unit(const FastAttn &a, int b, int h, 
       vr[i + HALF] = (uint16_t)f32_to_bf16_bits(v2);
     }
   }
-  __syncthreads();
+  lds_barrier();
   after_loads();
   float qf[8];
 #pragma unroll
@@ -593,31 +617,47 @@ __device__ __forceinline__ void fast_attn_unit(const FastAttn &a, int b, int h, 
     for (int off = LPK / 2; off > 0; off >>= 1) t += __shfl_xor(t, off, kWave);
     if (li == 0) sc[r] = t;
   };
-  // ---- pass 1: scores of the prefix keys, then of the block's keys 0..jq ----
+  // ---- pass 1: scores of the prefix keys on the matrix cores, then of the block's keys 0..jq with FMAs ----
+  // A = a tile of 16 cached keys (bf16, straight from the cache), B = the query: its bf16 head in column 0 and
+  // its bf16 tail in column 1 (q = head + tail to 16 mantissa bits; the products are exact in fp32), the other
+  // columns zero.  Output element (key 4 (l / 16) + i, column l % 16) is register i of lane l: lanes 0, 16, 32, 48
+  // add their neighbour's column and store four scores each.
+  {
+    constexpr int KS = HD / 32;
+    const int lr = lane & 15, lg = lane >> 4, wv = __builtin_amdgcn_readfirstlane(tid >> 6);
+    u32x4 bq[KS];
 #pragma unroll
-  for (int u = 0; u < kAttnR; ++u) {
-    const int r = u * G + g;
-    if (r < P) {
-      float kf[8];
-      unpack8(pre.k[u], kf);
-      score_row(kf, r);
+    for (int ks = 0; ks < KS; ++ks) {
+      const u32x4 qv = *reinterpret_cast<const u32x4 *>((lr == 0 ? qh : ql) + 32 * ks + 8 * lg);
+      bq[ks] = lr < 2 ? qv : u32x4{0u, 0u, 0u, 0u};
     }
-  }
-  for (int r0 = G * kAttnR; r0 < P; r0 += G * kAttnR) {
-    uint4 kk[kAttnR];
+    const int n_kt = (P + 15) >> 4;
+    auto emit = [&](int tile, const f32x4 acc) {
 #pragma unroll
-    for (int u = 0; u < kAttnR; ++u) {
-      const int r = r0 + u * G + g;
-      kk[u] = (r < P) ? *reinterpret_cast<const uint4 *>(kc + (size_t)r * HD + li * 8) : make_uint4(0, 0, 0, 0);
-    }
-#pragma unroll
-    for (int u = 0; u < kAttnR; ++u) {
-      const int r = r0 + u * G + g;
-      if (r < P) {
-        float kf[8];
-        unpack8(kk[u], kf);
-        score_row(kf, r);
+      for (int i = 0; i < 4; ++i) {
+        const float t = acc[i] + __shfl_down(acc[i], 1, kWave);
+        const int r = 16 * tile + 4 * lg + i;
+        if (lr == 0 && r < P) sc[r] = t;
       }
+    };
+#pragma unroll
+    for (int tt = 0; tt < kAttnKT; ++tt) {
+      const int tile = wv + 8 * tt;
+      if (tile < n_kt) {                                  // wave-uniform
+        f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) acc = fast_mfma(pre.k[tt * KS + ks], bq[ks], acc);
+        emit(tile, acc);
+      }
+    }
+    for (int tile = wv + 8 * kAttnKT; tile < n_kt; tile += 8) {
+      u32x4 kf[KS];
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) kf[ks] = fast_attn_key_frag<HD>(kc, tile, ks, P, lane);
+      f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) acc = fast_mfma(kf[ks], bq[ks], acc);
+      emit(tile, acc);
     }
   }
   if (g <= jq) {
@@ -626,14 +666,14 @@ __device__ __forceinline__ void fast_attn_unit(const FastAttn &a, int b, int h, 
     for (int i = 0; i < 8; ++i) kf[i] = kb[g * HD + li * 8 + i];
     score_row(kf, P + g);
   }
-  __syncthreads();
+  lds_barrier();
   const int nkeys = P + jq + 1;
   // ---- softmax over the visible keys (workgroup reduction) ----
   float mx = -INFINITY;
   for (int r = tid; r < nkeys; r += kFastThreads) mx = fmaxf(mx, sc[r]);
   mx = wave_max(mx);
   if (lane == 0) wred[wave] = mx;
-  __syncthreads();
+  lds_barrier();
   mx = wred[0];
 #pragma unroll
   for (int w = 1; w < kFastWaves; ++w) mx = fmaxf(mx, wred[w]);
@@ -645,7 +685,7 @@ __device__ __forceinline__ void fast_attn_unit(const FastAttn &a, int b, int h, 
   }
   sum = wave_sum(sum);
   if (lane == 0) wred[8 + wave] = sum;
-  __syncthreads();
+  lds_barrier();
   float tot = 0.f;
 #pragma unroll
   for (int w = 0; w < kFastWaves; ++w) tot += wred[8 + w];
@@ -697,7 +737,7 @@ __device__ __forceinline__ void fast_attn_unit(const FastAttn &a, int b, int h, 
 #pragma unroll
     for (int i = 0; i < 8; ++i) ored[wave * HD + lane * 8 + i] = o[i];
   }
-  __syncthreads();
+  lds_barrier();
   for (int c2 = tid; c2 < HALF; c2 += kFastThreads) {      // two adjacent channels per thread
     const int c = c2 * 2;
     float t0 = 0.f, t1 = 0.f;
@@ -713,7 +753,7 @@ __device__ __forceinline__ void fast_attn_unit(const FastAttn &a, int b, int h, 
     st_dev(rec + (m * 16 + (c & 15)) / 2, h0 | (h1 << 16));
     st_dev(rec + ((m + 8) * 16 + (c & 15)) / 2, l0 | (l1 << 16));
   }
-  __syncthreads();
+  lds_barrier();
 }
 
 // ---- one launch per phase ---------------------------------------------------------------------
