@@ -153,6 +153,9 @@ def run_aux_mode(args):
     weights = synth.make_weights(sh, wl.seed)
     ver = Verifier(DeviceModel(sh, weights, dev), B, max(chunks), cap)
     assert heisd_verify_set_path(ver.ctx, args.path) == 0
+    if args.act_bf16:
+        from paper_2603_17573_amd import heisd_verify_set_activations, HEISD_ACT_BF16
+        assert heisd_verify_set_activations(ver.ctx, HEISD_ACT_BF16) == 0
     kc, vc = ver.new_cache(B)
     stream = torch.cuda.current_stream(dev)
     calls = []                                   # (prefix_len tensor, keyword arguments) per call of one step
@@ -254,7 +257,8 @@ def run_aux_mode(args):
                                    (wl.name, L, d, P, B, "one new token per episode on a full prefix cache" if decode
                                     else "whole prefix from an empty cache in chunks of %s rows" % chunks),
                        "global_batch": B},
-            "kernel_path": args.path, "gemm_tflops_whole_step": round(gemm_flops_per_row * B * sum(chunks) / (ms * 1e-3) / 1e12, 2),
+            "kernel_path": args.path, "activations": "one bf16" if args.act_bf16 else "bf16 head + tail",
+            "gemm_tflops_whole_step": round(gemm_flops_per_row * B * sum(chunks) / (ms * 1e-3) / 1e12, 2),
             "kernels": kernels, "roofline": roofline, "cpu_baseline": cpu}
     print(json.dumps(line))
     ver.close()
@@ -400,6 +404,9 @@ def main():
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run three plain 1 GiB device copies (reference kernel for HBM traffic counters)")
     ap.add_argument("--path", type=int, default=0, help="0 auto, 1 generic, 2 fast (launch per phase), 3 persistent")
+    ap.add_argument("--act-bf16", action="store_true",
+                    help="activations enter the matrix cores as one bf16 each (heisd_verify_set_activations; calls of 65 "
+                         "rows or more), instead of a bf16 head and tail; reported in the JSON line as activations")
     ap.add_argument("--handover", type=int, default=0, choices=[0, 1, 2, 3, 4, 5],
                     help="--path 3 only: what the persistent kernel requests across its grid barriers "
                          "(heisd_verify_set_handover; 0 = default)")
@@ -459,6 +466,9 @@ def main():
     ver = Verifier(dm, B, rows, cap)
     from paper_2603_17573_amd import heisd_verify_set_path, heisd_verify_set_handover
     assert heisd_verify_set_path(ver.ctx, args.path) == 0
+    if args.act_bf16:
+        from paper_2603_17573_amd import heisd_verify_set_activations, HEISD_ACT_BF16
+        assert heisd_verify_set_activations(ver.ctx, HEISD_ACT_BF16) == 0
     if args.path == 3 and args.handover:
         assert heisd_verify_set_handover(ver.ctx, args.handover) == 0
     # prefix K/V drawn directly (the benchmark may not call the oracle's prefill); same shapes,
@@ -708,6 +718,7 @@ def main():
                                (wl.name, sh.n_layers, sh.d_model, P, B, K, wl.tau_tok, wl.tau_seq),
                    "prefix_kv": "drawn directly (no prefill)", "drafts": drafts_note, "global_batch": B, "K": K, "tree_tokens": T or None},
         "kernel_path": args.path, "handover_mode": args.handover if args.path == 3 else None,
+        "activations": "one bf16 (calls of 65 rows or more)" if args.act_bf16 else "bf16 head + tail",
         "hbm_frac_whole_step": round(total_bytes / (ms * 1e-3) / HBM_PEAK, 4),
         "algorithmic_bytes_per_step": total_bytes,
         "accepted_len": accepted[:8],

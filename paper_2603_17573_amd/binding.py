@@ -104,6 +104,8 @@ def load():
         lib.heisd_measure_empty_launch.restype = ctypes.c_int
         lib.heisd_verify_set_handover.argtypes = [c_void_p, ctypes.c_int]
         lib.heisd_verify_set_handover.restype = ctypes.c_int
+        lib.heisd_verify_set_activations.argtypes = [c_void_p, ctypes.c_int]
+        lib.heisd_verify_set_activations.restype = ctypes.c_int
         lib.heisd_debug_trace.argtypes = [c_void_p, ctypes.c_int, c_void_p, ctypes.c_int]
         lib.heisd_debug_trace.restype = ctypes.c_int
         lib.heisd_last_error.argtypes = [c_void_p]
@@ -223,6 +225,13 @@ def heisd_measure_empty_launch(workgroups, stream) -> int:
 
 def heisd_verify_set_handover(ctx, mode: int) -> int:
     return load().heisd_verify_set_handover(ctx, mode)
+
+
+HEISD_ACT_SPLIT, HEISD_ACT_BF16 = 0, 1
+
+
+def heisd_verify_set_activations(ctx, fmt: int) -> int:
+    return load().heisd_verify_set_activations(ctx, fmt)
 
 
 def heisd_debug_trace(ctx, enable: bool, max_entries: int = 0):

@@ -47,6 +47,7 @@ struct heisd_verify_ctx {
   bool persist_ok = false;
   int *attn_prod = nullptr;            // persistent kernel: [n_heads][3 * head_dim / 16] producer workgroups of a head's q/k/v
   int qkv_xcd_heads = 0;               // persistent kernel: QKV tiles dealt so that a head is produced on the XCD that consumes it
+  int act_bf16 = 0;                    // batch path from 65 rows: activations enter the GEMMs as one bf16 each (opt-in)
   int handover_mode = 0;               // persistent kernel: what crosses a grid barrier (see persist_build_program)
   unsigned long long *trace = nullptr; // device buffer [n_phases][8] when tracing is on
   bool trace_on = false;
@@ -706,6 +707,13 @@ extern "C" int heisd_verify_set_path(heisd_verify_ctx *ctx, int path) {
   return HEISD_OK;
 }
 
+extern "C" int heisd_verify_set_activations(heisd_verify_ctx *ctx, int format) {
+  if (!ctx) return HEISD_EINVAL;
+  if (format != HEISD_ACT_SPLIT && format != HEISD_ACT_BF16) return fail(ctx, HEISD_EINVAL, "set_activations: unknown format %d", format);
+  ctx->act_bf16 = format == HEISD_ACT_BF16;
+  return HEISD_OK;
+}
+
 extern "C" int heisd_verify_set_handover(heisd_verify_ctx *ctx, int mode) {
   if (!ctx) return HEISD_EINVAL;
   if (mode < 0 || mode > 5) return fail(ctx, HEISD_EINVAL, "set_handover: unknown mode %d", mode);
@@ -964,7 +972,7 @@ static void bat_wide_launch(const BatGemm &g, int mw, int n_cu, hipStream_t st, 
   double best = estimate(4, 1);
   for (int n : {4, 2})
     for (int k = 1; k <= kSplitMax; ++k) {
-      if (k > 1 && (!may_split || k * CT > room.tiles)) break;
+      if (k > 1 && (!may_split || k * CT * (g.single ? 2 : 1) > room.tiles)) break;
       if ((k - 1) * ((n_chunks + k - 1) / k) >= n_chunks) continue;      // the last run would be empty
       const double e = estimate(n, k);
       if (e < best) { best = e; nt = n; ks = k; }
@@ -982,6 +990,10 @@ static void bat_wide_launch(const BatGemm &g, int mw, int n_cu, hipStream_t st, 
 // it measured 60 against 49 us at 56 rows.)
 static void bat_launch(BatGemm g, int n_cu, hipStream_t st, const SplitRoom &room = SplitRoom()) {
   const int CT = g.CT;
+  if (g.single) {                      // single-bf16 records: the wide kernels only (the caller sees to CT >= 5)
+    bat_wide_launch(g, CT <= 8 ? 1 : 2, n_cu, st, g.epi == FEPI_SWIGLU ? SplitRoom() : room);
+    return;
+  }
   if (CT <= 8 && g.epi == FEPI_SWIGLU) {
     // column tiles per wave: 4, 6 or 8 (45 rows: 42.7 us with 6 against 46.7 us with 8; 7 tiles per wave
     // measured slower than 8 at 56 rows, 48.2 against 47.1 us)
@@ -1020,7 +1032,12 @@ static void batch_forward(heisd_verify_ctx *ctx, const heisd_kv_desc *kv, const 
   const heisd_model_desc &d = ctx->d;
   const int M = batch * K, dm = d.d_model, F = d.d_ffn, H = d.n_heads, HD = d.head_dim, cap = d.kv_capacity;
   const BatScratch bs(&d);
-  const int CT = (M + 7) / 8, CTS = bs.CTS;
+  const int CTS = bs.CTS;
+  // One bf16 per activation (opt-in, heisd_verify_set_activations): from 65 rows, where every projection runs on
+  // bat_gemm_wide, and only if the 16-row column tiles stay inside the buffers laid out for 8-row ones.
+  const int single = ctx->act_bf16 && M >= 65 && (M + 15) / 16 * 16 <= CTS * 8 ? 1 : 0;
+  const int RPT = single ? 16 : 8;                       // activation rows per column tile
+  const int CT = (M + RPT - 1) / RPT;
   uint16_t *rec_x = reinterpret_cast<uint16_t *>(ctx->bscr + bs.rec_x);
   uint16_t *rec_o = reinterpret_cast<uint16_t *>(ctx->bscr + bs.rec_o);
   uint16_t *rec_act = reinterpret_cast<uint16_t *>(ctx->bscr + bs.rec_act);
@@ -1031,18 +1048,19 @@ static void batch_forward(heisd_verify_ctx *ctx, const heisd_kv_desc *kv, const 
   part.tiles = bs.part_tiles();
   float *inv_rms = reinterpret_cast<float *>(ctx->bscr + bs.inv_rms);
   auto row_scales = [&]() {
-    bat_row_scales<<<dim3((CT * 8 + kBatWaves - 1) / kBatWaves), dim3(kBatThreads), 0, st>>>(ssq, dm / 16, CT * 8,
-                                                                                            CTS * 8, dm, d.rms_eps, inv_rms);
+    bat_row_scales<<<dim3((CT * RPT + kBatWaves - 1) / kBatWaves), dim3(kBatThreads), 0, st>>>(ssq, dm / 16, CT * RPT,
+                                                                                              CTS * 8, dm, d.rms_eps, inv_rms);
   };
   {
     ProfScope ps(ctx, HEISD_KC_EMBED, st, prof);
-    bat_embed<<<dim3(dm / 16, (CT + 7) / 8), dim3(64), 0, st>>>(draft_tokens, x_rows, static_cast<const uint16_t *>(d.tok_emb), d.vocab, dm, M,
-                                                  CT, CTS, ctx->attn_norm[0], ctx->x, rec_x, ssq);
+    bat_embed<<<dim3(dm / 16, (CT * (single ? 2 : 1) + 7) / 8), dim3(64), 0, st>>>(
+        draft_tokens, x_rows, static_cast<const uint16_t *>(d.tok_emb), d.vocab, dm, M, CT, CTS, ctx->attn_norm[0], ctx->x, rec_x,
+        ssq, single);
     row_scales();
   }
   const size_t layer_stride = (size_t)batch * H * cap * HD;
   BatGemm base{};
-  base.CT = CT; base.CTS = CTS; base.M = M;
+  base.CT = CT; base.CTS = CTS; base.M = M; base.single = single;
   for (int l = 0; l < d.n_layers; ++l) {
     // q, k, v = RMSNorm(x) . {Wq, Wk, Wv}^T  (fp32 rows for the attention kernel)
     BatGemm g = base;
@@ -1059,7 +1077,7 @@ static void batch_forward(heisd_verify_ctx *ctx, const heisd_kv_desc *kv, const 
     a.k_cache = static_cast<uint16_t *>(kv->k_cache) + (size_t)l * layer_stride;
     a.v_cache = static_cast<uint16_t *>(kv->v_cache) + (size_t)l * layer_stride;
     a.prefix_len = kv->prefix_len; a.skip = skip_mask; a.rope = ctx->rope; a.out = nullptr;
-    a.o_planes = rec_o; a.CTS = CTS;
+    a.o_planes = rec_o; a.CTS = CTS; a.single = single;
     a.K = K; a.H = H; a.cap = cap; a.d = dm; a.scale = 1.0f / std::sqrt((float)HD);
     a.depth = depth; a.anc = anc;
     {

@@ -43,6 +43,7 @@ struct AttnArgs {
   float *out;                // [M][d] fp32 rows, or nullptr
   uint16_t *o_planes;        // or: records [d/16][CTS][16][16] bf16 (head rows 0-7, tail rows 8-15 of each
   int CTS;                   //     column tile of 8 activation rows), the B-operand format of the GEMMs
+  int single;                // records hold ONE bf16 per value: 16 activation rows per column tile (see BatGemm::single)
   int K, H, cap, d;
   float scale;               // 1/sqrt(HD)
   const int32_t *depth;              // tree mode: [batch][K] tokens between the prefix and row j; else nullptr
@@ -61,6 +62,10 @@ __device__ __forceinline__ void attn_store(const AttnArgs &a, int m, int col, fl
   if (a.o_planes) {
     uint32_t hi, lo;
     split_bf16(v, hi, lo);
+    if (a.single) {
+      a.o_planes[((size_t)(col >> 4) * a.CTS + (m >> 4)) * 256 + (m & 15) * 16 + (col & 15)] = (uint16_t)hi;
+      return;
+    }
     uint16_t *rec = a.o_planes + ((size_t)(col >> 4) * a.CTS + (m >> 3)) * 256 + (m & 7) * 16 + (col & 15);
     rec[0] = (uint16_t)hi;
     rec[128] = (uint16_t)lo;

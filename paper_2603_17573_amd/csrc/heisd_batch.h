@@ -42,6 +42,10 @@ struct BatGemm {
   const float *next_gain; // RESID_NORM: gain of the norm that consumes x next
   uint16_t *o_planes;     // RESID_NORM / SWIGLU: records [unit][CTS][16][16]
   float *ssq_out;         // RESID_NORM: [n_units][CTS*8] partial sums of squares of the new x
+  int single;             // activations as ONE bf16 each (bat_gemm_wide, bat_split_finish, bat_embed and the attention
+                          // kernels only): a record then holds the bf16 values of 16 activation rows, a column tile
+                          // is 16 rows, CT = ceil(M/16), and the 16 columns of an accumulator tile are 16 rows'
+                          // results (nothing to add up).  0: head + tail of 8 rows, as described above
   int MW;                 // bat_gemm: waves across column tiles (1, 2, 4 or 8); the other 8/MW split k
   int NW;                 // bat_gemm_ns: computing waves across weight tiles (6 or 3); set by the launcher
 };
@@ -76,8 +80,13 @@ struct EmitPre {
   float2 xo;      // RESID_NORM: the residual stream's old values
   float2 gn;      // RESID_NORM: the next norm's gains
 };
-__device__ __forceinline__ EmitPre bat_emit_load(const BatGemm &g, int unit, int ct, int jm, int c2) {
-  const int i = 2 * c2, m = ct * 8 + jm;
+// hh: with single-bf16 activations a column tile has 16 rows and lane (jm, c2) serves rows jm (hh = 0) and jm + 8
+// (hh = 1) of it, from accumulator columns jm and jm + 8; otherwise hh = 0.
+__device__ __forceinline__ int bat_row_of(const BatGemm &g, int ct, int jm, int hh) {
+  return g.single ? ct * 16 + hh * 8 + jm : ct * 8 + jm;
+}
+__device__ __forceinline__ EmitPre bat_emit_load(const BatGemm &g, int unit, int ct, int jm, int c2, int hh = 0) {
+  const int i = 2 * c2, m = bat_row_of(g, ct, jm, hh);
   EmitPre p;
   p.sc = g.inv_rms ? g.inv_rms[m] : 1.0f;
   p.xo = make_float2(0.f, 0.f);
@@ -89,9 +98,9 @@ __device__ __forceinline__ EmitPre bat_emit_load(const BatGemm &g, int unit, int
   return p;
 }
 __device__ __forceinline__ void bat_emit_apply(const BatGemm &g, int unit, int ct, int jm, int c2, float s0, float s1,
-                                               float u0, float u1, const EmitPre &pre) {
+                                               float u0, float u1, const EmitPre &pre, int hh = 0) {
   const int i = 2 * c2;
-  const int m = ct * 8 + jm;
+  const int m = bat_row_of(g, ct, jm, hh);
   const bool live = m < g.M;
   const float sc = pre.sc;
   if (g.epi == FEPI_STORE_ROWS) {
@@ -123,8 +132,12 @@ __device__ __forceinline__ void bat_emit_apply(const BatGemm &g, int unit, int c
   split_bf16(a0, h0, l0);
   split_bf16(a1, h1, l1);
   uint32_t *rec = reinterpret_cast<uint32_t *>(g.o_planes + ((size_t)unit * g.CTS + ct) * 256);
-  rec[(jm * 16 + i) / 2] = h0 | (h1 << 16);
-  rec[((jm + 8) * 16 + i) / 2] = l0 | (l1 << 16);
+  if (g.single) {
+    rec[((jm + 8 * hh) * 16 + i) / 2] = h0 | (h1 << 16);         // the value rounded to bf16, nothing else
+  } else {
+    rec[(jm * 16 + i) / 2] = h0 | (h1 << 16);
+    rec[((jm + 8) * 16 + i) / 2] = l0 | (l1 << 16);
+  }
 }
 __device__ __forceinline__ void bat_emit(const BatGemm &g, int unit, int ct, int jm, int c2, float s0, float s1, float u0,
                                          float u1) {
@@ -495,29 +508,42 @@ __device__ __forceinline__ void bat_wide_finish_wave(const BatGemm &g, f32x4 (&a
           const float *p = mine + ((size_t)(tt * MC + ct) * 64) * 4;
           const float2 a = *reinterpret_cast<const float2 *>(p + l_hi * 4 + r);
           const float2 b = *reinterpret_cast<const float2 *>(p + (l_hi + 8) * 4 + r);
-          part[(((size_t)split * g.n_units + unit) * g.CT + ctg) * 64 + lane] = make_float2(a.x + b.x, a.y + b.y);
+          if (g.single) {                             // two rows' sums, kept apart
+            float2 *dst = part + ((((size_t)split * g.n_units + unit) * g.CT + ctg) * 2) * 64 + lane;
+            dst[0] = a;
+            dst[64] = b;
+          } else {
+            part[(((size_t)split * g.n_units + unit) * g.CT + ctg) * 64 + lane] = make_float2(a.x + b.x, a.y + b.y);
+          }
         }
         continue;
       }
-      EmitPre pre[MC];                                // everything the tile's 8 column tiles read, requested before the first store
+      const int n_half = g.single ? 2 : 1;
+#pragma unroll 1
+      for (int hh = 0; hh < n_half; ++hh) {
+        EmitPre pre[MC];                              // everything the tile's 8 column tiles read, requested before the first store
 #pragma unroll
-      for (int ct = 0; ct < MC; ++ct) pre[ct] = bat_emit_load(g, unit, min(ctg0 + ct, g.CT - 1), jm, c2);
+        for (int ct = 0; ct < MC; ++ct) pre[ct] = bat_emit_load(g, unit, min(ctg0 + ct, g.CT - 1), jm, c2, hh);
 #pragma unroll
-      for (int ct = 0; ct < MC; ++ct) {
-        const int ctg = ctg0 + ct;
-        if (ctg >= g.CT) continue;                    // uniform over the wave
-        const float *p = mine + ((size_t)(tt * MC + ct) * 64) * 4;
-        const float2 a = *reinterpret_cast<const float2 *>(p + l_hi * 4 + r);
-        const float2 b = *reinterpret_cast<const float2 *>(p + (l_hi + 8) * 4 + r);
-        float u0 = 0.f, u1 = 0.f;
-        if (swiglu) {
-          const float *qq = p + (size_t)MC * 256;
-          const float2 cg = *reinterpret_cast<const float2 *>(qq + l_hi * 4 + r);
-          const float2 dg = *reinterpret_cast<const float2 *>(qq + (l_hi + 8) * 4 + r);
-          u0 = cg.x + dg.x;
-          u1 = cg.y + dg.y;
+        for (int ct = 0; ct < MC; ++ct) {
+          const int ctg = ctg0 + ct;
+          if (ctg >= g.CT) continue;                  // uniform over the wave
+          const float *p = mine + ((size_t)(tt * MC + ct) * 64) * 4;
+          const float2 a = *reinterpret_cast<const float2 *>(p + l_hi * 4 + r);
+          const float2 b = *reinterpret_cast<const float2 *>(p + (l_hi + 8) * 4 + r);
+          float2 cg = make_float2(0.f, 0.f), dg = make_float2(0.f, 0.f);
+          if (swiglu) {
+            const float *qq = p + (size_t)MC * 256;
+            cg = *reinterpret_cast<const float2 *>(qq + l_hi * 4 + r);
+            dg = *reinterpret_cast<const float2 *>(qq + (l_hi + 8) * 4 + r);
+          }
+          if (g.single) {
+            const float2 s = hh ? b : a, u = hh ? dg : cg;
+            bat_emit_apply(g, unit, ctg, jm, c2, s.x, s.y, u.x, u.y, pre[ct], hh);
+          } else {
+            bat_emit_apply(g, unit, ctg, jm, c2, a.x + b.x, a.y + b.y, cg.x + dg.x, cg.y + dg.y, pre[ct]);
+          }
         }
-        bat_emit_apply(g, unit, ctg, jm, c2, a.x + b.x, a.y + b.y, u0, u1, pre[ct]);
       }
     }
   }
@@ -659,23 +685,26 @@ __global__ __launch_bounds__(256) void bat_split_finish(BatGemm g, int ksplit, c
   if (tile >= g.n_units * g.CT) return;               // uniform over the wave
   const int ct = tile / g.n_units, unit = tile - ct * g.n_units;     // neighbouring waves: neighbouring columns of the same rows
   const int c2 = lane & 7, jm = lane >> 3;
-  const EmitPre pre = bat_emit_load(g, unit, ct, jm, c2);
+  const int n_half = g.single ? 2 : 1;                // single-bf16 activations: two rows' sums per lane and tile
   // eight runs are requested together (one round trip, not one per run) and added in the order of the runs
-  const size_t run_stride = (size_t)g.n_units * g.CT * 64;
-  const float2 *mine = part + ((size_t)unit * g.CT + ct) * 64 + lane;
-  float2 s = make_float2(0.f, 0.f);
-  for (int k0 = 0; k0 < ksplit; k0 += 8) {
-    float2 v[8];
+  const size_t run_stride = (size_t)g.n_units * g.CT * 64 * n_half;
+  for (int hh = 0; hh < n_half; ++hh) {
+    const EmitPre pre = bat_emit_load(g, unit, ct, jm, c2, hh);
+    const float2 *mine = part + (((size_t)unit * g.CT + ct) * n_half + hh) * 64 + lane;
+    float2 s = make_float2(0.f, 0.f);
+    for (int k0 = 0; k0 < ksplit; k0 += 8) {
+      float2 v[8];
 #pragma unroll
-    for (int k = 0; k < 8; ++k) v[k] = mine[(size_t)min(k0 + k, ksplit - 1) * run_stride];
+      for (int k = 0; k < 8; ++k) v[k] = mine[(size_t)min(k0 + k, ksplit - 1) * run_stride];
 #pragma unroll
-    for (int k = 0; k < 8; ++k)
-      if (k0 + k < ksplit) {
-        s.x += v[k].x;
-        s.y += v[k].y;
-      }
+      for (int k = 0; k < 8; ++k)
+        if (k0 + k < ksplit) {
+          s.x += v[k].x;
+          s.y += v[k].y;
+        }
+    }
+    bat_emit_apply(g, unit, ct, jm, c2, s.x, s.y, 0.f, 0.f, pre, hh);
   }
-  bat_emit_apply(g, unit, ct, jm, c2, s.x, s.y, 0.f, 0.f, pre);
 }
 
 // ---- embedding: x rows (fp32), records of x*gain, partial sums of squares --------------------------
@@ -686,13 +715,15 @@ __global__ __launch_bounds__(256) void bat_split_finish(BatGemm g, int ksplit, c
 // `rows` otherwise.
 __global__ __launch_bounds__(64) void bat_embed(const int32_t *ids, const float *rows, const uint16_t *emb, int vocab, int d,
                                                 int M, int CT, int CTS, const float *gain, float *x, uint16_t *planes,
-                                                float *ssq_out) {
+                                                float *ssq_out, int single) {
   const int tile = blockIdx.x, tid = threadIdx.x;
   const int c2 = tid & 7, jm = tid >> 3;
   const int col = tile * 16 + 2 * c2;
   const float2 gn = *reinterpret_cast<const float2 *>(gain + col);
-  for (int ct = blockIdx.y; ct < CT; ct += gridDim.y) {       // the grid's second dimension shares the column tiles
-    const int m = ct * 8 + jm;
+  const int n_half = single ? 2 : 1;                          // single-bf16 records: 16 rows per column tile
+  for (int cth = blockIdx.y; cth < CT * n_half; cth += gridDim.y) {       // the grid's second dimension shares the column tiles
+    const int ct = cth / n_half, hh = cth - ct * n_half;
+    const int m = single ? ct * 16 + hh * 8 + jm : ct * 8 + jm;
     float v0 = 0.f, v1 = 0.f;
     if (m < M) {
       if (rows && (!ids || ids[m] < 0)) {           // both given: a negative id takes the row's embedding
@@ -717,8 +748,12 @@ __global__ __launch_bounds__(64) void bat_embed(const int32_t *ids, const float 
     split_bf16(v0 * gn.x, h0, l0);
     split_bf16(v1 * gn.y, h1, l1);
     uint32_t *rec = reinterpret_cast<uint32_t *>(planes + ((size_t)tile * CTS + ct) * 256);
-    rec[(jm * 16 + 2 * c2) / 2] = h0 | (h1 << 16);
-    rec[((jm + 8) * 16 + 2 * c2) / 2] = l0 | (l1 << 16);
+    if (single) {
+      rec[((jm + 8 * hh) * 16 + 2 * c2) / 2] = h0 | (h1 << 16);
+    } else {
+      rec[(jm * 16 + 2 * c2) / 2] = h0 | (h1 << 16);
+      rec[((jm + 8) * 16 + 2 * c2) / 2] = l0 | (l1 << 16);
+    }
   }
 }
 

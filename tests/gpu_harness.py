@@ -24,7 +24,7 @@ def _dev_to_bits(t):
 
 
 def run_gpu_step(shape, weights, kb, vb, plen, first, drafts, rule, skip, device="cuda:0",
-                 model=None, max_batch=None, max_k=None, repeat=1, path=0):
+                 model=None, max_batch=None, max_k=None, repeat=1, path=0, act=0):
     """One heisd_verify_step on the GPU.  kb/vb: bf16 bits [L][B][H][cap][hd].  Returns numpy outputs
     plus the caches after the step."""
     dm = model or DeviceModel(shape, weights, device)
@@ -33,6 +33,9 @@ def run_gpu_step(shape, weights, kb, vb, plen, first, drafts, rule, skip, device
     ver = Verifier(dm, max_batch or B, max_k or K, cap)
     from paper_2603_17573_amd import heisd_verify_set_path
     assert heisd_verify_set_path(ver.ctx, path) == 0
+    if act:
+        from paper_2603_17573_amd import heisd_verify_set_activations
+        assert heisd_verify_set_activations(ver.ctx, act) == 0
     kc, vc = _bits_to_dev(kb, device), _bits_to_dev(vb, device)
     t_plen = torch.from_numpy(np.asarray(plen, np.int32)).to(device)
     t_first = torch.from_numpy(np.asarray(first, np.int32)).to(device)

@@ -168,6 +168,25 @@ def test_c4_full_size_threshold_sweep(big, tau):
         assert hist[7] < 64                               # strict verification rejects somewhere in this batch
 
 
+def test_c4_full_size_single_bf16_activations(big):
+    """The C4 batch with activations entering the matrix cores as one bf16 each (the opt-in format): every
+    episode against the oracle to the logit bar, greedy bins equal wherever the bar cannot flip them."""
+    from gpu_harness import run_gpu_step, compare_with_oracle
+    import paper_2603_17573_amd as P
+    if "C4" not in _FULL:
+        _full_batch_case(big, "C4")
+    sh, weights, om, dm = big
+    c = _FULL["C4"]
+    wl = synth.WORKLOADS["C4"]
+    rule = oracle.AcceptRule(wl.tau_tok, wl.tau_seq)
+    got = run_gpu_step(sh, weights, c["kb"], c["vb"], c["plen"], c["first"], c["drafts"], rule, None, model=dm,
+                       act=P.HEISD_ACT_BF16)
+    stats = compare_with_oracle(got, c["ref"], c["drafts"], rule, sh)
+    print("C4, single-bf16 activations:", stats, "%d of 64 accepted lengths equal to the oracle's" %
+          int((got["accepted_len"] == c["ref"]["accepted_len"]).sum()), flush=True)
+    assert stats["max_logit_err_over_range"] > 1e-4          # the format took effect
+
+
 def test_c1_full_size_verify_step_on_prefilled_prefix(big):
     """App. A.1: the C1 prefix as the method has it - 256 visual rows fed as embeddings, then 20 prompt
     ids, prefilled (by the oracle, fp64, rounded once to bf16) - instead of drawn keys and values; the

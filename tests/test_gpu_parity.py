@@ -295,6 +295,37 @@ def test_split_reductions_are_deterministic(B, K):
         assert np.array_equal(a[k], b[k], equal_nan=True), k
 
 
+@pytest.mark.parametrize("B,K", [(10, 7), (25, 8), (9, 8)])
+def test_single_bf16_activations(B, K):
+    """The opt-in activation format (one bf16 per value instead of a bf16 head and tail) on the shape whose
+    reductions are split: 70 rows (blocks of 8 column tiles, six waves across the weight tiles), 200 rows (3 x 2
+    waves, 13 column tiles of 16 rows, a ragged last one) and 72 rows; against the oracle to the logit bar (the
+    cache rows are then bf16-accurate activations away from the oracle's, so they are not compared).  The format
+    takes effect (the logits differ from the split form's), and a step below 65 rows keeps the split form (same bits)."""
+    from gpu_harness import run_gpu_step, compare_with_oracle
+    import paper_2603_17573_amd as P
+    _need_gpu()
+    wl = synth.Workload("act_bf16", SPLIT, 0, 30, SPLIT.bin_base, batch=B, K=K, seed=23)
+    weights = synth.make_weights(wl.shape, wl.seed)
+    om = oracle_model(SPLIT, weights)
+    cap = 30 + K + 2
+    k0, v0, f0 = zip(*[synth.make_prefix_kv_direct(wl, e, cap) for e in range(B)])
+    kb, vb = np.stack(k0, axis=1), np.stack(v0, axis=1)
+    plen, first = np.full(B, 30, np.int32), np.array(f0, np.int32)
+    drafts = (SPLIT.bin_base + synth.make_drafts_uniform(wl)).astype(np.int32)
+    rule = oracle.AcceptRule(2, 6)
+    ref = oracle.verify_step(om, kb, vb, plen, first, drafts, rule)
+    split = run_gpu_step(SPLIT, weights, kb, vb, plen, first, drafts, rule, None)
+    single = run_gpu_step(SPLIT, weights, kb, vb, plen, first, drafts, rule, None, act=P.HEISD_ACT_BF16)
+    s0 = compare_with_oracle(split, ref, drafts, rule, SPLIT)
+    s1 = compare_with_oracle(single, ref, drafts, rule, SPLIT)
+    print("rows %d: split %s, single bf16 %s" % (B * K, s0, s1), flush=True)
+    assert s1["max_logit_err_over_range"] > 4 * s0["max_logit_err_over_range"]
+    small = run_gpu_step(SPLIT, weights, kb[:, :8], vb[:, :8], plen[:8], first[:8], drafts[:8], rule, None, act=P.HEISD_ACT_BF16)
+    small0 = run_gpu_step(SPLIT, weights, kb[:, :8], vb[:, :8], plen[:8], first[:8], drafts[:8], rule, None)
+    assert np.array_equal(small["bin_logits"], small0["bin_logits"])
+
+
 def test_step_argument_errors_enqueue_nothing():
     from paper_2603_17573_amd import DeviceModel, Verifier, make_accept_desc, binding as B
     _need_gpu()
