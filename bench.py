@@ -405,7 +405,7 @@ def main():
                     help="also run three plain 1 GiB device copies (reference kernel for HBM traffic counters)")
     ap.add_argument("--path", type=int, default=0, help="0 auto, 1 generic, 2 fast (launch per phase), 3 persistent")
     ap.add_argument("--act-bf16", action="store_true",
-                    help="activations enter the matrix cores as one bf16 each (heisd_verify_set_activations; calls of 65 "
+                    help="activations enter the matrix cores as one bf16 each (heisd_verify_set_activations; calls of 33 "
                          "rows or more), instead of a bf16 head and tail; reported in the JSON line as activations")
     ap.add_argument("--handover", type=int, default=0, choices=[0, 1, 2, 3, 4, 5],
                     help="--path 3 only: what the persistent kernel requests across its grid barriers "
@@ -718,7 +718,7 @@ def main():
                                (wl.name, sh.n_layers, sh.d_model, P, B, K, wl.tau_tok, wl.tau_seq),
                    "prefix_kv": "drawn directly (no prefill)", "drafts": drafts_note, "global_batch": B, "K": K, "tree_tokens": T or None},
         "kernel_path": args.path, "handover_mode": args.handover if args.path == 3 else None,
-        "activations": "one bf16 (calls of 65 rows or more)" if args.act_bf16 else "bf16 head + tail",
+        "activations": "one bf16 (calls of 33 rows or more)" if args.act_bf16 else "bf16 head + tail",
         "hbm_frac_whole_step": round(total_bytes / (ms * 1e-3) / HBM_PEAK, 4),
         "algorithmic_bytes_per_step": total_bytes,
         "accepted_len": accepted[:8],

@@ -388,7 +388,7 @@ int heisd_verify_set_path(heisd_verify_ctx *ctx, int path);
  * How activations enter the matrix cores on the path for more than 8 rows (paper Sec. 5.1 runs its models in
  * bf16; Eq. 2-2 is the forward this affects).  HEISD_ACT_SPLIT (default): every fp32 activation is a bf16 head
  * plus a bf16 tail (about 16 mantissa bits), two matrix-core operands.  HEISD_ACT_BF16: one bf16 (round to
- * nearest even), half the matrix-core work; used by steps, tree steps and prefill chunks of 65 rows or more
+ * nearest even), half the matrix-core work; used by steps, tree steps and prefill chunks of 33 rows or more
  * (smaller ones keep the split form), everything else - residual stream, softmax, accumulators, the
  * acceptance rule - unchanged.  Logits then differ from the fp32-activation result by about 1e-2 of a row's
  * range instead of 3e-5.  Takes effect with the next call.  Errors: EINVAL (NULL ctx, unknown format).

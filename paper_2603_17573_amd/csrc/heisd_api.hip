@@ -47,7 +47,7 @@ struct heisd_verify_ctx {
   bool persist_ok = false;
   int *attn_prod = nullptr;            // persistent kernel: [n_heads][3 * head_dim / 16] producer workgroups of a head's q/k/v
   int qkv_xcd_heads = 0;               // persistent kernel: QKV tiles dealt so that a head is produced on the XCD that consumes it
-  int act_bf16 = 0;                    // batch path from 65 rows: activations enter the GEMMs as one bf16 each (opt-in)
+  int act_bf16 = 0;                    // batch path from kActBf16MinRows rows: activations enter the GEMMs as one bf16 each (opt-in)
   int handover_mode = 0;               // persistent kernel: what crosses a grid barrier (see persist_build_program)
   unsigned long long *trace = nullptr; // device buffer [n_phases][8] when tracing is on
   bool trace_on = false;
@@ -907,6 +907,8 @@ constexpr int kWideMinCT = 24, kWideMinCTGateUp = 9, kWideMinCTSplit = 9;
 constexpr int kWide1MinCT = 5, kWide1MinCTFew = 3;
 
 // Room for the sums of split reductions: part holds up to `units` units x `tiles` column tiles (runs x tiles in use).
+constexpr int kActBf16MinRows = 33;
+
 struct SplitRoom {
   float2 *part = nullptr;
   int units = 0, tiles = 0;
@@ -990,8 +992,9 @@ static void bat_wide_launch(const BatGemm &g, int mw, int n_cu, hipStream_t st, 
 // it measured 60 against 49 us at 56 rows.)
 static void bat_launch(BatGemm g, int n_cu, hipStream_t st, const SplitRoom &room = SplitRoom()) {
   const int CT = g.CT;
-  if (g.single) {                      // single-bf16 records: the wide kernels only (the caller sees to CT >= 5)
-    bat_wide_launch(g, CT <= 8 ? 1 : 2, n_cu, st, g.epi == FEPI_SWIGLU ? SplitRoom() : room);
+  if (g.single) {                      // single-bf16 records: the wide kernels, and bat_gemm_ns for gate/up on few rows
+    if (CT <= 4 && g.epi == FEPI_SWIGLU) bat_ns_launch_mc<4>(g, n_cu, st);
+    else bat_wide_launch(g, CT <= 8 ? 1 : 2, n_cu, st, g.epi == FEPI_SWIGLU ? SplitRoom() : room);
     return;
   }
   if (CT <= 8 && g.epi == FEPI_SWIGLU) {
@@ -1033,9 +1036,9 @@ static void batch_forward(heisd_verify_ctx *ctx, const heisd_kv_desc *kv, const 
   const int M = batch * K, dm = d.d_model, F = d.d_ffn, H = d.n_heads, HD = d.head_dim, cap = d.kv_capacity;
   const BatScratch bs(&d);
   const int CTS = bs.CTS;
-  // One bf16 per activation (opt-in, heisd_verify_set_activations): from 65 rows, where every projection runs on
-  // bat_gemm_wide, and only if the 16-row column tiles stay inside the buffers laid out for 8-row ones.
-  const int single = ctx->act_bf16 && M >= 65 && (M + 15) / 16 * 16 <= CTS * 8 ? 1 : 0;
+  // One bf16 per activation (opt-in, heisd_verify_set_activations): from 33 rows, where every projection runs on
+  // bat_gemm_wide or bat_gemm_ns, and only if the 16-row column tiles stay inside the buffers laid out for 8-row ones.
+  const int single = ctx->act_bf16 && M >= kActBf16MinRows && (M + 15) / 16 * 16 <= CTS * 8 ? 1 : 0;
   const int RPT = single ? 16 : 8;                       // activation rows per column tile
   const int CT = (M + RPT - 1) / RPT;
   uint16_t *rec_x = reinterpret_cast<uint16_t *>(ctx->bscr + bs.rec_x);

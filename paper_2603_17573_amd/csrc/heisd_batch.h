@@ -42,8 +42,8 @@ struct BatGemm {
   const float *next_gain; // RESID_NORM: gain of the norm that consumes x next
   uint16_t *o_planes;     // RESID_NORM / SWIGLU: records [unit][CTS][16][16]
   float *ssq_out;         // RESID_NORM: [n_units][CTS*8] partial sums of squares of the new x
-  int single;             // activations as ONE bf16 each (bat_gemm_wide, bat_split_finish, bat_embed and the attention
-                          // kernels only): a record then holds the bf16 values of 16 activation rows, a column tile
+  int single;             // activations as ONE bf16 each (bat_gemm_wide, bat_gemm_ns, bat_split_finish, bat_embed and the
+                          // attention kernels; not bat_gemm): a record then holds the bf16 values of 16 activation rows, a column tile
                           // is 16 rows, CT = ceil(M/16), and the 16 columns of an accumulator tile are 16 rows'
                           // results (nothing to add up).  0: head + tail of 8 rows, as described above
   int MW;                 // bat_gemm: waves across column tiles (1, 2, 4 or 8); the other 8/MW split k
@@ -140,9 +140,9 @@ __device__ __forceinline__ void bat_emit_apply(const BatGemm &g, int unit, int c
   }
 }
 __device__ __forceinline__ void bat_emit(const BatGemm &g, int unit, int ct, int jm, int c2, float s0, float s1, float u0,
-                                         float u1) {
-  const EmitPre pre = bat_emit_load(g, unit, ct, jm, c2);
-  bat_emit_apply(g, unit, ct, jm, c2, s0, s1, u0, u1, pre);
+                                         float u1, int hh = 0) {
+  const EmitPre pre = bat_emit_load(g, unit, ct, jm, c2, hh);
+  bat_emit_apply(g, unit, ct, jm, c2, s0, s1, u0, u1, pre, hh);
 }
 
 // First column tile of wave group mw in the block that starts at cb: groups that would run past
@@ -433,23 +433,32 @@ __global__ __launch_bounds__(kBatThreads) __attribute__((amdgpu_waves_per_eu(2, 
           const int c2 = lane & 7, jm = lane >> 3;
           const int i = 2 * c2;
           const int l_hi = (i >> 2) * 16 + jm, r = i & 3;
-          float s0 = 0.f, s1 = 0.f, u0 = 0.f, u1 = 0.f;
+          float s0 = 0.f, s1 = 0.f, u0 = 0.f, u1 = 0.f, t0 = 0.f, t1 = 0.f, w0 = 0.f, w1 = 0.f;
 #pragma unroll
           for (int kk = 0; kk < KW; ++kk) {
             const float *p = red + ((size_t)(((kk * NW + nw) * NT) * MC + ct) * 64) * 4;
             const float2 a = *reinterpret_cast<const float2 *>(p + l_hi * 4 + r);
             const float2 b = *reinterpret_cast<const float2 *>(p + (l_hi + 8) * 4 + r);
-            s0 += a.x + b.x;
-            s1 += a.y + b.y;
+            s0 += a.x;
+            s1 += a.y;
+            t0 += b.x;
+            t1 += b.y;
             if (NT == 2) {
               const float *q = p + (size_t)MC * 256;
               const float2 cg = *reinterpret_cast<const float2 *>(q + l_hi * 4 + r);
               const float2 dg = *reinterpret_cast<const float2 *>(q + (l_hi + 8) * 4 + r);
-              u0 += cg.x + dg.x;
-              u1 += cg.y + dg.y;
+              u0 += cg.x;
+              u1 += cg.y;
+              w0 += dg.x;
+              w1 += dg.y;
             }
           }
-          bat_emit(g, unit, ct, jm, c2, s0, s1, u0, u1);
+          if (g.single) {                             // accumulator columns jm and jm + 8 are two rows' results
+            bat_emit(g, unit, ct, jm, c2, s0, s1, u0, u1, 0);
+            bat_emit(g, unit, ct, jm, c2, t0, t1, w0, w1, 1);
+          } else {
+            bat_emit(g, unit, ct, jm, c2, s0 + t0, s1 + t1, u0 + w0, u1 + w1);
+          }
         }
       }
     }

@@ -295,13 +295,13 @@ def test_split_reductions_are_deterministic(B, K):
         assert np.array_equal(a[k], b[k], equal_nan=True), k
 
 
-@pytest.mark.parametrize("B,K", [(10, 7), (25, 8), (9, 8)])
+@pytest.mark.parametrize("B,K", [(10, 7), (25, 8), (9, 8), (7, 7)])
 def test_single_bf16_activations(B, K):
     """The opt-in activation format (one bf16 per value instead of a bf16 head and tail) on the shape whose
     reductions are split: 70 rows (blocks of 8 column tiles, six waves across the weight tiles), 200 rows (3 x 2
-    waves, 13 column tiles of 16 rows, a ragged last one) and 72 rows; against the oracle to the logit bar (the
+    waves, 13 column tiles of 16 rows, a ragged last one), 72 rows and 49 rows (gate/up on the kernel for up to 64 rows); against the oracle to the logit bar (the
     cache rows are then bf16-accurate activations away from the oracle's, so they are not compared).  The format
-    takes effect (the logits differ from the split form's), and a step below 65 rows keeps the split form (same bits)."""
+    takes effect (the logits differ from the split form's), and a step below 33 rows keeps the split form (same bits)."""
     from gpu_harness import run_gpu_step, compare_with_oracle
     import paper_2603_17573_amd as P
     _need_gpu()
@@ -321,8 +321,8 @@ def test_single_bf16_activations(B, K):
     s1 = compare_with_oracle(single, ref, drafts, rule, SPLIT)
     print("rows %d: split %s, single bf16 %s" % (B * K, s0, s1), flush=True)
     assert s1["max_logit_err_over_range"] > 4 * s0["max_logit_err_over_range"]
-    small = run_gpu_step(SPLIT, weights, kb[:, :8], vb[:, :8], plen[:8], first[:8], drafts[:8], rule, None, act=P.HEISD_ACT_BF16)
-    small0 = run_gpu_step(SPLIT, weights, kb[:, :8], vb[:, :8], plen[:8], first[:8], drafts[:8], rule, None)
+    small = run_gpu_step(SPLIT, weights, kb[:, :4], vb[:, :4], plen[:4], first[:4], drafts[:4], rule, None, act=P.HEISD_ACT_BF16)
+    small0 = run_gpu_step(SPLIT, weights, kb[:, :4], vb[:, :4], plen[:4], first[:4], drafts[:4], rule, None)
     assert np.array_equal(small["bin_logits"], small0["bin_logits"])
 
 
