@@ -32,6 +32,8 @@ constexpr int kFlagStride = 1;           // flags are packed: a poll of all of t
 constexpr int kSpinLimit = 1 << 22;
 
 constexpr int kPF = kKS;                 // k-steps of a wave's first weight tile handed over through LDS: a whole ring
+constexpr int kPfBefore = 12;            // of those, handed over BEFORE the barrier; the rest follows when the barrier is passed (16 / 12 / 8 / 4
+                                         // before it: 2.905 / 2.887 / 2.914 / 3.030 ms per step at the 7B shape)
 constexpr int kPfWave0 = 6;              // waves kPfWave0 .. 7 issue the transfers (they never store in a GEMM epilogue)
 // LDS map.  The hand-over region (128 KB) and the reduction buffer share their bytes: a phase reads what was
 // handed over into registers when it starts and reduces through the same bytes when it ends, and the next
@@ -45,6 +47,7 @@ constexpr size_t kOkOff = kCtlOff + 128;                             // 1 word: 
 constexpr size_t kAttnOff = kCtlOff + 256;                           // the attention units' buffers (fast_attn_lds bytes)
 inline size_t persist_lds_bytes(int hd, int cap) { return kAttnOff + fast_attn_lds(hd, cap); }
 static_assert(kPfBytes >= kFastRedBytes, "the reduction buffer lies inside the hand-over region");
+static_assert(kPfBefore % 4 == 0 && kPfBefore >= 4 && kPfBefore <= kPF, "the products read LDS four steps at a time");
 static_assert(kMaxT <= kPfWave0, "the waves that issue transfers must not take part in epilogue stores");
 static_assert(kFastWaves % (kFastWaves - kPfWave0) == 0 && kPF <= 31, "an issuing wave serves a whole number of wave shares");
 
@@ -354,13 +357,27 @@ __device__ __forceinline__ void p2_handover_issue(const PersistArgs &p, int ng, 
 #pragma unroll 1
   for (int i = 0; i < SH; ++i) {
     const int w = (wave - kPfWave0) * SH + i;
-    if ((i + 1) * kPF > 63) wait_vmcnt<63 - kPF>();            // a wave keeps at most 63 memory operations outstanding
+    if ((i + 1) * kPfBefore > 63) wait_vmcnt<63 - kPfBefore>();   // a wave keeps at most 63 memory operations outstanding
 #pragma unroll
-    for (int s = 0; s < kPF; ++s) {
+    for (int s = 0; s < kPfBefore; ++s) {
       const int ks = __builtin_amdgcn_readfirstlane(p2_a_step(Kd, stream, w, s));
       lds_dma16_s(tbase + (size_t)ks * 512, lane_off,
                   __builtin_amdgcn_readfirstlane(pf_lds + (uint32_t)((w * kPF + s) * 1024)));
     }
+  }
+}
+
+// The rest of the hand-over (steps kPfBefore .. kPF-1), started by every wave for its own share when the barrier
+// is passed, in front of its other requests: what the wave reads from LDS at those steps it reads behind
+// activation fragments requested later, so the transfers have landed by then (a wave's memory operations
+// complete in order).
+__device__ __forceinline__ void p2_handover_rest(const uint16_t *tb0, int Kd, bool stream, int wave, int lane, uint32_t pf_lds) {
+  if (kPfBefore >= kPF) return;
+  const uint32_t lane_off = (uint32_t)lane * 16u;
+#pragma unroll
+  for (int s = kPfBefore; s < kPF; ++s) {
+    const int ks = __builtin_amdgcn_readfirstlane(p2_a_step(Kd, stream, wave, s));
+    lds_dma16_s(tb0 + (size_t)ks * 512, lane_off, __builtin_amdgcn_readfirstlane(pf_lds + (uint32_t)((wave * kPF + s) * 1024)));
   }
 }
 
@@ -401,6 +418,7 @@ __device__ __forceinline__ bool p2_gemm_phase(const PersistArgs &p, int ph, int 
     gemm_publish(p, wg, wait_epoch + 1, smem, tid);
     return true;
   }
+  if (in_lds) p2_handover_rest(tb0, g.Kd, false, wave, lane, pf_lds);
   const bool ring_now = (wave == 0 || !early) && tb_ring;
   if (ring_now && !in_lds) {
 #pragma unroll
@@ -504,6 +522,7 @@ __device__ __forceinline__ bool p2_gemm_stream_phase(const PersistArgs &p, int p
     gemm_publish(p, wg, wait_epoch + 1, smem, tid);
     return true;
   }
+  if (in_lds) p2_handover_rest(tb0, g.Kd, true, wave, lane, pf_lds);
   if (wave == 0 || !early) {
 #pragma unroll
     for (int s = 0; s < kKS; ++s)
@@ -520,7 +539,13 @@ __device__ __forceinline__ bool p2_gemm_stream_phase(const PersistArgs &p, int p
     for (int s = 0; s < kKS; ++s) Bs.v[s] = p2_ld_b(g.b, g.Kd, ks0, s, ns, b_off);
     if (e == 0 && in_lds) {
 #pragma unroll
-      for (int s = 0; s < kPF; ++s) A.v[s] = pf[(wave * kPF + s) * 64 + lane];
+      for (int s = 0; s < kPfBefore; ++s) A.v[s] = pf[(wave * kPF + s) * 64 + lane];
+      if (kPfBefore < kPF) {               // the rest was requested in front of the fragments above: wait for those
+        wait_vmcnt_all();
+        asm volatile("" ::: "memory");
+#pragma unroll
+        for (int s = kPfBefore; s < kPF; ++s) A.v[s] = pf[(wave * kPF + s) * 64 + lane];
+      }
     } else if (e > 0) {
 #pragma unroll
       for (int s = 0; s < kKS; ++s) A.v[s] = p2_ld_a(tb, p2_a_step(g.Kd, true, wave, s), a_off);
