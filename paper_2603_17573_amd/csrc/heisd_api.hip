@@ -48,6 +48,7 @@ struct heisd_verify_ctx {
   int *attn_prod = nullptr;            // persistent kernel: [n_heads][3 * head_dim / 16] producer workgroups of a head's q/k/v
   int qkv_xcd_heads = 0;               // persistent kernel: QKV tiles dealt so that a head is produced on the XCD that consumes it
   int act_bf16 = 0;                    // batch path from kActBf16MinRows rows: activations enter the GEMMs as one bf16 each (opt-in)
+  unsigned scale_epoch = 0;            // batch path: epoch of the last projection of a normalised input (see BatGemm::scale_tag)
   int handover_mode = 0;               // persistent kernel: what crosses a grid barrier (see persist_build_program)
   unsigned long long *trace = nullptr; // device buffer [n_phases][8] when tracing is on
   bool trace_on = false;
@@ -119,7 +120,7 @@ struct BatScratch {
     rec_o = off;   off += kd * CTS * 512;
     rec_act = off; off += kf * CTS * 512;
     ssq = off;     off += align256((size_t)(d->d_model / 16) * CTS * 8 * sizeof(float));
-    inv_rms = off; off += align256((size_t)CTS * 8 * sizeof(float));
+    inv_rms = off; off += align256((size_t)CTS * 8 * sizeof(unsigned long long));   // epoch-tagged 1/rms of the rows
     // sums of split reductions (bat_gemm_wide): up to 3*d_model/16 units (QKV) x part_tiles() column tiles
     // (runs x tiles in use) x 64 lanes x float2
     part = off;    off += (size_t)(3 * d->d_model / 16) * part_tiles() * 512;
@@ -1049,17 +1050,19 @@ static void batch_forward(heisd_verify_ctx *ctx, const heisd_kv_desc *kv, const 
   part.part = reinterpret_cast<float2 *>(ctx->bscr + bs.part);
   part.units = 3 * dm / 16;
   part.tiles = bs.part_tiles();
-  float *inv_rms = reinterpret_cast<float *>(ctx->bscr + bs.inv_rms);
-  auto row_scales = [&]() {
-    bat_row_scales<<<dim3((CT * RPT + kBatWaves - 1) / kBatWaves), dim3(kBatThreads), 0, st>>>(ssq, dm / 16, CT * RPT,
-                                                                                              CTS * 8, dm, d.rms_eps, inv_rms);
+  // The projections of a normalised input take the rows' 1/rms from words their own launch computes (bat_scales_produce):
+  // one epoch per such projection.
+  auto normalised = [&](BatGemm &g) {
+    g.ssq_in = ssq; g.ssq_tiles = dm / 16; g.eps = d.rms_eps;
+    g.scale_tag = reinterpret_cast<unsigned long long *>(ctx->bscr + bs.inv_rms);
+    if (++ctx->scale_epoch == 0u) ctx->scale_epoch = 1u;
+    g.scale_epoch = ctx->scale_epoch; g.err = ctx->dev_err;
   };
   {
     ProfScope ps(ctx, HEISD_KC_EMBED, st, prof);
     bat_embed<<<dim3(dm / 16, (CT * (single ? 2 : 1) + 7) / 8), dim3(64), 0, st>>>(
         draft_tokens, x_rows, static_cast<const uint16_t *>(d.tok_emb), d.vocab, dm, M, CT, CTS, ctx->attn_norm[0], ctx->x, rec_x,
-        ssq, single);
-    row_scales();
+        ssq, single, reinterpret_cast<unsigned long long *>(ctx->bscr + bs.inv_rms));
   }
   const size_t layer_stride = (size_t)batch * H * cap * HD;
   BatGemm base{};
@@ -1072,7 +1075,7 @@ static void batch_forward(heisd_verify_ctx *ctx, const heisd_kv_desc *kv, const 
     g.w[1] = ctx->pk[l];
     g.w[2] = ctx->pv[l];
     g.seg_tiles = dm / 16; g.n_units = 3 * dm / 16; g.Kd = dm;
-    g.b = rec_x; g.inv_rms = inv_rms; g.out = ctx->qkv; g.ldo = 3 * dm;
+    g.b = rec_x; normalised(g); g.out = ctx->qkv; g.ldo = 3 * dm;
     { ProfScope ps(ctx, HEISD_KC_QKV, st, prof); bat_launch(g, ctx->n_cu, st, part); }
     // RoPE + KV-append + attention; the output goes straight into records
     AttnArgs a{};
@@ -1092,12 +1095,11 @@ static void batch_forward(heisd_verify_ctx *ctx, const heisd_kv_desc *kv, const 
     g.epi = FEPI_RESID_NORM;
     g.w[0] = ctx->po[l];
     g.seg_tiles = dm / 16; g.n_units = dm / 16; g.Kd = dm;
-    g.b = rec_o; g.inv_rms = nullptr; g.out = ctx->x; g.ldo = dm;
+    g.b = rec_o; g.out = ctx->x; g.ldo = dm;
     g.next_gain = ctx->ffn_norm[l]; g.o_planes = rec_x; g.ssq_out = ssq;
     {
       ProfScope ps(ctx, HEISD_KC_OPROJ, st, prof);
       bat_launch(g, ctx->n_cu, st, part);
-      row_scales();
     }
     // a = silu(RMSNorm(x) . Wg^T) * (RMSNorm(x) . Wu^T), as records
     g = base;
@@ -1105,20 +1107,19 @@ static void batch_forward(heisd_verify_ctx *ctx, const heisd_kv_desc *kv, const 
     g.w[0] = ctx->pg[l];
     g.w[1] = ctx->pu[l];
     g.seg_tiles = F / 16; g.n_units = F / 16; g.Kd = dm;
-    g.b = rec_x; g.inv_rms = inv_rms; g.o_planes = rec_act;
+    g.b = rec_x; normalised(g); g.o_planes = rec_act;
     { ProfScope ps(ctx, HEISD_KC_GATEUP, st, prof); bat_launch(g, ctx->n_cu, st); }
     // x += a . Wd^T; records of x * (next norm's gain), partial sums of squares
     g = base;
     g.epi = FEPI_RESID_NORM;
     g.w[0] = ctx->pd[l];
     g.seg_tiles = dm / 16; g.n_units = dm / 16; g.Kd = F;
-    g.b = rec_act; g.inv_rms = nullptr; g.out = ctx->x; g.ldo = dm;
+    g.b = rec_act; g.out = ctx->x; g.ldo = dm;
     g.next_gain = (l + 1 < d.n_layers) ? ctx->attn_norm[l + 1] : d.final_norm;
     g.o_planes = rec_x; g.ssq_out = ssq;
     {
       ProfScope ps(ctx, HEISD_KC_DOWN, st, prof);
       bat_launch(g, ctx->n_cu, st, part);
-      row_scales();
     }
   }
   // logits over the action bins = RMSNorm(x; final) . W_lm[bin rows]^T
@@ -1126,7 +1127,7 @@ static void batch_forward(heisd_verify_ctx *ctx, const heisd_kv_desc *kv, const 
   g.epi = FEPI_STORE_ROWS;
   g.w[0] = ctx->plm;
   g.seg_tiles = d.n_bins / 16; g.n_units = d.n_bins / 16; g.Kd = dm;
-  g.b = rec_x; g.inv_rms = inv_rms; g.out = logits; g.ldo = d.n_bins;
+  g.b = rec_x; normalised(g); g.out = logits; g.ldo = d.n_bins;
   ProfScope ps(ctx, HEISD_KC_LMHEAD, st, prof);
   bat_launch(g, ctx->n_cu, st, part);
 }

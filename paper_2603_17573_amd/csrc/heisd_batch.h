@@ -36,7 +36,15 @@ struct BatGemm {
   int CTS;                // column tiles allocated per k-tile (the stride; fixed at init, so that the
                           // zero k-tile stays where it is when M changes between calls)
   int M;
-  const float *inv_rms;   // [CT*8] scale of each output row, or nullptr
+  // A projection of a normalised input (QKV, gate/up, LM head) multiplies its output rows by 1/rms.  The
+  // scales are computed inside the consuming launch (bat_scales_produce) and handed to its epilogues
+  // through epoch-tagged words (bat_row_scale); scale_tag == nullptr: the input is not normalised.
+  const float *ssq_in;    // [ssq_tiles][CTS*8] partial sums of squares of the raw input rows
+  int ssq_tiles;          // Kd / 16
+  float eps;
+  unsigned long long *scale_tag;   // [CTS*8] low word: bits of 1/rms of the row, high word: epoch of the launch that wrote it
+  unsigned scale_epoch;   // this launch's epoch (unique per consuming projection; never 0)
+  unsigned *err;          // device error word (a scale that never arrives raises kErrBarrier)
   float *out;             // STORE_ROWS: [M][ldo]; RESID_NORM: residual stream x [M][ldo], updated in place
   int ldo;
   const float *next_gain; // RESID_NORM: gain of the norm that consumes x next
@@ -49,6 +57,41 @@ struct BatGemm {
   int MW;                 // bat_gemm: waves across column tiles (1, 2, 4 or 8); the other 8/MW split k
   int NW;                 // bat_gemm_ns: computing waves across weight tiles (6 or 3); set by the launcher
 };
+
+// 1/rms of every row in use, by the first workgroups of the launch that consumes them: wave w of workgroup
+// b takes rows 8 b + w, 8 b + w + 8 * workgroups, ...; the partial sums are added in a fixed order (lanes
+// stride over the producer's tiles, butterfly sum).  Called first thing by every GEMM kernel, before any
+// workgroup leaves: the epilogues of ALL workgroups wait for these words, and the workgroups with the lowest
+// ids are dispatched first and wait for nobody, so the wait ends.  A launch that only stores partial sums
+// for a finishing launch produces the scales for that launch (same epoch, already there when it starts).
+constexpr int kScaleSpin = 1 << 20;
+__device__ __forceinline__ void bat_scales_produce(const BatGemm &g) {
+  if (!g.scale_tag) return;
+  const int rows = g.CT * (g.single ? 16 : 8), stride = g.CTS * 8;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nw = blockDim.x >> 6;
+  int m = blockIdx.x * nw + wave;
+  if (m >= rows) return;                                     // uniform over the wave
+  for (; m < rows; m += gridDim.x * nw) {
+    float t = 0.f;
+    for (int p = lane; p < g.ssq_tiles; p += kWave) t += g.ssq_in[(size_t)p * stride + m];
+    t = wave_sum(t);
+    const unsigned long long v = ((unsigned long long)g.scale_epoch << 32) | __float_as_uint(rsqrtf(t / (float)g.Kd + g.eps));
+    if (lane == 0) __hip_atomic_store(g.scale_tag + m, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  }
+  wait_vmcnt_all();                                          // nothing of this is pending when the counted waits begin
+}
+// The scale of row m (bounded wait for this launch's epoch; 1 if the input is not normalised).
+__device__ __forceinline__ float bat_row_scale(const BatGemm &g, int m) {
+  if (!g.scale_tag) return 1.0f;
+  if (m >= g.CT * (g.single ? 16 : 8)) return 0.f;
+  for (int spin = 0; spin < kScaleSpin; ++spin) {
+    const unsigned long long v = __hip_atomic_load(g.scale_tag + m, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if ((unsigned)(v >> 32) == g.scale_epoch) return __uint_as_float((unsigned)v);
+    __builtin_amdgcn_s_sleep(4);
+  }
+  __hip_atomic_fetch_or(g.err, kErrBarrier, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  return 0.f;
+}
 
 template <int MC>
 constexpr size_t bat_lds_bytes() {
@@ -85,10 +128,14 @@ struct EmitPre {
 __device__ __forceinline__ int bat_row_of(const BatGemm &g, int ct, int jm, int hh) {
   return g.single ? ct * 16 + hh * 8 + jm : ct * 8 + jm;
 }
-__device__ __forceinline__ EmitPre bat_emit_load(const BatGemm &g, int unit, int ct, int jm, int c2, int hh = 0) {
+// tab (optional): the scales of rows tab_m0 .. tab_m0 + kScaleTab - 1 in LDS, read once by the caller (a wait
+// for a tagged word is a round trip to the L2, the table is not).
+constexpr int kScaleTab = 128;
+__device__ __forceinline__ EmitPre bat_emit_load(const BatGemm &g, int unit, int ct, int jm, int c2, int hh = 0,
+                                                 const float *tab = nullptr, int tab_m0 = 0) {
   const int i = 2 * c2, m = bat_row_of(g, ct, jm, hh);
   EmitPre p;
-  p.sc = g.inv_rms ? g.inv_rms[m] : 1.0f;
+  p.sc = !g.scale_tag ? 1.0f : (tab ? tab[max(0, min(m - tab_m0, kScaleTab - 1))] : bat_row_scale(g, m));
   p.xo = make_float2(0.f, 0.f);
   p.gn = make_float2(0.f, 0.f);
   if (g.epi == FEPI_RESID_NORM) {
@@ -140,8 +187,8 @@ __device__ __forceinline__ void bat_emit_apply(const BatGemm &g, int unit, int c
   }
 }
 __device__ __forceinline__ void bat_emit(const BatGemm &g, int unit, int ct, int jm, int c2, float s0, float s1, float u0,
-                                         float u1, int hh = 0) {
-  const EmitPre pre = bat_emit_load(g, unit, ct, jm, c2, hh);
+                                         float u1, int hh = 0, const float *tab = nullptr, int tab_m0 = 0) {
+  const EmitPre pre = bat_emit_load(g, unit, ct, jm, c2, hh, tab, tab_m0);
   bat_emit_apply(g, unit, ct, jm, c2, s0, s1, u0, u1, pre, hh);
 }
 
@@ -195,6 +242,7 @@ __global__ __launch_bounds__(kBatThreads) __attribute__((amdgpu_waves_per_eu(2, 
   const int wg = blockIdx.x, nwg = gridDim.x;
   const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int lr = lane & 15, lg = lane >> 4;
+  bat_scales_produce(g);
   const int MW = g.MW, KW = kBatWaves / MW;
   const int mw = wave % MW, kw = wave / MW;
   const int total = (g.Kd + 31) / 32;
@@ -303,7 +351,8 @@ constexpr int kNsBufs = 4;                        // chunks resident in LDS: thr
 constexpr int kNsCompute = 6;
 template <int MC>
 constexpr size_t bat_ns_lds_bytes() {
-  return (size_t)kNsBufs * kNsSlots * MC * 1024;  // the ring; reused for the waves' accumulators at the end
+  return (size_t)kNsBufs * kNsSlots * MC * 1024   // the ring; reused for the waves' accumulators at the end
+         + kScaleTab * sizeof(float);             // the rows' 1/rms
 }
 
 template <int MC, int NT, int KW>
@@ -318,6 +367,7 @@ __global__ __launch_bounds__(kBatThreads) __attribute__((amdgpu_waves_per_eu(2, 
   const int wg = blockIdx.x, nwg = gridDim.x;
   const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int lr = lane & 15, lg = lane >> 4;
+  bat_scales_produce(g);
   const bool filler = wave >= kNsCompute;
   const int nw = wave % NW, kw = filler ? 0 : wave / NW;
   const int total = (g.Kd + 31) / 32;
@@ -418,6 +468,8 @@ __global__ __launch_bounds__(kBatThreads) __attribute__((amdgpu_waves_per_eu(2, 
     lds_barrier();                                    // every transfer has landed: the ring is free
     // the shares of the reduction meet in LDS; the wave with share 0 finishes the unit
     float *red = reinterpret_cast<float *>(smem);
+    float *sc_tab = reinterpret_cast<float *>(smem + (size_t)kNsBufs * kNsSlots * MC * 1024);
+    if (grp == wg && g.scale_tag && threadIdx.x < kScaleTab) sc_tab[threadIdx.x] = bat_row_scale(g, threadIdx.x);   // once per workgroup
     if (!filler) {
 #pragma unroll
       for (int t = 0; t < NT; ++t)
@@ -454,10 +506,10 @@ __global__ __launch_bounds__(kBatThreads) __attribute__((amdgpu_waves_per_eu(2, 
             }
           }
           if (g.single) {                             // accumulator columns jm and jm + 8 are two rows' results
-            bat_emit(g, unit, ct, jm, c2, s0, s1, u0, u1, 0);
-            bat_emit(g, unit, ct, jm, c2, t0, t1, w0, w1, 1);
+            bat_emit(g, unit, ct, jm, c2, s0, s1, u0, u1, 0, sc_tab);
+            bat_emit(g, unit, ct, jm, c2, t0, t1, w0, w1, 1, sc_tab);
           } else {
-            bat_emit(g, unit, ct, jm, c2, s0 + t0, s1 + t1, u0 + w0, u1 + w1);
+            bat_emit(g, unit, ct, jm, c2, s0 + t0, s1 + t1, u0 + w0, u1 + w1, 0, sc_tab);
           }
         }
       }
@@ -494,7 +546,8 @@ constexpr size_t kBatWideLds = (size_t)kWdNB * kWdS * kWdCols * 1024;  // 128 KB
 // column tiles.
 template <int NT, int MC>
 __device__ __forceinline__ void bat_wide_finish_wave(const BatGemm &g, f32x4 (&acc)[NT][MC], const int (&unit_of)[NT], float *mine,
-                                                     int ctg0, int lane, bool swiglu, int split, int ksplit, float2 *part) {
+                                                     int ctg0, int lane, bool swiglu, int split, int ksplit, float2 *part,
+                                                     const float *tab, int tab_m0) {
   const int c2 = lane & 7, jm = lane >> 3, i = 2 * c2;
   const int l_hi = (i >> 2) * 16 + jm, r = i & 3;
 #pragma unroll
@@ -532,7 +585,7 @@ __device__ __forceinline__ void bat_wide_finish_wave(const BatGemm &g, f32x4 (&a
       for (int hh = 0; hh < n_half; ++hh) {
         EmitPre pre[MC];                              // everything the tile's 8 column tiles read, requested before the first store
 #pragma unroll
-        for (int ct = 0; ct < MC; ++ct) pre[ct] = bat_emit_load(g, unit, min(ctg0 + ct, g.CT - 1), jm, c2, hh);
+        for (int ct = 0; ct < MC; ++ct) pre[ct] = bat_emit_load(g, unit, min(ctg0 + ct, g.CT - 1), jm, c2, hh, tab, tab_m0);
 #pragma unroll
         for (int ct = 0; ct < MC; ++ct) {
           const int ctg = ctg0 + ct;
@@ -574,6 +627,7 @@ __global__ __launch_bounds__(kBatThreads) __attribute__((amdgpu_waves_per_eu(2, 
   const uint32_t smem_lds = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char *)smem;
   const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int lr = lane & 15, lg = lane >> 4;
+  bat_scales_produce(g);
   const bool filler = wave >= kWdCompute;
   const int nwv = wave % NWV, mwv = filler ? 0 : wave / NWV;
   const bool swiglu = g.epi == FEPI_SWIGLU;
@@ -682,8 +736,19 @@ __global__ __launch_bounds__(kBatThreads) __attribute__((amdgpu_waves_per_eu(2, 
   }
   lds_barrier();                                      // the B buffers are free: every wave turns its own tiles around in them
   if (filler) return;
+  // the 1/rms of this wave's rows, once, into a table of its own above the computing waves' 16 KB each
+  const float *tab = nullptr;
+  int tab_m0 = 0;
+  if (ksplit == 1 && g.scale_tag) {
+    static_assert((size_t)kWdCompute * (2 * kWdMC * 1024) + kWdCompute * kScaleTab * sizeof(float) <= kBatWideLds, "room for the tables");
+    float *t = reinterpret_cast<float *>(smem + (size_t)kWdCompute * (2 * kWdMC * 1024)) + wave * kScaleTab;
+    const int rpt = g.single ? 16 : 8;
+    tab_m0 = (blk * COLS + mwv * MC) * rpt;
+    for (int i = lane; i < MC * rpt; i += kWave) t[i] = bat_row_scale(g, tab_m0 + i);
+    tab = t;
+  }
   bat_wide_finish_wave<NT, MC>(g, acc, unit_of, reinterpret_cast<float *>(smem + (size_t)wave * (2 * kWdMC * 1024)), blk * COLS + mwv * MC,
-                           lane, swiglu, split, ksplit, part);
+                           lane, swiglu, split, ksplit, part, tab, tab_m0);
 }
 
 // Second half of a split reduction: one wave per (column tile, unit); lane (jm, c2) adds the pair of every
@@ -724,12 +789,16 @@ __global__ __launch_bounds__(256) void bat_split_finish(BatGemm g, int ksplit, c
 // `rows` otherwise.
 __global__ __launch_bounds__(64) void bat_embed(const int32_t *ids, const float *rows, const uint16_t *emb, int vocab, int d,
                                                 int M, int CT, int CTS, const float *gain, float *x, uint16_t *planes,
-                                                float *ssq_out, int single) {
+                                                float *ssq_out, int single, unsigned long long *scale_tag) {
   const int tile = blockIdx.x, tid = threadIdx.x;
   const int c2 = tid & 7, jm = tid >> 3;
   const int col = tile * 16 + 2 * c2;
   const float2 gn = *reinterpret_cast<const float2 *>(gain + col);
   const int n_half = single ? 2 : 1;                          // single-bf16 records: 16 rows per column tile
+  // The step's first launch clears the tagged row scales (BatGemm::scale_tag): a step replayed from a HIP
+  // graph carries the epochs of its capture, and a projection must not take last replay's words for its own.
+  if (blockIdx.x == 0 && blockIdx.y == 0)
+    for (int i = tid; i < CT * 8 * n_half; i += 64) scale_tag[i] = 0ull;
   for (int cth = blockIdx.y; cth < CT * n_half; cth += gridDim.y) {       // the grid's second dimension shares the column tiles
     const int ct = cth / n_half, hh = cth - ct * n_half;
     const int m = single ? ct * 16 + hh * 8 + jm : ct * 8 + jm;
@@ -764,19 +833,6 @@ __global__ __launch_bounds__(64) void bat_embed(const int32_t *ids, const float 
       rec[((jm + 8) * 16 + 2 * c2) / 2] = l0 | (l1 << 16);
     }
   }
-}
-
-// inv_rms[m] = 1/sqrt(mean(x[m]^2) + eps) from the per-tile partial sums [n_tiles][stride] (fixed
-// order: lanes stride over the tiles, butterfly sum).  One wave per row.
-__global__ __launch_bounds__(kBatThreads) void bat_row_scales(const float *ssq, int n_tiles, int rows, int stride, int d,
-                                                             float eps, float *inv_rms) {
-  const int lane = threadIdx.x & 63;
-  const int m = blockIdx.x * kBatWaves + (threadIdx.x >> 6);
-  if (m >= rows) return;
-  float t = 0.f;
-  for (int p = lane; p < n_tiles; p += kWave) t += ssq[(size_t)p * stride + m];
-  t = wave_sum(t);
-  if (lane == 0) inv_rms[m] = rsqrtf(t / (float)d + eps);
 }
 
 }  // namespace heisd

@@ -1,0 +1,76 @@
+"""A verify step captured in a HIP graph and replayed: every replay gives the bits of the eager call.
+
+The step's kernels exchange data through device memory that the launches themselves prepare (flags,
+counters, epoch-tagged row scales whose epochs are kernel arguments and therefore frozen at capture), so a
+replay must not depend on what the previous replay left behind.  The graph is replayed several times with
+different drafts, with eager work and synchronisations of the program's own between the replays, and each
+replay is compared with the eager result for the same drafts (paper Sec. 2.2: one verification pass)."""
+import numpy as np
+import pytest
+
+import oracle
+import synth
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+MID = synth.ModelShape(n_layers=3, d_model=512, n_heads=4, head_dim=128, d_ffn=1376, vocab=2048)
+
+
+@pytest.mark.parametrize("B,K", [(1, 7), (2, 7), (6, 7)])
+def test_graph_replays_give_the_bits_of_the_eager_step(B, K):
+    """7 rows (the <= 8-row kernels, one launch per phase under capture), 14 rows (register-B GEMMs) and
+    42 rows (LDS-shared B, split reductions): the row scales of the last two are handed over inside
+    their launches."""
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    import paper_2603_17573_amd as P
+    from gpu_harness import _bits_to_dev, accept_desc_of
+    wl = synth.Workload("graph_%dx%d" % (B, K), MID, 30, 11, MID.bin_base, batch=B, K=K, draft=("geometric", 0.5), seed=B + 40)
+    weights = synth.make_weights(MID, wl.seed)
+    cap = wl.prefix_len + K + 1
+    k0, v0, f0 = zip(*[synth.make_prefix_kv_direct(wl, e, cap) for e in range(B)])
+    kb, vb = np.stack(k0, axis=1), np.stack(v0, axis=1)
+    dev = "cuda:0"
+    dm = P.DeviceModel(MID, weights)
+    ver = P.Verifier(dm, B, K, cap)
+    acc = accept_desc_of(oracle.AcceptRule(2, 6))
+    kc, vc = _bits_to_dev(kb, dev), _bits_to_dev(vb, dev)
+    plen = torch.full((B,), wl.prefix_len, dtype=torch.int32, device=dev)
+    first = torch.from_numpy(np.asarray(f0, np.int32)).to(dev)
+    rng = np.random.default_rng(7)
+    draft_sets = [torch.from_numpy((MID.bin_base + rng.integers(0, MID.n_bins, size=(B, K))).astype(np.int32)).to(dev)
+                  for _ in range(2)]
+    drafts = draft_sets[0].clone()
+
+    def snapshot(out):
+        torch.cuda.synchronize()
+        assert P.heisd_verify_check(ver.ctx) == 0
+        return {k: v.cpu().numpy().copy() for k, v in out.items()}
+
+    eager = []
+    for d in draft_sets:
+        drafts.copy_(d)
+        eager.append(snapshot(ver.step(kc, vc, plen, first, drafts, acc, None)))
+    assert not np.array_equal(eager[0]["bin_logits"], eager[1]["bin_logits"])
+
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        out = ver.step(kc, vc, plen, first, drafts, acc, None)       # allocates the outputs outside the capture
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        ver.step(kc, vc, plen, first, drafts, acc, None, out=out)
+    for which in (0, 1, 1, 0, 1):
+        drafts.copy_(draft_sets[which])
+        scratch = torch.randn(256, 256, device=dev) @ torch.randn(256, 256, device=dev)      # eager work between replays
+        torch.cuda.synchronize()
+        graph.replay()
+        got = snapshot(out)
+        for k in got:
+            assert np.array_equal(got[k], eager[which][k], equal_nan=True), (k, which)
+        del scratch
+    ver.close()
