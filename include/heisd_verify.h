@@ -398,6 +398,19 @@ int heisd_verify_set_path(heisd_verify_ctx *ctx, int path);
 int heisd_verify_set_activations(heisd_verify_ctx *ctx, int format);
 
 /*
+ * Footprint (App. A.1: the 7B target model is 13 GB of projection weights).  heisd_verify_init copies the
+ * seven projection matrices of every layer (wq, wk, wv, wo, w_gate, w_up, w_down) and the n_bins LM-head rows
+ * into the workspace in the order the matrix cores consume them; after that only HEISD_PATH_GENERIC reads the
+ * caller's originals.  A caller that keeps both holds the model twice.  This call records the caller's promise
+ * that it will not select HEISD_PATH_GENERIC again: from then on the library never dereferences those eight
+ * pointers, the caller may free that memory (tok_emb, attn_norm, ffn_norm and final_norm are still read in place
+ * and must stay alive), and heisd_verify_set_path(ctx, HEISD_PATH_GENERIC) fails with EUNSUPPORTED.  Not
+ * reversible for this context.  Host-side only; enqueues nothing.
+ * Errors: EINVAL (NULL ctx), EUNSUPPORTED (HEISD_PATH_GENERIC is the selected path).
+ */
+int heisd_verify_release_projections(heisd_verify_ctx *ctx);
+
+/*
  * Measurement aid for the persistent kernel (not part of the method): with enable != 0 every later
  * persistent step records device timestamps (100 MHz counter) of every workgroup in every phase of its
  * program, as [phase][workgroup][8]: [0] phase entered, [1] inputs seen (grid barrier passed),

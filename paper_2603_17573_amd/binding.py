@@ -106,6 +106,8 @@ def load():
         lib.heisd_verify_set_handover.restype = ctypes.c_int
         lib.heisd_verify_set_activations.argtypes = [c_void_p, ctypes.c_int]
         lib.heisd_verify_set_activations.restype = ctypes.c_int
+        lib.heisd_verify_release_projections.argtypes = [c_void_p]
+        lib.heisd_verify_release_projections.restype = ctypes.c_int
         lib.heisd_debug_trace.argtypes = [c_void_p, ctypes.c_int, c_void_p, ctypes.c_int]
         lib.heisd_debug_trace.restype = ctypes.c_int
         lib.heisd_last_error.argtypes = [c_void_p]
@@ -228,6 +230,10 @@ def heisd_verify_set_handover(ctx, mode: int) -> int:
 
 
 HEISD_ACT_SPLIT, HEISD_ACT_BF16 = 0, 1
+
+
+def heisd_verify_release_projections(ctx) -> int:
+    return load().heisd_verify_release_projections(ctx)
 
 
 def heisd_verify_set_activations(ctx, fmt: int) -> int:

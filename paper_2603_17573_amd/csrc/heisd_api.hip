@@ -55,6 +55,7 @@ struct heisd_verify_ctx {
   int n_cu = 256;
   int path = 0;                        // HEISD_PATH_*
   bool fast_ok = false;                // the shape fits the fast kernels
+  bool originals_gone = false;         // heisd_verify_release_projections: the caller's projection matrices may be freed
   char err[256];
   // optional per-launch event timing
   bool prof_on = false;
@@ -700,11 +701,23 @@ extern "C" int heisd_verify_set_path(heisd_verify_ctx *ctx, int path) {
   if (path != HEISD_PATH_AUTO && path != HEISD_PATH_GENERIC && path != HEISD_PATH_FAST && path != HEISD_PATH_PERSIST &&
       path != HEISD_PATH_BATCH)
     return fail(ctx, HEISD_EINVAL, "set_path: unknown path %d", path);
+  if (path == HEISD_PATH_GENERIC && ctx->originals_gone)
+    return fail(ctx, HEISD_EUNSUPPORTED, "set_path: the projection matrices were released (heisd_verify_release_projections)");
   if (path == HEISD_PATH_FAST && !ctx->fast_ok)
     return fail(ctx, HEISD_EUNSUPPORTED, "set_path: model shape outside the fast kernels");
   if (path == HEISD_PATH_PERSIST && !ctx->persist_ok)
     return fail(ctx, HEISD_EUNSUPPORTED, "set_path: the persistent kernel does not fit this device or shape");
   ctx->path = path;
+  return HEISD_OK;
+}
+
+extern "C" int heisd_verify_release_projections(heisd_verify_ctx *ctx) {
+  if (!ctx) return HEISD_EINVAL;
+  if (ctx->path == HEISD_PATH_GENERIC)
+    return fail(ctx, HEISD_EUNSUPPORTED, "release_projections: HEISD_PATH_GENERIC is selected and reads them");
+  ctx->originals_gone = true;
+  for (auto *v : {&ctx->wq, &ctx->wk, &ctx->wv, &ctx->wo, &ctx->w_gate, &ctx->w_up, &ctx->w_down}) v->assign(v->size(), nullptr);
+  ctx->d.lm_head = nullptr;
   return HEISD_OK;
 }
 

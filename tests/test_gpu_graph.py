@@ -74,3 +74,51 @@ def test_graph_replays_give_the_bits_of_the_eager_step(B, K):
             assert np.array_equal(got[k], eager[which][k], equal_nan=True), (k, which)
         del scratch
     ver.close()
+
+
+@pytest.mark.parametrize("B,K,path", [(1, 7, 0), (1, 7, 2), (2, 7, 0), (6, 7, 4)])
+def test_released_projection_matrices_are_never_read(B, K, path):
+    """After heisd_verify_release_projections the caller's wq .. w_down and lm_head may be freed: here their
+    memory is overwritten with NaN patterns instead, and the step still gives the bits it gave before; the
+    generic path, which reads them in place, can no longer be selected."""
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    import paper_2603_17573_amd as P
+    from gpu_harness import _bits_to_dev, accept_desc_of
+    wl = synth.Workload("rel_%dx%d" % (B, K), MID, 30, 11, MID.bin_base, batch=B, K=K, draft=("geometric", 0.5), seed=B + 60)
+    weights = synth.make_weights(MID, wl.seed)
+    cap = wl.prefix_len + K
+    k0, v0, f0 = zip(*[synth.make_prefix_kv_direct(wl, e, cap) for e in range(B)])
+    kb, vb = np.stack(k0, axis=1), np.stack(v0, axis=1)
+    dev = "cuda:0"
+    dm = P.DeviceModel(MID, weights)
+    ver = P.Verifier(dm, B, K, cap)
+    assert P.heisd_verify_set_path(ver.ctx, path) == 0
+    acc = accept_desc_of(oracle.AcceptRule(2, 6))
+    plen = torch.full((B,), wl.prefix_len, dtype=torch.int32, device=dev)
+    first = torch.from_numpy(np.asarray(f0, np.int32)).to(dev)
+    drafts = torch.from_numpy((MID.bin_base + synth.make_drafts_uniform(wl)).astype(np.int32)).to(dev)
+
+    def run():
+        kc, vc = _bits_to_dev(kb, dev), _bits_to_dev(vb, dev)
+        out = ver.step(kc, vc, plen, first, drafts, acc, None)
+        torch.cuda.synchronize()
+        assert P.heisd_verify_check(ver.ctx) == 0
+        return {k: v.cpu().numpy().copy() for k, v in out.items()}
+
+    before = run()
+    assert P.heisd_verify_set_path(ver.ctx, P.HEISD_PATH_GENERIC) == 0
+    assert P.heisd_verify_release_projections(ver.ctx) == P.HEISD_EUNSUPPORTED      # the selected path reads them
+    assert P.heisd_verify_set_path(ver.ctx, path) == 0
+    assert P.heisd_verify_release_projections(ver.ctx) == 0
+    assert P.heisd_verify_set_path(ver.ctx, P.HEISD_PATH_GENERIC) == P.HEISD_EUNSUPPORTED
+    for name in ("wq", "wk", "wv", "wo", "w_gate", "w_up", "w_down"):
+        for w in dm.t[name]:
+            w.view(torch.int16).fill_(0x7FC1)                  # a NaN in every bf16
+    dm.t["lm_head"].view(torch.int16).fill_(0x7FC1)
+    torch.cuda.synchronize()
+    after = run()
+    for k in before:
+        assert np.array_equal(before[k], after[k], equal_nan=True), k
+    assert np.all(np.isfinite(after["bin_logits"]))
+    ver.close()
