@@ -168,9 +168,7 @@ __device__ __forceinline__ void bat_emit_apply(const BatGemm &g, int unit, int c
       *reinterpret_cast<float2 *>(g.out + (size_t)m * g.ldo + unit * 16 + i) = make_float2(a0, a1);
     }
     float q = a0 * a0 + a1 * a1;          // over the tile's 16 columns: 8 adjacent lanes
-    q += __shfl_xor(q, 4, kWave);
-    q += __shfl_xor(q, 2, kWave);
-    q += __shfl_xor(q, 1, kWave);
+    q = sum8(q);
     if (c2 == 0) g.ssq_out[(size_t)unit * (g.CTS * 8) + m] = q;
     a0 *= pre.gn.x;
     a1 *= pre.gn.y;
@@ -818,9 +816,7 @@ __global__ __launch_bounds__(64) void bat_embed(const int32_t *ids, const float 
       *reinterpret_cast<float2 *>(x + (size_t)m * d + col) = make_float2(v0, v1);
     }
     float q = v0 * v0 + v1 * v1;
-    q += __shfl_xor(q, 4, kWave);
-    q += __shfl_xor(q, 2, kWave);
-    q += __shfl_xor(q, 1, kWave);
+    q = sum8(q);
     if (c2 == 0) ssq_out[(size_t)tile * (CTS * 8) + m] = q;
     uint32_t h0, l0, h1, l1;
     split_bf16(v0 * gn.x, h0, l0);

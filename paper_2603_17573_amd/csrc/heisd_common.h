@@ -81,16 +81,49 @@ __device__ __forceinline__ bool episode_sits_out(const uint8_t *skip, const int3
 }
 constexpr unsigned kErrBarrier = 1u, kErrOverflow = 2u;      // bits of the device error word
 
-__device__ __forceinline__ float wave_sum(float v) {
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, kWave);
+// Lane exchanges inside a row of 16 lanes run in the vector ALU (DPP operand modifiers, a few cycles each);
+// a general lane exchange goes through the LDS crossbar and costs an LDS round trip, and a butterfly of six
+// of them is a chain of six such round trips - most of the time of a wave-wide sum.  CTRL: quad_perm
+// selectors (0x00-0xFF), 0x140 row_mirror (lane i <-> 15 - i), 0x141 row_half_mirror (i <-> 7 - i).
+template <int CTRL>
+__device__ __forceinline__ float dpp_move(float v) {
+  return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xf, 0xf, true));
+}
+constexpr int kDppXor1 = 0xB1;           // quad_perm [1,0,3,2]
+constexpr int kDppXor2 = 0x4E;           // quad_perm [2,3,0,1]
+constexpr int kDppNext = 0xF5;           // quad_perm [1,1,3,3]: an even lane reads its odd neighbour
+constexpr int kDppHalfMirror = 0x141, kDppMirror = 0x140;
+
+// Sum over each aligned group of 8 (16) adjacent lanes, in every lane of the group.  After the two quad
+// steps the four lanes of a quad hold the same value, so a mirror delivers the other quad's (half's) sum.
+__device__ __forceinline__ float sum8(float v) {
+  v += dpp_move<kDppXor1>(v);
+  v += dpp_move<kDppXor2>(v);
+  v += dpp_move<kDppHalfMirror>(v);
   return v;
+}
+__device__ __forceinline__ float sum16(float v) {
+  v = sum8(v);
+  v += dpp_move<kDppMirror>(v);
+  return v;
+}
+__device__ __forceinline__ float lane_value(float v, int lane) {
+  return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), lane));
+}
+
+// Sum (maximum) over the wave, the same value in every lane: the four rows of 16, then the rows' results
+// through scalar registers, in a fixed order.
+__device__ __forceinline__ float wave_sum(float v) {
+  v = sum16(v);
+  return (lane_value(v, 0) + lane_value(v, 16)) + (lane_value(v, 32) + lane_value(v, 48));
 }
 
 __device__ __forceinline__ float wave_max(float v) {
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, kWave));
-  return v;
+  v = fmaxf(v, dpp_move<kDppXor1>(v));
+  v = fmaxf(v, dpp_move<kDppXor2>(v));
+  v = fmaxf(v, dpp_move<kDppHalfMirror>(v));
+  v = fmaxf(v, dpp_move<kDppMirror>(v));
+  return fmaxf(fmaxf(lane_value(v, 0), lane_value(v, 16)), fmaxf(lane_value(v, 32), lane_value(v, 48)));
 }
 
 }  // namespace heisd

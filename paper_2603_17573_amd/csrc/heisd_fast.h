@@ -297,9 +297,7 @@ __device__ __forceinline__ void fast_epilogue(const FastGemm &g, int wg, int nwg
           *reinterpret_cast<float2 *>(xp) = make_float2(a0, a1);
         }
         float q = a0 * a0 + a1 * a1;       // sum over the tile's 16 columns: 8 adjacent lanes
-        q += __shfl_xor(q, 4, kWave);
-        q += __shfl_xor(q, 2, kWave);
-        q += __shfl_xor(q, 1, kWave);
+        q = sum8(q);
         if (c2 == 0) st_dev(g.ssq_out + (size_t)unit * kSsqStride + jm, q);
         a0 *= pre.gn.x;
         a1 *= pre.gn.y;
@@ -443,9 +441,7 @@ __device__ __forceinline__ void fast_embed_tile(const int32_t *ids, const uint16
     *reinterpret_cast<float2 *>(x + (size_t)m * d + col) = make_float2(v0, v1);
   }
   float q = v0 * v0 + v1 * v1;
-  q += __shfl_xor(q, 4, kWave);
-  q += __shfl_xor(q, 2, kWave);
-  q += __shfl_xor(q, 1, kWave);
+  q = sum8(q);
   if (c2 == 0) st_dev(ssq_out + (size_t)tile * kSsqStride + m, q);
   const float2 gn = *reinterpret_cast<const float2 *>(gain + col);
   uint32_t h0, l0, h1, l1;
@@ -613,8 +609,7 @@ __device__ __forceinline__ void fast_attn_unit(const FastAttn &a, int b, int h, 
     float t = 0.f;
 #pragma unroll
     for (int i = 0; i < 8; ++i) t = fmaf(qf[i], kf[i], t);
-#pragma unroll
-    for (int off = LPK / 2; off > 0; off >>= 1) t += __shfl_xor(t, off, kWave);
+    t = LPK == 16 ? sum16(t) : sum8(t);
     if (li == 0) sc[r] = t;
   };
   // ---- pass 1: scores of the prefix keys on the matrix cores, then of the block's keys 0..jq with FMAs ----
@@ -635,7 +630,7 @@ __device__ __forceinline__ void fast_attn_unit(const FastAttn &a, int b, int h, 
     auto emit = [&](int tile, const f32x4 acc) {
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
-        const float t = acc[i] + __shfl_down(acc[i], 1, kWave);
+        const float t = acc[i] + dpp_move<kDppNext>(acc[i]);
         const int r = 16 * tile + 4 * lg + i;
         if (lr == 0 && r < P) sc[r] = t;
       }
