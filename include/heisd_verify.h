@@ -371,9 +371,12 @@ int heisd_verify_profile_read(heisd_verify_ctx *ctx, double *ms, int64_t *launch
  *
  * The persistent kernel spins at its grid barriers with a bound; if the bound expires (the
  * GPU was shared with work that kept some of its workgroups from running) it raises a bit of the
- * context's device error word and ends; its outputs are then undefined.  An episode whose new rows did
+ * context's device error word and ends; its outputs are then undefined.  The path for more than 8 rows has
+ * one bounded wait of the same kind: the epilogues of a projection of a normalised input take each row's
+ * 1/rms from a word the first workgroups of the same launch compute, and a word that never arrives raises
+ * the same bit (the row's outputs are then zero).  An episode whose new rows did
  * not fit its cache raises another bit (see heisd_kv_desc).  heisd_verify_check synchronises the
- * device, clears the word and returns EHIP for an expired barrier, EINVAL for an episode that did
+ * device, clears the word and returns EHIP for an expired wait, EINVAL for an episode that did
  * not fit, else OK (heisd_last_error says which).
  */
 #define HEISD_PATH_AUTO 0
