@@ -428,6 +428,17 @@ int heisd_verify_release_projections(heisd_verify_ctx *ctx);
 int heisd_debug_trace(heisd_verify_ctx *ctx, int enable, unsigned long long *out, int max_entries);
 
 /*
+ * Test aid: the bounds of the waits inside the kernels (see heisd_verify_check), so that a test can make them
+ * give up while every kernel still runs to its end.  grid_polls: polls a workgroup of the persistent kernel makes at
+ * a grid barrier before it raises the error word and leaves (<= 0: the default, about 4 million); scale_polls: polls an
+ * epilogue of the path for more than 8 rows makes for a row's 1/rms word (<= 0: the default, about 1 million);
+ * skip_scales != 0: those launches do not produce the words at all, so every such epilogue gives up.  After a step
+ * that gave up, heisd_verify_check returns EHIP and the step's outputs are undefined; with the defaults restored the
+ * next step is unaffected.  Host-side only.  Errors: EINVAL (NULL ctx).
+ */
+int heisd_debug_set_wait_limits(heisd_verify_ctx *ctx, int grid_polls, int scale_polls, int skip_scales);
+
+/*
  * Measurement aid for the persistent kernel: what a phase requests across the grid barrier that ends it.
  *   0 (default)  the whole first weight tile of the next GEMM phase (16 k-steps of every wave: 128 KB per
  *                workgroup) is handed over through LDS, started as soon as the phase's own stores have been

@@ -9,7 +9,7 @@ from .binding import (heisd_model_desc, heisd_kv_desc, heisd_accept_desc, heisd_
                       heisd_build_sequence_tree, heisd_prefill_chunk, heisd_export_features,
                       heisd_feature_similarity, heisd_skip_offline, heisd_skip_decide,
                       heisd_retrieve_workspace_bytes, heisd_retrieve_topk, heisd_retrieve_static_bytes,
-                      heisd_retrieve_topk_static, heisd_debug_trace, heisd_verify_set_handover, heisd_verify_set_activations, heisd_verify_release_projections, HEISD_ACT_SPLIT, HEISD_ACT_BF16, heisd_measure_read,
+                      heisd_retrieve_topk_static, heisd_debug_trace, heisd_verify_set_handover, heisd_verify_set_activations, heisd_verify_release_projections, heisd_debug_set_wait_limits, HEISD_ACT_SPLIT, HEISD_ACT_BF16, heisd_measure_read,
                       heisd_measure_empty_launch, heisd_free, heisd_last_error,
                       heisd_verify_profile_enable, heisd_verify_profile_read, KERNEL_CLASSES,
                       heisd_verify_set_path, heisd_verify_check, HEISD_PATH_AUTO, HEISD_PATH_GENERIC, HEISD_PATH_FAST,

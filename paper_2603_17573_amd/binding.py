@@ -106,6 +106,8 @@ def load():
         lib.heisd_verify_set_handover.restype = ctypes.c_int
         lib.heisd_verify_set_activations.argtypes = [c_void_p, ctypes.c_int]
         lib.heisd_verify_set_activations.restype = ctypes.c_int
+        lib.heisd_debug_set_wait_limits.argtypes = [c_void_p, ctypes.c_int, ctypes.c_int, ctypes.c_int]
+        lib.heisd_debug_set_wait_limits.restype = ctypes.c_int
         lib.heisd_verify_release_projections.argtypes = [c_void_p]
         lib.heisd_verify_release_projections.restype = ctypes.c_int
         lib.heisd_debug_trace.argtypes = [c_void_p, ctypes.c_int, c_void_p, ctypes.c_int]
@@ -230,6 +232,10 @@ def heisd_verify_set_handover(ctx, mode: int) -> int:
 
 
 HEISD_ACT_SPLIT, HEISD_ACT_BF16 = 0, 1
+
+
+def heisd_debug_set_wait_limits(ctx, grid_polls: int, scale_polls: int, skip_scales: int) -> int:
+    return load().heisd_debug_set_wait_limits(ctx, grid_polls, scale_polls, skip_scales)
 
 
 def heisd_verify_release_projections(ctx) -> int:

@@ -48,6 +48,8 @@ struct heisd_verify_ctx {
   int *attn_prod = nullptr;            // persistent kernel: [n_heads][3 * head_dim / 16] producer workgroups of a head's q/k/v
   int qkv_xcd_heads = 0;               // persistent kernel: QKV tiles dealt so that a head is produced on the XCD that consumes it
   int act_bf16 = 0;                    // batch path from kActBf16MinRows rows: activations enter the GEMMs as one bf16 each (opt-in)
+  int wait_limit = kSpinLimit, scale_spin = kScaleSpin;   // bounds of the in-kernel waits (heisd_debug_set_wait_limits)
+  bool skip_scales = false;
   unsigned scale_epoch = 0;            // batch path: epoch of the last projection of a normalised input (see BatGemm::scale_tag)
   int handover_mode = 0;               // persistent kernel: what crosses a grid barrier (see persist_build_program)
   unsigned long long *trace = nullptr; // device buffer [n_phases][8] when tracing is on
@@ -583,6 +585,7 @@ static void persist_launch(heisd_verify_ctx *ctx, const heisd_kv_desc *kv, const
   p.flags = ctx->flags; p.err = ctx->dev_err;
   p.trace = ctx->trace_on ? ctx->trace : nullptr;
   p.attn_prod = ctx->attn_prod; p.n_prod = 3 * d.head_dim / 16;
+  p.spin_limit = ctx->wait_limit;
   p.acc = accept;
   p.epoch0 = ctx->epoch;
   ctx->epoch += persist_epochs(ctx->n_phases);
@@ -769,10 +772,24 @@ extern "C" int heisd_verify_check(heisd_verify_ctx *ctx) {
     return fail(ctx, HEISD_EHIP, "check: device error");
   if (w != 0) {
     (void)hipMemset(ctx->dev_err, 0, sizeof(w));
-    if (w & kErrBarrier) return fail(ctx, HEISD_EHIP, "check: a grid barrier of the persistent kernel timed out");
+    if (w & kErrBarrier)
+      return fail(ctx, HEISD_EHIP, "check: a bounded wait inside a launch gave up (a grid barrier of the persistent kernel, or a row scale "
+                  "of the path for more than 8 rows)");
     return fail(ctx, HEISD_EINVAL, "check: an episode's new rows did not fit its cache (prefix_len + rows > kv_capacity, or "
                 "a negative prefix_len): it was left unverified, its cache untouched, its accepted_len / next_bin -1");
   }
+  return HEISD_OK;
+}
+
+// Test aid: the bounds of the waits inside the kernels, so that their give-up paths can be exercised with every
+// kernel still running to its end.  grid_polls: polls of a grid barrier of the persistent kernel (<= 0: the
+// default); scale_polls: polls for a row's 1/rms word (<= 0: the default); skip_scales != 0: the launches of the
+// path for more than 8 rows do not produce those words, so every epilogue gives up after scale_polls polls.
+extern "C" int heisd_debug_set_wait_limits(heisd_verify_ctx *ctx, int grid_polls, int scale_polls, int skip_scales) {
+  if (!ctx) return HEISD_EINVAL;
+  ctx->wait_limit = grid_polls > 0 ? grid_polls : kSpinLimit;
+  ctx->scale_spin = scale_polls > 0 ? scale_polls : kScaleSpin;
+  ctx->skip_scales = skip_scales != 0;
   return HEISD_OK;
 }
 
@@ -1070,6 +1087,7 @@ static void batch_forward(heisd_verify_ctx *ctx, const heisd_kv_desc *kv, const 
     g.scale_tag = reinterpret_cast<unsigned long long *>(ctx->bscr + bs.inv_rms);
     if (++ctx->scale_epoch == 0u) ctx->scale_epoch = 1u;
     g.scale_epoch = ctx->scale_epoch; g.err = ctx->dev_err;
+    g.scale_spin = ctx->scale_spin; g.scale_skip = ctx->skip_scales ? 1 : 0;
   };
   {
     ProfScope ps(ctx, HEISD_KC_EMBED, st, prof);

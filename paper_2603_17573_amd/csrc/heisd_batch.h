@@ -45,6 +45,8 @@ struct BatGemm {
   unsigned long long *scale_tag;   // [CTS*8] low word: bits of 1/rms of the row, high word: epoch of the launch that wrote it
   unsigned scale_epoch;   // this launch's epoch (unique per consuming projection; never 0)
   unsigned *err;          // device error word (a scale that never arrives raises kErrBarrier)
+  int scale_spin;         // polls an epilogue makes for a row's word before it gives up (kScaleSpin unless a test lowers it)
+  int scale_skip;         // != 0 (tests of the give-up path only): the launch does not produce the words
   float *out;             // STORE_ROWS: [M][ldo]; RESID_NORM: residual stream x [M][ldo], updated in place
   int ldo;
   const float *next_gain; // RESID_NORM: gain of the norm that consumes x next
@@ -66,7 +68,7 @@ struct BatGemm {
 // for a finishing launch produces the scales for that launch (same epoch, already there when it starts).
 constexpr int kScaleSpin = 1 << 20;
 __device__ __forceinline__ void bat_scales_produce(const BatGemm &g) {
-  if (!g.scale_tag) return;
+  if (!g.scale_tag || g.scale_skip) return;
   const int rows = g.CT * (g.single ? 16 : 8), stride = g.CTS * 8;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nw = blockDim.x >> 6;
   int m = blockIdx.x * nw + wave;
@@ -84,7 +86,7 @@ __device__ __forceinline__ void bat_scales_produce(const BatGemm &g) {
 __device__ __forceinline__ float bat_row_scale(const BatGemm &g, int m) {
   if (!g.scale_tag) return 1.0f;
   if (m >= g.CT * (g.single ? 16 : 8)) return 0.f;
-  for (int spin = 0; spin < kScaleSpin; ++spin) {
+  for (int spin = 0; spin < g.scale_spin; ++spin) {
     const unsigned long long v = __hip_atomic_load(g.scale_tag + m, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     if ((unsigned)(v >> 32) == g.scale_epoch) return __uint_as_float((unsigned)v);
     __builtin_amdgcn_s_sleep(4);

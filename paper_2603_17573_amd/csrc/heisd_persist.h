@@ -87,6 +87,7 @@ struct PersistArgs {
   unsigned long long *trace;             // optional [n_phases][workgroups][8] timestamps (measurement aid)
   const int *attn_prod;                  // [H][n_prod]: the workgroups that produce head h's q/k/v in a QKV phase
   int n_prod;                            // 3 * head_dim / 16 (at most 64)
+  int spin_limit;                        // polls a grid wait makes before it gives up (kSpinLimit unless a test lowers it)
   AcceptArgs acc;                        // greedy bins + acceptance scan of the step (paper Sec. 4.2), run by workgroups 0 .. batch-1
 };
 
@@ -208,7 +209,7 @@ __device__ __forceinline__ bool grid_wait(const PersistArgs &p, int nwg, unsigne
       }
       if (__all(ok)) break;
       __builtin_amdgcn_s_sleep(8);      // 256 pollers at full rate slow the loads they wait for (1 % of the step)
-      if (++spins > kSpinLimit ||
+      if (++spins > p.spin_limit ||
           ((spins & 255) == 0 && (__hip_atomic_load(p.err, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) & kErrBarrier) != 0u)) {
         good = false;
         break;
@@ -659,7 +660,10 @@ __global__ __launch_bounds__(kFastThreads) void persist_forward(PersistArgs p) {
                         P->g.ssq_out, p2_tid());
       grid_arrive(p, wg, wait_epoch + 1, true);
     }
-    if (!ok) return;
+    if (!ok) {                 // a wait gave up: nothing of this workgroup's may still be on its way into LDS when it ends
+      wait_vmcnt_all();
+      return;
+    }
     p2_stamp(p, wg, ph, 3);
   }
   // Greedy bins and the acceptance scan: workgroup b judges episode b once every workgroup has published its

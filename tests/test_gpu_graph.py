@@ -122,3 +122,48 @@ def test_released_projection_matrices_are_never_read(B, K, path):
         assert np.array_equal(before[k], after[k], equal_nan=True), k
     assert np.all(np.isfinite(after["bin_logits"]))
     ver.close()
+
+
+@pytest.mark.parametrize("B,K,path", [(1, 7, 3), (6, 7, 4)])
+def test_waits_inside_the_kernels_give_up_and_the_next_step_is_unaffected(B, K, path):
+    """The bounded waits inside the kernels - the grid barriers of the persistent kernel (path 3), the row scales
+    handed over inside a launch on the path for more than 8 rows (path 4) - are made to give up from the host
+    (one poll per barrier; scales never produced and eight polls for each): every kernel runs to its end,
+    heisd_verify_check reports EHIP, and with the defaults restored the next step gives the bits of the step
+    before."""
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    import paper_2603_17573_amd as P
+    from gpu_harness import _bits_to_dev, accept_desc_of
+    wl = synth.Workload("giveup_%dx%d" % (B, K), MID, 30, 11, MID.bin_base, batch=B, K=K, draft=("geometric", 0.5), seed=B + 80)
+    weights = synth.make_weights(MID, wl.seed)
+    cap = wl.prefix_len + K
+    k0, v0, f0 = zip(*[synth.make_prefix_kv_direct(wl, e, cap) for e in range(B)])
+    kb, vb = np.stack(k0, axis=1), np.stack(v0, axis=1)
+    dev = "cuda:0"
+    dm = P.DeviceModel(MID, weights)
+    ver = P.Verifier(dm, B, K, cap)
+    assert P.heisd_verify_set_path(ver.ctx, path) == 0
+    acc = accept_desc_of(oracle.AcceptRule(2, 6))
+    plen = torch.full((B,), wl.prefix_len, dtype=torch.int32, device=dev)
+    first = torch.from_numpy(np.asarray(f0, np.int32)).to(dev)
+    drafts = torch.from_numpy((MID.bin_base + synth.make_drafts_uniform(wl)).astype(np.int32)).to(dev)
+
+    def run():
+        kc, vc = _bits_to_dev(kb, dev), _bits_to_dev(vb, dev)
+        out = ver.step(kc, vc, plen, first, drafts, acc, None)
+        torch.cuda.synchronize()
+        return {k: v.cpu().numpy().copy() for k, v in out.items()}
+
+    before = run()
+    assert P.heisd_verify_check(ver.ctx) == 0
+    assert P.heisd_debug_set_wait_limits(ver.ctx, 1, 8, 1) == 0
+    run()
+    assert P.heisd_verify_check(ver.ctx) == P.HEISD_EHIP
+    assert P.heisd_verify_check(ver.ctx) == 0                      # the word is cleared by the check that reports it
+    assert P.heisd_debug_set_wait_limits(ver.ctx, 0, 0, 0) == 0
+    after = run()
+    assert P.heisd_verify_check(ver.ctx) == 0
+    for k in before:
+        assert np.array_equal(before[k], after[k], equal_nan=True), k
+    ver.close()
