@@ -50,6 +50,8 @@ struct heisd_verify_ctx {
   int act_bf16 = 0;                    // batch path from kActBf16MinRows rows: activations enter the GEMMs as one bf16 each (opt-in)
   int wait_limit = kSpinLimit, scale_spin = kScaleSpin;   // bounds of the in-kernel waits (heisd_debug_set_wait_limits)
   bool skip_scales = false;
+  unsigned *sflags = nullptr;          // persistent kernel: barrier flags in uncached memory (flag_slot_acquire), or nullptr
+  int sflag_slot = -1, sflag_dev = -1;
   unsigned scale_epoch = 0;            // batch path: epoch of the last projection of a normalised input (see BatGemm::scale_tag)
   int handover_mode = 0;               // persistent kernel: what crosses a grid barrier (see persist_build_program)
   unsigned long long *trace = nullptr; // device buffer [n_phases][8] when tracing is on
@@ -490,6 +492,51 @@ static void fast_forward(heisd_verify_ctx *ctx, const heisd_kv_desc *kv, const i
 
 // ---- persistent whole-step kernel ----------------------------------------------------------
 
+// Barrier flags that scalar loads can poll: one allocation of uncached device memory per device, made on first
+// use, cut into slots of 8 KB (1024 flags + spare), handed to contexts at init and taken back at heisd_free.  The
+// allocation itself is never freed (memory of this kind that a kernel has read must outlive the process's
+// other allocations).  A context that gets no slot keeps its flags in the workspace and polls them with vector
+// loads.
+constexpr int kFlagSlots = 32, kFlagDevices = 16;
+constexpr size_t kFlagSlotBytes = 8192;
+struct FlagPool {
+  unsigned char *base = nullptr;
+  bool tried = false;
+  uint32_t used = 0;
+};
+static FlagPool g_flag_pool[kFlagDevices];
+static std::mutex g_flag_mutex;
+
+static unsigned *flag_slot_acquire(int dev, int *slot) {
+  std::lock_guard<std::mutex> lock(g_flag_mutex);
+  *slot = -1;
+  if (dev < 0 || dev >= kFlagDevices) return nullptr;
+  FlagPool &pool = g_flag_pool[dev];
+  if (!pool.tried) {
+    pool.tried = true;
+    void *p = nullptr;
+    if (hipExtMallocWithFlags(&p, kFlagSlots * kFlagSlotBytes, hipDeviceMallocUncached) == hipSuccess) pool.base = static_cast<unsigned char *>(p);
+    else (void)hipGetLastError();
+  }
+  if (!pool.base) return nullptr;
+  for (int s = 0; s < kFlagSlots; ++s)
+    if (!(pool.used & (1u << s))) {
+      unsigned char *q = pool.base + (size_t)s * kFlagSlotBytes;
+      if (hipMemset(q, 0, kFlagSlotBytes) != hipSuccess) {
+        (void)hipGetLastError();
+        return nullptr;
+      }
+      pool.used |= 1u << s;
+      *slot = s;
+      return reinterpret_cast<unsigned *>(q);
+    }
+  return nullptr;
+}
+static void flag_slot_release(int dev, int slot) {
+  std::lock_guard<std::mutex> lock(g_flag_mutex);
+  if (dev >= 0 && dev < kFlagDevices && slot >= 0 && slot < kFlagSlots) g_flag_pool[dev].used &= ~(1u << slot);
+}
+
 static const void *persist_pick(const heisd_verify_ctx *c) {
   return c->d.head_dim == 128 ? reinterpret_cast<const void *>(&persist_forward<128>)
                               : reinterpret_cast<const void *>(&persist_forward<64>);
@@ -586,6 +633,7 @@ static void persist_launch(heisd_verify_ctx *ctx, const heisd_kv_desc *kv, const
   p.trace = ctx->trace_on ? ctx->trace : nullptr;
   p.attn_prod = ctx->attn_prod; p.n_prod = 3 * d.head_dim / 16;
   p.spin_limit = ctx->wait_limit;
+  if (ctx->sflags) p.flags = ctx->sflags;
   p.acc = accept;
   p.epoch0 = ctx->epoch;
   ctx->epoch += persist_epochs(ctx->n_phases);
@@ -683,6 +731,13 @@ extern "C" int heisd_verify_init(const heisd_model_desc *desc, heisd_verify_ctx 
   if (e == hipSuccess) e = fast_prepare(desc->head_dim, desc->kv_capacity);
   if (e == hipSuccess) e = persist_prepare(c);
   if (e == hipSuccess && c->persist_ok) e = persist_build_program(c);
+  if (e == hipSuccess && c->persist_ok && c->n_cu == 256) {
+    int dev = 0;
+    if (hipGetDevice(&dev) == hipSuccess) {
+      c->sflags = flag_slot_acquire(dev, &c->sflag_slot);
+      c->sflag_dev = dev;
+    }
+  }
   if (e == hipSuccess) e = bat_prepare();
   if (e == hipSuccess) e = gemm_prepare_mc<1>();
   if (e == hipSuccess) e = gemm_prepare_mc<2>();
@@ -691,6 +746,7 @@ extern "C" int heisd_verify_init(const heisd_model_desc *desc, heisd_verify_ctx 
   if (e == hipSuccess) e = attn_prepare(desc->head_dim, desc->kv_capacity);
   if (e != hipSuccess) {
     const int rc = fail(nullptr, HEISD_EHIP, "init: %s", hipGetErrorString(e));
+    if (c->sflags) flag_slot_release(c->sflag_dev, c->sflag_slot);
     delete c;
     return rc;
   }
@@ -840,6 +896,10 @@ extern "C" int heisd_verify_profile_read(heisd_verify_ctx *ctx, double *ms, int6
 extern "C" void heisd_free(heisd_verify_ctx *ctx) {
   if (!ctx) return;
   for (hipEvent_t e : ctx->ev) (void)hipEventDestroy(e);
+  if (ctx->sflags) {
+    (void)hipDeviceSynchronize();      // the slot goes to another context only when nothing of this one runs any more
+    flag_slot_release(ctx->sflag_dev, ctx->sflag_slot);
+  }
   delete ctx;
 }
 
