@@ -33,7 +33,7 @@ constexpr int kSpinLimit = 1 << 22;
 
 constexpr int kPF = kKS;                 // k-steps of a wave's first weight tile handed over through LDS: a whole ring
 constexpr int kPfBefore = 12;            // of those, handed over BEFORE the barrier; the rest follows when the barrier is passed (16 / 12 / 8 / 4
-                                         // before it: 2.905 / 2.887 / 2.914 / 3.030 ms per step at the 7B shape)
+                                         // before it: 2.905 / 2.887 / 2.914 / 3.030 ms per step at the 7B shape; with the flags in uncached memory 16 / 12 / 8: 2.798 / 2.776 / 2.827 ms)
 constexpr int kPfWave0 = 6;              // waves kPfWave0 .. 7 issue the transfers (they never store in a GEMM epilogue)
 // LDS map.  The hand-over region (128 KB) and the reduction buffer share their bytes: a phase reads what was
 // handed over into registers when it starts and reduces through the same bytes when it ends, and the next
