@@ -1,10 +1,13 @@
-"""A verify step captured in a HIP graph and replayed: every replay gives the bits of the eager call.
+"""Properties of the library's run-time behaviour on the GPU, beyond what one step computes (paper Sec. 2.2: one
+verification pass per step): a step captured in a HIP graph replays to the bits of the eager call; the caller's
+projection matrices are never read once released; the bounded waits inside the kernels give up cleanly and the
+next step is unaffected; a context without a slot of uncached barrier flags still runs the persistent kernel.
 
-The step's kernels exchange data through device memory that the launches themselves prepare (flags,
+A captured step: the kernels exchange data through device memory that the launches themselves prepare (flags,
 counters, epoch-tagged row scales whose epochs are kernel arguments and therefore frozen at capture), so a
 replay must not depend on what the previous replay left behind.  The graph is replayed several times with
 different drafts, with eager work and synchronisations of the program's own between the replays, and each
-replay is compared with the eager result for the same drafts (paper Sec. 2.2: one verification pass)."""
+replay is compared with the eager result for the same drafts."""
 import numpy as np
 import pytest
 
@@ -167,3 +170,49 @@ def test_waits_inside_the_kernels_give_up_and_the_next_step_is_unaffected(B, K, 
     for k in before:
         assert np.array_equal(before[k], after[k], equal_nan=True), k
     ver.close()
+
+
+def test_context_without_a_slot_of_uncached_flags_still_runs_the_persistent_kernel():
+    """The persistent kernel's barrier flags live in a slot of a small per-device pool of uncached memory (32 slots);
+    a context that gets none keeps its flags in the workspace.  40 contexts alive at once: the last ones are
+    without a slot, and their persistent-kernel steps give the bits of the first context's."""
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    import paper_2603_17573_amd as P
+    from gpu_harness import _bits_to_dev, accept_desc_of
+    sh = synth.ModelShape(n_layers=2, d_model=256, n_heads=4, head_dim=64, d_ffn=688, vocab=1024)
+    B, K = 1, 7
+    wl = synth.Workload("slots", sh, 20, 9, sh.bin_base, batch=B, K=K, draft=("geometric", 0.5), seed=91)
+    weights = synth.make_weights(sh, wl.seed)
+    cap = wl.prefix_len + K
+    k0, v0, f0 = zip(*[synth.make_prefix_kv_direct(wl, e, cap) for e in range(B)])
+    kb, vb = np.stack(k0, axis=1), np.stack(v0, axis=1)
+    dev = "cuda:0"
+    dm = P.DeviceModel(sh, weights)
+    vers = [P.Verifier(dm, B, K, cap) for _ in range(40)]
+    acc = accept_desc_of(oracle.AcceptRule(2, 6))
+    plen = torch.full((B,), wl.prefix_len, dtype=torch.int32, device=dev)
+    first = torch.from_numpy(np.asarray(f0, np.int32)).to(dev)
+    drafts = torch.from_numpy((sh.bin_base + synth.make_drafts_uniform(wl)).astype(np.int32)).to(dev)
+    outs = []
+    for ver in (vers[0], vers[35], vers[39]):
+        assert P.heisd_verify_set_path(ver.ctx, P.HEISD_PATH_PERSIST) == 0
+        kc, vc = _bits_to_dev(kb, dev), _bits_to_dev(vb, dev)
+        out = ver.step(kc, vc, plen, first, drafts, acc, None)
+        torch.cuda.synchronize()
+        assert P.heisd_verify_check(ver.ctx) == 0
+        outs.append({k: v.cpu().numpy().copy() for k, v in out.items()})
+    for o in outs[1:]:
+        for k in outs[0]:
+            assert np.array_equal(outs[0][k], o[k], equal_nan=True), k
+    for ver in vers:
+        ver.close()
+    again = P.Verifier(dm, B, K, cap)                   # the slots are back in the pool
+    assert P.heisd_verify_set_path(again.ctx, P.HEISD_PATH_PERSIST) == 0
+    kc, vc = _bits_to_dev(kb, dev), _bits_to_dev(vb, dev)
+    out = again.step(kc, vc, plen, first, drafts, acc, None)
+    torch.cuda.synchronize()
+    assert P.heisd_verify_check(again.ctx) == 0
+    for k in outs[0]:
+        assert np.array_equal(outs[0][k], out[k].cpu().numpy(), equal_nan=True), k
+    again.close()
