@@ -123,6 +123,11 @@ size_t heisd_verify_workspace_bytes(const heisd_model_desc *desc);
  * must hold their final values when init is called; later changes to them are not seen by the
  * record kernels).  Synchronises the device.  *out receives a context to be released
  * with heisd_free.  Not thread-safe; one step in flight per context.
+ * Everything the library keeps on the device lives in the caller's workspace, with one exception: the first
+ * init on a device allocates 256 KB of uncached device memory (hipExtMallocWithFlags) that is never freed, a pool
+ * of 32 slots for the grid-barrier flags of the persistent kernel; a context takes a slot here and returns it in
+ * heisd_free, and one that finds no slot (or no such memory) keeps its flags in the workspace, which is slower
+ * and no less correct.
  * Errors: EINVAL (NULL pointers, non-positive sizes, d_model != n_heads*head_dim,
  * bins outside the vocabulary), EUNSUPPORTED (head_dim not 64 or 128, d_model or d_ffn
  * or n_bins not a multiple of 16, max_k > 1024, kv_capacity > 4096), ENOMEM (workspace too
