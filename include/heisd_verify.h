@@ -124,7 +124,7 @@ size_t heisd_verify_workspace_bytes(const heisd_model_desc *desc);
  * record kernels).  Synchronises the device.  *out receives a context to be released
  * with heisd_free.  Not thread-safe; one step in flight per context.
  * Everything the library keeps on the device lives in the caller's workspace, with one exception: the first
- * init on a device allocates 256 KB of uncached device memory (hipExtMallocWithFlags) that is never freed, a pool
+ * init on a device allocates 2 MB of uncached device memory (hipExtMallocWithFlags) that is never freed, a pool
  * of 32 slots for the grid-barrier flags of the persistent kernel; a context takes a slot here and returns it in
  * heisd_free, and one that finds no slot (or no such memory) keeps its flags in the workspace, which is slower
  * and no less correct.

@@ -493,12 +493,13 @@ static void fast_forward(heisd_verify_ctx *ctx, const heisd_kv_desc *kv, const i
 // ---- persistent whole-step kernel ----------------------------------------------------------
 
 // Barrier flags that scalar loads can poll: one allocation of uncached device memory per device, made on first
-// use, cut into slots of 8 KB (1024 flags + spare), handed to contexts at init and taken back at heisd_free.  The
+// use, cut into slots of 64 KB (eight copies of 1024 flags + spare), handed to contexts at init and taken back at heisd_free.  The
 // allocation itself is never freed (memory of this kind that a kernel has read must outlive the process's
 // other allocations).  A context that gets no slot keeps its flags in the workspace and polls them with vector
 // loads.
 constexpr int kFlagSlots = 32, kFlagDevices = 16;
-constexpr size_t kFlagSlotBytes = 8192;
+constexpr size_t kFlagSlotBytes = 65536;      // room for kFlagCopies copies of the flag array
+static_assert((size_t)kFlagCopies * kFlagCopyWords * 4 <= kFlagSlotBytes, "the copies fit a slot");
 struct FlagPool {
   unsigned char *base = nullptr;
   bool tried = false;
@@ -633,7 +634,11 @@ static void persist_launch(heisd_verify_ctx *ctx, const heisd_kv_desc *kv, const
   p.trace = ctx->trace_on ? ctx->trace : nullptr;
   p.attn_prod = ctx->attn_prod; p.n_prod = 3 * d.head_dim / 16;
   p.spin_limit = ctx->wait_limit;
-  if (ctx->sflags) p.flags = ctx->sflags;
+  p.flag_copies = 1;
+  if (ctx->sflags) {
+    p.flags = ctx->sflags;
+    p.flag_copies = kFlagCopies;
+  }
   p.acc = accept;
   p.epoch0 = ctx->epoch;
   ctx->epoch += persist_epochs(ctx->n_phases);
