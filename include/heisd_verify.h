@@ -360,8 +360,8 @@ int heisd_verify_profile_read(heisd_verify_ctx *ctx, double *ms, int64_t *launch
 /*
  * Kernel-path selection, for tests and measurement.  AUTO (default) picks the fastest path
  * that covers the call.  For batch*K <= 8 (when the model fits those kernels: d_model <= 4096) that
- * is PERSIST - if it fits the device, the model is large enough for it to pay (320 MB of projection
- * weights per layer or more), the stream is not being captured into a graph, and the last
+ * is PERSIST - if it fits the device, the model is large enough for it to pay (80 MB of projection
+ * weights per layer or more; 320 MB if the context got no slot of uncached barrier flags), the stream is not being captured into a graph, and the last
  * persistent kernel launched through this library on the device went to the same stream or has
  * finished (two of them started together from two streams could each hold half of the compute units
  * and wait for the other half) - and FAST otherwise; for more rows it is BATCH.  GENERIC forces the first any-M path

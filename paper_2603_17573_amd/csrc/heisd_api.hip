@@ -1316,14 +1316,16 @@ struct PersistGuard {
 static PersistGuard g_persist_guard[kMaxDevices];
 
 // Does the context's path selection ask for the persistent kernel (for a call of at most 8 rows)?  AUTO asks for
-// it where it pays: measured at batch 1, K = 7 over model widths 512 .. 4096 (8 layers each), it is 4.5 % faster
-// than one launch per phase at 405 MB of projection weights per layer and 6 % slower at 227 MB (a barrier costs
-// more than a kernel boundary; what is handed over across it has to make up for that).
+// it where it pays: measured at batch 1, K = 7 over model widths 512 .. 4096 (8 layers each), with its barrier flags
+// in uncached memory it is 9 % faster than one launch per phase at 405 MB of projection weights per layer, 11 % at
+// 227 MB, 6 % at 101 MB, 2 % at 57 MB, and 11 % slower at 26 MB (five barriers per layer cost about what five kernel
+// boundaries cost; what is handed over across them has to pay); with the flags in the workspace (no slot of
+// uncached memory) it wins only from about 320 MB.
 static bool persist_wanted(const heisd_verify_ctx *ctx) {
   if (!ctx->persist_ok) return false;
   if (ctx->path == HEISD_PATH_PERSIST) return true;
   const double dm = ctx->d.d_model, F = ctx->d.d_ffn;
-  return ctx->path == HEISD_PATH_AUTO && (4.0 * dm * dm + 3.0 * dm * F) * 2.0 >= 320e6;
+  return ctx->path == HEISD_PATH_AUTO && (4.0 * dm * dm + 3.0 * dm * F) * 2.0 >= (ctx->sflags ? 80e6 : 320e6);
 }
 
 // Launch the persistent kernel if it may run now (or unconditionally with force); returns whether it was launched.
